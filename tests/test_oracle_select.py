@@ -1,0 +1,151 @@
+"""Pins for the oracle's scores, normalisation and threshold selection (Sec. 3.3-3.4, Eq. 3-4)."""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import vmoba_oracle as vo
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "two_block_example.json")
+
+
+def test_scores_are_scaled_dot_products():
+    rng = np.random.default_rng(2)
+    Q = rng.standard_normal((11, 6)).astype(np.float32)
+    Bm = rng.standard_normal((4, 6)).astype(np.float32)
+    S_hat = vo.block_scores(Q, Bm, 0.5)
+    assert S_hat.shape == (11, 4) and S_hat.dtype == np.float32
+    for q in range(11):
+        for j in range(4):
+            ref = 0.5 * math.fsum(float(Q[q, d]) * float(Bm[j, d]) for d in range(6))
+            assert abs(S_hat[q, j] - ref) <= 1e-6 * max(1.0, abs(ref))
+    # a transposed operand or a dropped scale would break this asymmetric case
+    Q1 = np.array([[1.0, 2.0]], dtype=np.float32)
+    B1 = np.array([[3.0, 0.0], [0.0, 5.0], [1.0, 1.0]], dtype=np.float32)
+    assert np.allclose(vo.block_scores(Q1, B1, 2.0), [[6.0, 20.0, 6.0]])
+
+
+def test_rows_of_P_sum_to_one_and_zero_query_is_uniform():
+    rng = np.random.default_rng(3)
+    S_hat = (rng.standard_normal((200, 13)) * 5).astype(np.float32)
+    P = vo.normalise_rows(S_hat)
+    assert P.dtype == np.float32 and np.all(P >= 0)
+    np.testing.assert_allclose(P.sum(1, dtype=np.float64), 1.0, atol=1e-6)
+    # soft-max definition against float64 exp
+    ref = np.exp(S_hat.astype(np.float64))
+    ref /= ref.sum(1, keepdims=True)
+    np.testing.assert_allclose(P, ref, rtol=2e-6, atol=1e-9)
+    # shift invariance and no overflow for large logits
+    P2 = vo.normalise_rows(S_hat + np.float32(1000.0))
+    assert np.all(np.isfinite(P2))
+    P0 = vo.normalise_rows(np.zeros((5, 8), dtype=np.float32))
+    assert np.all(P0 == np.float32(1.0 / 8))
+
+
+def _brute_k(P, tau):
+    """Enumerate every prefix length of the descending pool with exact rational-ish sums."""
+    vals = sorted((float(v) for v in P.reshape(-1)), reverse=True)
+    target = float(np.float32(tau)) * P.shape[0]
+    for kk in range(1, len(vals) + 1):
+        if math.fsum(vals[:kk]) >= target:
+            return kk
+    return len(vals)
+
+
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("tau", [0.1, 0.25, 0.5, 0.9])
+def test_threshold_k_brute_force(seed, tau):
+    rng = np.random.default_rng(100 + seed)
+    S, nb = int(rng.integers(3, 9)), int(rng.integers(2, 6))
+    P = vo.normalise_rows((rng.standard_normal((S, nb)) * 2).astype(np.float32))
+    k, theta, mask = vo.threshold_topk(P, tau)
+    assert k == _brute_k(P, tau)
+    assert mask.sum() == k
+    # the mask holds the k largest values: nothing unselected exceeds anything selected
+    assert P[mask].min() >= P[~mask].max() if k < P.size else True
+    assert theta == P[mask].min()
+    # minimality: one pair fewer does not reach the threshold
+    top = np.sort(P.reshape(-1).astype(np.float64))[::-1]
+    assert top[:k].sum() >= np.float32(tau) * S - 1e-9
+    assert k == 1 or top[:k - 1].sum() < np.float32(tau) * S + 1e-9
+
+
+def test_threshold_invariants():
+    rng = np.random.default_rng(7)
+    P = vo.normalise_rows((rng.standard_normal((300, 24)) * 3).astype(np.float32))
+    N = P.size
+    prev = 0
+    for tau in [0.05, 0.15, 0.25, 0.35, 0.5, 0.75, 0.95]:
+        k, theta, mask = vo.threshold_topk(P, tau)
+        # Sec. 4.1: the kept fraction is always smaller than tau -> k <= ceil(tau * N)
+        assert k <= math.ceil(np.float32(tau) * N)
+        assert k >= prev                       # monotone in tau (cf. the tau ablation)
+        prev = k
+    k, theta, mask = vo.threshold_topk(P, 1.0)
+    assert k == N and mask.all()
+
+
+def test_uniform_pool_and_tie_order():
+    P = np.full((16, 8), 1.0 / 8, dtype=np.float32)
+    for tau in [0.25, 0.3, 0.5]:
+        k, theta, mask = vo.threshold_topk(P, tau)
+        assert k == math.ceil(float(np.float32(tau)) * 128 - 1e-9)
+        # equal values are taken in ascending (q, j) order: the mask is a prefix of the
+        # row-major flattening
+        flat = mask.reshape(-1)
+        assert flat[:k].all() and not flat[k:].any()
+
+
+def test_hand_worked_two_block_example():
+    g = json.load(open(GOLD))
+    K = np.array(g["keys"], dtype=np.float32)[:, None]
+    q = np.array([0.5 * math.log(3), 0.5 * math.log(1.5), -math.log(2),
+                  -0.5 * math.log(7 / 3)], dtype=np.float32)[:, None]
+    off = np.array(g["blk_off"])
+    Bm = vo.block_means(K, off)
+    assert Bm.reshape(-1).tolist() == [1.0, -1.0]
+    P = vo.normalise_rows(vo.block_scores(q, Bm, 1.0))
+    np.testing.assert_allclose(P, np.array(g["P"]), atol=2e-7)
+    order = np.argsort(-P.reshape(-1), kind="stable")
+    assert [[int(i // 2), int(i % 2)] for i in order] == g["sorted_pairs_q_b"]
+    np.testing.assert_allclose(np.cumsum(P.reshape(-1)[order].astype(np.float64)) / 4,
+                               g["cumsum_over_S"], atol=1e-6)
+    for tau, k_ref in g["k_by_tau"].items():
+        k, theta, mask = vo.threshold_topk(P, float(tau))
+        assert k == k_ref
+        sel = {(int(a), int(b)) for a, b in zip(*np.nonzero(mask))}
+        assert sel == {tuple(p) for p in g["sorted_pairs_q_b"][:k_ref]}
+    # attention on top of it: keys are constant inside a block, so a query that keeps one
+    # block outputs that block's mean value; q1 keeps nothing at tau = 0.5
+    V = np.array(g["values"], dtype=np.float64)
+    k, theta, mask = vo.threshold_topk(P, 0.5)
+    O, LSE = vo.masked_attention_fwd(q, K, V, mask, off, 1.0)
+    for qi, ref in g["O_tau_0.5"].items():
+        np.testing.assert_allclose(O[int(qi)], ref, atol=1e-12)
+    assert LSE[1] == -np.inf and np.all(np.isfinite(LSE[[0, 2, 3]]))
+    k, theta, mask = vo.threshold_topk(P, 0.75)
+    O, LSE = vo.masked_attention_fwd(q, K, V, mask, off, 1.0)
+    np.testing.assert_allclose(O[1], g["O_tau_0.75_q1"], atol=1e-6)
+
+
+def test_csr_views_are_consistent():
+    rng = np.random.default_rng(9)
+    mask = rng.random((50, 7)) < 0.3
+    mask[5] = False
+    blk_ptr, q_idx, row_ptr, col_idx = vo.csr_from_mask(mask)
+    assert blk_ptr[-1] == row_ptr[-1] == mask.sum()
+    rebuilt = np.zeros_like(mask)
+    for j in range(7):
+        qs = q_idx[blk_ptr[j]:blk_ptr[j + 1]]
+        assert np.all(np.diff(qs) > 0)
+        rebuilt[qs, j] = True
+    assert np.array_equal(rebuilt, mask)
+    rebuilt2 = np.zeros_like(mask)
+    for q in range(50):
+        cs = col_idx[row_ptr[q]:row_ptr[q + 1]]
+        assert np.all(np.diff(cs) > 0)
+        rebuilt2[q, cs] = True
+    assert np.array_equal(rebuilt2, mask)
+    assert row_ptr[5] == row_ptr[6]
