@@ -1,0 +1,181 @@
+/*
+ * libvmoba -- VMoBA block-sparse attention for AMD MI355X (gfx950), C ABI.
+ *
+ * One attention layer of "VMoBA: Mixture-of-Block Attention for Video Diffusion Models"
+ * (arxiv 2506.23858) is four calls, in this order:
+ *
+ *     vmoba_partition  ->  vmoba_select  ->  vmoba_attn_fwd  ( ->  vmoba_attn_bwd )
+ *
+ * followed by vmoba_partition(inverse = 1) to bring O (and dQ, dK, dV) back to the
+ * caller's token order.
+ *
+ * General conventions
+ *  - Every data pointer is a DEVICE pointer unless it says "host".  The library never
+ *    allocates or frees device memory and keeps no state between calls; the caller owns
+ *    every buffer, including workspaces (size them with vmoba_workspace_bytes).
+ *  - `stream` is a hipStream_t passed as void*.  Calls only enqueue work on it and return;
+ *    nothing on this path waits for the device.  Sizes that depend on the data (k, nnz)
+ *    stay on the device.
+ *  - Return value: VMOBA_OK or a negative vmoba_status.  Arguments are validated on the
+ *    host before anything is launched; a failing call launches nothing.  No C++ exception
+ *    crosses this boundary.
+ *  - "Block order" is the token order produced by the partition (Eq. 1 of the paper):
+ *    the tokens of key block 0 first, then block 1, ...  All index arrays (mask, CSR lists)
+ *    are in block-order positions.
+ *  - Tensors are described by vmoba_tensor: element (b, s, h, d) lives at
+ *    ptr + (b*stride_b + s*stride_s + h*stride_h + d) elements; the D channels of one
+ *    (token, head) are contiguous and 16-byte aligned.
+ *  - Supported: head dimension D in {64, 128}; dtype float32 or bfloat16 (all tensors of a
+ *    call share one dtype); 1 <= n_blocks <= 256; bidirectional attention (no causal mask).
+ */
+#ifndef VMOBA_H
+#define VMOBA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    VMOBA_OK = 0,
+    VMOBA_ERR_INVALID_ARG = -1, /* null pointer, non-positive extent, tau outside (0, 1], ... */
+    VMOBA_ERR_UNSUPPORTED = -2, /* D, dtype or n_blocks outside the supported set            */
+    VMOBA_ERR_WORKSPACE = -3,   /* workspace_bytes smaller than vmoba_workspace_bytes(...)    */
+    VMOBA_ERR_CAPACITY = -4,    /* (device status word) a head selected more than nnz_capacity */
+    VMOBA_ERR_HIP = -5          /* a HIP launch reported an error                             */
+} vmoba_status;
+
+typedef enum { VMOBA_F32 = 0, VMOBA_BF16 = 1 } vmoba_dtype;
+
+/* Operations that need a workspace (argument `op` of vmoba_workspace_bytes). */
+typedef enum { VMOBA_OP_SELECT = 1, VMOBA_OP_ATTN_FWD = 2, VMOBA_OP_ATTN_BWD = 3 } vmoba_op;
+
+/* Latent grid and key-block shape (Sec. 3.2, Eq. 1).  A block is a box of bt x bh x bw
+ * latent positions: the paper's 1D partition is (s^T, H, W), its 2D partition (T, s^H, s^W),
+ * its 3D partition (s^T, s^H, s^W).  If chunk > 0 the box is ignored and a block is `chunk`
+ * consecutive tokens of the row-major (t, h, w) order.  Extents that do not divide the grid
+ * leave truncated blocks at the far edges. */
+typedef struct {
+    int32_t T, H, W;
+    int32_t bt, bh, bw;
+    int64_t chunk;
+} vmoba_grid;
+
+typedef struct {
+    void* ptr;        /* device */
+    int32_t dtype;    /* vmoba_dtype */
+    int64_t stride_b; /* elements */
+    int64_t stride_s;
+    int64_t stride_h;
+} vmoba_tensor;
+
+/* Host helpers (no GPU work). */
+
+/* Partition kind of transformer layer `layer` (0-based): 0 = 1D, 1 = 2D, 2 = 3D.
+ * (Sec. 3.2, Eq. 1: the case is chosen by l mod 3.) */
+int vmoba_layer_kind(int layer);
+
+/* Token count S = T*H*W and block count N_b of a partition (Eq. 1-2).  Host pointers. */
+int vmoba_partition_dims(const vmoba_grid* g, int64_t* S, int32_t* n_blocks);
+
+/* Bytes of workspace `op` needs for this geometry.  nnz_capacity is per (batch, head). */
+size_t vmoba_workspace_bytes(int op, int B, int Hh, int64_t S, int D, int32_t n_blocks,
+                             int64_t nnz_capacity, int dtype);
+
+const char* vmoba_status_string(int status);
+
+/*
+ * vmoba_partition -- the rearrangement K' = rearrange(K) of Sec. 3.2, Eq. 1, applied to
+ * n_tensors tensors at once (the library also keeps Q and V in block order), or its inverse.
+ *
+ *  inverse = 0:  out[i](b, p, h, :) = in[i](b, perm[p], h, :)      caller order -> block order
+ *  inverse = 1:  out[i](b, perm[p], h, :) = in[i](b, p, h, :)      block order -> caller order
+ *
+ *  perm     [S]   int32, perm[p] = row-major token index (t*H + h)*W + w at block-order position p
+ *  inv_perm [S]   int32, inverse permutation
+ *  blk_off  [n_blocks + 1] int32, first position of every block, blk_off[n_blocks] = S
+ *  With inverse = 0 and inv_perm, blk_off non-null the three arrays are WRITTEN (rebuilt from
+ *  `g`); with inverse = 0 and both null, or with inverse = 1, perm is READ as an earlier call
+ *  wrote it and the other two are not touched.
+ *  in / out: host arrays of n_tensors descriptors (1..8); a pair must have equal dtype, except
+ *  that a float32 input may be written to a bfloat16 output (round to nearest even).
+ *  Pure data movement: results are bit-exact.
+ */
+int vmoba_partition(const vmoba_grid* g, int inverse, int B, int Hh, int D, int n_tensors,
+                    const vmoba_tensor* in, const vmoba_tensor* out, int32_t* perm,
+                    int32_t* inv_perm, int32_t* blk_off, void* stream);
+
+/*
+ * vmoba_select -- Steps 1-2 of Sec. 3.1: mean key blocks (Eq. 2), query x block similarity
+ * (Eq. 3), soft-max normalisation over the blocks of each query, head-global descending
+ * cumulative-sum threshold (Eq. 4) and the TopkMask of Eq. 3, returned as a bit mask and as
+ * two sparse lists.
+ *
+ *  Qp, Kp      block-order tensors (b, s, h, d) with the strides given
+ *  tau         threshold in (0, 1]; tau >= 1 keeps every pair
+ *  score_scale factor applied to <q, b> before the soft-max (1/sqrt(D) by convention)
+ *  mode        0 = global pool + threshold (the paper's training setting); others reserved
+ *  Bmean  out  [B, Hh, n_blocks, D] float32 block means
+ *  P      out  [B, Hh, S, n_blocks] float32 normalised similarities (each row sums to 1)
+ *  mask   out  [B, Hh, S, ceil(n_blocks/32)] uint32, bit j of a row = query keeps block j
+ *  Per (b, h) the pool of S*n_blocks values is cut after the k best, k = the shortest
+ *  descending prefix whose sum reaches tau*S; equal values at the cut are taken in ascending
+ *  (query, block) order.  k_out [B*Hh] int64 and theta_out [B*Hh] float (the k-th value).
+ *  Sparse lists, every (b, h) owning a segment of nnz_capacity entries starting at
+ *  (b*Hh + h)*nnz_capacity:
+ *    blk_ptr  [B*Hh, n_blocks + 1] int32  offsets (relative to the segment) of block j's queries
+ *    q_idx    [B*Hh * nnz_capacity] int32 queries (ascending) that keep block j
+ *    row_ptr  [B*Hh, S + 1]        int32  offsets of query q's blocks
+ *    col_idx  [B*Hh * nnz_capacity] int32 blocks (ascending) kept by query q
+ *    pair_pos [B*Hh * nnz_capacity] int32 for each (q, block) in query-major order, its offset
+ *                                         in the block-major list
+ *  k <= ceil(tau*S*n_blocks) always holds, so nnz_capacity = min(S*n_blocks,
+ *  ceil(tau*S*n_blocks)) suffices.  If a head would still exceed it, nothing is written out of
+ *  bounds, its lists are left incomplete and *dev_status is set to VMOBA_ERR_CAPACITY
+ *  (dev_status is a device int32 the caller zeroes and reads after its own synchronisation).
+ */
+int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
+                 const vmoba_tensor* Qp, const vmoba_tensor* Kp, float tau, float score_scale,
+                 int mode, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
+                 int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
+                 int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * vmoba_attn_fwd -- Step 3 of Sec. 3.1: every query attends to the keys/values of its selected
+ * blocks only.  O(q) = sum_n softmax_n(softmax_scale * <Q'(q), K'(n)>) V'(n) over the keys n of
+ * the selected blocks; LSE [B, Hh, S] float32 is the natural-log-sum-exp of the scaled scores.
+ * A query that selected nothing gets O = 0 and LSE = -inf.
+ * Inputs: block-order Q', K', V', blk_off, and the lists written by vmoba_select with the same
+ * nnz_capacity.  O is written in block order.  Accumulation and soft-max are float32; bfloat16
+ * inputs are multiplied on the matrix cores.
+ */
+int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
+                   const vmoba_tensor* Qp, const vmoba_tensor* Kp, const vmoba_tensor* Vp,
+                   const int32_t* blk_ptr, const int32_t* q_idx, const int32_t* row_ptr,
+                   const int32_t* pair_pos, int64_t nnz_capacity, float softmax_scale,
+                   const vmoba_tensor* O, float* LSE, void* workspace, size_t workspace_bytes,
+                   void* stream);
+
+/*
+ * vmoba_attn_bwd -- gradient of vmoba_attn_fwd with the selection held fixed (the paper trains
+ * through Step 3; the hard selection of Step 2 passes no gradient).  With A the attention
+ * weights over the selected keys: delta = rowsum(dO * O), dV = A^T dO, dP = dO V^T,
+ * dS = A * (dP - delta), dQ = softmax_scale * dS K, dK = softmax_scale * dS^T Q.
+ * O and LSE are the forward results; all tensors in block order; dQ, dK, dV are written
+ * (not accumulated into).  Rows that selected nothing get dQ = 0 and contribute nothing.
+ */
+int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
+                   const vmoba_tensor* Qp, const vmoba_tensor* Kp, const vmoba_tensor* Vp,
+                   const vmoba_tensor* O, const float* LSE, const vmoba_tensor* dO,
+                   const int32_t* blk_ptr, const int32_t* q_idx, const int32_t* row_ptr,
+                   const int32_t* pair_pos, int64_t nnz_capacity, float softmax_scale,
+                   const vmoba_tensor* dQ, const vmoba_tensor* dK, const vmoba_tensor* dV,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VMOBA_H */

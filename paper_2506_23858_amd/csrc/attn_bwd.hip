@@ -1,0 +1,682 @@
+// vmoba_attn_bwd: gradient of the block-sparse attention of Sec. 3.1 Step 3 with the selection
+// held fixed.  With A the attention weights over the selected keys:
+//   delta = rowsum(dO * O),  dV = A^T dO,  dP = dO V^T,  dS = A * (dP - delta),
+//   dQ = scale * dS K,       dK = scale * dS^T Q.
+//
+// Three phases.  (1) delta kernel.  (2) dQ: the forward's decomposition (tile of gathered
+// queries x one key block), one partial dQ per (query, block) pair, summed query-major by a
+// merge kernel.  (3) dK/dV: a workgroup owns a run of keys of one block and walks the whole
+// query list of that block, so dK and dV of its keys stay in registers and are written once --
+// no atomics anywhere, results are reproducible.  The attention weights are recomputed from
+// Q, K and the forward's LSE in both (2) and (3).
+#include "attn_common.h"
+
+#include <algorithm>
+#include <cmath>
+
+namespace {
+
+constexpr float LOG2E = 1.4426950408889634f;
+
+// ---------------------------------------------------------------------------------------------
+template <bool BF16, int D>
+__global__ __launch_bounds__(256) void delta_kernel(TensorView O, TensorView dO, float* __restrict__ delta, int Hh, int S) {
+    constexpr int EPP = BF16 ? 8 : 4;
+    constexpr int LPQ = D / EPP;
+    constexpr int QPW = 256 / LPQ;
+    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
+    const int q = blockIdx.x * QPW + threadIdx.x / LPQ;
+    const int part = threadIdx.x % LPQ;
+    float acc = 0.f;
+    if (q < S) {
+        const char* po = O.ptr + ((long long)b * O.stride_b + (long long)q * O.stride_s + (long long)h * O.stride_h) * (BF16 ? 2 : 4) + part * 16;
+        const char* pd = dO.ptr + ((long long)b * dO.stride_b + (long long)q * dO.stride_s + (long long)h * dO.stride_h) * (BF16 ? 2 : 4) + part * 16;
+        const u32x4_t a = *reinterpret_cast<const u32x4_t*>(po);
+        const u32x4_t c = *reinterpret_cast<const u32x4_t*>(pd);
+        if constexpr (BF16) {
+            acc = bf16lo_to_f32(a.x) * bf16lo_to_f32(c.x) + bf16hi_to_f32(a.x) * bf16hi_to_f32(c.x) +
+                  bf16lo_to_f32(a.y) * bf16lo_to_f32(c.y) + bf16hi_to_f32(a.y) * bf16hi_to_f32(c.y) +
+                  bf16lo_to_f32(a.z) * bf16lo_to_f32(c.z) + bf16hi_to_f32(a.z) * bf16hi_to_f32(c.z) +
+                  bf16lo_to_f32(a.w) * bf16lo_to_f32(c.w) + bf16hi_to_f32(a.w) * bf16hi_to_f32(c.w);
+        } else {
+            acc = __uint_as_float(a.x) * __uint_as_float(c.x) + __uint_as_float(a.y) * __uint_as_float(c.y) +
+                  __uint_as_float(a.z) * __uint_as_float(c.z) + __uint_as_float(a.w) * __uint_as_float(c.w);
+        }
+    }
+#pragma unroll
+    for (int off = LPQ / 2; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if (q < S && part == 0) delta[(long long)bh * S + q] = acc;
+}
+
+// key-run table: kb_start[j] = number of key runs (of KPW keys) in blocks 0..j-1
+__global__ __launch_bounds__(64) void key_run_start_kernel(const int* __restrict__ blk_off, int* __restrict__ kb_start, int nb, int KPW) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    int run = 0;
+    for (int j = 0; j < nb; ++j) {
+        kb_start[j] = run;
+        run += (blk_off[j + 1] - blk_off[j] + KPW - 1) / KPW;
+    }
+    kb_start[nb] = run;
+}
+
+__device__ __forceinline__ float load_elem(const char* p, int d, bool bf16) {
+    return bf16 ? bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(p)[d]) : reinterpret_cast<const float*>(p)[d];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Plain FMA dQ tile kernel: one wavefront per 64 gathered queries of one key block, lane = query.
+template <bool BF16, int D>
+__global__ __launch_bounds__(64) void attn_bwd_dq_simple_kernel(
+    TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
+    const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
+    const int* __restrict__ tile_start, float* __restrict__ dQpart, int Hh, int S, int nb, long long cap, float scale_log2) {
+    constexpr int TM = 64, KC = 32;
+    constexpr int ES = BF16 ? 2 : 4;
+    __shared__ float sK[KC][D];
+    __shared__ float sV[KC][D];
+    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
+    TileCoord tc;
+    if (!find_tile(tile_start, blk_ptr, blk_off, bh, nb, blockIdx.x, TM, tc)) return;
+    const int lane = threadIdx.x;
+    const long long seg = (long long)bh * cap;
+    const int e = min(lane, tc.count - 1);
+    const int q = q_idx[seg + tc.list0 + tc.t0 + e];
+    float qr[D], dor[D], dq[D];
+    {
+        const char* sq = Q.ptr + ((long long)b * Q.stride_b + (long long)q * Q.stride_s + (long long)h * Q.stride_h) * ES;
+        const char* sd = dO.ptr + ((long long)b * dO.stride_b + (long long)q * dO.stride_s + (long long)h * dO.stride_h) * ES;
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            qr[d] = load_elem(sq, d, BF16);
+            dor[d] = load_elem(sd, d, BF16);
+            dq[d] = 0.f;
+        }
+    }
+    const float lse2 = LSE[(long long)bh * S + q] * LOG2E;
+    const float dl = delta[(long long)bh * S + q];
+    const char* kbase = K.ptr + ((long long)b * K.stride_b + (long long)h * K.stride_h) * ES;
+    const char* vbase = V.ptr + ((long long)b * V.stride_b + (long long)h * V.stride_h) * ES;
+    for (int c0 = 0; c0 < tc.L; c0 += KC) {
+        const int kc = min(KC, tc.L - c0);
+        __syncthreads();
+        for (int i = lane; i < kc * D; i += 64) {
+            const int r = i / D, d = i % D;
+            const long long row = tc.k0 + c0 + r;
+            sK[r][d] = load_elem(kbase + row * K.stride_s * ES, d, BF16);
+            sV[r][d] = load_elem(vbase + row * V.stride_s * ES, d, BF16);
+        }
+        __syncthreads();
+        for (int r = 0; r < kc; ++r) {
+            float s = 0.f, dp = 0.f;
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                s = fmaf(qr[d], sK[r][d], s);
+                dp = fmaf(dor[d], sV[r][d], dp);
+            }
+            const float p = exp2f(s * scale_log2 - lse2);
+            const float ds = p * (dp - dl);
+#pragma unroll
+            for (int d = 0; d < D; ++d) dq[d] = fmaf(ds, sK[r][d], dq[d]);
+        }
+    }
+    if (lane < tc.count) {
+        float* dst = dQpart + (seg + tc.list0 + tc.t0 + lane) * D;
+#pragma unroll
+        for (int d = 0; d < D; ++d) dst[d] = dq[d];
+    }
+}
+
+// Plain FMA dK/dV kernel: one wavefront per run of 64 keys of one block, lane = key; walks the
+// block's whole query list through LDS.
+template <bool BF16, int D>
+__global__ __launch_bounds__(64) void attn_bwd_dkv_simple_kernel(
+    TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
+    const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
+    const int* __restrict__ kb_start, TensorView dK, TensorView dV, int Hh, int S, int nb, long long cap,
+    float scale_log2, float scale) {
+    constexpr int KPW = 64, QC = 16;
+    constexpr int ES = BF16 ? 2 : 4;
+    __shared__ float sQ[QC][D];
+    __shared__ float sdO[QC][D];
+    __shared__ float sL[QC], sDl[QC];
+    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
+    if ((int)blockIdx.x >= kb_start[nb]) return;
+    int lo = 0, hi = nb;
+    while (hi - lo > 1) { int mid = (lo + hi) >> 1; if (kb_start[mid] <= (int)blockIdx.x) lo = mid; else hi = mid; }
+    const int j = lo;
+    const int k0 = blk_off[j], L = blk_off[j + 1] - k0;
+    const int kk0 = ((int)blockIdx.x - kb_start[j]) * KPW;       // first key of this run inside the block
+    const int lane = threadIdx.x;
+    const bool live = kk0 + lane < L;
+    const int krow = k0 + min(kk0 + lane, L - 1);
+    const long long seg = (long long)bh * cap;
+    const int list0 = blk_ptr[(long long)bh * (nb + 1) + j];
+    const int cnt = blk_ptr[(long long)bh * (nb + 1) + j + 1] - list0;
+    float kr[D], vr[D], dk[D], dv[D];
+    {
+        const char* sk = K.ptr + ((long long)b * K.stride_b + (long long)krow * K.stride_s + (long long)h * K.stride_h) * ES;
+        const char* sv = V.ptr + ((long long)b * V.stride_b + (long long)krow * V.stride_s + (long long)h * V.stride_h) * ES;
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            kr[d] = load_elem(sk, d, BF16);
+            vr[d] = load_elem(sv, d, BF16);
+            dk[d] = 0.f;
+            dv[d] = 0.f;
+        }
+    }
+    const char* qbase = Q.ptr + ((long long)b * Q.stride_b + (long long)h * Q.stride_h) * ES;
+    const char* dobase = dO.ptr + ((long long)b * dO.stride_b + (long long)h * dO.stride_h) * ES;
+    for (int c0 = 0; c0 < cnt; c0 += QC) {
+        const int qc = min(QC, cnt - c0);
+        __syncthreads();
+        for (int i = lane; i < qc * D; i += 64) {
+            const int r = i / D, d = i % D;
+            const long long q = q_idx[seg + list0 + c0 + r];
+            sQ[r][d] = load_elem(qbase + q * Q.stride_s * ES, d, BF16);
+            sdO[r][d] = load_elem(dobase + q * dO.stride_s * ES, d, BF16);
+        }
+        if (lane < qc) {
+            const long long q = q_idx[seg + list0 + c0 + lane];
+            sL[lane] = LSE[(long long)bh * S + q] * LOG2E;
+            sDl[lane] = delta[(long long)bh * S + q];
+        }
+        __syncthreads();
+        for (int r = 0; r < qc; ++r) {
+            float s = 0.f, dp = 0.f;
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                s = fmaf(sQ[r][d], kr[d], s);
+                dp = fmaf(sdO[r][d], vr[d], dp);
+            }
+            const float p = exp2f(s * scale_log2 - sL[r]);
+            const float ds = p * (dp - sDl[r]);
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                dv[d] = fmaf(p, sdO[r][d], dv[d]);
+                dk[d] = fmaf(ds, sQ[r][d], dk[d]);
+            }
+        }
+    }
+    if (live) {
+        char* pk = dK.ptr + ((long long)b * dK.stride_b + (long long)krow * dK.stride_s + (long long)h * dK.stride_h) * ES;
+        char* pv = dV.ptr + ((long long)b * dV.stride_b + (long long)krow * dV.stride_s + (long long)h * dV.stride_h) * ES;
+#pragma unroll
+        for (int d = 0; d < D; d += 2) {
+            if (BF16) {
+                reinterpret_cast<uint32_t*>(pk)[d / 2] = pack_bf16x2(dk[d] * scale, dk[d + 1] * scale);
+                reinterpret_cast<uint32_t*>(pv)[d / 2] = pack_bf16x2(dv[d], dv[d + 1]);
+            } else {
+                reinterpret_cast<float*>(pk)[d] = dk[d] * scale;
+                reinterpret_cast<float*>(pk)[d + 1] = dk[d + 1] * scale;
+                reinterpret_cast<float*>(pv)[d] = dv[d];
+                reinterpret_cast<float*>(pv)[d + 1] = dv[d + 1];
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Stage R rows x D channels of bf16, given by a row-address functor, into LDS transposed:
+// dst[d * TSTR + r].  Each thread moves 4 rows x 4 channels at a time: four 8-byte loads, a 4x4
+// transpose of 16-bit values with byte permutes, four 8-byte LDS stores.
+template <int R, int D, int TSTR, int NT, typename RowPtr>
+__device__ __forceinline__ void stage_transposed(__bf16* __restrict__ dst, int tid, RowPtr row_ptr_fn) {
+    constexpr int QUADS = R * D / 16;
+#pragma unroll
+    for (int i = 0; i < (QUADS + NT - 1) / NT; ++i) {
+        const int quad = tid + NT * i;
+        if (QUADS % NT == 0 || quad < QUADS) {
+            const int rq = quad / (D / 4), dq = quad % (D / 4);
+            u32x2_t v[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] = *reinterpret_cast<const u32x2_t*>(row_ptr_fn(rq * 4 + r) + dq * 8);
+            u32x2_t t0, t1, t2, t3;
+            t0.x = __builtin_amdgcn_perm(v[1].x, v[0].x, 0x05040100u);
+            t0.y = __builtin_amdgcn_perm(v[3].x, v[2].x, 0x05040100u);
+            t1.x = __builtin_amdgcn_perm(v[1].x, v[0].x, 0x07060302u);
+            t1.y = __builtin_amdgcn_perm(v[3].x, v[2].x, 0x07060302u);
+            t2.x = __builtin_amdgcn_perm(v[1].y, v[0].y, 0x05040100u);
+            t2.y = __builtin_amdgcn_perm(v[3].y, v[2].y, 0x05040100u);
+            t3.x = __builtin_amdgcn_perm(v[1].y, v[0].y, 0x07060302u);
+            t3.y = __builtin_amdgcn_perm(v[3].y, v[2].y, 0x07060302u);
+            *reinterpret_cast<u32x2_t*>(&dst[(dq * 4 + 0) * TSTR + rq * 4]) = t0;
+            *reinterpret_cast<u32x2_t*>(&dst[(dq * 4 + 1) * TSTR + rq * 4]) = t1;
+            *reinterpret_cast<u32x2_t*>(&dst[(dq * 4 + 2) * TSTR + rq * 4]) = t2;
+            *reinterpret_cast<u32x2_t*>(&dst[(dq * 4 + 3) * TSTR + rq * 4]) = t3;
+        }
+    }
+}
+
+// Row-major staging: dst[r * RSTR + d], 16-byte pieces.
+template <int R, int D, int RSTR, int NT, typename RowPtr>
+__device__ __forceinline__ void stage_rows(__bf16* __restrict__ dst, int tid, RowPtr row_ptr_fn) {
+    constexpr int PIECES = R * D / 8;
+#pragma unroll
+    for (int i = 0; i < (PIECES + NT - 1) / NT; ++i) {
+        const int piece = tid + NT * i;
+        if (PIECES % NT == 0 || piece < PIECES) {
+            const int r = piece / (D / 8), pc = piece % (D / 8);
+            *reinterpret_cast<u32x4_t*>(&dst[r * RSTR + pc * 8]) = *reinterpret_cast<const u32x4_t*>(row_ptr_fn(r) + pc * 16);
+        }
+    }
+}
+
+__device__ __forceinline__ bf16x8_t pack8(const float* p) {
+    f32x4_t lo = {p[0], p[1], p[2], p[3]};
+    f32x4_t hi = {p[4], p[5], p[6], p[7]};
+    bf16x4_t blo = __builtin_convertvector(lo, bf16x4_t);
+    bf16x4_t bhi = __builtin_convertvector(hi, bf16x4_t);
+    return __builtin_shufflevector(blo, bhi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// ---------------------------------------------------------------------------------------------
+// bf16 MFMA dQ tile kernel.  Same decomposition and operand orientation as the forward tile
+// kernel (query = MFMA column = lane % 32):
+//   S^T  = K . Q^T                    A = K rows (LDS),  B = Q^T (registers)
+//   dP^T = V . dO^T                   A = V rows (LDS),  B = dO^T (registers)
+//   dS^T = P^T * (dP^T - delta)       in registers, packed to bf16 as the next B operand
+//   dQ^T += K^T . dS^T                A = K^T (LDS, transposed copy)
+template <int D>
+__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(
+    TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
+    const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
+    const int* __restrict__ tile_start, float* __restrict__ dQpart, int Hh, int S, int nb, long long cap, float scale_log2) {
+    constexpr int TM = 128, KC = 64;
+    constexpr int RSTR = D + 8, TSTR = KC + 8;
+    constexpr int KSTEPS = D / 16, DT = D / 32;
+    __shared__ __align__(16) __bf16 sK[KC * RSTR];
+    __shared__ __align__(16) __bf16 sV[KC * RSTR];
+    __shared__ __align__(16) __bf16 sKt[D * TSTR];
+
+    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
+    TileCoord tc;
+    if (!find_tile(tile_start, blk_ptr, blk_off, bh, nb, blockIdx.x, TM, tc)) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hf = lane >> 5;
+    const long long seg = (long long)bh * cap;
+
+    const int ent = wave * 32 + l32;
+    const int e = min(ent, tc.count - 1);
+    const int q = q_idx[seg + tc.list0 + tc.t0 + e];
+    bf16x8_t qf[KSTEPS], dof[KSTEPS];
+    {
+        const char* sq = Q.ptr + ((long long)b * Q.stride_b + (long long)q * Q.stride_s + (long long)h * Q.stride_h) * 2;
+        const char* sd = dO.ptr + ((long long)b * dO.stride_b + (long long)q * dO.stride_s + (long long)h * dO.stride_h) * 2;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            qf[ks] = *reinterpret_cast<const bf16x8_t*>(sq + (ks * 16 + hf * 8) * 2);
+            dof[ks] = *reinterpret_cast<const bf16x8_t*>(sd + (ks * 16 + hf * 8) * 2);
+        }
+    }
+    const float lse2 = LSE[(long long)bh * S + q] * LOG2E;
+    const float dl = delta[(long long)bh * S + q];
+
+    f32x16_t dqacc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dqacc[dt][i] = 0.f;
+
+    const char* kbase = K.ptr + ((long long)b * K.stride_b + (long long)h * K.stride_h) * 2;
+    const char* vbase = V.ptr + ((long long)b * V.stride_b + (long long)h * V.stride_h) * 2;
+    const long long kss = K.stride_s * 2, vss = V.stride_s * 2;
+    const int n_chunks = (tc.L + KC - 1) / KC;
+
+    for (int c = 0; c < n_chunks; ++c) {
+        const int c0 = c * KC;
+        auto krow = [&](int r) { return kbase + (long long)(tc.k0 + min(c0 + r, tc.L - 1)) * kss; };
+        auto vrow = [&](int r) { return vbase + (long long)(tc.k0 + min(c0 + r, tc.L - 1)) * vss; };
+        __syncthreads();
+        stage_rows<KC, D, RSTR, 256>(sK, tid, krow);
+        stage_rows<KC, D, RSTR, 256>(sV, tid, vrow);
+        stage_transposed<KC, D, TSTR, 256>(sKt, tid, krow);
+        __syncthreads();
+        const int valid = tc.L - c0;
+        const int n_mt = valid > 32 ? 2 : 1;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            if (mt < n_mt) {
+                f32x16_t sacc, dpacc;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dpacc[i] = 0.f; }
+                const int row = mt * 32 + swap23(l32);
+#pragma unroll
+                for (int ks = 0; ks < KSTEPS; ++ks) {
+                    const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(&sK[row * RSTR + ks * 16 + hf * 8]);
+                    const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(&sV[row * RSTR + ks * 16 + hf * 8]);
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc, 0, 0, 0);
+                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[ks], dpacc, 0, 0, 0);
+                }
+                float ds[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int key = mt * 32 + ((i >> 3) << 4) + hf * 8 + (i & 7);
+                    float p = exp2_raw(sacc[i] * scale_log2 - lse2);
+                    if (key >= valid) p = 0.f;
+                    ds[i] = p * (dpacc[i] - dl);
+                }
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const bf16x8_t dsf = pack8(&ds[8 * s]);
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt) {
+                        const bf16x8_t ktf = *reinterpret_cast<const bf16x8_t*>(
+                            &sKt[(dt * 32 + l32) * TSTR + mt * 32 + s * 16 + hf * 8]);
+                        dqacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf, dqacc[dt], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+    if (ent < tc.count) {
+        float* dst = dQpart + (seg + tc.list0 + tc.t0 + ent) * D;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4_t v = {dqacc[dt][4 * g + 0], dqacc[dt][4 * g + 1], dqacc[dt][4 * g + 2], dqacc[dt][4 * g + 3]};
+                *reinterpret_cast<f32x4_t*>(dst + dt * 32 + g * 8 + hf * 4) = v;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// bf16 MFMA dK/dV kernel.  A workgroup of NW wavefronts owns 32*NW consecutive keys of one
+// block (wavefront w: 32 keys, key = MFMA column = lane % 32) and walks the block's query list
+// in chunks of 64 gathered queries:
+//   S   = Q . K^T                     A = Q rows (LDS),   B = K^T (registers, loaded once)
+//   dP  = dO . V^T                    A = dO rows (LDS),  B = V^T (registers, loaded once)
+//   P = exp(S - LSE), dS = P * (dP - delta)        packed to bf16 as B operands
+//   dV^T += dO^T . P                  A = dO^T (LDS, transposed copy)
+//   dK^T += Q^T . dS                  A = Q^T  (LDS, transposed copy)
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
+    TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
+    const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
+    const int* __restrict__ kb_start, TensorView dK, TensorView dV, int Hh, int S, int nb, long long cap,
+    float scale_log2, float scale) {
+    constexpr int NT = 64 * NW;
+    constexpr int QC = 64;
+    constexpr int RSTR = D + 8, TSTR = QC + 8;
+    constexpr int KSTEPS = D / 16, DT = D / 32;
+    __shared__ __align__(16) __bf16 sQ[QC * RSTR];
+    __shared__ __align__(16) __bf16 sdO[QC * RSTR];
+    __shared__ __align__(16) __bf16 sQt[D * TSTR];
+    __shared__ __align__(16) __bf16 sdOt[D * TSTR];
+    __shared__ __align__(16) float sL[QC];
+    __shared__ __align__(16) float sDl[QC];
+    __shared__ int sIdx[QC];
+
+    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
+    if ((int)blockIdx.x >= kb_start[nb]) return;
+    int lo = 0, hi = nb;
+    while (hi - lo > 1) { int mid = (lo + hi) >> 1; if (kb_start[mid] <= (int)blockIdx.x) lo = mid; else hi = mid; }
+    const int j = lo;
+    const int k0 = blk_off[j], L = blk_off[j + 1] - k0;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hf = lane >> 5;
+    const int kk = ((int)blockIdx.x - kb_start[j]) * (32 * NW) + wave * 32 + l32;   // key inside the block
+    const bool key_live = kk < L;
+    const bool wave_live = ((int)blockIdx.x - kb_start[j]) * (32 * NW) + wave * 32 < L;
+    const int krow = k0 + min(kk, L - 1);
+    const long long seg = (long long)bh * cap;
+    const int list0 = blk_ptr[(long long)bh * (nb + 1) + j];
+    const int cnt = blk_ptr[(long long)bh * (nb + 1) + j + 1] - list0;
+
+    bf16x8_t kf[KSTEPS], vf[KSTEPS];
+    {
+        const char* sk = K.ptr + ((long long)b * K.stride_b + (long long)krow * K.stride_s + (long long)h * K.stride_h) * 2;
+        const char* sv = V.ptr + ((long long)b * V.stride_b + (long long)krow * V.stride_s + (long long)h * V.stride_h) * 2;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            kf[ks] = *reinterpret_cast<const bf16x8_t*>(sk + (ks * 16 + hf * 8) * 2);
+            vf[ks] = *reinterpret_cast<const bf16x8_t*>(sv + (ks * 16 + hf * 8) * 2);
+        }
+    }
+    f32x16_t dkacc[DT], dvacc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { dkacc[dt][i] = 0.f; dvacc[dt][i] = 0.f; }
+
+    const char* qbase = Q.ptr + ((long long)b * Q.stride_b + (long long)h * Q.stride_h) * 2;
+    const char* dobase = dO.ptr + ((long long)b * dO.stride_b + (long long)h * dO.stride_h) * 2;
+    const long long qss = Q.stride_s * 2, doss = dO.stride_s * 2;
+
+    for (int c0 = 0; c0 < cnt; c0 += QC) {
+        const int qc = min(QC, cnt - c0);
+        __syncthreads();                 // previous chunk fully consumed
+        if (tid < QC) {
+            const int e = min(tid, qc - 1);
+            const int q = q_idx[seg + list0 + c0 + e];
+            sIdx[tid] = q;
+            // rows past the end of the list get LSE = +inf (weight 0) and delta = 0
+            sL[tid] = (tid < qc) ? LSE[(long long)bh * S + q] * LOG2E : INFINITY;
+            sDl[tid] = (tid < qc) ? delta[(long long)bh * S + q] : 0.f;
+        }
+        __syncthreads();
+        auto qrow = [&](int r) { return qbase + (long long)sIdx[r] * qss; };
+        auto dorow = [&](int r) { return dobase + (long long)sIdx[r] * doss; };
+        stage_rows<QC, D, RSTR, NT>(sQ, tid, qrow);
+        stage_rows<QC, D, RSTR, NT>(sdO, tid, dorow);
+        stage_transposed<QC, D, TSTR, NT>(sQt, tid, qrow);
+        stage_transposed<QC, D, TSTR, NT>(sdOt, tid, dorow);
+        __syncthreads();
+        if (wave_live) {
+            const int n_mt = qc > 32 ? 2 : 1;
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+                if (mt < n_mt) {
+                    f32x16_t sacc, dpacc;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dpacc[i] = 0.f; }
+                    const int row = mt * 32 + swap23(l32);
+#pragma unroll
+                    for (int ks = 0; ks < KSTEPS; ++ks) {
+                        const bf16x8_t qa = *reinterpret_cast<const bf16x8_t*>(&sQ[row * RSTR + ks * 16 + hf * 8]);
+                        const bf16x8_t da = *reinterpret_cast<const bf16x8_t*>(&sdO[row * RSTR + ks * 16 + hf * 8]);
+                        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[ks], sacc, 0, 0, 0);
+                        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[ks], dpacc, 0, 0, 0);
+                    }
+                    // accumulator value i <-> query 32*mt + 16*(i>>3) + 8*hf + (i&7) of the chunk
+                    float p[16], ds[16];
+#pragma unroll
+                    for (int s = 0; s < 2; ++s) {
+                        const int qoff = mt * 32 + s * 16 + hf * 8;
+                        const f32x4_t l0 = *reinterpret_cast<const f32x4_t*>(&sL[qoff]);
+                        const f32x4_t l1 = *reinterpret_cast<const f32x4_t*>(&sL[qoff + 4]);
+                        const f32x4_t d0 = *reinterpret_cast<const f32x4_t*>(&sDl[qoff]);
+                        const f32x4_t d1 = *reinterpret_cast<const f32x4_t*>(&sDl[qoff + 4]);
+                        const float lv[8] = {l0.x, l0.y, l0.z, l0.w, l1.x, l1.y, l1.z, l1.w};
+                        const float dv8[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const int i = 8 * s + u;
+                            p[i] = exp2_raw(sacc[i] * scale_log2 - lv[u]);
+                            ds[i] = p[i] * (dpacc[i] - dv8[u]);
+                        }
+                    }
+#pragma unroll
+                    for (int s = 0; s < 2; ++s) {
+                        const bf16x8_t pfr = pack8(&p[8 * s]);
+                        const bf16x8_t dsf = pack8(&ds[8 * s]);
+#pragma unroll
+                        for (int dt = 0; dt < DT; ++dt) {
+                            const int off = (dt * 32 + l32) * TSTR + mt * 32 + s * 16 + hf * 8;
+                            const bf16x8_t dot = *reinterpret_cast<const bf16x8_t*>(&sdOt[off]);
+                            const bf16x8_t qt = *reinterpret_cast<const bf16x8_t*>(&sQt[off]);
+                            dvacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot, pfr, dvacc[dt], 0, 0, 0);
+                            dkacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf, dkacc[dt], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+        }
+    }
+    if (key_live) {
+        char* pk = dK.ptr + ((long long)b * dK.stride_b + (long long)krow * dK.stride_s + (long long)h * dK.stride_h) * 2;
+        char* pv = dV.ptr + ((long long)b * dV.stride_b + (long long)krow * dV.stride_s + (long long)h * dV.stride_h) * 2;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int d = dt * 32 + g * 8 + hf * 4;
+                u32x2_t wk, wv;
+                wk.x = pack_bf16x2(dkacc[dt][4 * g + 0] * scale, dkacc[dt][4 * g + 1] * scale);
+                wk.y = pack_bf16x2(dkacc[dt][4 * g + 2] * scale, dkacc[dt][4 * g + 3] * scale);
+                wv.x = pack_bf16x2(dvacc[dt][4 * g + 0], dvacc[dt][4 * g + 1]);
+                wv.y = pack_bf16x2(dvacc[dt][4 * g + 2], dvacc[dt][4 * g + 3]);
+                *reinterpret_cast<u32x2_t*>(pk + d * 2) = wk;
+                *reinterpret_cast<u32x2_t*>(pv + d * 2) = wv;
+            }
+    }
+}
+
+// dQ[q] = scale * sum over the query's pairs of dQpart[pair].
+template <bool BF16, int D>
+__global__ __launch_bounds__(256) void dq_merge_kernel(const float* __restrict__ dQpart, const int* __restrict__ row_ptr,
+                                                       const int* __restrict__ pair_pos, TensorView dQ, int Hh, int S,
+                                                       long long cap, float scale) {
+    constexpr int LPQ = D / 4;
+    constexpr int QPW = 256 / LPQ;
+    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
+    const int q = blockIdx.x * QPW + threadIdx.x / LPQ;
+    const int part = threadIdx.x % LPQ;
+    if (q >= S) return;
+    const int r0 = row_ptr[(long long)bh * (S + 1) + q], r1 = row_ptr[(long long)bh * (S + 1) + q + 1];
+    const long long seg = (long long)bh * cap;
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    for (int r = r0; r < r1; ++r) {
+        const long long pair = seg + pair_pos[seg + r];
+        acc += *reinterpret_cast<const f32x4_t*>(dQpart + pair * D + part * 4);
+    }
+    acc *= scale;
+    char* dst = dQ.ptr + ((long long)b * dQ.stride_b + (long long)q * dQ.stride_s + (long long)h * dQ.stride_h) * (BF16 ? 2 : 4);
+    if (BF16) {
+        u32x2_t w;
+        w.x = pack_bf16x2(acc.x, acc.y);
+        w.y = pack_bf16x2(acc.z, acc.w);
+        *reinterpret_cast<u32x2_t*>(dst + part * 8) = w;
+    } else {
+        *reinterpret_cast<f32x4_t*>(dst + part * 16) = acc;
+    }
+}
+
+struct BwdWs {
+    float* dQpart;     // [BH * cap][D]
+    float* delta;      // [BH][S]
+    int* tile_start;   // [BH][257]
+    int* kb_start;     // [257]
+    size_t total;
+};
+
+BwdWs carve_bwd(void* base, int BH, int64_t S, int D, int64_t cap) {
+    BwdWs w;
+    char* p = (char*)base;
+    size_t off = 0;
+    w.dQpart = (float*)(p + off);    off += align_up((size_t)BH * cap * D * 4, 256);
+    w.delta = (float*)(p + off);     off += align_up((size_t)BH * S * 4, 256);
+    w.tile_start = (int*)(p + off);  off += align_up((size_t)BH * (VMOBA_MAX_BLOCKS + 1) * 4, 256);
+    w.kb_start = (int*)(p + off);    off += align_up((size_t)(VMOBA_MAX_BLOCKS + 1) * 4, 256);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+size_t vmoba_attn_bwd_workspace_bytes(int B, int Hh, int64_t S, int D, int64_t cap, int dtype) {
+    (void)dtype;
+    return carve_bwd(nullptr, B * Hh, S, D, cap).total;
+}
+
+extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
+                              const vmoba_tensor* Qp, const vmoba_tensor* Kp, const vmoba_tensor* Vp,
+                              const vmoba_tensor* O, const float* LSE, const vmoba_tensor* dO,
+                              const int32_t* blk_ptr, const int32_t* q_idx, const int32_t* row_ptr,
+                              const int32_t* pair_pos, int64_t nnz_capacity, float softmax_scale,
+                              const vmoba_tensor* dQ, const vmoba_tensor* dK, const vmoba_tensor* dV,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+    if (B <= 0 || Hh <= 0 || S <= 0 || n_blocks <= 0 || nnz_capacity <= 0) return VMOBA_ERR_INVALID_ARG;
+    if (!blk_off || !blk_ptr || !q_idx || !row_ptr || !pair_pos || !LSE || !workspace) return VMOBA_ERR_INVALID_ARG;
+    if (!tensor_ok(Qp) || !tensor_ok(Kp) || !tensor_ok(Vp) || !tensor_ok(O) || !tensor_ok(dO) || !tensor_ok(dQ) ||
+        !tensor_ok(dK) || !tensor_ok(dV))
+        return VMOBA_ERR_INVALID_ARG;
+    if (!std::isfinite(softmax_scale)) return VMOBA_ERR_INVALID_ARG;
+    if (D != 64 && D != 128) return VMOBA_ERR_UNSUPPORTED;
+    if (n_blocks > VMOBA_MAX_BLOCKS) return VMOBA_ERR_UNSUPPORTED;
+    const int dt = Qp->dtype;
+    if (Kp->dtype != dt || Vp->dtype != dt || O->dtype != dt || dO->dtype != dt || dQ->dtype != dt ||
+        dK->dtype != dt || dV->dtype != dt)
+        return VMOBA_ERR_UNSUPPORTED;
+    const int BH = B * Hh;
+    if (nnz_capacity > INT32_MAX) return VMOBA_ERR_UNSUPPORTED;
+    BwdWs ws = carve_bwd(workspace, BH, S, D, nnz_capacity);
+    if (workspace_bytes < ws.total) return VMOBA_ERR_WORKSPACE;
+    if (((uintptr_t)workspace) & 255) return VMOBA_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const bool bf16 = dt == VMOBA_BF16;
+    const TensorView Qv = make_view(Qp), Kv = make_view(Kp), Vv = make_view(Vp), Ov = make_view(O), dOv = make_view(dO);
+    const TensorView dQv = make_view(dQ), dKv = make_view(dK), dVv = make_view(dV);
+    const float scale_log2 = softmax_scale * LOG2E;
+    const bool simple = !bf16 || getenv("VMOBA_FORCE_SIMPLE") != nullptr;
+
+    {   // delta
+        const int epp = bf16 ? 8 : 4;
+        const int qpw = 256 / (D / epp);
+        dim3 grid((unsigned)ceil_div64(S, qpw), (unsigned)BH);
+        if (bf16 && D == 128) delta_kernel<true, 128><<<grid, dim3(256), 0, st>>>(Ov, dOv, ws.delta, Hh, (int)S);
+        else if (bf16) delta_kernel<true, 64><<<grid, dim3(256), 0, st>>>(Ov, dOv, ws.delta, Hh, (int)S);
+        else if (D == 128) delta_kernel<false, 128><<<grid, dim3(256), 0, st>>>(Ov, dOv, ws.delta, Hh, (int)S);
+        else delta_kernel<false, 64><<<grid, dim3(256), 0, st>>>(Ov, dOv, ws.delta, Hh, (int)S);
+        VMOBA_CHECK_LAUNCH();
+    }
+    // ---- dQ
+    const int TM = simple ? 64 : 128;
+    tile_start_kernel<<<dim3((BH + 63) / 64), dim3(64), 0, st>>>(blk_ptr, ws.tile_start, BH, n_blocks, TM);
+    VMOBA_CHECK_LAUNCH();
+    {
+        dim3 grid((unsigned)(nnz_capacity / TM + n_blocks), (unsigned)BH);
+#define DQ_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.tile_start, ws.dQpart, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2
+        if (simple) {
+            if (bf16 && D == 128) attn_bwd_dq_simple_kernel<true, 128><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
+            else if (bf16) attn_bwd_dq_simple_kernel<true, 64><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
+            else if (D == 128) attn_bwd_dq_simple_kernel<false, 128><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
+            else attn_bwd_dq_simple_kernel<false, 64><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
+        } else {
+            if (D == 128) attn_bwd_dq_mfma_kernel<128><<<grid, dim3(256), 0, st>>>(DQ_ARGS);
+            else attn_bwd_dq_mfma_kernel<64><<<grid, dim3(256), 0, st>>>(DQ_ARGS);
+        }
+#undef DQ_ARGS
+        VMOBA_CHECK_LAUNCH();
+        const int qpw = 256 / (D / 4);
+        dim3 mgrid((unsigned)ceil_div64(S, qpw), (unsigned)BH);
+#define MG_ARGS ws.dQpart, row_ptr, pair_pos, dQv, Hh, (int)S, (long long)nnz_capacity, softmax_scale
+        if (bf16 && D == 128) dq_merge_kernel<true, 128><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
+        else if (bf16) dq_merge_kernel<true, 64><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
+        else if (D == 128) dq_merge_kernel<false, 128><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
+        else dq_merge_kernel<false, 64><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
+#undef MG_ARGS
+        VMOBA_CHECK_LAUNCH();
+    }
+    // ---- dK, dV
+    {
+        constexpr int NW = 4;
+        const int KPW = simple ? 64 : 32 * NW;
+        key_run_start_kernel<<<dim3(1), dim3(64), 0, st>>>(blk_off, ws.kb_start, n_blocks, KPW);
+        VMOBA_CHECK_LAUNCH();
+        dim3 grid((unsigned)(S / KPW + n_blocks), (unsigned)BH);
+#define DKV_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.kb_start, dKv, dVv, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
+        if (simple) {
+            if (bf16 && D == 128) attn_bwd_dkv_simple_kernel<true, 128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
+            else if (bf16) attn_bwd_dkv_simple_kernel<true, 64><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
+            else if (D == 128) attn_bwd_dkv_simple_kernel<false, 128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
+            else attn_bwd_dkv_simple_kernel<false, 64><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
+        } else {
+            if (D == 128) attn_bwd_dkv_mfma_kernel<128, NW><<<grid, dim3(64 * NW), 0, st>>>(DKV_ARGS);
+            else attn_bwd_dkv_mfma_kernel<64, NW><<<grid, dim3(64 * NW), 0, st>>>(DKV_ARGS);
+        }
+#undef DKV_ARGS
+        VMOBA_CHECK_LAUNCH();
+    }
+    return VMOBA_OK;
+}

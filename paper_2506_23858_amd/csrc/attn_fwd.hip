@@ -1,0 +1,472 @@
+// vmoba_attn_fwd: Step 3 of Sec. 3.1 -- every query attends to the keys/values of its selected
+// blocks only.
+//
+// Two phases.  (1) Tile kernel, block-major: a workgroup takes TM gathered queries of one key
+// block j and runs flash-attention (online soft-max) over the L_j keys of that block alone,
+// writing a normalised partial output and its log-sum-exp per (query, block) pair.  (2) Merge
+// kernel, query-major: the partials of a query's selected blocks are combined with weights
+// exp(lse_pair - LSE).  bfloat16 inputs use the 32x32x16 bf16 MFMA; float32 inputs use a plain
+// FMA kernel of the same structure.
+#include "attn_common.h"
+
+#include <algorithm>
+#include <cmath>
+
+__global__ __launch_bounds__(64) void tile_start_kernel(const int* __restrict__ blk_ptr, int* __restrict__ tile_start,
+                                                        int BH, int nb, int TM) {
+    const int bh = blockIdx.x * 64 + threadIdx.x;
+    if (bh >= BH) return;
+    const int* bp = blk_ptr + (long long)bh * (nb + 1);
+    int* ts = tile_start + (long long)bh * (nb + 1);
+    int run = 0;
+    for (int j = 0; j < nb; ++j) {
+        ts[j] = run;
+        run += (bp[j + 1] - bp[j] + TM - 1) / TM;
+    }
+    ts[nb] = run;
+}
+
+namespace {
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+// ---------------------------------------------------------------------------------------------
+// Plain FMA tile kernel (float32 or bfloat16 inputs, float32 arithmetic).  One wavefront per
+// tile of 64 gathered queries, lane = query.  Keys and values of the block pass through LDS in
+// chunks of KC rows.
+template <bool BF16, int D>
+__global__ __launch_bounds__(64) void attn_fwd_tile_simple_kernel(
+    TensorView Q, TensorView K, TensorView V, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr,
+    const int* __restrict__ q_idx, const int* __restrict__ tile_start, float* __restrict__ Opart,
+    float* __restrict__ lse_part, int Hh, int nb, long long cap, float scale_log2) {
+    constexpr int TM = 64, KC = 32;
+    constexpr int ES = BF16 ? 2 : 4;
+    __shared__ float sK[KC][D];
+    __shared__ float sV[KC][D];
+    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
+    TileCoord tc;
+    if (!find_tile(tile_start, blk_ptr, blk_off, bh, nb, blockIdx.x, TM, tc)) return;
+    const int lane = threadIdx.x;
+    const long long seg = (long long)bh * cap;
+    const int e = min(lane, tc.count - 1);
+    const int q = q_idx[seg + tc.list0 + tc.t0 + e];
+    float qr[D], o[D];
+    {
+        const char* src = Q.ptr + ((long long)b * Q.stride_b + (long long)q * Q.stride_s + (long long)h * Q.stride_h) * ES;
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            qr[d] = BF16 ? bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(src)[d])
+                         : reinterpret_cast<const float*>(src)[d];
+            o[d] = 0.f;
+        }
+    }
+    float m = -INFINITY, l = 0.f;
+    const char* kbase = K.ptr + ((long long)b * K.stride_b + (long long)h * K.stride_h) * ES;
+    const char* vbase = V.ptr + ((long long)b * V.stride_b + (long long)h * V.stride_h) * ES;
+    for (int c0 = 0; c0 < tc.L; c0 += KC) {
+        const int kc = min(KC, tc.L - c0);
+        __syncthreads();
+        for (int i = lane; i < kc * D; i += 64) {
+            const int r = i / D, d = i % D;
+            const long long row = tc.k0 + c0 + r;
+            const char* ks = kbase + row * K.stride_s * ES;
+            const char* vs = vbase + row * V.stride_s * ES;
+            sK[r][d] = BF16 ? bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(ks)[d]) : reinterpret_cast<const float*>(ks)[d];
+            sV[r][d] = BF16 ? bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(vs)[d]) : reinterpret_cast<const float*>(vs)[d];
+        }
+        __syncthreads();
+        for (int r = 0; r < kc; ++r) {
+            float a = 0.f;
+#pragma unroll
+            for (int d = 0; d < D; ++d) a = fmaf(qr[d], sK[r][d], a);
+            a *= scale_log2;
+            const float mc = fmaxf(m, a);
+            const float alpha = exp2f(m - mc);
+            const float p = exp2f(a - mc);
+            l = l * alpha + p;
+#pragma unroll
+            for (int d = 0; d < D; ++d) o[d] = fmaf(p, sV[r][d], o[d] * alpha);
+            m = mc;
+        }
+    }
+    if (lane < tc.count) {
+        const long long pair = seg + tc.list0 + tc.t0 + lane;
+        const float inv = 1.f / l;
+        float* dst = Opart + pair * D;
+#pragma unroll
+        for (int d = 0; d < D; ++d) dst[d] = o[d] * inv;
+        lse_part[pair] = (m + log2f(l)) * LN2;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// bf16 MFMA tile kernel.  4 wavefronts; wavefront w owns NQ groups of 32 gathered queries
+// (TM = 128 * NQ per workgroup) and walks the block's keys in chunks of 64.
+//
+// All products are computed transposed so that the query index is the MFMA column (= lane % 32):
+//   S^T[key, q] = K[key, :] . Q[q, :]          A = K rows from LDS, B = Q^T held in registers
+//   O^T[d, q]  += V^T[d, key] . P^T[key, q]    A = V^T from LDS,   B = P^T packed from S^T registers
+// With the query on the lane, the row maximum and row sum of the online soft-max are reductions
+// over a lane's own registers plus one exchange with lane ^ 32.
+// MFMA row m of the first product is fed key swap23(m) of the 32-key group, which makes the 8
+// accumulator values a lane holds per 16-key step belong to 8 consecutive keys.
+template <int D, int NQ>
+__global__ __launch_bounds__(256) void attn_fwd_tile_mfma_kernel(
+    TensorView Q, TensorView K, TensorView V, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr,
+    const int* __restrict__ q_idx, const int* __restrict__ tile_start, float* __restrict__ Opart,
+    float* __restrict__ lse_part, int Hh, int nb, long long cap, float scale_log2) {
+    constexpr int TM = 128 * NQ;
+    constexpr int KC = 64;                  // keys per chunk
+    constexpr int KSTR = D + 8;             // sK row stride (bf16 elements): 16 bytes of padding
+    constexpr int VSTR = KC + 8;            // sVt row stride
+    constexpr int KSTEPS = D / 16;          // MFMA k-steps of the first product
+    constexpr int DT = D / 32;              // 32-row tiles of O^T
+    constexpr int KLOADS = KC * D * 2 / 16 / 256;   // 16-byte K pieces per thread per chunk
+    constexpr int VQUADS = KC * D / 16 / 256;       // 4x4 V quads per thread per chunk
+    __shared__ __align__(16) __bf16 sK[KC * KSTR];
+    __shared__ __align__(16) __bf16 sVt[D * VSTR];
+
+    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
+    TileCoord tc;
+    if (!find_tile(tile_start, blk_ptr, blk_off, bh, nb, blockIdx.x, TM, tc)) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hf = lane >> 5;
+    const long long seg = (long long)bh * cap;
+
+    // ---- Q^T operand: lane holds, for each of its NQ queries, 8 channels per k-step
+    bf16x8_t qf[NQ][KSTEPS];
+    int my_entry[NQ];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        const int ent = (wave * NQ + nq) * 32 + l32;          // entry inside the tile
+        my_entry[nq] = ent;
+        const int e = min(ent, tc.count - 1);                 // surplus rows repeat the last query
+        const int q = q_idx[seg + tc.list0 + tc.t0 + e];
+        const char* src = Q.ptr + ((long long)b * Q.stride_b + (long long)q * Q.stride_s + (long long)h * Q.stride_h) * 2;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks)
+            qf[nq][ks] = *reinterpret_cast<const bf16x8_t*>(src + (ks * 16 + hf * 8) * 2);
+    }
+
+    f32x16_t oacc[NQ][DT];
+    float m_run[NQ], l_run[NQ];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        m_run[nq] = -INFINITY;
+        l_run[nq] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) oacc[nq][dt][i] = 0.f;
+    }
+
+    const char* kbase = K.ptr + ((long long)b * K.stride_b + (long long)h * K.stride_h) * 2;
+    const char* vbase = V.ptr + ((long long)b * V.stride_b + (long long)h * V.stride_h) * 2;
+    const long long kss = K.stride_s * 2, vss = V.stride_s * 2;
+    const int n_chunks = (tc.L + KC - 1) / KC;
+
+    u32x4_t kreg[KLOADS];
+    u32x2_t vreg[VQUADS][4];
+    auto prefetch = [&](int c) {
+        const int c0 = c * KC;
+#pragma unroll
+        for (int i = 0; i < KLOADS; ++i) {
+            const int piece = tid + 256 * i;
+            const int r = piece / (D / 8), pc = piece % (D / 8);
+            const int row = tc.k0 + min(c0 + r, tc.L - 1);     // rows past the block repeat its last key
+            kreg[i] = *reinterpret_cast<const u32x4_t*>(kbase + (long long)row * kss + pc * 16);
+        }
+#pragma unroll
+        for (int i = 0; i < VQUADS; ++i) {
+            const int quad = tid + 256 * i;
+            const int kq = quad / (D / 4), dq = quad % (D / 4);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = tc.k0 + min(c0 + kq * 4 + r, tc.L - 1);
+                vreg[i][r] = *reinterpret_cast<const u32x2_t*>(vbase + (long long)row * vss + dq * 8);
+            }
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int i = 0; i < KLOADS; ++i) {
+            const int piece = tid + 256 * i;
+            const int r = piece / (D / 8), pc = piece % (D / 8);
+            *reinterpret_cast<u32x4_t*>(&sK[r * KSTR + pc * 8]) = kreg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < VQUADS; ++i) {
+            const int quad = tid + 256 * i;
+            const int kq = quad / (D / 4), dq = quad % (D / 4);
+            // 4 keys x 4 channels of bf16 -> 4 channels x 4 keys
+            const uint32_t a0 = vreg[i][0].x, a1 = vreg[i][0].y;   // key 0: ch 0,1 | 2,3
+            const uint32_t b0 = vreg[i][1].x, b1 = vreg[i][1].y;
+            const uint32_t c0 = vreg[i][2].x, c1 = vreg[i][2].y;
+            const uint32_t d0 = vreg[i][3].x, d1 = vreg[i][3].y;
+            u32x2_t t0, t1, t2, t3;
+            t0.x = __builtin_amdgcn_perm(b0, a0, 0x05040100u);  // ch0: key0 | key1
+            t0.y = __builtin_amdgcn_perm(d0, c0, 0x05040100u);  // ch0: key2 | key3
+            t1.x = __builtin_amdgcn_perm(b0, a0, 0x07060302u);  // ch1
+            t1.y = __builtin_amdgcn_perm(d0, c0, 0x07060302u);
+            t2.x = __builtin_amdgcn_perm(b1, a1, 0x05040100u);  // ch2
+            t2.y = __builtin_amdgcn_perm(d1, c1, 0x05040100u);
+            t3.x = __builtin_amdgcn_perm(b1, a1, 0x07060302u);  // ch3
+            t3.y = __builtin_amdgcn_perm(d1, c1, 0x07060302u);
+            *reinterpret_cast<u32x2_t*>(&sVt[(dq * 4 + 0) * VSTR + kq * 4]) = t0;
+            *reinterpret_cast<u32x2_t*>(&sVt[(dq * 4 + 1) * VSTR + kq * 4]) = t1;
+            *reinterpret_cast<u32x2_t*>(&sVt[(dq * 4 + 2) * VSTR + kq * 4]) = t2;
+            *reinterpret_cast<u32x2_t*>(&sVt[(dq * 4 + 3) * VSTR + kq * 4]) = t3;
+        }
+    };
+
+    prefetch(0);
+    for (int c = 0; c < n_chunks; ++c) {
+        __syncthreads();                      // everyone is done reading the previous chunk
+        stage();
+        __syncthreads();
+        if (c + 1 < n_chunks) prefetch(c + 1);
+
+        const int valid = tc.L - c * KC;      // keys of this chunk inside the block (may exceed KC)
+        const int n_mt = valid > 32 ? 2 : 1;  // 32-key groups with at least one valid key
+
+        // ---- S^T = K . Q^T
+        f32x16_t sacc[NQ][2];
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sacc[nq][mt][i] = 0.f;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            if (mt < n_mt) {
+                const int krow = mt * 32 + swap23(l32);
+#pragma unroll
+                for (int ks = 0; ks < KSTEPS; ++ks) {
+                    const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(&sK[krow * KSTR + ks * 16 + hf * 8]);
+#pragma unroll
+                    for (int nq = 0; nq < NQ; ++nq)
+                        sacc[nq][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nq][ks], sacc[nq][mt], 0, 0, 0);
+                }
+            }
+        }
+        // ---- online soft-max (per lane = per query), in base-2 units
+        bf16x8_t pf[NQ][2][2];
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    // accumulator value i of lane half hf <-> key 32*mt + 16*(i>>3) + 8*hf + (i&7)
+                    const int key = mt * 32 + ((i >> 3) << 4) + hf * 8 + (i & 7);
+                    float v = sacc[nq][mt][i] * scale_log2;
+                    if (key >= valid) v = -INFINITY;
+                    sacc[nq][mt][i] = v;
+                    mx = fmaxf(mx, v);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_run[nq], mx);
+            const float alpha = exp2_raw(m_run[nq] - m_new);
+            float rs = 0.f;
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+                float p[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    p[i] = exp2_raw(sacc[nq][mt][i] - m_new);
+                    rs += p[i];
+                }
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    f32x4_t lo = {p[8 * s + 0], p[8 * s + 1], p[8 * s + 2], p[8 * s + 3]};
+                    f32x4_t hi = {p[8 * s + 4], p[8 * s + 5], p[8 * s + 6], p[8 * s + 7]};
+                    bf16x4_t blo = __builtin_convertvector(lo, bf16x4_t);
+                    bf16x4_t bhi = __builtin_convertvector(hi, bf16x4_t);
+                    pf[nq][mt][s] = __builtin_shufflevector(blo, bhi, 0, 1, 2, 3, 4, 5, 6, 7);
+                }
+            }
+            rs += __shfl_xor(rs, 32, 64);
+            l_run[nq] = l_run[nq] * alpha + rs;
+            m_run[nq] = m_new;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) oacc[nq][dt][i] *= alpha;
+        }
+        // ---- O^T += V^T . P^T
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            if (mt < n_mt) {
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt) {
+                        const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(
+                            &sVt[(dt * 32 + l32) * VSTR + mt * 32 + s * 16 + hf * 8]);
+#pragma unroll
+                        for (int nq = 0; nq < NQ; ++nq)
+                            oacc[nq][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nq][mt][s], oacc[nq][dt], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- partial output: O^T value i of tile dt <-> channel 32*dt + 8*(i>>2) + 4*hf + (i&3)
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        if (my_entry[nq] < tc.count) {
+            const long long pair = seg + tc.list0 + tc.t0 + my_entry[nq];
+            const float inv = 1.f / l_run[nq];
+            float* dst = Opart + pair * D;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    f32x4_t v = {oacc[nq][dt][4 * g + 0] * inv, oacc[nq][dt][4 * g + 1] * inv,
+                                 oacc[nq][dt][4 * g + 2] * inv, oacc[nq][dt][4 * g + 3] * inv};
+                    *reinterpret_cast<f32x4_t*>(dst + dt * 32 + g * 8 + hf * 4) = v;
+                }
+            if (hf == 0) lse_part[pair] = (m_run[nq] + log2f(l_run[nq])) * LN2;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Merge: O[q] = sum_pairs exp(lse_pair - LSE[q]) * Opart[pair], LSE[q] = logsumexp(lse_pair).
+// D/4 lanes per query, each owning 4 channels.
+template <bool BF16, int D>
+__global__ __launch_bounds__(256) void attn_fwd_merge_kernel(const float* __restrict__ Opart, const float* __restrict__ lse_part,
+                                                             const int* __restrict__ row_ptr, const int* __restrict__ pair_pos,
+                                                             TensorView O, float* __restrict__ LSE, int Hh, int S, long long cap) {
+    constexpr int LPQ = D / 4;               // lanes per query
+    constexpr int QPW = 256 / LPQ;           // queries per workgroup
+    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
+    const int q = blockIdx.x * QPW + threadIdx.x / LPQ;
+    const int part = threadIdx.x % LPQ;
+    if (q >= S) return;
+    const int r0 = row_ptr[(long long)bh * (S + 1) + q], r1 = row_ptr[(long long)bh * (S + 1) + q + 1];
+    const long long seg = (long long)bh * cap;
+    float mx = -INFINITY;
+    for (int r = r0; r < r1; ++r) mx = fmaxf(mx, lse_part[seg + pair_pos[seg + r]]);
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    float wsum = 0.f;
+    for (int r = r0; r < r1; ++r) {
+        const long long pair = seg + pair_pos[seg + r];
+        const float w = expf(lse_part[pair] - mx);
+        wsum += w;
+        const f32x4_t v = *reinterpret_cast<const f32x4_t*>(Opart + pair * D + part * 4);
+        acc += v * w;
+    }
+    float lse = -INFINITY;
+    if (r1 > r0) {
+        const float inv = 1.f / wsum;
+        acc *= inv;
+        lse = mx + logf(wsum);
+    }
+    char* dst = O.ptr + ((long long)b * O.stride_b + (long long)q * O.stride_s + (long long)h * O.stride_h) * (BF16 ? 2 : 4);
+    if (BF16) {
+        u32x2_t w;
+        w.x = pack_bf16x2(acc.x, acc.y);
+        w.y = pack_bf16x2(acc.z, acc.w);
+        *reinterpret_cast<u32x2_t*>(dst + part * 8) = w;
+    } else {
+        *reinterpret_cast<f32x4_t*>(dst + part * 16) = acc;
+    }
+    if (part == 0) LSE[(long long)bh * S + q] = lse;
+}
+
+struct FwdWs {
+    float* Opart;      // [BH * cap][D]
+    float* lse_part;   // [BH * cap]
+    int* tile_start;   // [BH][nb + 1]
+    size_t total;
+};
+
+FwdWs carve_fwd(void* base, int BH, int D, int64_t cap, int nb) {
+    FwdWs w;
+    char* p = (char*)base;
+    size_t off = 0;
+    w.Opart = (float*)(p + off);     off += align_up((size_t)BH * cap * D * 4, 256);
+    w.lse_part = (float*)(p + off);  off += align_up((size_t)BH * cap * 4, 256);
+    w.tile_start = (int*)(p + off);  off += align_up((size_t)BH * (VMOBA_MAX_BLOCKS + 1) * 4, 256);
+    (void)nb;
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+size_t vmoba_attn_fwd_workspace_bytes(int B, int Hh, int64_t S, int D, int64_t cap, int dtype) {
+    (void)S; (void)dtype;
+    return carve_fwd(nullptr, B * Hh, D, cap, 0).total;
+}
+
+// Which MFMA tile width the bf16 path uses (queries per workgroup = 128 * NQ).
+int vmoba_fwd_nq() {
+    static int nq = [] {
+        const char* e = getenv("VMOBA_FWD_NQ");
+        int v = e ? atoi(e) : 2;
+        return (v == 1) ? 1 : 2;
+    }();
+    return nq;
+}
+
+extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
+                              const vmoba_tensor* Qp, const vmoba_tensor* Kp, const vmoba_tensor* Vp,
+                              const int32_t* blk_ptr, const int32_t* q_idx, const int32_t* row_ptr,
+                              const int32_t* pair_pos, int64_t nnz_capacity, float softmax_scale,
+                              const vmoba_tensor* O, float* LSE, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+    if (B <= 0 || Hh <= 0 || S <= 0 || n_blocks <= 0 || nnz_capacity <= 0) return VMOBA_ERR_INVALID_ARG;
+    if (!blk_off || !blk_ptr || !q_idx || !row_ptr || !pair_pos || !LSE || !workspace) return VMOBA_ERR_INVALID_ARG;
+    if (!tensor_ok(Qp) || !tensor_ok(Kp) || !tensor_ok(Vp) || !tensor_ok(O)) return VMOBA_ERR_INVALID_ARG;
+    if (!std::isfinite(softmax_scale)) return VMOBA_ERR_INVALID_ARG;
+    if (D != 64 && D != 128) return VMOBA_ERR_UNSUPPORTED;
+    if (n_blocks > VMOBA_MAX_BLOCKS) return VMOBA_ERR_UNSUPPORTED;
+    const int dt = Qp->dtype;
+    if (Kp->dtype != dt || Vp->dtype != dt || O->dtype != dt) return VMOBA_ERR_UNSUPPORTED;
+    const int BH = B * Hh;
+    if (nnz_capacity > INT32_MAX || (int64_t)BH * nnz_capacity * D > ((int64_t)1 << 40)) return VMOBA_ERR_UNSUPPORTED;
+    FwdWs ws = carve_fwd(workspace, BH, D, nnz_capacity, n_blocks);
+    if (workspace_bytes < ws.total) return VMOBA_ERR_WORKSPACE;
+    if (((uintptr_t)workspace) & 255) return VMOBA_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const bool bf16 = dt == VMOBA_BF16;
+    const TensorView Qv = make_view(Qp), Kv = make_view(Kp), Vv = make_view(Vp), Ov = make_view(O);
+    const float scale_log2 = softmax_scale * LOG2E;
+    const bool simple = !bf16 || getenv("VMOBA_FORCE_SIMPLE") != nullptr;
+    const int nq = vmoba_fwd_nq();
+    const int TM = simple ? 64 : 128 * nq;
+    tile_start_kernel<<<dim3((BH + 63) / 64), dim3(64), 0, st>>>(blk_ptr, ws.tile_start, BH, n_blocks, TM);
+    VMOBA_CHECK_LAUNCH();
+    const int64_t max_tiles = nnz_capacity / TM + n_blocks;
+    dim3 grid((unsigned)max_tiles, (unsigned)BH);
+#define TILE_ARGS Qv, Kv, Vv, blk_off, blk_ptr, q_idx, ws.tile_start, ws.Opart, ws.lse_part, Hh, n_blocks, (long long)nnz_capacity, scale_log2
+    if (simple) {
+        if (bf16 && D == 128) attn_fwd_tile_simple_kernel<true, 128><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
+        else if (bf16) attn_fwd_tile_simple_kernel<true, 64><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
+        else if (D == 128) attn_fwd_tile_simple_kernel<false, 128><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
+        else attn_fwd_tile_simple_kernel<false, 64><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
+    } else {
+        if (D == 128 && nq == 2) attn_fwd_tile_mfma_kernel<128, 2><<<grid, dim3(256), 0, st>>>(TILE_ARGS);
+        else if (D == 128) attn_fwd_tile_mfma_kernel<128, 1><<<grid, dim3(256), 0, st>>>(TILE_ARGS);
+        else if (nq == 2) attn_fwd_tile_mfma_kernel<64, 2><<<grid, dim3(256), 0, st>>>(TILE_ARGS);
+        else attn_fwd_tile_mfma_kernel<64, 1><<<grid, dim3(256), 0, st>>>(TILE_ARGS);
+    }
+#undef TILE_ARGS
+    VMOBA_CHECK_LAUNCH();
+    const int qpw = 256 / (D / 4);
+    dim3 mgrid((unsigned)ceil_div64(S, qpw), (unsigned)BH);
+#define MERGE_ARGS ws.Opart, ws.lse_part, row_ptr, pair_pos, Ov, LSE, Hh, (int)S, (long long)nnz_capacity
+    if (bf16 && D == 128) attn_fwd_merge_kernel<true, 128><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
+    else if (bf16) attn_fwd_merge_kernel<true, 64><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
+    else if (D == 128) attn_fwd_merge_kernel<false, 128><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
+    else attn_fwd_merge_kernel<false, 64><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
+#undef MERGE_ARGS
+    VMOBA_CHECK_LAUNCH();
+    return VMOBA_OK;
+}

@@ -1,0 +1,694 @@
+// vmoba_select: mean key blocks (Eq. 2), query x block similarities (Eq. 3), soft-max
+// normalisation per query, head-global cumulative threshold (Eq. 4), TopkMask (Eq. 3) as a
+// bit mask plus block-major and query-major sparse lists.
+//
+// The descending-sort-and-accumulate of Eq. 4 is done without sorting: P >= 0, so the order
+// of its float bit patterns is the order of its values, and a three-level radix histogram
+// (12 + 10 + 10 bits) with per-bin counts and per-bin sums locates the value theta at which
+// the descending cumulative sum reaches tau * S.  Per-bin sums are kept as 64-bit integers
+// (value * 2^fix_shift, truncated) so the result does not depend on the order of atomics.
+#include "common.h"
+
+#include <algorithm>
+#include <cmath>
+
+namespace {
+
+constexpr int HIST_BINS = 1024;
+constexpr int QT = 64;          // queries per score tile
+constexpr int SCAN_THREADS = 1024;
+constexpr int SCAN_ITEMS = 16;
+
+struct HeadState {              // one per (b, h), lives in the workspace
+    unsigned long long need;    // fixed-point mass still missing inside the current bin range
+    unsigned long long cnt_above;  // pool entries strictly above the current bin range
+    unsigned int prefix;        // float bits of theta found so far (high bits)
+    unsigned int all;           // 1: threshold never reached -> keep every pair
+    unsigned int n_tie;         // entries equal to theta
+    unsigned int take;          // how many of them belong to the top k
+};
+
+struct SelectWs {               // workspace carve-up (device pointers)
+    unsigned int* hist_cnt;         // [3][BH][1024]
+    unsigned long long* hist_sum;   // [3][BH][1024]
+    HeadState* state;               // [BH]
+    int* ties;                      // [BH][S]   per-row count of entries equal to theta
+    int* tie_base;                  // [BH][S+1] exclusive scan of ties
+    int* rowcnt;                    // [BH][S]
+    int* wcnt;                      // [BH][n_blocks][n_waves]
+    int* blk_cnt;                   // [BH][n_blocks]
+    size_t zero_bytes;              // leading bytes (hist + state) cleared on every call
+    size_t total;
+};
+
+SelectWs carve(void* base, int BH, int64_t S, int nb) {
+    SelectWs w;
+    char* p = (char*)base;
+    size_t off = 0;
+    w.hist_sum = (unsigned long long*)(p + off);  off += (size_t)3 * BH * HIST_BINS * 8;
+    w.hist_cnt = (unsigned int*)(p + off);        off += (size_t)3 * BH * HIST_BINS * 4;
+    w.state = (HeadState*)(p + off);              off += align_up((size_t)BH * sizeof(HeadState), 256);
+    w.zero_bytes = off;
+    w.ties = (int*)(p + off);                     off += align_up((size_t)BH * S * 4, 256);
+    w.tie_base = (int*)(p + off);                 off += align_up((size_t)BH * (S + 1) * 4, 256);
+    w.rowcnt = (int*)(p + off);                   off += align_up((size_t)BH * S * 4, 256);
+    int64_t n_waves = ceil_div64(S, 64);
+    w.wcnt = (int*)(p + off);                     off += align_up((size_t)BH * nb * n_waves * 4, 256);
+    w.blk_cnt = (int*)(p + off);                  off += align_up((size_t)BH * nb * 4, 256);
+    w.total = off;
+    return w;
+}
+
+__global__ __launch_bounds__(256) void zero_words_kernel(unsigned int* p, size_t n_words) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_words; i += (size_t)gridDim.x * 256) p[i] = 0u;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Block means, Eq. 2.  One workgroup per (block, b*Hh + h).  Threads are laid out as
+// (row group, 16-byte piece of a row); every thread sums its piece over the rows of its group,
+// the groups are then added in a fixed order, so the result is reproducible.
+template <bool BF16, int D>
+__global__ __launch_bounds__(256) void block_mean_kernel(TensorView K, const int* __restrict__ blk_off,
+                                                         float* __restrict__ Bmean, int Hh, int nb) {
+    constexpr int EPP = BF16 ? 8 : 4;          // elements per 16-byte piece
+    constexpr int PIECES = D / EPP;            // pieces per row
+    constexpr int GROUPS = 256 / PIECES;
+    const int j = blockIdx.x, bh = blockIdx.y;
+    const int b = bh / Hh, h = bh % Hh;
+    const int piece = threadIdx.x % PIECES, grp = threadIdx.x / PIECES;
+    const int r0 = blk_off[j], r1 = blk_off[j + 1];
+    float acc[EPP];
+#pragma unroll
+    for (int e = 0; e < EPP; ++e) acc[e] = 0.f;
+    const char* base = K.ptr + ((long long)b * K.stride_b + (long long)h * K.stride_h) * (BF16 ? 2 : 4);
+    for (int r = r0 + grp; r < r1; r += GROUPS) {
+        const char* src = base + (long long)r * K.stride_s * (BF16 ? 2 : 4) + piece * 16;
+        u32x4_t v = *reinterpret_cast<const u32x4_t*>(src);
+        if constexpr (BF16) {
+            acc[0] += bf16lo_to_f32(v.x); acc[1] += bf16hi_to_f32(v.x);
+            acc[2] += bf16lo_to_f32(v.y); acc[3] += bf16hi_to_f32(v.y);
+            acc[4] += bf16lo_to_f32(v.z); acc[5] += bf16hi_to_f32(v.z);
+            acc[6] += bf16lo_to_f32(v.w); acc[7] += bf16hi_to_f32(v.w);
+        } else {
+            acc[0] += __uint_as_float(v.x); acc[1] += __uint_as_float(v.y);
+            acc[2] += __uint_as_float(v.z); acc[3] += __uint_as_float(v.w);
+        }
+    }
+    __shared__ float red[GROUPS][D + 4];
+#pragma unroll
+    for (int e = 0; e < EPP; ++e) red[grp][piece * EPP + e] = acc[e];
+    __syncthreads();
+    if (threadIdx.x < D) {
+        float s = 0.f;
+        for (int g = 0; g < GROUPS; ++g) s += red[g][threadIdx.x];
+        Bmean[((long long)bh * nb + j) * D + threadIdx.x] = s / (float)(r1 - r0);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Scores (Eq. 3), row soft-max, P write-out and the first radix level, fused.
+// A workgroup owns a tile of QT = 64 queries of one head.  The head's block means sit in LDS
+// as float32; thread (q = tid % 64, g = tid / 64) keeps its query row in registers and
+// computes the dot products with blocks g, g+4, g+8, ...
+__device__ __forceinline__ unsigned long long to_fixed(float p, int fix_shift) {
+    return (unsigned long long)((double)p * (double)(1ull << fix_shift));
+}
+
+template <bool BF16, int D>
+__global__ __launch_bounds__(256) void score_kernel(TensorView Q, const float* __restrict__ Bmean,
+                                                    float* __restrict__ P, unsigned int* __restrict__ hist_cnt,
+                                                    unsigned long long* __restrict__ hist_sum,
+                                                    int Hh, int S, int nb, float score_scale, int fix_shift) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* sB = reinterpret_cast<float*>(smem);                       // [nb][D]
+    const int pstride = nb | 1;
+    float* sP = sB + (size_t)nb * D;                                  // [QT][pstride]
+    unsigned int* sCnt = reinterpret_cast<unsigned int*>(sP + QT * pstride);   // [1024]
+    unsigned long long* sSum = reinterpret_cast<unsigned long long*>(sCnt + HIST_BINS);  // [1024]
+
+    const int bh = blockIdx.y;
+    const int b = bh / Hh, h = bh % Hh;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+
+    for (int i = tid; i < nb * D / 4; i += 256)
+        reinterpret_cast<f32x4_t*>(sB)[i] = reinterpret_cast<const f32x4_t*>(Bmean + (long long)bh * nb * D)[i];
+    for (int i = tid; i < HIST_BINS; i += 256) { sCnt[i] = 0u; sSum[i] = 0ull; }
+    __syncthreads();
+
+    const int n_tiles = (S + QT - 1) / QT;
+    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int q0 = tile * QT;
+        const int ql = lane;
+        const int q = min(q0 + ql, S - 1);          // tail rows recompute the last query; never stored
+        // query row -> registers (float32)
+        float qr[D];
+        {
+            const char* src = Q.ptr + ((long long)b * Q.stride_b + (long long)q * Q.stride_s +
+                                       (long long)h * Q.stride_h) * (BF16 ? 2 : 4);
+            if (BF16) {
+#pragma unroll
+                for (int i = 0; i < D / 8; ++i) {
+                    u32x4_t v = reinterpret_cast<const u32x4_t*>(src)[i];
+                    qr[8 * i + 0] = bf16lo_to_f32(v.x); qr[8 * i + 1] = bf16hi_to_f32(v.x);
+                    qr[8 * i + 2] = bf16lo_to_f32(v.y); qr[8 * i + 3] = bf16hi_to_f32(v.y);
+                    qr[8 * i + 4] = bf16lo_to_f32(v.z); qr[8 * i + 5] = bf16hi_to_f32(v.z);
+                    qr[8 * i + 6] = bf16lo_to_f32(v.w); qr[8 * i + 7] = bf16hi_to_f32(v.w);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < D / 4; ++i) {
+                    f32x4_t v = reinterpret_cast<const f32x4_t*>(src)[i];
+                    qr[4 * i + 0] = v.x; qr[4 * i + 1] = v.y; qr[4 * i + 2] = v.z; qr[4 * i + 3] = v.w;
+                }
+            }
+        }
+        for (int j = wave; j < nb; j += 4) {
+            const f32x4_t* bj = reinterpret_cast<const f32x4_t*>(sB + (size_t)j * D);
+            float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+#pragma unroll
+            for (int i = 0; i < D / 4; ++i) {
+                f32x4_t bv = bj[i];
+                a0 = fmaf(qr[4 * i + 0], bv.x, a0);
+                a1 = fmaf(qr[4 * i + 1], bv.y, a1);
+                a2 = fmaf(qr[4 * i + 2], bv.z, a2);
+                a3 = fmaf(qr[4 * i + 3], bv.w, a3);
+            }
+            sP[ql * pstride + j] = ((a0 + a1) + (a2 + a3)) * score_scale;
+        }
+        __syncthreads();
+        // row maximum and denominator (every one of the 4 threads of a row computes both)
+        float m = -INFINITY;
+        for (int j = 0; j < nb; ++j) m = fmaxf(m, sP[ql * pstride + j]);
+        float den = 0.f;
+        for (int j = 0; j < nb; ++j) den += expf(sP[ql * pstride + j] - m);
+        __syncthreads();
+        for (int j = wave; j < nb; j += 4) sP[ql * pstride + j] = expf(sP[ql * pstride + j] - m) / den;
+        __syncthreads();
+        // coalesced write-out of the [64 x nb] tile + level-0 histogram
+        const int rows = min(QT, S - q0);
+        for (int r = wave; r < rows; r += 4) {
+            float* dst = P + ((long long)bh * S + q0 + r) * nb;
+            for (int j = lane; j < nb; j += 64) {
+                float p = sP[r * pstride + j];
+                dst[j] = p;
+                unsigned int bin = min(__float_as_uint(p) >> 20, (unsigned)(HIST_BINS - 1));
+                atomicAdd(&sCnt[bin], 1u);
+                atomicAdd(&sSum[bin], to_fixed(p, fix_shift));
+            }
+        }
+        __syncthreads();
+    }
+    for (int i = tid; i < HIST_BINS; i += 256) {
+        unsigned int c = sCnt[i];
+        if (c) {
+            atomicAdd(&hist_cnt[(long long)bh * HIST_BINS + i], c);
+            atomicAdd(&hist_sum[(long long)bh * HIST_BINS + i], sSum[i]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Descending scan of one radix level.  One workgroup of 1024 threads per head; thread t owns
+// bin 1023 - t, so an inclusive prefix sum over t is the descending cumulative sum.
+template <int LEVEL>
+__global__ __launch_bounds__(HIST_BINS) void scan_level_kernel(const unsigned int* __restrict__ hist_cnt,
+                                                               const unsigned long long* __restrict__ hist_sum,
+                                                               HeadState* __restrict__ state,
+                                                               unsigned long long target, int fix_shift,
+                                                               long long pool_size, long long* __restrict__ k_out,
+                                                               float* __restrict__ theta_out) {
+    __shared__ unsigned long long sS[HIST_BINS];
+    __shared__ unsigned long long sC[HIST_BINS];
+    const int bh = blockIdx.x, t = threadIdx.x;
+    const int bin = HIST_BINS - 1 - t;
+    HeadState st = state[bh];
+    if (LEVEL > 0 && st.all) {
+        if (LEVEL == 2 && t == 0) { k_out[bh] = pool_size; theta_out[bh] = 0.f; }
+        return;
+    }
+    const unsigned long long my_s = hist_sum[(long long)bh * HIST_BINS + bin];
+    const unsigned long long my_c = hist_cnt[(long long)bh * HIST_BINS + bin];
+    sS[t] = my_s;
+    sC[t] = my_c;
+    __syncthreads();
+    for (int off = 1; off < HIST_BINS; off <<= 1) {
+        unsigned long long a = 0, c = 0;
+        if (t >= off) { a = sS[t - off]; c = sC[t - off]; }
+        __syncthreads();
+        sS[t] += a;
+        sC[t] += c;
+        __syncthreads();
+    }
+    const unsigned long long need = (LEVEL == 0) ? target : st.need;
+    const unsigned long long incl = sS[t], excl = incl - my_s;
+    const unsigned long long cexcl = sC[t] - my_c;
+    if (LEVEL == 0 && t == HIST_BINS - 1 && incl < need) {
+        // the whole pool does not reach the target (tau >= 1, or rounding): keep everything
+        HeadState ns = st;
+        ns.all = 1u;
+        state[bh] = ns;
+    }
+    if (excl < need && need <= incl) {
+        HeadState ns = st;
+        ns.need = need - excl;
+        ns.cnt_above = (LEVEL == 0 ? 0ull : st.cnt_above) + cexcl;
+        ns.all = 0u;
+        if (LEVEL == 0) ns.prefix = ((unsigned)bin) << 20;
+        if (LEVEL == 1) ns.prefix = st.prefix | (((unsigned)bin) << 10);
+        if (LEVEL == 2) {
+            ns.prefix = st.prefix | (unsigned)bin;
+            const float theta = __uint_as_float(ns.prefix);
+            const unsigned long long each = to_fixed(theta, fix_shift);   // > 0: this bin has mass
+            unsigned long long take = (ns.need + each - 1) / each;
+            if (take > my_c) take = my_c;
+            if (take < 1) take = 1;
+            ns.n_tie = (unsigned)my_c;
+            ns.take = (unsigned)take;
+            k_out[bh] = (long long)(ns.cnt_above + take);
+            theta_out[bh] = theta;
+        }
+        state[bh] = ns;
+    }
+}
+
+// Radix levels 1 and 2: histogram of the next 10 bits over the entries whose higher bits
+// equal the prefix found so far.
+template <int LEVEL>
+__global__ __launch_bounds__(256) void refine_hist_kernel(const float* __restrict__ P, const HeadState* __restrict__ state,
+                                                          unsigned int* __restrict__ hist_cnt,
+                                                          unsigned long long* __restrict__ hist_sum,
+                                                          long long pool_size, int fix_shift) {
+    __shared__ unsigned int sCnt[HIST_BINS];
+    __shared__ unsigned long long sSum[HIST_BINS];
+    const int bh = blockIdx.y;
+    const HeadState st = state[bh];
+    if (st.all) return;
+    for (int i = threadIdx.x; i < HIST_BINS; i += 256) { sCnt[i] = 0u; sSum[i] = 0ull; }
+    __syncthreads();
+    constexpr int SHIFT_HI = (LEVEL == 1) ? 20 : 10;
+    constexpr int SHIFT_LO = (LEVEL == 1) ? 10 : 0;
+    const unsigned int want = st.prefix >> SHIFT_HI;
+    const u32x4_t* src = reinterpret_cast<const u32x4_t*>(P + (long long)bh * pool_size);
+    // 16-byte loads need every head's pool to start on a 16-byte boundary
+    const long long n4 = (pool_size % 4 == 0) ? pool_size / 4 : 0;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n4; i += (long long)gridDim.x * 256) {
+        u32x4_t v = src[i];
+        unsigned int u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if ((u[e] >> SHIFT_HI) == want) {
+                unsigned int bin = (u[e] >> SHIFT_LO) & (HIST_BINS - 1);
+                atomicAdd(&sCnt[bin], 1u);
+                atomicAdd(&sSum[bin], to_fixed(__uint_as_float(u[e]), fix_shift));
+            }
+        }
+    }
+    {
+        const unsigned int* s1 = reinterpret_cast<const unsigned int*>(P + (long long)bh * pool_size);
+        for (long long i = n4 * 4 + (long long)blockIdx.x * 256 + threadIdx.x; i < pool_size;
+             i += (long long)gridDim.x * 256) {
+            unsigned int u = s1[i];
+            if ((u >> SHIFT_HI) == want) {
+                unsigned int bin = (u >> SHIFT_LO) & (HIST_BINS - 1);
+                atomicAdd(&sCnt[bin], 1u);
+                atomicAdd(&sSum[bin], to_fixed(__uint_as_float(u), fix_shift));
+            }
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < HIST_BINS; i += 256) {
+        unsigned int c = sCnt[i];
+        if (c) {
+            atomicAdd(&hist_cnt[(long long)bh * HIST_BINS + i], c);
+            atomicAdd(&hist_sum[(long long)bh * HIST_BINS + i], sSum[i]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Per-row count of entries equal to theta.  Only needed when some but not all of them belong
+// to the top k; otherwise the kernel returns at once.
+__global__ __launch_bounds__(256) void tie_count_kernel(const float* __restrict__ P, const HeadState* __restrict__ state,
+                                                        int* __restrict__ ties, int S, int nb) {
+    const int bh = blockIdx.y;
+    const HeadState st = state[bh];
+    if (st.all || st.take == st.n_tie) return;
+    const int lane = threadIdx.x & 63;
+    const int gw = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int n_gw = gridDim.x * 4;
+    for (int q = gw; q < S; q += n_gw) {
+        const unsigned int* row = reinterpret_cast<const unsigned int*>(P + ((long long)bh * S + q) * nb);
+        int c = 0;
+        for (int j0 = 0; j0 < nb; j0 += 64) {
+            int j = j0 + lane;
+            bool tie = (j < nb) && (row[j] == st.prefix);
+            c += __popcll(__ballot(tie));
+        }
+        if (lane == 0) ties[(long long)bh * S + q] = c;
+    }
+}
+
+// Exclusive prefix sum of in[bh][0..S) into out[bh][0..S], out[bh][S] = total.  One workgroup
+// per head.  `needs_ties` = 1 makes the launch a no-op for heads that do not need tie ranks.
+__global__ __launch_bounds__(SCAN_THREADS) void row_scan_kernel(const int* __restrict__ in, int* __restrict__ out,
+                                                                const HeadState* __restrict__ state, int needs_ties,
+                                                                int S) {
+    __shared__ int sW[SCAN_THREADS / 64];
+    __shared__ int sCarry;
+    const int bh = blockIdx.x, t = threadIdx.x;
+    if (needs_ties) {
+        const HeadState st = state[bh];
+        if (st.all || st.take == st.n_tie) return;
+    }
+    const int* src = in + (long long)bh * S;
+    int* dst = out + (long long)bh * (S + 1);
+    if (t == 0) sCarry = 0;
+    __syncthreads();
+    for (int base = 0; base < S; base += SCAN_THREADS * SCAN_ITEMS) {
+        int v[SCAN_ITEMS];
+        int sum = 0;
+        const int i0 = base + t * SCAN_ITEMS;
+#pragma unroll
+        for (int e = 0; e < SCAN_ITEMS; ++e) {
+            v[e] = (i0 + e < S) ? src[i0 + e] : 0;
+            sum += v[e];
+        }
+        // inclusive scan of `sum` across the workgroup: wave scan, then scan of wave totals
+        int incl = sum;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            int n = __shfl_up(incl, off, 64);
+            if ((t & 63) >= off) incl += n;
+        }
+        if ((t & 63) == 63) sW[t >> 6] = incl;
+        __syncthreads();
+        int wave_base = 0;
+        for (int w = 0; w < (t >> 6); ++w) wave_base += sW[w];
+        int run = sCarry + wave_base + incl - sum;
+#pragma unroll
+        for (int e = 0; e < SCAN_ITEMS; ++e) {
+            if (i0 + e < S) dst[i0 + e] = run;
+            run += v[e];
+        }
+        __syncthreads();
+        if (t == SCAN_THREADS - 1) sCarry = run;
+        __syncthreads();
+    }
+    if (t == 0) dst[S] = sCarry;
+}
+
+// ---------------------------------------------------------------------------------------------
+// TopkMask (Eq. 3): bit (q, j) = P[q, j] is among the k best of the head.  One wavefront per
+// 64 consecutive queries.  Also counts, per wavefront, how many of its queries keep each block
+// (the raw material of the block-major list).
+__global__ __launch_bounds__(256) void mask_kernel(const float* __restrict__ P, const HeadState* __restrict__ state,
+                                                   const int* __restrict__ tie_base, unsigned int* __restrict__ mask,
+                                                   int* __restrict__ rowcnt, int* __restrict__ wcnt,
+                                                   int S, int nb, int n_waves) {
+    __shared__ unsigned int sGt[4][64][VMOBA_MAX_MASK_WORDS + 1];
+    __shared__ unsigned int sTie[4][64][VMOBA_MAX_MASK_WORDS + 1];
+    const int bh = blockIdx.y;
+    const HeadState st = state[bh];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int w = blockIdx.x * 4 + wv;           // global wavefront index = 64-query group
+    const bool active = w < n_waves;             // surplus wavefronts only keep the barriers company
+    const int q0 = active ? w * 64 : 0;
+    const int words = (nb + 31) / 32;
+    const int rows = active ? min(64, S - q0) : 0;
+#pragma unroll 4
+    for (int r = 0; r < 64; ++r) {
+        const bool live = r < rows;
+        const unsigned int* row = reinterpret_cast<const unsigned int*>(P + ((long long)bh * S + q0 + (live ? r : 0)) * nb);
+        for (int j0 = 0; j0 < nb; j0 += 64) {
+            const int j = j0 + lane;
+            const unsigned int u = (live && j < nb) ? row[j] : 0u;
+            const bool in = live && j < nb;
+            const unsigned long long gt = __ballot(in && (st.all || u > st.prefix));
+            const unsigned long long ti = __ballot(in && !st.all && u == st.prefix);
+            if (lane == 0) {
+                sGt[wv][r][j0 / 32] = (unsigned)gt;
+                sTie[wv][r][j0 / 32] = (unsigned)ti;
+                if (j0 + 32 < nb) {
+                    sGt[wv][r][j0 / 32 + 1] = (unsigned)(gt >> 32);
+                    sTie[wv][r][j0 / 32 + 1] = (unsigned)(ti >> 32);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    // lane = row
+    unsigned int mw[VMOBA_MAX_MASK_WORDS];
+    const int q = q0 + lane;
+    const bool live = lane < rows;
+    int cnt = 0;
+    if (live) {
+        const bool all_ties = (st.take == st.n_tie);
+        int rank = all_ties ? 0 : tie_base[(long long)bh * (S + 1) + q];
+#pragma unroll
+        for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) {
+            unsigned int g = 0;
+            if (wd < words) {
+                g = sGt[wv][lane][wd];
+                unsigned int t = sTie[wv][lane][wd];
+                if (all_ties) {
+                    g |= t;
+                } else {
+                    while (t) {
+                        const int bpos = __ffs(t) - 1;
+                        t &= t - 1;
+                        if ((unsigned)rank < st.take) g |= 1u << bpos;
+                        ++rank;
+                    }
+                }
+                mask[((long long)bh * S + q) * words + wd] = g;
+                cnt += __popc(g);
+            }
+            mw[wd] = g;
+        }
+        rowcnt[(long long)bh * S + q] = cnt;
+    } else {
+#pragma unroll
+        for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) mw[wd] = 0;
+    }
+    // per-block count over the 64 rows of this wavefront
+    for (int j = 0; j < nb; ++j) {
+        unsigned int word = 0;
+#pragma unroll
+        for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) if (wd == (j >> 5)) word = mw[wd];
+        const unsigned long long bal = __ballot((word >> (j & 31)) & 1u);
+        if (lane == 0 && active) wcnt[((long long)bh * nb + j) * n_waves + w] = __popcll(bal);
+    }
+}
+
+// Exclusive scan of wcnt over the wavefront index for every (head, block) (in place) and the
+// per-block totals.  One workgroup of 256 threads per (block, head).
+__global__ __launch_bounds__(256) void wave_scan_kernel(int* __restrict__ wcnt, int* __restrict__ blk_cnt,
+                                                        int nb, int n_waves) {
+    __shared__ int sW[4];
+    __shared__ int sCarry;
+    const int j = blockIdx.x, bh = blockIdx.y, t = threadIdx.x;
+    int* col = wcnt + ((long long)bh * nb + j) * n_waves;
+    if (t == 0) sCarry = 0;
+    __syncthreads();
+    for (int base = 0; base < n_waves; base += 256) {
+        const int i = base + t;
+        const int v = (i < n_waves) ? col[i] : 0;
+        int incl = v;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            int n = __shfl_up(incl, off, 64);
+            if ((t & 63) >= off) incl += n;
+        }
+        if ((t & 63) == 63) sW[t >> 6] = incl;
+        __syncthreads();
+        int wave_base = 0;
+        for (int w = 0; w < (t >> 6); ++w) wave_base += sW[w];
+        const int excl = sCarry + wave_base + incl - v;
+        if (i < n_waves) col[i] = excl;
+        __syncthreads();
+        if (t == 255) sCarry = excl + v;
+        __syncthreads();
+    }
+    if (t == 0) blk_cnt[(long long)bh * nb + j] = sCarry;
+}
+
+// blk_ptr = exclusive scan of blk_cnt over blocks; capacity check.  One wavefront-sized loop per head.
+__global__ __launch_bounds__(64) void blk_ptr_kernel(const int* __restrict__ blk_cnt, int* __restrict__ blk_ptr,
+                                                     int nb, long long cap, int* __restrict__ dev_status) {
+    const int bh = blockIdx.x;
+    if (threadIdx.x != 0) return;
+    long long run = 0;
+    for (int j = 0; j < nb; ++j) {
+        blk_ptr[(long long)bh * (nb + 1) + j] = (int)min(run, cap);
+        run += blk_cnt[(long long)bh * nb + j];
+    }
+    blk_ptr[(long long)bh * (nb + 1) + nb] = (int)min(run, cap);
+    if (run > cap) atomicExch(dev_status, (int)VMOBA_ERR_CAPACITY);
+}
+
+// Fill q_idx (block-major), col_idx and pair_pos (query-major).  One wavefront per 64 queries,
+// lane = query; a ballot per block gives every query its rank inside the wavefront.
+__global__ __launch_bounds__(256) void fill_lists_kernel(const unsigned int* __restrict__ mask, const int* __restrict__ row_ptr,
+                                                         const int* __restrict__ blk_ptr, const int* __restrict__ wcnt,
+                                                         int* __restrict__ q_idx, int* __restrict__ col_idx,
+                                                         int* __restrict__ pair_pos, int S, int nb, int n_waves,
+                                                         long long cap) {
+    __shared__ int sBase[4][VMOBA_MAX_BLOCKS];
+    const int bh = blockIdx.y;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int w = blockIdx.x * 4 + wv;
+    const bool active = w < n_waves;
+    const int words = (nb + 31) / 32;
+    if (active)
+        for (int j = lane; j < nb; j += 64)
+            sBase[wv][j] = blk_ptr[(long long)bh * (nb + 1) + j] + wcnt[((long long)bh * nb + j) * n_waves + w];
+    __syncthreads();
+    const int q = w * 64 + lane;
+    const bool live = active && q < S;
+    unsigned int mw[VMOBA_MAX_MASK_WORDS];
+#pragma unroll
+    for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd)
+        mw[wd] = (live && wd < words) ? mask[((long long)bh * S + q) * words + wd] : 0u;
+    long long r = live ? row_ptr[(long long)bh * (S + 1) + q] : 0;
+    const long long seg = (long long)bh * cap;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    for (int j = 0; j < nb; ++j) {
+        unsigned int word = 0;
+#pragma unroll
+        for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) if (wd == (j >> 5)) word = mw[wd];
+        const bool bit = (word >> (j & 31)) & 1u;
+        const unsigned long long bal = __ballot(bit);
+        if (bit) {
+            const long long pos = (long long)sBase[wv][j] + __popcll(bal & lt_mask);
+            if (pos < cap) q_idx[seg + pos] = q;
+            if (r < cap) { col_idx[seg + r] = j; pair_pos[seg + r] = (int)pos; }
+            ++r;
+        }
+    }
+}
+
+size_t score_lds_bytes(int nb, int D) {
+    return (size_t)nb * D * 4 + (size_t)QT * (nb | 1) * 4 + HIST_BINS * 4 + HIST_BINS * 8;
+}
+
+int fix_shift_for(int64_t S) {
+    int bits = 0;
+    while (((int64_t)1 << bits) < S) ++bits;
+    return 61 - bits;
+}
+
+}  // namespace
+
+size_t vmoba_select_workspace_bytes(int B, int Hh, int64_t S, int nb) {
+    return carve(nullptr, B * Hh, S, nb).total;
+}
+
+extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
+                            const vmoba_tensor* Qp, const vmoba_tensor* Kp, float tau, float score_scale,
+                            int mode, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
+                            int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
+                            int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    if (B <= 0 || Hh <= 0 || S <= 0 || n_blocks <= 0 || nnz_capacity <= 0) return VMOBA_ERR_INVALID_ARG;
+    if (!blk_off || !Bmean || !P || !mask || !blk_ptr || !q_idx || !row_ptr || !col_idx || !pair_pos ||
+        !k_out || !theta_out || !dev_status || !workspace)
+        return VMOBA_ERR_INVALID_ARG;
+    if (!tensor_ok(Qp) || !tensor_ok(Kp)) return VMOBA_ERR_INVALID_ARG;
+    if (!(tau > 0.f) || !(tau <= 1.f) || !std::isfinite(score_scale)) return VMOBA_ERR_INVALID_ARG;
+    if (mode != 0) return VMOBA_ERR_UNSUPPORTED;
+    if (D != 64 && D != 128) return VMOBA_ERR_UNSUPPORTED;
+    if (Qp->dtype != Kp->dtype) return VMOBA_ERR_UNSUPPORTED;
+    if (n_blocks > VMOBA_MAX_BLOCKS || S > ((int64_t)1 << 30) || S * n_blocks > (int64_t)INT32_MAX)
+        return VMOBA_ERR_UNSUPPORTED;
+    const size_t lds = score_lds_bytes(n_blocks, D);
+    if (lds > 160 * 1024) return VMOBA_ERR_UNSUPPORTED;
+    const int BH = B * Hh;
+    SelectWs ws = carve(workspace, BH, S, n_blocks);
+    if (workspace_bytes < ws.total) return VMOBA_ERR_WORKSPACE;
+    if (((uintptr_t)workspace) & 255) return VMOBA_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const bool bf16 = Qp->dtype == VMOBA_BF16;
+    const int n_waves = (int)ceil_div64(S, 64);
+    const long long pool = (long long)S * n_blocks;
+    const int fix_shift = fix_shift_for(S);
+    // target mass tau * S in fixed point (rounded up); tau >= 1 asks for more than the pool can hold
+    unsigned long long target;
+    if (tau >= 1.f) {
+        target = ~0ull;
+    } else {
+        target = (unsigned long long)std::ceil((double)tau * (double)S * (double)(1ull << fix_shift));
+        if (target == 0) target = 1;
+    }
+    const TensorView Qv = make_view(Qp), Kv = make_view(Kp);
+
+    zero_words_kernel<<<dim3(64), dim3(256), 0, st>>>((unsigned int*)workspace, ws.zero_bytes / 4);
+    VMOBA_CHECK_LAUNCH();
+
+#define LAUNCH_MEAN(BF, DD) block_mean_kernel<BF, DD><<<dim3(n_blocks, BH), dim3(256), 0, st>>>(Kv, blk_off, Bmean, Hh, n_blocks)
+    if (bf16 && D == 128) LAUNCH_MEAN(true, 128);
+    else if (bf16 && D == 64) LAUNCH_MEAN(true, 64);
+    else if (D == 128) LAUNCH_MEAN(false, 128);
+    else LAUNCH_MEAN(false, 64);
+#undef LAUNCH_MEAN
+    VMOBA_CHECK_LAUNCH();
+
+    const int n_tiles = (int)ceil_div64(S, QT);
+    const int tiles_per_wg = 4;
+    dim3 sgrid((unsigned)ceil_div64(n_tiles, tiles_per_wg), (unsigned)BH);
+#define LAUNCH_SCORE(BF, DD)                                                                              \
+    do {                                                                                                  \
+        auto kfn = score_kernel<BF, DD>;                                                                  \
+        if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
+            return VMOBA_ERR_HIP;                                                                         \
+        kfn<<<sgrid, dim3(256), lds, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks,  \
+                                           score_scale, fix_shift);                                       \
+    } while (0)
+    if (bf16 && D == 128) LAUNCH_SCORE(true, 128);
+    else if (bf16 && D == 64) LAUNCH_SCORE(true, 64);
+    else if (D == 128) LAUNCH_SCORE(false, 128);
+    else LAUNCH_SCORE(false, 64);
+#undef LAUNCH_SCORE
+    VMOBA_CHECK_LAUNCH();
+
+    unsigned int* hc1 = ws.hist_cnt + (size_t)BH * HIST_BINS;
+    unsigned int* hc2 = ws.hist_cnt + (size_t)2 * BH * HIST_BINS;
+    unsigned long long* hs1 = ws.hist_sum + (size_t)BH * HIST_BINS;
+    unsigned long long* hs2 = ws.hist_sum + (size_t)2 * BH * HIST_BINS;
+    const unsigned refine_gx = (unsigned)std::max<int64_t>(1, std::min<int64_t>(ceil_div64(pool / 4, 256 * 8), 2048));
+
+    scan_level_kernel<0><<<dim3(BH), dim3(HIST_BINS), 0, st>>>(ws.hist_cnt, ws.hist_sum, ws.state, target, fix_shift,
+                                                              pool, (long long*)k_out, theta_out);
+    VMOBA_CHECK_LAUNCH();
+    refine_hist_kernel<1><<<dim3(refine_gx, BH), dim3(256), 0, st>>>(P, ws.state, hc1, hs1, pool, fix_shift);
+    VMOBA_CHECK_LAUNCH();
+    scan_level_kernel<1><<<dim3(BH), dim3(HIST_BINS), 0, st>>>(hc1, hs1, ws.state, target, fix_shift, pool,
+                                                              (long long*)k_out, theta_out);
+    VMOBA_CHECK_LAUNCH();
+    refine_hist_kernel<2><<<dim3(refine_gx, BH), dim3(256), 0, st>>>(P, ws.state, hc2, hs2, pool, fix_shift);
+    VMOBA_CHECK_LAUNCH();
+    scan_level_kernel<2><<<dim3(BH), dim3(HIST_BINS), 0, st>>>(hc2, hs2, ws.state, target, fix_shift, pool,
+                                                              (long long*)k_out, theta_out);
+    VMOBA_CHECK_LAUNCH();
+
+    const unsigned row_gx = (unsigned)std::min<int64_t>(ceil_div64(S, 4 * 8), 4096);
+    tie_count_kernel<<<dim3(row_gx, BH), dim3(256), 0, st>>>(P, ws.state, ws.ties, (int)S, n_blocks);
+    VMOBA_CHECK_LAUNCH();
+    row_scan_kernel<<<dim3(BH), dim3(SCAN_THREADS), 0, st>>>(ws.ties, ws.tie_base, ws.state, 1, (int)S);
+    VMOBA_CHECK_LAUNCH();
+    const unsigned wave_gx = (unsigned)ceil_div64(n_waves, 4);
+    mask_kernel<<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, ws.state, ws.tie_base, mask, ws.rowcnt, ws.wcnt,
+                                                        (int)S, n_blocks, n_waves);
+    VMOBA_CHECK_LAUNCH();
+    row_scan_kernel<<<dim3(BH), dim3(SCAN_THREADS), 0, st>>>(ws.rowcnt, row_ptr, ws.state, 0, (int)S);
+    VMOBA_CHECK_LAUNCH();
+    wave_scan_kernel<<<dim3(n_blocks, BH), dim3(256), 0, st>>>(ws.wcnt, ws.blk_cnt, n_blocks, n_waves);
+    VMOBA_CHECK_LAUNCH();
+    blk_ptr_kernel<<<dim3(BH), dim3(64), 0, st>>>(ws.blk_cnt, blk_ptr, n_blocks, (long long)nnz_capacity, dev_status);
+    VMOBA_CHECK_LAUNCH();
+    fill_lists_kernel<<<dim3(wave_gx, BH), dim3(256), 0, st>>>(mask, row_ptr, blk_ptr, ws.wcnt, q_idx, col_idx,
+                                                              pair_pos, (int)S, n_blocks, n_waves,
+                                                              (long long)nnz_capacity);
+    VMOBA_CHECK_LAUNCH();
+    return VMOBA_OK;
+}

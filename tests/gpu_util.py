@@ -1,0 +1,88 @@
+"""Helpers of the GPU parity tests: run the HIP path through the C-ABI binding and hand back
+numpy arrays; run the oracle on the same inputs."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import vmoba_oracle as vo
+from paper_2506_23858_amd import binding as vb
+
+
+def to_dev(x: np.ndarray, dtype):
+    return torch.from_numpy(np.ascontiguousarray(x)).to("cuda").to(dtype).contiguous()
+
+
+def np32(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float32).cpu().numpy()
+
+
+def unpack_mask(words: np.ndarray, nb: int) -> np.ndarray:
+    """[..., S, words] int32 -> bool [..., S, nb]"""
+    w = words.view(np.uint32)
+    bits = ((w[..., :, None] >> np.arange(32, dtype=np.uint32)) & 1).astype(bool)
+    return bits.reshape(*w.shape[:-1], -1)[..., :nb]
+
+
+def run_gpu(Q, K, V, dO, grid, block=(0, 0, 0), chunk=0, tau=0.25, dtype=torch.float32,
+            score_scale=None, softmax_scale=None):
+    """Whole layer on the GPU.  Q, K, V, dO: numpy [B, S, Hh, D] float32 (dO may be None)."""
+    B, S, Hh, D = Q.shape
+    plan = vb.LayerPlan(B, Hh, D, grid, block, chunk, tau, dtype, score_scale=score_scale,
+                        softmax_scale=softmax_scale, need_bwd=dO is not None)
+    assert plan.S == S
+    q, k, v = (to_dev(x, dtype) for x in (Q, K, V))
+    plan.forward(q, k, v)
+    out = {}
+    if dO is not None:
+        plan.backward(to_dev(dO, dtype))
+    torch.cuda.synchronize()
+    assert int(plan.dev_status.item()) == 0
+    nb = plan.nb
+    out.update(plan=plan, nb=nb, cap=plan.cap,
+               perm=plan.perm.cpu().numpy(), inv_perm=plan.inv_perm.cpu().numpy(),
+               blk_off=plan.blk_off.cpu().numpy(),
+               Qp=np32(plan.Qp.permute(0, 2, 1, 3)), Kp=np32(plan.Kp.permute(0, 2, 1, 3)),
+               Vp=np32(plan.Vp.permute(0, 2, 1, 3)), Op=np32(plan.Op.permute(0, 2, 1, 3)),
+               O=np32(plan.O), LSE=plan.LSE.cpu().numpy(), Bmean=plan.Bmean.cpu().numpy(),
+               P=plan.P.cpu().numpy(), mask=unpack_mask(plan.mask.cpu().numpy(), nb),
+               k=plan.k_out.cpu().numpy().reshape(B, Hh), theta=plan.theta.cpu().numpy().reshape(B, Hh),
+               blk_ptr=plan.blk_ptr.cpu().numpy().reshape(B, Hh, nb + 1),
+               row_ptr=plan.row_ptr.cpu().numpy().reshape(B, Hh, S + 1),
+               q_idx=plan.q_idx.cpu().numpy().reshape(B, Hh, plan.cap),
+               col_idx=plan.col_idx.cpu().numpy().reshape(B, Hh, plan.cap),
+               pair_pos=plan.pair_pos.cpu().numpy().reshape(B, Hh, plan.cap))
+    if dO is not None:
+        out.update(dQ=np32(plan.dQ), dK=np32(plan.dK), dV=np32(plan.dV),
+                   dQp=np32(plan.dQp.permute(0, 2, 1, 3)), dKp=np32(plan.dKp.permute(0, 2, 1, 3)),
+                   dVp=np32(plan.dVp.permute(0, 2, 1, 3)))
+    return out
+
+
+def check_lists(g, b, h):
+    """The sparse lists of head (b, h) must describe exactly the GPU's own bit mask."""
+    mask = g["mask"][b, h]
+    blk_ptr, q_idx, row_ptr, col_idx = vo.csr_from_mask(mask)
+    nnz = int(mask.sum())
+    assert nnz == int(g["k"][b, h]), (nnz, g["k"][b, h])
+    assert np.array_equal(g["blk_ptr"][b, h], blk_ptr)
+    assert np.array_equal(g["row_ptr"][b, h], row_ptr)
+    assert np.array_equal(g["q_idx"][b, h][:nnz], q_idx)
+    assert np.array_equal(g["col_idx"][b, h][:nnz], col_idx)
+    # pair_pos: entry r of the query-major list points at the same (q, j) in the block-major list
+    pp = g["pair_pos"][b, h][:nnz]
+    rows = np.repeat(np.arange(mask.shape[0]), np.diff(row_ptr))
+    assert np.array_equal(q_idx[pp], rows)
+    blk_of_entry = np.repeat(np.arange(mask.shape[1]), np.diff(blk_ptr))
+    assert np.array_equal(blk_of_entry[pp], col_idx)
+
+
+def check_selection(g, o, b, h, band_tol=1e-6):
+    """Selection of head (b, h): GPU (g) against oracle (o).  Pairs whose oracle P lies within
+    band_tol of the oracle threshold are exempt (they flip with summation order)."""
+    P_or, th_or = o["P"][b, h], o["theta"][b, h]
+    band = np.abs(P_or - th_or) <= band_tol
+    diff = g["mask"][b, h] != o["mask"][b, h]
+    assert not (diff & ~band).any(), f"{(diff & ~band).sum()} mask bits differ outside the band"
+    assert abs(int(g["k"][b, h]) - int(o["k"][b, h])) <= int(band.sum())
+    return int(band.sum()), int(diff.sum())

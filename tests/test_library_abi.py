@@ -1,0 +1,77 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every function the header declares,
+and its host-only helpers and argument validation work without a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2506_23858_amd import binding as vb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(vb.LIB_PATH):
+        from paper_2506_23858_amd import build
+        build.build_lib(verbose=False)
+    return vb.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    hdr = open(os.path.join(ROOT, "include", "vmoba.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(vmoba_[a-z_]+)\s*\(", hdr))
+    assert {"vmoba_partition", "vmoba_select", "vmoba_attn_fwd", "vmoba_attn_bwd"} <= declared
+    for name in declared:
+        assert hasattr(L, name), name
+    assert declared == set(vb.EXPORTS)
+
+
+def test_layer_kind_cycle():
+    assert [vb.vmoba_layer_kind(l) for l in range(6)] == [0, 1, 2, 0, 1, 2]
+
+
+@pytest.mark.parametrize("grid,block,chunk,S,nb", [
+    ((21, 30, 52), (3, 30, 52), 0, 32760, 7), ((21, 30, 52), (21, 5, 13), 0, 32760, 24),
+    ((21, 30, 52), (7, 5, 13), 0, 32760, 72), ((21, 30, 52), (0, 0, 0), 1560, 32760, 21),
+    ((21, 45, 80), (1, 30, 40), 0, 75600, 84), ((31, 45, 80), (3, 15, 16), 0, 111600, 165),
+    ((5, 7, 9), (2, 3, 4), 0, 315, 27),
+])
+def test_partition_dims(grid, block, chunk, S, nb):
+    g = vb.make_grid(*grid, *block, chunk)
+    assert vb.vmoba_partition_dims(g) == (S, nb)
+    from oracle import vmoba_oracle as vo
+    assert vo.partition_dims(*grid, *block, chunk) == (S, nb)
+
+
+def test_bad_arguments_are_rejected_before_any_launch(L):
+    g = vb.make_grid(0, 4, 4, 1, 1, 1)
+    S, nb = C.c_int64(), C.c_int32()
+    assert L.vmoba_partition_dims(C.byref(g), C.byref(S), C.byref(nb)) == vb.VMOBA_ERR_INVALID_ARG
+    g = vb.make_grid(4, 4, 4, 2, 2, 2)
+    # null perm
+    assert L.vmoba_partition(C.byref(g), 0, 1, 1, 64, 0, None, None, None, None, None, None) == vb.VMOBA_ERR_INVALID_ARG
+    # unsupported head dimension
+    dummy = C.c_void_p(256)
+    assert L.vmoba_partition(C.byref(g), 1, 1, 1, 48, 0, None, None, dummy, None, None, None) == vb.VMOBA_ERR_UNSUPPORTED
+    t = vb.vmoba_tensor(256, vb.VMOBA_F32, 64 * 64, 64, 64)
+    args = [1, 1, 64, 64, 8, dummy, C.byref(t), C.byref(t)]
+    tail = [dummy] * 8 + [100, dummy, dummy, dummy, dummy, 1 << 30, None]
+    assert L.vmoba_select(*args, 0.0, 0.125, 0, *tail) == vb.VMOBA_ERR_INVALID_ARG      # tau = 0
+    assert L.vmoba_select(*args, 1.5, 0.125, 0, *tail) == vb.VMOBA_ERR_INVALID_ARG      # tau > 1
+    assert L.vmoba_select(*args, 0.25, 0.125, 7, *tail) == vb.VMOBA_ERR_UNSUPPORTED     # unknown mode
+    tail_small = [dummy] * 8 + [100, dummy, dummy, dummy, dummy, 16, None]
+    assert L.vmoba_select(*args, 0.25, 0.125, 0, *tail_small) == vb.VMOBA_ERR_WORKSPACE
+    assert vb.status_string(vb.VMOBA_ERR_WORKSPACE) == "workspace too small"
+
+
+def test_workspace_sizes_grow_with_capacity(L):
+    a = vb.vmoba_workspace_bytes(vb.OP_ATTN_FWD, 1, 2, 512, 64, 16, 1000, vb.VMOBA_F32)
+    b = vb.vmoba_workspace_bytes(vb.OP_ATTN_FWD, 1, 2, 512, 64, 16, 2000, vb.VMOBA_F32)
+    assert 0 < a < b
+    assert vb.vmoba_workspace_bytes(vb.OP_SELECT, 1, 2, 512, 64, 16, 1000, vb.VMOBA_F32) > 0
+    assert vb.vmoba_workspace_bytes(vb.OP_ATTN_BWD, 1, 2, 512, 64, 16, 1000, vb.VMOBA_F32) > 0
+    assert vb.vmoba_workspace_bytes(99, 1, 2, 512, 64, 16, 1000, vb.VMOBA_F32) == 0
+    assert vb.nnz_capacity_for(512, 16, 0.25) == 2049
