@@ -1,0 +1,269 @@
+#!/usr/bin/env python3
+"""Benchmark of the VMoBA hot path on one MI355X.
+
+A step = one attention layer, forward and backward, through the whole path:
+partition(Q,K,V) -> select -> attn_fwd -> inverse partition(O) -> partition(dO) -> attn_bwd ->
+inverse partition(dQ,dK,dV).  Steps cycle through the 1D / 2D / 3D partitions (layer l uses kind
+l mod 3), so a multiple of 3 steps covers the cycle evenly.  Inputs are synthetic (blurred noise
+on the 480p latent grid 21x30x52, 12 heads x 128, bf16) and resident in HBM before timing.
+
+Prints ONE JSON line.  `value` is effective TFLOP/s of the whole step: 14 * D * (sum over
+selected (query, block) pairs of the block length) per layer, divided by the wall time of the
+step -- selected work only, no credit for recompute, padding or the dense work avoided.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+BF16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak (published)
+METRIC = "VMoBA attn fwd+bwd ms/layer + effective TFLOP/s (%MFMA peak), 480p shape"
+
+
+class Hip:
+    """The few HIP runtime calls the benchmark needs for raw events."""
+
+    def __init__(self):
+        self.lib = C.CDLL("libamdhip64.so")
+        self.lib.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.lib.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.lib.hipEventDestroy.argtypes = [C.c_void_p]
+
+    def event(self):
+        e = C.c_void_p()
+        rc = self.lib.hipEventCreate(C.byref(e))
+        assert rc == 0, rc
+        return e.value
+
+    def elapsed_ms(self, a, b):
+        ms = C.c_float()
+        rc = self.lib.hipEventElapsedTime(C.byref(ms), C.c_void_p(a), C.c_void_p(b))
+        assert rc == 0, rc
+        return ms.value
+
+
+def selected_key_sum(plan):
+    """sum over selected (query, block) pairs of L_j, over all heads (host, after a sync)."""
+    blk_ptr = plan.blk_ptr.cpu().numpy().astype(np.int64)
+    L = np.diff(plan.blk_off.cpu().numpy().astype(np.int64))
+    cnt = np.diff(blk_ptr, axis=1)
+    return int((cnt * L[None, :]).sum()), int(cnt.sum())
+
+
+def cpu_baseline(Q, K, V, dO, cfg, part, tau, rows=4096):
+    """The CPU oracle on head 0: selection over the whole head, masked attention forward and
+    backward on every (S/rows)-th query row; time scaled to the whole head."""
+    from oracle import vmoba_oracle as vo
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    T, H, W = cfg["grid"]
+    bt, bh, bw, chunk = part
+    D = Q.shape[-1]
+    scale = 1.0 / math.sqrt(D)
+    t0 = time.perf_counter()
+    perm, inv, off = vo.partition_index(T, H, W, bt, bh, bw, chunk)
+    Qp, Kp, Vp, dOp = (vo.gather_rows(x[:, :, :1], perm)[0, 0] for x in (Q, K, V, dO))
+    sel = vo.select_blocks(Qp, Kp, off, tau, scale)
+    t_sel = time.perf_counter() - t0
+    S = Qp.shape[0]
+    step = max(1, S // rows)
+    idx = np.arange(0, S, step)
+    t0 = time.perf_counter()
+    vo.masked_attention_fwd(Qp[idx], Kp, Vp, sel["mask"][idx], off, scale)
+    vo.masked_attention_bwd(Qp[idx], Kp, Vp, sel["mask"][idx], off, scale, dOp[idx])
+    t_att = time.perf_counter() - t0
+    L = np.diff(off).astype(np.int64)
+    keysum_head = int((sel["mask"].sum(0).astype(np.int64) * L).sum())
+    est = t_sel + t_att * (S / len(idx))
+    return {"value": 14.0 * D * keysum_head / est / 1e12, "unit": "TFLOP/s (effective, fwd+bwd)",
+            "cores": int(cores), "kind": "oracle",
+            "sample": f"head 0 of {Q.shape[2]}, 3D partition: selection on the whole head ({t_sel:.1f} s) + float64 masked "
+                      f"attention fwd+bwd on {len(idx)} of {S} query rows ({t_att:.1f} s), scaled to the head: {est:.1f} s/head",
+            "seconds_per_head_est": est}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=12)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="480p")
+    ap.add_argument("--tau", type=float, default=0.25)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--no-dense", action="store_true", help="skip the dense comparators")
+    ap.add_argument("--kinds", default="1d,2d,3d")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU; --gpus must be 1 (the path shards by head, see DESIGN.md)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2506_23858_amd import binding as vb, synth
+
+    if not os.path.exists(vb.LIB_PATH):
+        raise SystemExit("libvmoba.so is missing: run `python -c 'import __graft_entry__ as g; g.build()'` first")
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda"
+    torch.cuda.set_device(0)
+    hip = Hip()
+    cfg = synth.CONFIGS[args.config]
+    Hh, D = cfg["heads"], cfg["D"]
+    dtype = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+    t_gen = time.perf_counter()
+    Qn, Kn, Vn, dOn = synth.make_qkv(args.config)
+    t_gen = time.perf_counter() - t_gen
+    Q, K, V, dO = (torch.from_numpy(x).to(dev).to(dtype).contiguous() for x in (Qn, Kn, Vn, dOn))
+    S = Q.shape[1]
+    kinds = [k for k in args.kinds.split(",") if k in cfg["partitions"]]
+    plans = {}
+    for kind in kinds:
+        bt, bh, bw, chunk = cfg["partitions"][kind]
+        plans[kind] = vb.LayerPlan(1, Hh, D, cfg["grid"], (bt, bh, bw), chunk, args.tau, dtype)
+
+    def step(i):
+        p = plans[kinds[i % len(kinds)]]
+        p.forward(Q, K, V)
+        p.backward(dO)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    for p in plans.values():
+        assert int(p.dev_status.item()) == 0
+
+    # ---- timed region: exactly `steps` steps, kernel events on the launch stream
+    SLOTS = {0: "attn_fwd_tile", 1: "attn_bwd_dq_tile", 2: "attn_bwd_dkv"}
+    ev = {s: [(hip.event(), hip.event()) for _ in range(args.steps)] for s in SLOTS}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        for s in SLOTS:
+            vb.vmoba_profile_events(s, *ev[s][i])
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for s in SLOTS:
+        vb.vmoba_profile_events(s, None, None)
+    total_s = t1 - t0
+    ms_per_step = total_s * 1e3 / args.steps
+
+    # ---- work accounting (selected blocks only)
+    keysum, pairs = {}, {}
+    for kind, p in plans.items():
+        keysum[kind], pairs[kind] = selected_key_sum(p)
+    step_kinds = [kinds[i % len(kinds)] for i in range(args.steps)]
+    flops_total = sum(14.0 * D * keysum[k] for k in step_kinds)
+    value = flops_total / total_s / 1e12
+
+    # ---- dominant kernel and its roofline
+    kflops = {0: 4.0, 1: 2.0, 2: 8.0}     # algorithmic FLOP per (pair, key, channel): fwd 2 GEMMs; dQ 1; S,dP,dV,dK 4
+    ktime = {s: [hip.elapsed_ms(a, b) for a, b in ev[s]] for s in SLOTS}
+    dom = max(SLOTS, key=lambda s: sum(ktime[s]))
+    dom_flops = sum(kflops[dom] * D * keysum[k] for k in step_kinds)
+    dom_ms = sum(ktime[dom])
+    achieved = dom_flops / (dom_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": SLOTS[dom], "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": None,
+                "avg_launch_ms": dom_ms / args.steps,
+                "all_kernels": {SLOTS[s]: {"avg_launch_ms": sum(ktime[s]) / args.steps,
+                                           "tflops": sum(kflops[s] * D * keysum[k] for k in step_kinds) / (sum(ktime[s]) * 1e-3) / 1e12}
+                                for s in SLOTS}}
+
+    # ---- per-call breakdown (outside the timed region), per kind
+    def timed_calls(p):
+        names = ["partition", "select", "attn_fwd", "unpartition_O", "partition_dO", "attn_bwd", "unpartition_grads"]
+        fns = [lambda: p.partition(Q, K, V), p.select, p.attn_fwd, p.unpartition_out,
+               lambda: p.partition_dO(dO), p.attn_bwd, p.unpartition_grads]
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(fns) + 1)]
+        evs[0].record()
+        for f, e in zip(fns, evs[1:]):
+            f()
+            e.record()
+        torch.cuda.synchronize()
+        return {n: evs[i].elapsed_time(evs[i + 1]) for i, n in enumerate(names)}
+
+    breakdown = {kind: timed_calls(p) for kind, p in plans.items()}
+    per_kind = {kind: {"ms_per_layer": sum(b.values()),
+                       "selected_pair_fraction": pairs[kind] / (Hh * S * plans[kind].nb),
+                       "token_sparsity": keysum[kind] / (Hh * S * S),
+                       "n_blocks": plans[kind].nb,
+                       "attn_fwd_bwd_tflops": 14.0 * D * keysum[kind] / ((b["attn_fwd"] + b["attn_bwd"]) * 1e-3) / 1e12}
+                for kind, b in breakdown.items()}
+
+    out = {"metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16" if dtype == torch.bfloat16 else "f32", "data": "synthetic",
+           "config": {"workload": f"{args.config}: grid {cfg['grid']}, {Hh} heads x {D}, tau={args.tau}, "
+                                  f"layer cycle {'/'.join(kinds)}, fwd+bwd per layer", "tokens": S,
+                      "input_generation_s": round(t_gen, 1)},
+           "frac_of_bf16_mfma_peak": value / BF16_MFMA_PEAK_TFLOPS,
+           "roofline": roofline, "per_kind": per_kind, "breakdown_ms": breakdown}
+
+    # ---- dense comparators on the same GPU
+    if not args.no_dense:
+        dense = {}
+        try:
+            q, k, v = (x.permute(0, 2, 1, 3).detach().clone().requires_grad_(True) for x in (Q, K, V))
+            g = dO.permute(0, 2, 1, 3).contiguous()
+            def sdpa():
+                o = torch.nn.functional.scaled_dot_product_attention(q, k, v)
+                o.backward(g)
+                q.grad = k.grad = v.grad = None
+            sdpa()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(3):
+                sdpa()
+            torch.cuda.synchronize()
+            dense["torch_sdpa_fwd_bwd_ms"] = (time.perf_counter() - t) * 1e3 / 3
+            del q, k, v, g
+        except Exception as e:   # comparator only; never part of the product path
+            dense["torch_sdpa_error"] = repr(e)[:200]
+        try:
+            kind0 = "1d" if "1d" in plans else kinds[0]
+            bt, bh, bw, chunk = cfg["partitions"][kind0]
+            for p in plans.values():
+                p.ws_attn = None
+            torch.cuda.empty_cache()
+            pd = vb.LayerPlan(1, Hh, D, cfg["grid"], (bt, bh, bw), chunk, 1.0, dtype)
+            pd.forward(Q, K, V); pd.backward(dO)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(2):
+                pd.forward(Q, K, V); pd.backward(dO)
+            torch.cuda.synchronize()
+            dense["this_library_tau1_fwd_bwd_ms"] = (time.perf_counter() - t) * 1e3 / 2
+            dense["this_library_tau1_tflops"] = 14.0 * D * Hh * S * S / (dense["this_library_tau1_fwd_bwd_ms"] * 1e-3) / 1e12
+            del pd
+        except Exception as e:
+            dense["tau1_error"] = repr(e)[:200]
+        if "torch_sdpa_fwd_bwd_ms" in dense:
+            dense["speedup_vs_torch_sdpa"] = dense["torch_sdpa_fwd_bwd_ms"] / ms_per_step
+        out["dense"] = dense
+
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(Qn, Kn, Vn, dOn, cfg, cfg["partitions"]["3d"], args.tau)
+    else:
+        out["cpu_baseline"] = None
+    out["paper_context"] = ("paper reports whole-model numbers on NVIDIA H800 only: 2.92x FLOPs / 1.48x latency (training, "
+                            "55-56K tokens), 2.40x / 1.35x (720p inference); at this 33K-token shape its sparse path "
+                            "breaks even with dense (1.01x)")
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

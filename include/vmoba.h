@@ -122,7 +122,8 @@ int vmoba_partition(const vmoba_grid* g, int inverse, int B, int Hh, int D, int 
  *  mask   out  [B, Hh, S, ceil(n_blocks/32)] uint32, bit j of a row = query keeps block j
  *  Per (b, h) the pool of S*n_blocks values is cut after the k best, k = the shortest
  *  descending prefix whose sum reaches tau*S; equal values at the cut are taken in ascending
- *  (query, block) order.  k_out [B*Hh] int64 and theta_out [B*Hh] float (the k-th value).
+ *  (query, block) order.  k_out [B*Hh] int64 and theta_out [B*Hh] float (the k-th value; 0 when
+ *  every pair is kept).
  *  Sparse lists, every (b, h) owning a segment of nnz_capacity entries starting at
  *  (b*Hh + h)*nnz_capacity:
  *    blk_ptr  [B*Hh, n_blocks + 1] int32  offsets (relative to the segment) of block j's queries
@@ -174,6 +175,16 @@ int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int3
                    const int32_t* pair_pos, int64_t nnz_capacity, float softmax_scale,
                    const vmoba_tensor* dQ, const vmoba_tensor* dK, const vmoba_tensor* dV,
                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * vmoba_profile_events -- measurement aid, not part of the method.  Asks the library to record
+ * the caller's two hipEvent_t (passed as void*) on the call's stream immediately before and after
+ * the launch of one of its compute kernels, so a benchmark can time that kernel alone:
+ *   slot 0: forward tile kernel (vmoba_attn_fwd)      slot 1: dQ tile kernel (vmoba_attn_bwd)
+ *   slot 2: dK/dV kernel (vmoba_attn_bwd)             slot 3: row copy kernel (vmoba_partition)
+ * Pass null events to switch a slot off (the default).  Process-wide, not thread-safe.
+ */
+int vmoba_profile_events(int slot, void* start_event, void* stop_event);
 
 #ifdef __cplusplus
 }

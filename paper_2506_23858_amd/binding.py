@@ -20,7 +20,7 @@ VMOBA_F32, VMOBA_BF16 = 0, 1
 OP_SELECT, OP_ATTN_FWD, OP_ATTN_BWD = 1, 2, 3
 
 EXPORTS = ["vmoba_layer_kind", "vmoba_partition_dims", "vmoba_workspace_bytes", "vmoba_status_string",
-           "vmoba_partition", "vmoba_select", "vmoba_attn_fwd", "vmoba_attn_bwd"]
+           "vmoba_partition", "vmoba_select", "vmoba_attn_fwd", "vmoba_attn_bwd", "vmoba_profile_events"]
 
 
 class vmoba_grid(C.Structure):
@@ -78,6 +78,8 @@ def lib():
                                  C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor),
                                  P, C.c_size_t, P]
     L.vmoba_attn_bwd.restype = C.c_int
+    L.vmoba_profile_events.argtypes = [C.c_int, P, P]
+    L.vmoba_profile_events.restype = C.c_int
     _lib = L
     return L
 
@@ -137,6 +139,13 @@ def nnz_capacity_for(S: int, n_blocks: int, tau: float) -> int:
     """Per-head list capacity: the selection never keeps more than ceil(tau * S * N_b) pairs."""
     n = S * n_blocks
     return max(1, min(n, math.ceil(float(tau) * n) + 1))
+
+
+def vmoba_profile_events(slot: int, start_event=None, stop_event=None):
+    """start_event / stop_event: raw hipEvent_t handles (ints) or None."""
+    _check("vmoba_profile_events", lib().vmoba_profile_events(
+        int(slot), C.c_void_p(start_event) if start_event else None,
+        C.c_void_p(stop_event) if stop_event else None))
 
 
 # ------------------------------------------------------------------------------- entry points

@@ -636,6 +636,7 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     VMOBA_CHECK_LAUNCH();
     {
         dim3 grid((unsigned)(nnz_capacity / TM + n_blocks), (unsigned)BH);
+        VMOBA_PROFILE_BEGIN(1, st);
 #define DQ_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.tile_start, ws.dQpart, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2
         if (simple) {
             if (bf16 && D == 128) attn_bwd_dq_simple_kernel<true, 128><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
@@ -647,6 +648,7 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
             else attn_bwd_dq_mfma_kernel<64><<<grid, dim3(256), 0, st>>>(DQ_ARGS);
         }
 #undef DQ_ARGS
+        VMOBA_PROFILE_END(1, st);
         VMOBA_CHECK_LAUNCH();
         const int qpw = 256 / (D / 4);
         dim3 mgrid((unsigned)ceil_div64(S, qpw), (unsigned)BH);
@@ -665,6 +667,7 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         key_run_start_kernel<<<dim3(1), dim3(64), 0, st>>>(blk_off, ws.kb_start, n_blocks, KPW);
         VMOBA_CHECK_LAUNCH();
         dim3 grid((unsigned)(S / KPW + n_blocks), (unsigned)BH);
+        VMOBA_PROFILE_BEGIN(2, st);
 #define DKV_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.kb_start, dKv, dVv, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
         if (simple) {
             if (bf16 && D == 128) attn_bwd_dkv_simple_kernel<true, 128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
@@ -676,6 +679,7 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
             else attn_bwd_dkv_mfma_kernel<64, NW><<<grid, dim3(64 * NW), 0, st>>>(DKV_ARGS);
         }
 #undef DKV_ARGS
+        VMOBA_PROFILE_END(2, st);
         VMOBA_CHECK_LAUNCH();
     }
     return VMOBA_OK;

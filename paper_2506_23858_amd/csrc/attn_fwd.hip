@@ -445,6 +445,7 @@ extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     VMOBA_CHECK_LAUNCH();
     const int64_t max_tiles = nnz_capacity / TM + n_blocks;
     dim3 grid((unsigned)max_tiles, (unsigned)BH);
+    VMOBA_PROFILE_BEGIN(0, st);
 #define TILE_ARGS Qv, Kv, Vv, blk_off, blk_ptr, q_idx, ws.tile_start, ws.Opart, ws.lse_part, Hh, n_blocks, (long long)nnz_capacity, scale_log2
     if (simple) {
         if (bf16 && D == 128) attn_fwd_tile_simple_kernel<true, 128><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
@@ -458,6 +459,7 @@ extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         else attn_fwd_tile_mfma_kernel<64, 1><<<grid, dim3(256), 0, st>>>(TILE_ARGS);
     }
 #undef TILE_ARGS
+    VMOBA_PROFILE_END(0, st);
     VMOBA_CHECK_LAUNCH();
     const int qpw = 256 / (D / 4);
     dim3 mgrid((unsigned)ceil_div64(S, qpw), (unsigned)BH);

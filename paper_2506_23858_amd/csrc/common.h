@@ -61,3 +61,9 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
     bf16x2_t w = __builtin_convertvector(v, bf16x2_t);
     return *reinterpret_cast<uint32_t*>(&w);
 }
+
+// Optional event pairs recorded around single kernel launches (see vmoba_profile_events).
+struct ProfileSlot { hipEvent_t start, stop; };
+extern ProfileSlot g_profile[4];
+#define VMOBA_PROFILE_BEGIN(slot, st) do { if (g_profile[slot].start) (void)hipEventRecord(g_profile[slot].start, st); } while (0)
+#define VMOBA_PROFILE_END(slot, st) do { if (g_profile[slot].stop) (void)hipEventRecord(g_profile[slot].stop, st); } while (0)

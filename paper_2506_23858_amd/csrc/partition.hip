@@ -165,10 +165,12 @@ extern "C" int vmoba_partition(const vmoba_grid* g, int inverse, int B, int Hh, 
         int64_t items = S * Hh * (D * 4 / 16);
         unsigned gx = (unsigned)std::min<int64_t>(ceil_div64(items, 256 * 4), 1 << 20);
         dim3 grid(gx, (unsigned)B, (unsigned)n_tensors);
+        VMOBA_PROFILE_BEGIN(3, st);
         if (inverse)
             permute_rows_kernel<true><<<grid, dim3(256), 0, st>>>(cd, perm, (int)S, Hh, D);
         else
             permute_rows_kernel<false><<<grid, dim3(256), 0, st>>>(cd, perm, (int)S, Hh, D);
+        VMOBA_PROFILE_END(3, st);
         VMOBA_CHECK_LAUNCH();
     }
     return VMOBA_OK;

@@ -15,3 +15,12 @@ extern "C" size_t vmoba_workspace_bytes(int op, int B, int Hh, int64_t S, int D,
         default: return 0;
     }
 }
+
+ProfileSlot g_profile[4] = {};
+
+extern "C" int vmoba_profile_events(int slot, void* start_event, void* stop_event) {
+    if (slot < 0 || slot >= 4) return VMOBA_ERR_INVALID_ARG;
+    g_profile[slot].start = (hipEvent_t)start_event;
+    g_profile[slot].stop = (hipEvent_t)stop_event;
+    return VMOBA_OK;
+}

@@ -64,7 +64,8 @@ def compare_layer(Q, K, V, dO, grid, block, chunk, tau, dtype, label=""):
         for h in range(Hh):
             nband, ndiff = gu.check_selection(g, o, b, h)
             gu.check_lists(g, b, h)
-            np.testing.assert_allclose(g["theta"][b, h], o["theta"][b, h], atol=1e-6)
+            if int(g["k"][b, h]) < S * g["nb"]:      # theta is reported as 0 when every pair is kept
+                np.testing.assert_allclose(g["theta"][b, h], o["theta"][b, h], atol=1e-6)
             print(f"   head {h}: k_gpu={g['k'][b, h]} k_oracle={o['k'][b, h]} band={nband} flipped={ndiff}", flush=True)
     # --- attention under the GPU's own mask
     ref = oracle_with_gpu_mask(g, Q, K, V, dO, 1.0 / math.sqrt(D))
@@ -80,8 +81,11 @@ def compare_layer(Q, K, V, dO, grid, block, chunk, tau, dtype, label=""):
         for name in ("dQp", "dKp", "dVp"):
             err = np.abs(g[name] - ref[name]).max()
             rel = rel_err(g[name], ref[name])
-            print(f"   {name}: max-abs {err:.3e} rel {rel:.3e}", flush=True)
-            assert err <= tol, (name, err)
+            mag = np.abs(ref[name]).max()
+            print(f"   {name}: max-abs {err:.3e} rel {rel:.3e} max|ref| {mag:.3e}", flush=True)
+            # the absolute tolerance is for O(1) values; a bfloat16 result of magnitude x carries a
+            # rounding error of up to x * 2^-9 on its own, so the bound grows with the range
+            assert err <= tol * max(1.0, mag), (name, err, mag)
             assert rel <= rtol, (name, rel)
         assert np.all(g["dQp"][~live] == 0)
         for name in ("dQ", "dK", "dV"):
@@ -184,8 +188,12 @@ def test_selection_is_deterministic():
     Q, K, V, dO = synth.make_qkv("tiny")
     runs = [gu.run_gpu(Q, K, V, dO, c["grid"], (2, 4, 4), 0, 0.25) for _ in range(3)]
     for r in runs[1:]:
-        for name in ("mask", "q_idx", "col_idx", "pair_pos", "blk_ptr", "row_ptr", "k", "P", "Op", "dQp", "dKp", "dVp"):
+        for name in ("mask", "blk_ptr", "row_ptr", "k", "P", "Op", "dQp", "dKp", "dVp"):
             assert np.array_equal(r[name], runs[0][name]), name
+        for h in range(2):
+            n = int(r["k"][0, h])            # list entries past the head's nnz are never written
+            for name in ("q_idx", "col_idx", "pair_pos"):
+                assert np.array_equal(r[name][0, h][:n], runs[0][name][0, h][:n]), name
 
 
 def test_capacity_overflow_is_reported_not_written():
