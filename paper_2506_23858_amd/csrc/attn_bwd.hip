@@ -216,77 +216,23 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_simple_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// Stage R rows x D channels of bf16, given by a row-address functor, into LDS transposed:
-// dst[d * TSTR + r].  Each thread moves 4 rows x 4 channels at a time: four 8-byte loads, a 4x4
-// transpose of 16-bit values with byte permutes, four 8-byte LDS stores.
-template <int R, int D, int TSTR, int NT, typename RowPtr>
-__device__ __forceinline__ void stage_transposed(__bf16* __restrict__ dst, int tid, RowPtr row_ptr_fn) {
-    constexpr int QUADS = R * D / 16;
-#pragma unroll
-    for (int i = 0; i < (QUADS + NT - 1) / NT; ++i) {
-        const int quad = tid + NT * i;
-        if (QUADS % NT == 0 || quad < QUADS) {
-            const int rq = quad / (D / 4), dq = quad % (D / 4);
-            u32x2_t v[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) v[r] = *reinterpret_cast<const u32x2_t*>(row_ptr_fn(rq * 4 + r) + dq * 8);
-            u32x2_t t0, t1, t2, t3;
-            t0.x = __builtin_amdgcn_perm(v[1].x, v[0].x, 0x05040100u);
-            t0.y = __builtin_amdgcn_perm(v[3].x, v[2].x, 0x05040100u);
-            t1.x = __builtin_amdgcn_perm(v[1].x, v[0].x, 0x07060302u);
-            t1.y = __builtin_amdgcn_perm(v[3].x, v[2].x, 0x07060302u);
-            t2.x = __builtin_amdgcn_perm(v[1].y, v[0].y, 0x05040100u);
-            t2.y = __builtin_amdgcn_perm(v[3].y, v[2].y, 0x05040100u);
-            t3.x = __builtin_amdgcn_perm(v[1].y, v[0].y, 0x07060302u);
-            t3.y = __builtin_amdgcn_perm(v[3].y, v[2].y, 0x07060302u);
-            *reinterpret_cast<u32x2_t*>(&dst[(dq * 4 + 0) * TSTR + rq * 4]) = t0;
-            *reinterpret_cast<u32x2_t*>(&dst[(dq * 4 + 1) * TSTR + rq * 4]) = t1;
-            *reinterpret_cast<u32x2_t*>(&dst[(dq * 4 + 2) * TSTR + rq * 4]) = t2;
-            *reinterpret_cast<u32x2_t*>(&dst[(dq * 4 + 3) * TSTR + rq * 4]) = t3;
-        }
-    }
-}
-
-// Row-major staging: dst[r * RSTR + d], 16-byte pieces.
-template <int R, int D, int RSTR, int NT, typename RowPtr>
-__device__ __forceinline__ void stage_rows(__bf16* __restrict__ dst, int tid, RowPtr row_ptr_fn) {
-    constexpr int PIECES = R * D / 8;
-#pragma unroll
-    for (int i = 0; i < (PIECES + NT - 1) / NT; ++i) {
-        const int piece = tid + NT * i;
-        if (PIECES % NT == 0 || piece < PIECES) {
-            const int r = piece / (D / 8), pc = piece % (D / 8);
-            *reinterpret_cast<u32x4_t*>(&dst[r * RSTR + pc * 8]) = *reinterpret_cast<const u32x4_t*>(row_ptr_fn(r) + pc * 16);
-        }
-    }
-}
-
-__device__ __forceinline__ bf16x8_t pack8(const float* p) {
-    f32x4_t lo = {p[0], p[1], p[2], p[3]};
-    f32x4_t hi = {p[4], p[5], p[6], p[7]};
-    bf16x4_t blo = __builtin_convertvector(lo, bf16x4_t);
-    bf16x4_t bhi = __builtin_convertvector(hi, bf16x4_t);
-    return __builtin_shufflevector(blo, bhi, 0, 1, 2, 3, 4, 5, 6, 7);
-}
-
-// ---------------------------------------------------------------------------------------------
 // bf16 MFMA dQ tile kernel.  Same decomposition and operand orientation as the forward tile
-// kernel (query = MFMA column = lane % 32):
+// kernel (query = MFMA column = lane % 32); 4 wavefronts x 32 gathered queries, key chunks of 64:
 //   S^T  = K . Q^T                    A = K rows (LDS),  B = Q^T (registers)
 //   dP^T = V . dO^T                   A = V rows (LDS),  B = dO^T (registers)
 //   dS^T = P^T * (dP^T - delta)       in registers, packed to bf16 as the next B operand
-//   dQ^T += K^T . dS^T                A = K^T (LDS, transposed copy)
+//   dQ^T += K^T . dS^T                A = K^T by transpose reads of the same K tile
 template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
     const int* __restrict__ tile_start, float* __restrict__ dQpart, int Hh, int S, int nb, long long cap, float scale_log2) {
     constexpr int TM = 128, KC = 64;
-    constexpr int RSTR = D + 8, TSTR = KC + 8;
+    constexpr int STR = D + 8;
     constexpr int KSTEPS = D / 16, DT = D / 32;
-    __shared__ __align__(16) __bf16 sK[KC * RSTR];
-    __shared__ __align__(16) __bf16 sV[KC * RSTR];
-    __shared__ __align__(16) __bf16 sKt[D * TSTR];
+    constexpr int LOADS = KC * D * 2 / 16 / 256;
+    __shared__ __align__(16) __bf16 sK[KC * STR];
+    __shared__ __align__(16) __bf16 sV[KC * STR];
 
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
     TileCoord tc;
@@ -322,16 +268,38 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(
     const long long kss = K.stride_s * 2, vss = V.stride_s * 2;
     const int n_chunks = (tc.L + KC - 1) / KC;
 
-    for (int c = 0; c < n_chunks; ++c) {
+    u32x4_t kreg[LOADS], vreg[LOADS];
+    auto prefetch = [&](int c) {
         const int c0 = c * KC;
-        auto krow = [&](int r) { return kbase + (long long)(tc.k0 + min(c0 + r, tc.L - 1)) * kss; };
-        auto vrow = [&](int r) { return vbase + (long long)(tc.k0 + min(c0 + r, tc.L - 1)) * vss; };
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int piece = tid + 256 * i;
+            const int r = piece / (D / 8), pc = piece % (D / 8);
+            const long long row = tc.k0 + min(c0 + r, tc.L - 1);
+            kreg[i] = *reinterpret_cast<const u32x4_t*>(kbase + row * kss + pc * 16);
+            vreg[i] = *reinterpret_cast<const u32x4_t*>(vbase + row * vss + pc * 16);
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int piece = tid + 256 * i;
+            const int r = piece / (D / 8), pc = piece % (D / 8);
+            *reinterpret_cast<u32x4_t*>(&sK[r * STR + pc * 8]) = kreg[i];
+            *reinterpret_cast<u32x4_t*>(&sV[r * STR + pc * 8]) = vreg[i];
+        }
+    };
+    const __bf16* sK_lane = sK + rho(l32) * STR + hf * 8;
+    const __bf16* sV_lane = sV + rho(l32) * STR + hf * 8;
+    const __bf16* sKt_lane = sK + tr_lane_offset<STR>(lane);
+
+    prefetch(0);
+    for (int c = 0; c < n_chunks; ++c) {
         __syncthreads();
-        stage_rows<KC, D, RSTR, 256>(sK, tid, krow);
-        stage_rows<KC, D, RSTR, 256>(sV, tid, vrow);
-        stage_transposed<KC, D, TSTR, 256>(sKt, tid, krow);
+        stage();
         __syncthreads();
-        const int valid = tc.L - c0;
+        if (c + 1 < n_chunks) prefetch(c + 1);
+        const int valid = tc.L - c * KC;
         const int n_mt = valid > 32 ? 2 : 1;
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
@@ -339,20 +307,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(
                 f32x16_t sacc, dpacc;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dpacc[i] = 0.f; }
-                const int row = mt * 32 + swap23(l32);
 #pragma unroll
                 for (int ks = 0; ks < KSTEPS; ++ks) {
-                    const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(&sK[row * RSTR + ks * 16 + hf * 8]);
-                    const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(&sV[row * RSTR + ks * 16 + hf * 8]);
+                    const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sK_lane + mt * 32 * STR + ks * 16);
+                    const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(sV_lane + mt * 32 * STR + ks * 16);
                     sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc, 0, 0, 0);
                     dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[ks], dpacc, 0, 0, 0);
                 }
                 float ds[16];
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int key = mt * 32 + ((i >> 3) << 4) + hf * 8 + (i & 7);
-                    float p = exp2_raw(sacc[i] * scale_log2 - lse2);
-                    if (key >= valid) p = 0.f;
+                    float p = exp2_raw(fmaf(sacc[i], scale_log2, -lse2));
+                    if (valid < KC && mt * 32 + acc_row(i, hf) >= valid) p = 0.f;
                     ds[i] = p * (dpacc[i] - dl);
                 }
 #pragma unroll
@@ -360,8 +326,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(
                     const bf16x8_t dsf = pack8(&ds[8 * s]);
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt) {
-                        const bf16x8_t ktf = *reinterpret_cast<const bf16x8_t*>(
-                            &sKt[(dt * 32 + l32) * TSTR + mt * 32 + s * 16 + hf * 8]);
+                        const bf16x8_t ktf = tr_operand<STR>(sKt_lane, mt * 32, s, dt * 32);
                         dqacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf, dqacc[dt], 0, 0, 0);
                     }
                 }
@@ -383,12 +348,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(
 // ---------------------------------------------------------------------------------------------
 // bf16 MFMA dK/dV kernel.  A workgroup of NW wavefronts owns 32*NW consecutive keys of one
 // block (wavefront w: 32 keys, key = MFMA column = lane % 32) and walks the block's query list
-// in chunks of 64 gathered queries:
+// in chunks of 64 gathered queries, staged row-major in LDS with register prefetch:
 //   S   = Q . K^T                     A = Q rows (LDS),   B = K^T (registers, loaded once)
 //   dP  = dO . V^T                    A = dO rows (LDS),  B = V^T (registers, loaded once)
 //   P = exp(S - LSE), dS = P * (dP - delta)        packed to bf16 as B operands
-//   dV^T += dO^T . P                  A = dO^T (LDS, transposed copy)
-//   dK^T += Q^T . dS                  A = Q^T  (LDS, transposed copy)
+//   dV^T += dO^T . P                  A = dO^T by transpose reads of the dO tile
+//   dK^T += Q^T . dS                  A = Q^T  by transpose reads of the Q tile
 template <int D, int NW>
 __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
@@ -397,27 +362,27 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
     float scale_log2, float scale) {
     constexpr int NT = 64 * NW;
     constexpr int QC = 64;
-    constexpr int RSTR = D + 8, TSTR = QC + 8;
+    constexpr int STR = D + 8;
     constexpr int KSTEPS = D / 16, DT = D / 32;
-    __shared__ __align__(16) __bf16 sQ[QC * RSTR];
-    __shared__ __align__(16) __bf16 sdO[QC * RSTR];
-    __shared__ __align__(16) __bf16 sQt[D * TSTR];
-    __shared__ __align__(16) __bf16 sdOt[D * TSTR];
+    constexpr int LOADS = QC * D * 2 / 16 / NT;     // 16-byte pieces per thread per chunk and tensor
+    static_assert(QC * D * 2 / 16 % NT == 0, "chunk must divide evenly over the threads");
+    __shared__ __align__(16) __bf16 sQ[QC * STR];
+    __shared__ __align__(16) __bf16 sdO[QC * STR];
     __shared__ __align__(16) float sL[QC];
     __shared__ __align__(16) float sDl[QC];
-    __shared__ int sIdx[QC];
 
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
-    if ((int)blockIdx.x >= kb_start[nb]) return;
+    const int run = (int)blockIdx.x;
+    if (run >= kb_start[nb]) return;
     int lo = 0, hi = nb;
-    while (hi - lo > 1) { int mid = (lo + hi) >> 1; if (kb_start[mid] <= (int)blockIdx.x) lo = mid; else hi = mid; }
+    while (hi - lo > 1) { int mid = (lo + hi) >> 1; if (kb_start[mid] <= run) lo = mid; else hi = mid; }
     const int j = lo;
     const int k0 = blk_off[j], L = blk_off[j + 1] - k0;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hf = lane >> 5;
-    const int kk = ((int)blockIdx.x - kb_start[j]) * (32 * NW) + wave * 32 + l32;   // key inside the block
+    const int kk = (run - kb_start[j]) * (32 * NW) + wave * 32 + l32;   // key inside the block
     const bool key_live = kk < L;
-    const bool wave_live = ((int)blockIdx.x - kb_start[j]) * (32 * NW) + wave * 32 < L;
+    const bool wave_live = (run - kb_start[j]) * (32 * NW) + wave * 32 < L;
     const int krow = k0 + min(kk, L - 1);
     const long long seg = (long long)bh * cap;
     const int list0 = blk_ptr[(long long)bh * (nb + 1) + j];
@@ -442,26 +407,58 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
     const char* qbase = Q.ptr + ((long long)b * Q.stride_b + (long long)h * Q.stride_h) * 2;
     const char* dobase = dO.ptr + ((long long)b * dO.stride_b + (long long)h * dO.stride_h) * 2;
     const long long qss = Q.stride_s * 2, doss = dO.stride_s * 2;
+    const int* list = q_idx + seg + list0;
+    const float* lse_h = LSE + (long long)bh * S;
+    const float* dl_h = delta + (long long)bh * S;
 
+    // register prefetch of the next chunk: the gathered Q and dO rows, and LSE / delta of its queries
+    u32x4_t qreg[LOADS], doreg[LOADS];
+    float lreg = 0.f, dreg = 0.f;
+    auto prefetch = [&](int c0) {
+        const int qc = min(QC, cnt - c0);
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int piece = tid + NT * i;
+            const int r = piece / (D / 8), pc = piece % (D / 8);
+            const long long q = list[c0 + min(r, qc - 1)];        // rows past the list repeat its last query
+            qreg[i] = *reinterpret_cast<const u32x4_t*>(qbase + q * qss + pc * 16);
+            doreg[i] = *reinterpret_cast<const u32x4_t*>(dobase + q * doss + pc * 16);
+        }
+        if (tid < QC) {
+            const long long q = list[c0 + min(tid, qc - 1)];
+            // rows past the end of the list get LSE = +inf (weight 0) and delta = 0
+            lreg = (tid < qc) ? lse_h[q] * LOG2E : INFINITY;
+            dreg = (tid < qc) ? dl_h[q] : 0.f;
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int piece = tid + NT * i;
+            const int r = piece / (D / 8), pc = piece % (D / 8);
+            *reinterpret_cast<u32x4_t*>(&sQ[r * STR + pc * 8]) = qreg[i];
+            *reinterpret_cast<u32x4_t*>(&sdO[r * STR + pc * 8]) = doreg[i];
+        }
+        if (tid < QC) {
+            // stored in accumulator order: the 16 values a lane half needs per 32-query group are contiguous
+            const int r = tid & 31;
+            const int pos = (tid & 32) + ((r & 1) << 4) + ((r >> 4) << 3) + (((r >> 1) & 1) << 2) + ((r >> 2) & 3);
+            sL[pos] = lreg;
+            sDl[pos] = dreg;
+        }
+    };
+    const __bf16* sQ_lane = sQ + rho(l32) * STR + hf * 8;
+    const __bf16* sdO_lane = sdO + rho(l32) * STR + hf * 8;
+    const __bf16* sQt_lane = sQ + tr_lane_offset<STR>(lane);
+    const __bf16* sdOt_lane = sdO + tr_lane_offset<STR>(lane);
+
+    if (cnt > 0) prefetch(0);
     for (int c0 = 0; c0 < cnt; c0 += QC) {
         const int qc = min(QC, cnt - c0);
         __syncthreads();                 // previous chunk fully consumed
-        if (tid < QC) {
-            const int e = min(tid, qc - 1);
-            const int q = q_idx[seg + list0 + c0 + e];
-            sIdx[tid] = q;
-            // rows past the end of the list get LSE = +inf (weight 0) and delta = 0
-            sL[tid] = (tid < qc) ? LSE[(long long)bh * S + q] * LOG2E : INFINITY;
-            sDl[tid] = (tid < qc) ? delta[(long long)bh * S + q] : 0.f;
-        }
+        stage();
         __syncthreads();
-        auto qrow = [&](int r) { return qbase + (long long)sIdx[r] * qss; };
-        auto dorow = [&](int r) { return dobase + (long long)sIdx[r] * doss; };
-        stage_rows<QC, D, RSTR, NT>(sQ, tid, qrow);
-        stage_rows<QC, D, RSTR, NT>(sdO, tid, dorow);
-        stage_transposed<QC, D, TSTR, NT>(sQt, tid, qrow);
-        stage_transposed<QC, D, TSTR, NT>(sdOt, tid, dorow);
-        __syncthreads();
+        if (c0 + QC < cnt) prefetch(c0 + QC);
         if (wave_live) {
             const int n_mt = qc > 32 ? 2 : 1;
 #pragma unroll
@@ -470,30 +467,24 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
                     f32x16_t sacc, dpacc;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dpacc[i] = 0.f; }
-                    const int row = mt * 32 + swap23(l32);
 #pragma unroll
                     for (int ks = 0; ks < KSTEPS; ++ks) {
-                        const bf16x8_t qa = *reinterpret_cast<const bf16x8_t*>(&sQ[row * RSTR + ks * 16 + hf * 8]);
-                        const bf16x8_t da = *reinterpret_cast<const bf16x8_t*>(&sdO[row * RSTR + ks * 16 + hf * 8]);
+                        const bf16x8_t qa = *reinterpret_cast<const bf16x8_t*>(sQ_lane + mt * 32 * STR + ks * 16);
+                        const bf16x8_t da = *reinterpret_cast<const bf16x8_t*>(sdO_lane + mt * 32 * STR + ks * 16);
                         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[ks], sacc, 0, 0, 0);
                         dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[ks], dpacc, 0, 0, 0);
                     }
-                    // accumulator value i <-> query 32*mt + 16*(i>>3) + 8*hf + (i&7) of the chunk
+                    // accumulator value i <-> query mt*32 + acc_row(i, hf) of the chunk
                     float p[16], ds[16];
 #pragma unroll
-                    for (int s = 0; s < 2; ++s) {
-                        const int qoff = mt * 32 + s * 16 + hf * 8;
-                        const f32x4_t l0 = *reinterpret_cast<const f32x4_t*>(&sL[qoff]);
-                        const f32x4_t l1 = *reinterpret_cast<const f32x4_t*>(&sL[qoff + 4]);
-                        const f32x4_t d0 = *reinterpret_cast<const f32x4_t*>(&sDl[qoff]);
-                        const f32x4_t d1 = *reinterpret_cast<const f32x4_t*>(&sDl[qoff + 4]);
-                        const float lv[8] = {l0.x, l0.y, l0.z, l0.w, l1.x, l1.y, l1.z, l1.w};
-                        const float dv8[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+                    for (int g4 = 0; g4 < 4; ++g4) {
+                        const f32x4_t lv = *reinterpret_cast<const f32x4_t*>(&sL[mt * 32 + hf * 16 + g4 * 4]);
+                        const f32x4_t dv4 = *reinterpret_cast<const f32x4_t*>(&sDl[mt * 32 + hf * 16 + g4 * 4]);
 #pragma unroll
-                        for (int u = 0; u < 8; ++u) {
-                            const int i = 8 * s + u;
-                            p[i] = exp2_raw(sacc[i] * scale_log2 - lv[u]);
-                            ds[i] = p[i] * (dpacc[i] - dv8[u]);
+                        for (int u = 0; u < 4; ++u) {
+                            const int i = g4 * 4 + u;
+                            p[i] = exp2_raw(fmaf(sacc[i], scale_log2, -lv[u]));
+                            ds[i] = p[i] * (dpacc[i] - dv4[u]);
                         }
                     }
 #pragma unroll
@@ -502,9 +493,8 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
                         const bf16x8_t dsf = pack8(&ds[8 * s]);
 #pragma unroll
                         for (int dt = 0; dt < DT; ++dt) {
-                            const int off = (dt * 32 + l32) * TSTR + mt * 32 + s * 16 + hf * 8;
-                            const bf16x8_t dot = *reinterpret_cast<const bf16x8_t*>(&sdOt[off]);
-                            const bf16x8_t qt = *reinterpret_cast<const bf16x8_t*>(&sQt[off]);
+                            const bf16x8_t dot = tr_operand<STR>(sdOt_lane, mt * 32, s, dt * 32);
+                            const bf16x8_t qt = tr_operand<STR>(sQt_lane, mt * 32, s, dt * 32);
                             dvacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot, pfr, dvacc[dt], 0, 0, 0);
                             dkacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf, dkacc[dt], 0, 0, 0);
                         }
@@ -635,7 +625,7 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     tile_start_kernel<<<dim3((BH + 63) / 64), dim3(64), 0, st>>>(blk_ptr, ws.tile_start, BH, n_blocks, TM);
     VMOBA_CHECK_LAUNCH();
     {
-        dim3 grid((unsigned)(nnz_capacity / TM + n_blocks), (unsigned)BH);
+        dim3 grid((unsigned)((nnz_capacity / TM + n_blocks + 7) / 8 * 8 + 8), (unsigned)BH);
         VMOBA_PROFILE_BEGIN(1, st);
 #define DQ_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.tile_start, ws.dQpart, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2
         if (simple) {
@@ -666,7 +656,8 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         const int KPW = simple ? 64 : 32 * NW;
         key_run_start_kernel<<<dim3(1), dim3(64), 0, st>>>(blk_off, ws.kb_start, n_blocks, KPW);
         VMOBA_CHECK_LAUNCH();
-        dim3 grid((unsigned)(S / KPW + n_blocks), (unsigned)BH);
+        // a multiple of 8 so that (workgroup id % 8) is the same for every head; + 8 for the per-XCD rounding
+        dim3 grid((unsigned)((S / KPW + n_blocks + 7) / 8 * 8 + 8), (unsigned)BH);
         VMOBA_PROFILE_BEGIN(2, st);
 #define DKV_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.kb_start, dKv, dVv, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
         if (simple) {

@@ -6,13 +6,62 @@
 // queries that all attend to the same key block.  tile_start[bh][j] = number of tiles of blocks
 // 0..j-1, written on the device from blk_ptr, so the host never learns the data-dependent counts;
 // the grid is sized from nnz_capacity and surplus workgroups leave at once.
+//
+// MFMA operand plumbing (v_mfma_f32_32x32x16_bf16; lane = 32*hf + l32):
+//   A operand: lane holds row l32, 8 consecutive k at 8*hf;   B operand: column l32, same k.
+//   C/D:       lane holds column l32, rows 8*i + 4*hf + r as value 4*i + r (i, r = 0..3).
+// LDS tiles are row-major [row][D] with a row stride of D + 8 bf16 (16 bytes of padding).
+//   * An operand that contracts over the channels of a row is a 16-byte row read.
+//   * An operand that contracts over the ROWS (the transposed tile) is two ds_read_b64_tr_b16:
+//     in each group of 16 lanes, lane 4*e + a supplies the address of 4 consecutive channels of
+//     one row and receives, for channel 4*a' + c of the group (lane = 4*a' + c), the values of
+//     the 4 rows supplied by lanes a', a'+4, a'+8, a'+12.
+//   * Rows are fed to the first MFMA through the bit permutation rho below.  With it the 8
+//     accumulator values a lane holds per 16-row step belong to rows {16*s + 4*e + 2*t + hf},
+//     e = 0..3, t = 0..1: they pack straight into the next MFMA's B operand (no shuffle), the
+//     matching transposed A operand is exactly what the two transpose reads (t = 0, 1) deliver,
+//     and both kinds of LDS access are bank-conflict free with the one padded layout.
 #pragma once
 #include "common.h"
 
-// bits 2 and 3 of a 5-bit row index exchanged.  Feeding MFMA row m with key (or query)
-// swap23(m) makes the accumulator registers of a lane hold 8 *consecutive* keys per 16-key
-// step, so they can be packed straight into the next MFMA's operand without a shuffle.
-__device__ __forceinline__ int swap23(int m) { return (m & 0x13) | ((m & 4) << 1) | ((m & 8) >> 1); }
+// MFMA row m (0..31) of a 32-row group is fed tile row rho(m):
+//   rho = 16*m[4] + 4*m[1:0] + 2*m[3] + m[2]
+__device__ __forceinline__ int rho(int m) {
+    return (m & 16) | ((m & 3) << 2) | ((m & 8) >> 2) | ((m & 4) >> 2);
+}
+// Tile row (0..31) that accumulator value v (0..15) of lane half hf belongs to.
+__device__ __forceinline__ int acc_row(int v, int hf) {
+    return ((v >> 3) << 4) | ((v & 3) << 2) | (((v >> 2) & 1) << 1) | hf;
+}
+
+typedef __bf16 __attribute__((address_space(3))) lds_bf16_t;
+typedef bf16x4_t __attribute__((address_space(3))) lds_bf16x4_t;
+
+// Per-lane element offset of the transposed-operand reads inside a tile of row stride STR:
+// row 4*e + hf, channel 16*(g&1) + 4*a, with lane = 16*g + 4*e + a.
+template <int STR>
+__device__ __forceinline__ int tr_lane_offset(int lane) {
+    const int g = lane >> 4, e = (lane >> 2) & 3, a = lane & 3, hf = lane >> 5;
+    return (4 * e + hf) * STR + 16 * (g & 1) + 4 * a;
+}
+
+// Transposed A operand: m = channel col0 + l32, k-slots = rows {row0 + 16*s + 4*e + 2*t + hf}.
+// `tile_lane` = tile base + tr_lane_offset (per lane); row0 = 32 * (row group), s = 16-row step.
+template <int STR>
+__device__ __forceinline__ bf16x8_t tr_operand(const __bf16* tile_lane, int row0, int s, int col0) {
+    const __bf16* p = tile_lane + (row0 + 16 * s) * STR + col0;
+    const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_t*)(p));
+    const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_t*)(p + 2 * STR));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+__device__ __forceinline__ bf16x8_t pack8(const float* p) {
+    f32x4_t lo = {p[0], p[1], p[2], p[3]};
+    f32x4_t hi = {p[4], p[5], p[6], p[7]};
+    bf16x4_t blo = __builtin_convertvector(lo, bf16x4_t);
+    bf16x4_t bhi = __builtin_convertvector(hi, bf16x4_t);
+    return __builtin_shufflevector(blo, bhi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
 
 struct TileCoord {
     int j;        // key block

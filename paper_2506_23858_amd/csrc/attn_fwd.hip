@@ -106,26 +106,26 @@ __global__ __launch_bounds__(64) void attn_fwd_tile_simple_kernel(
 //
 // All products are computed transposed so that the query index is the MFMA column (= lane % 32):
 //   S^T[key, q] = K[key, :] . Q[q, :]          A = K rows from LDS, B = Q^T held in registers
-//   O^T[d, q]  += V^T[d, key] . P^T[key, q]    A = V^T from LDS,   B = P^T packed from S^T registers
+//   O^T[d, q]  += V^T[d, key] . P^T[key, q]    A = V^T by transpose reads, B = P^T packed from S^T
 // With the query on the lane, the row maximum and row sum of the online soft-max are reductions
-// over a lane's own registers plus one exchange with lane ^ 32.
-// MFMA row m of the first product is fed key swap23(m) of the 32-key group, which makes the 8
-// accumulator values a lane holds per 16-key step belong to 8 consecutive keys.
+// over a lane's own registers plus one exchange with lane ^ 32.  The running maximum is only
+// raised when a chunk exceeds it by more than 2^8 (the probabilities then stay below 2^8, well
+// inside float32/bf16 range), so the accumulator rescale is rare; the final division by the row
+// sum makes the result independent of which maximum was used.
 template <int D, int NQ>
-__global__ __launch_bounds__(256) void attn_fwd_tile_mfma_kernel(
+__global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void attn_fwd_tile_mfma_kernel(
     TensorView Q, TensorView K, TensorView V, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr,
     const int* __restrict__ q_idx, const int* __restrict__ tile_start, float* __restrict__ Opart,
     float* __restrict__ lse_part, int Hh, int nb, long long cap, float scale_log2) {
     constexpr int TM = 128 * NQ;
     constexpr int KC = 64;                  // keys per chunk
-    constexpr int KSTR = D + 8;             // sK row stride (bf16 elements): 16 bytes of padding
-    constexpr int VSTR = KC + 8;            // sVt row stride
+    constexpr int STR = D + 8;              // LDS row stride (bf16 elements)
     constexpr int KSTEPS = D / 16;          // MFMA k-steps of the first product
     constexpr int DT = D / 32;              // 32-row tiles of O^T
-    constexpr int KLOADS = KC * D * 2 / 16 / 256;   // 16-byte K pieces per thread per chunk
-    constexpr int VQUADS = KC * D / 16 / 256;       // 4x4 V quads per thread per chunk
-    __shared__ __align__(16) __bf16 sK[KC * KSTR];
-    __shared__ __align__(16) __bf16 sVt[D * VSTR];
+    constexpr int LOADS = KC * D * 2 / 16 / 256;   // 16-byte pieces per thread per chunk and tensor
+    constexpr float LAZY = 8.f;
+    __shared__ __align__(16) __bf16 sK[KC * STR];
+    __shared__ __align__(16) __bf16 sV[KC * STR];
 
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
     TileCoord tc;
@@ -166,59 +166,29 @@ __global__ __launch_bounds__(256) void attn_fwd_tile_mfma_kernel(
     const long long kss = K.stride_s * 2, vss = V.stride_s * 2;
     const int n_chunks = (tc.L + KC - 1) / KC;
 
-    u32x4_t kreg[KLOADS];
-    u32x2_t vreg[VQUADS][4];
+    u32x4_t kreg[LOADS], vreg[LOADS];
     auto prefetch = [&](int c) {
         const int c0 = c * KC;
 #pragma unroll
-        for (int i = 0; i < KLOADS; ++i) {
+        for (int i = 0; i < LOADS; ++i) {
             const int piece = tid + 256 * i;
             const int r = piece / (D / 8), pc = piece % (D / 8);
-            const int row = tc.k0 + min(c0 + r, tc.L - 1);     // rows past the block repeat its last key
-            kreg[i] = *reinterpret_cast<const u32x4_t*>(kbase + (long long)row * kss + pc * 16);
-        }
-#pragma unroll
-        for (int i = 0; i < VQUADS; ++i) {
-            const int quad = tid + 256 * i;
-            const int kq = quad / (D / 4), dq = quad % (D / 4);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int row = tc.k0 + min(c0 + kq * 4 + r, tc.L - 1);
-                vreg[i][r] = *reinterpret_cast<const u32x2_t*>(vbase + (long long)row * vss + dq * 8);
-            }
+            const long long row = tc.k0 + min(c0 + r, tc.L - 1);   // rows past the block repeat its last key
+            kreg[i] = *reinterpret_cast<const u32x4_t*>(kbase + row * kss + pc * 16);
+            vreg[i] = *reinterpret_cast<const u32x4_t*>(vbase + row * vss + pc * 16);
         }
     };
     auto stage = [&]() {
 #pragma unroll
-        for (int i = 0; i < KLOADS; ++i) {
+        for (int i = 0; i < LOADS; ++i) {
             const int piece = tid + 256 * i;
             const int r = piece / (D / 8), pc = piece % (D / 8);
-            *reinterpret_cast<u32x4_t*>(&sK[r * KSTR + pc * 8]) = kreg[i];
-        }
-#pragma unroll
-        for (int i = 0; i < VQUADS; ++i) {
-            const int quad = tid + 256 * i;
-            const int kq = quad / (D / 4), dq = quad % (D / 4);
-            // 4 keys x 4 channels of bf16 -> 4 channels x 4 keys
-            const uint32_t a0 = vreg[i][0].x, a1 = vreg[i][0].y;   // key 0: ch 0,1 | 2,3
-            const uint32_t b0 = vreg[i][1].x, b1 = vreg[i][1].y;
-            const uint32_t c0 = vreg[i][2].x, c1 = vreg[i][2].y;
-            const uint32_t d0 = vreg[i][3].x, d1 = vreg[i][3].y;
-            u32x2_t t0, t1, t2, t3;
-            t0.x = __builtin_amdgcn_perm(b0, a0, 0x05040100u);  // ch0: key0 | key1
-            t0.y = __builtin_amdgcn_perm(d0, c0, 0x05040100u);  // ch0: key2 | key3
-            t1.x = __builtin_amdgcn_perm(b0, a0, 0x07060302u);  // ch1
-            t1.y = __builtin_amdgcn_perm(d0, c0, 0x07060302u);
-            t2.x = __builtin_amdgcn_perm(b1, a1, 0x05040100u);  // ch2
-            t2.y = __builtin_amdgcn_perm(d1, c1, 0x05040100u);
-            t3.x = __builtin_amdgcn_perm(b1, a1, 0x07060302u);  // ch3
-            t3.y = __builtin_amdgcn_perm(d1, c1, 0x07060302u);
-            *reinterpret_cast<u32x2_t*>(&sVt[(dq * 4 + 0) * VSTR + kq * 4]) = t0;
-            *reinterpret_cast<u32x2_t*>(&sVt[(dq * 4 + 1) * VSTR + kq * 4]) = t1;
-            *reinterpret_cast<u32x2_t*>(&sVt[(dq * 4 + 2) * VSTR + kq * 4]) = t2;
-            *reinterpret_cast<u32x2_t*>(&sVt[(dq * 4 + 3) * VSTR + kq * 4]) = t3;
+            *reinterpret_cast<u32x4_t*>(&sK[r * STR + pc * 8]) = kreg[i];
+            *reinterpret_cast<u32x4_t*>(&sV[r * STR + pc * 8]) = vreg[i];
         }
     };
+    const __bf16* sK_lane = sK + rho(l32) * STR + hf * 8;
+    const __bf16* sV_lane = sV + tr_lane_offset<STR>(lane);
 
     prefetch(0);
     for (int c = 0; c < n_chunks; ++c) {
@@ -232,71 +202,75 @@ __global__ __launch_bounds__(256) void attn_fwd_tile_mfma_kernel(
 
         // ---- S^T = K . Q^T
         f32x16_t sacc[NQ][2];
-#pragma unroll
-        for (int nq = 0; nq < NQ; ++nq)
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) sacc[nq][mt][i] = 0.f;
+        const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
             if (mt < n_mt) {
-                const int krow = mt * 32 + swap23(l32);
 #pragma unroll
                 for (int ks = 0; ks < KSTEPS; ++ks) {
-                    const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(&sK[krow * KSTR + ks * 16 + hf * 8]);
+                    const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sK_lane + mt * 32 * STR + ks * 16);
 #pragma unroll
                     for (int nq = 0; nq < NQ; ++nq)
-                        sacc[nq][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nq][ks], sacc[nq][mt], 0, 0, 0);
+                        sacc[nq][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nq][ks], ks == 0 ? zero16 : sacc[nq][mt], 0, 0, 0);
                 }
+            } else {
+#pragma unroll
+                for (int nq = 0; nq < NQ; ++nq) sacc[nq][mt] = zero16;   // masked to -inf below
             }
+        }
+        __builtin_amdgcn_s_setprio(0);
+        if (valid < KC) {                     // last chunk: keys past the block get -inf
+#pragma unroll
+            for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        if (mt * 32 + acc_row(i, hf) >= valid) sacc[nq][mt][i] = -INFINITY;
         }
         // ---- online soft-max (per lane = per query), in base-2 units
         bf16x8_t pf[NQ][2][2];
+        bool need_rescale = false;
+        float alpha[NQ];
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq) {
-            float mx = -INFINITY;
+            float mx = sacc[nq][0][0];
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    // accumulator value i of lane half hf <-> key 32*mt + 16*(i>>3) + 8*hf + (i&7)
-                    const int key = mt * 32 + ((i >> 3) << 4) + hf * 8 + (i & 7);
-                    float v = sacc[nq][mt][i] * scale_log2;
-                    if (key >= valid) v = -INFINITY;
-                    sacc[nq][mt][i] = v;
-                    mx = fmaxf(mx, v);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run[nq], mx);
-            const float alpha = exp2_raw(m_run[nq] - m_new);
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[nq][mt][i]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;       // scale_log2 > 0
+            const bool raise = mx > m_run[nq] + LAZY;
+            const float m_new = raise ? mx : m_run[nq];
+            alpha[nq] = raise ? exp2_raw(m_run[nq] - m_new) : 1.f;
+            need_rescale |= raise;
+            m_run[nq] = m_new;
             float rs = 0.f;
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
                 float p[16];
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    p[i] = exp2_raw(sacc[nq][mt][i] - m_new);
+                    p[i] = exp2_raw(fmaf(sacc[nq][mt][i], scale_log2, -m_new));
                     rs += p[i];
                 }
-#pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    f32x4_t lo = {p[8 * s + 0], p[8 * s + 1], p[8 * s + 2], p[8 * s + 3]};
-                    f32x4_t hi = {p[8 * s + 4], p[8 * s + 5], p[8 * s + 6], p[8 * s + 7]};
-                    bf16x4_t blo = __builtin_convertvector(lo, bf16x4_t);
-                    bf16x4_t bhi = __builtin_convertvector(hi, bf16x4_t);
-                    pf[nq][mt][s] = __builtin_shufflevector(blo, bhi, 0, 1, 2, 3, 4, 5, 6, 7);
-                }
+                pf[nq][mt][0] = pack8(&p[0]);
+                pf[nq][mt][1] = pack8(&p[8]);
             }
             rs += __shfl_xor(rs, 32, 64);
-            l_run[nq] = l_run[nq] * alpha + rs;
-            m_run[nq] = m_new;
+            l_run[nq] = l_run[nq] * alpha[nq] + rs;
+        }
+        if (__any(need_rescale)) {
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
+            for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) oacc[nq][dt][i] *= alpha;
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) oacc[nq][dt][i] *= alpha[nq];
         }
         // ---- O^T += V^T . P^T
+        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
             if (mt < n_mt) {
@@ -304,8 +278,7 @@ __global__ __launch_bounds__(256) void attn_fwd_tile_mfma_kernel(
                 for (int s = 0; s < 2; ++s) {
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt) {
-                        const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(
-                            &sVt[(dt * 32 + l32) * VSTR + mt * 32 + s * 16 + hf * 8]);
+                        const bf16x8_t vf = tr_operand<STR>(sV_lane, mt * 32, s, dt * 32);
 #pragma unroll
                         for (int nq = 0; nq < NQ; ++nq)
                             oacc[nq][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nq][mt][s], oacc[nq][dt], 0, 0, 0);
@@ -313,6 +286,7 @@ __global__ __launch_bounds__(256) void attn_fwd_tile_mfma_kernel(
                 }
             }
         }
+        __builtin_amdgcn_s_setprio(0);
     }
 
     // ---- partial output: O^T value i of tile dt <-> channel 32*dt + 8*(i>>2) + 4*hf + (i&3)
@@ -409,8 +383,8 @@ size_t vmoba_attn_fwd_workspace_bytes(int B, int Hh, int64_t S, int D, int64_t c
 int vmoba_fwd_nq() {
     static int nq = [] {
         const char* e = getenv("VMOBA_FWD_NQ");
-        int v = e ? atoi(e) : 2;
-        return (v == 1) ? 1 : 2;
+        int v = e ? atoi(e) : 1;      // 1: two workgroups per CU (measured faster); 2: wider tile, one per CU
+        return (v == 2) ? 2 : 1;
     }();
     return nq;
 }
@@ -443,7 +417,8 @@ extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     const int TM = simple ? 64 : 128 * nq;
     tile_start_kernel<<<dim3((BH + 63) / 64), dim3(64), 0, st>>>(blk_ptr, ws.tile_start, BH, n_blocks, TM);
     VMOBA_CHECK_LAUNCH();
-    const int64_t max_tiles = nnz_capacity / TM + n_blocks;
+    // a multiple of 8 so that (workgroup id % 8) is the same for every head; + 8 for the per-XCD rounding
+    const int64_t max_tiles = (nnz_capacity / TM + n_blocks + 7) / 8 * 8 + 8;
     dim3 grid((unsigned)max_tiles, (unsigned)BH);
     VMOBA_PROFILE_BEGIN(0, st);
 #define TILE_ARGS Qv, Kv, Vv, blk_off, blk_ptr, q_idx, ws.tile_start, ws.Opart, ws.lse_part, Hh, n_blocks, (long long)nnz_capacity, scale_log2
