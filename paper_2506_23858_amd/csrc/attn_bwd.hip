@@ -14,6 +14,10 @@
 #include <algorithm>
 #include <cmath>
 
+#ifndef VMOBA_DKV_SCHED
+#define VMOBA_DKV_SCHED 0
+#endif
+
 namespace {
 
 constexpr float LOG2E = 1.4426950408889634f;
@@ -57,6 +61,22 @@ __global__ __launch_bounds__(64) void key_run_start_kernel(const int* __restrict
         run += (blk_off[j + 1] - blk_off[j] + KPW - 1) / KPW;
     }
     kb_start[nb] = run;
+}
+
+// XCD-aware work table of the dK/dV kernel.  Workgroups go to the 8 XCDs round-robin (workgroup
+// id % 8) and every XCD has its own L2.  All key runs of one block gather the same query rows, so
+// they should meet in one L2: XCD x gets the blocks j = x, x+8, x+16, ...; entry 8*slot + x of the
+// table is its slot-th (block, run) as j | run << 8, or -1 past its last one.  One thread per XCD.
+__global__ __launch_bounds__(64) void key_run_xcd_kernel(const int* __restrict__ blk_off, int* __restrict__ work,
+                                                         int nb, int KPW, int max_slots) {
+    const int x = threadIdx.x;
+    if (x >= 8 || blockIdx.x != 0) return;
+    int slot = 0;
+    for (int j = x; j < nb; j += 8) {
+        const int runs = (blk_off[j + 1] - blk_off[j] + KPW - 1) / KPW;
+        for (int r = 0; r < runs && slot < max_slots; ++r, ++slot) work[slot * 8 + x] = j | (r << 8);
+    }
+    for (; slot < max_slots; ++slot) work[slot * 8 + x] = -1;
 }
 
 __device__ __forceinline__ float load_elem(const char* p, int d, bool bf16) {
@@ -334,13 +354,15 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
         }
     }
     if (ent < tc.count) {
-        float* dst = dQpart + (seg + tc.list0 + tc.t0 + ent) * D;
+        uint16_t* dst = reinterpret_cast<uint16_t*>(dQpart) + (seg + tc.list0 + tc.t0 + ent) * D;   // bf16 partials
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                f32x4_t v = {dqacc[dt][4 * g + 0], dqacc[dt][4 * g + 1], dqacc[dt][4 * g + 2], dqacc[dt][4 * g + 3]};
-                *reinterpret_cast<f32x4_t*>(dst + dt * 32 + g * 8 + hf * 4) = v;
+                u32x2_t v;
+                v.x = pack_bf16x2(dqacc[dt][4 * g + 0], dqacc[dt][4 * g + 1]);
+                v.y = pack_bf16x2(dqacc[dt][4 * g + 2], dqacc[dt][4 * g + 3]);
+                *reinterpret_cast<u32x2_t*>(dst + dt * 32 + g * 8 + hf * 4) = v;
             }
     }
 }
@@ -348,41 +370,45 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
 // ---------------------------------------------------------------------------------------------
 // bf16 MFMA dK/dV kernel.  A workgroup of NW wavefronts owns 32*NW consecutive keys of one
 // block (wavefront w: 32 keys, key = MFMA column = lane % 32) and walks the block's query list
-// in chunks of 64 gathered queries, staged row-major in LDS with register prefetch:
+// in chunks of 64 gathered queries (two half-chunks of 32):
 //   S   = Q . K^T                     A = Q rows (LDS),   B = K^T (registers, loaded once)
 //   dP  = dO . V^T                    A = dO rows (LDS),  B = V^T (registers, loaded once)
 //   P = exp(S - LSE), dS = P * (dP - delta)        packed to bf16 as B operands
 //   dV^T += dO^T . P                  A = dO^T by transpose reads of the dO tile
 //   dK^T += Q^T . dS                  A = Q^T  by transpose reads of the Q tile
+// One wavefront per SIMD, so the overlap of matrix and vector work is arranged in the program
+// order: the exp/dS arithmetic of one half-chunk is interleaved with the S, dP products of the next
+// half-chunk or the dV, dK products of the previous one, which do not depend on it.
+// Chunks pass through a ring of three LDS buffers with one barrier per chunk; the gathered rows are
+// prefetched into registers one chunk ahead and the query indices two chunks ahead.
 template <int D, int NW>
 __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
     const int* __restrict__ kb_start, TensorView dK, TensorView dV, int Hh, int S, int nb, long long cap,
-    float scale_log2, float scale) {
+    float scale_log2, float scale, int dbg) {
     constexpr int NT = 64 * NW;
     constexpr int QC = 64;
     constexpr int STR = D + 8;
     constexpr int KSTEPS = D / 16, DT = D / 32;
     constexpr int LOADS = QC * D * 2 / 16 / NT;     // 16-byte pieces per thread per chunk and tensor
+    constexpr int NBUF = 3;
     static_assert(QC * D * 2 / 16 % NT == 0, "chunk must divide evenly over the threads");
-    __shared__ __align__(16) __bf16 sQ[QC * STR];
-    __shared__ __align__(16) __bf16 sdO[QC * STR];
-    __shared__ __align__(16) float sL[QC];
-    __shared__ __align__(16) float sDl[QC];
+    __shared__ __align__(16) __bf16 sQ[NBUF][QC * STR];
+    __shared__ __align__(16) __bf16 sdO[NBUF][QC * STR];
+    __shared__ __align__(16) float sL[NBUF][QC];
+    __shared__ __align__(16) float sDl[NBUF][QC];
 
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
-    const int run = (int)blockIdx.x;
-    if (run >= kb_start[nb]) return;
-    int lo = 0, hi = nb;
-    while (hi - lo > 1) { int mid = (lo + hi) >> 1; if (kb_start[mid] <= run) lo = mid; else hi = mid; }
-    const int j = lo;
+    const int w = kb_start[blockIdx.x];          // XCD-aware work table: block | run << 8, or -1
+    if (w < 0) return;
+    const int j = w & 255, run = w >> 8;
     const int k0 = blk_off[j], L = blk_off[j + 1] - k0;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hf = lane >> 5;
-    const int kk = (run - kb_start[j]) * (32 * NW) + wave * 32 + l32;   // key inside the block
+    const int kk = run * (32 * NW) + wave * 32 + l32;   // key inside the block
     const bool key_live = kk < L;
-    const bool wave_live = (run - kb_start[j]) * (32 * NW) + wave * 32 < L;
+    const bool wave_live = run * (32 * NW) + wave * 32 < L;
     const int krow = k0 + min(kk, L - 1);
     const long long seg = (long long)bh * cap;
     const int list0 = blk_ptr[(long long)bh * (nb + 1) + j];
@@ -404,103 +430,179 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
 #pragma unroll
         for (int i = 0; i < 16; ++i) { dkacc[dt][i] = 0.f; dvacc[dt][i] = 0.f; }
 
-    const char* qbase = Q.ptr + ((long long)b * Q.stride_b + (long long)h * Q.stride_h) * 2;
-    const char* dobase = dO.ptr + ((long long)b * dO.stride_b + (long long)h * dO.stride_h) * 2;
-    const long long qss = Q.stride_s * 2, doss = dO.stride_s * 2;
-    const int* list = q_idx + seg + list0;
-    const float* lse_h = LSE + (long long)bh * S;
-    const float* dl_h = delta + (long long)bh * S;
+    if (cnt > 0) {
+        const char* qbase = Q.ptr + ((long long)b * Q.stride_b + (long long)h * Q.stride_h) * 2;
+        const char* dobase = dO.ptr + ((long long)b * dO.stride_b + (long long)h * dO.stride_h) * 2;
+        const long long qss = Q.stride_s * 2, doss = dO.stride_s * 2;
+        const int* list = q_idx + seg + list0;
+        const float* lse_h = LSE + (long long)bh * S;
+        const float* dl_h = delta + (long long)bh * S;
+        const int n_chunks = (cnt + QC - 1) / QC;
 
-    // register prefetch of the next chunk: the gathered Q and dO rows, and LSE / delta of its queries
-    u32x4_t qreg[LOADS], doreg[LOADS];
-    float lreg = 0.f, dreg = 0.f;
-    auto prefetch = [&](int c0) {
-        const int qc = min(QC, cnt - c0);
+        u32x4_t qreg[LOADS], doreg[LOADS];
+        float lreg = 0.f, dreg = 0.f;
+        int qn[LOADS], ql = 0;
+        bool ql_live = false, rows_live = false;
+        // chunk indices past the list behave as chunks without live rows (indices clamp, LSE = +inf)
+        auto prefetch_idx = [&](int c) {
+            const int c0 = c * QC;
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int piece = tid + NT * i;
-            const int r = piece / (D / 8), pc = piece % (D / 8);
-            const long long q = list[c0 + min(r, qc - 1)];        // rows past the list repeat its last query
-            qreg[i] = *reinterpret_cast<const u32x4_t*>(qbase + q * qss + pc * 16);
-            doreg[i] = *reinterpret_cast<const u32x4_t*>(dobase + q * doss + pc * 16);
-        }
-        if (tid < QC) {
-            const long long q = list[c0 + min(tid, qc - 1)];
-            // rows past the end of the list get LSE = +inf (weight 0) and delta = 0
-            lreg = (tid < qc) ? lse_h[q] * LOG2E : INFINITY;
-            dreg = (tid < qc) ? dl_h[q] : 0.f;
-        }
-    };
-    auto stage = [&]() {
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int piece = tid + NT * i;
-            const int r = piece / (D / 8), pc = piece % (D / 8);
-            *reinterpret_cast<u32x4_t*>(&sQ[r * STR + pc * 8]) = qreg[i];
-            *reinterpret_cast<u32x4_t*>(&sdO[r * STR + pc * 8]) = doreg[i];
-        }
-        if (tid < QC) {
-            // stored in accumulator order: the 16 values a lane half needs per 32-query group are contiguous
-            const int r = tid & 31;
-            const int pos = (tid & 32) + ((r & 1) << 4) + ((r >> 4) << 3) + (((r >> 1) & 1) << 2) + ((r >> 2) & 3);
-            sL[pos] = lreg;
-            sDl[pos] = dreg;
-        }
-    };
-    const __bf16* sQ_lane = sQ + rho(l32) * STR + hf * 8;
-    const __bf16* sdO_lane = sdO + rho(l32) * STR + hf * 8;
-    const __bf16* sQt_lane = sQ + tr_lane_offset<STR>(lane);
-    const __bf16* sdOt_lane = sdO + tr_lane_offset<STR>(lane);
-
-    if (cnt > 0) prefetch(0);
-    for (int c0 = 0; c0 < cnt; c0 += QC) {
-        const int qc = min(QC, cnt - c0);
-        __syncthreads();                 // previous chunk fully consumed
-        stage();
-        __syncthreads();
-        if (c0 + QC < cnt) prefetch(c0 + QC);
-        if (wave_live) {
-            const int n_mt = qc > 32 ? 2 : 1;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                if (mt < n_mt) {
-                    f32x16_t sacc, dpacc;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dpacc[i] = 0.f; }
-#pragma unroll
-                    for (int ks = 0; ks < KSTEPS; ++ks) {
-                        const bf16x8_t qa = *reinterpret_cast<const bf16x8_t*>(sQ_lane + mt * 32 * STR + ks * 16);
-                        const bf16x8_t da = *reinterpret_cast<const bf16x8_t*>(sdO_lane + mt * 32 * STR + ks * 16);
-                        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[ks], sacc, 0, 0, 0);
-                        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[ks], dpacc, 0, 0, 0);
-                    }
-                    // accumulator value i <-> query mt*32 + acc_row(i, hf) of the chunk
-                    float p[16], ds[16];
-#pragma unroll
-                    for (int g4 = 0; g4 < 4; ++g4) {
-                        const f32x4_t lv = *reinterpret_cast<const f32x4_t*>(&sL[mt * 32 + hf * 16 + g4 * 4]);
-                        const f32x4_t dv4 = *reinterpret_cast<const f32x4_t*>(&sDl[mt * 32 + hf * 16 + g4 * 4]);
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            const int i = g4 * 4 + u;
-                            p[i] = exp2_raw(fmaf(sacc[i], scale_log2, -lv[u]));
-                            ds[i] = p[i] * (dpacc[i] - dv4[u]);
-                        }
-                    }
-#pragma unroll
-                    for (int s = 0; s < 2; ++s) {
-                        const bf16x8_t pfr = pack8(&p[8 * s]);
-                        const bf16x8_t dsf = pack8(&ds[8 * s]);
-#pragma unroll
-                        for (int dt = 0; dt < DT; ++dt) {
-                            const bf16x8_t dot = tr_operand<STR>(sdOt_lane, mt * 32, s, dt * 32);
-                            const bf16x8_t qt = tr_operand<STR>(sQt_lane, mt * 32, s, dt * 32);
-                            dvacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot, pfr, dvacc[dt], 0, 0, 0);
-                            dkacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf, dkacc[dt], 0, 0, 0);
-                        }
-                    }
-                }
+            for (int i = 0; i < LOADS; ++i) {
+                const int r = (tid + NT * i) / (D / 8);
+                qn[i] = list[min(c0 + r, cnt - 1)];
             }
+            if (tid < QC) {
+                ql = list[min(c0 + tid, cnt - 1)];
+                ql_live = c0 + tid < cnt;
+            }
+        };
+        auto prefetch_rows = [&]() {
+#pragma unroll
+            for (int i = 0; i < LOADS; ++i) {
+                const int pc = (tid + NT * i) % (D / 8);
+                qreg[i] = *reinterpret_cast<const u32x4_t*>(qbase + (long long)qn[i] * qss + pc * 16);
+                doreg[i] = *reinterpret_cast<const u32x4_t*>(dobase + (long long)qn[i] * doss + pc * 16);
+            }
+            if (tid < QC) {
+                lreg = lse_h[ql];            // used only at the next stage(): no wait on these loads here
+                dreg = dl_h[ql];
+                rows_live = ql_live;
+            }
+        };
+        auto stage = [&](int buf) {
+#pragma unroll
+            for (int i = 0; i < LOADS; ++i) {
+                const int piece = tid + NT * i;
+                const int r = piece / (D / 8), pc = piece % (D / 8);
+                *reinterpret_cast<u32x4_t*>(&sQ[buf][r * STR + pc * 8]) = qreg[i];
+                *reinterpret_cast<u32x4_t*>(&sdO[buf][r * STR + pc * 8]) = doreg[i];
+            }
+            if (tid < QC) {
+                // accumulator order: the 16 values a lane half needs per 32-query group are contiguous
+                const int r = tid & 31;
+                const int pos = (tid & 32) + ((r & 1) << 4) + ((r >> 4) << 3) + (((r >> 1) & 1) << 2) + ((r >> 2) & 3);
+                // rows past the end of the list get LSE = +inf (weight 0) and delta = 0
+                sL[buf][pos] = rows_live ? lreg * LOG2E : INFINITY;
+                sDl[buf][pos] = rows_live ? dreg : 0.f;
+            }
+        };
+        const int row_lane = rho(l32) * STR + hf * 8;
+        const int tr_lane = tr_lane_offset<STR>(lane);
+        const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+        // S and dP of half-chunk (buf, mt); optionally interleaved with the vector work of another
+        // half-chunk whose S, dP (sv, dv) are complete: p/ds values 2*ks, 2*ks+1 per k-step.
+        auto sdp_step = [&](int buf, int mt, int ks, f32x16_t& sa, f32x16_t& dp) {
+            const bf16x8_t qa = *reinterpret_cast<const bf16x8_t*>(&sQ[buf][row_lane + mt * 32 * STR + ks * 16]);
+            const bf16x8_t da = *reinterpret_cast<const bf16x8_t*>(&sdO[buf][row_lane + mt * 32 * STR + ks * 16]);
+            sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[ks], ks == 0 ? zero16 : sa, 0, 0, 0);
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[ks], ks == 0 ? zero16 : dp, 0, 0, 0);
+        };
+        auto load_ld = [&](int buf, int mt, float* lv, float* dl) {
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const f32x4_t a = *reinterpret_cast<const f32x4_t*>(&sL[buf][mt * 32 + hf * 16 + g4 * 4]);
+                const f32x4_t c = *reinterpret_cast<const f32x4_t*>(&sDl[buf][mt * 32 + hf * 16 + g4 * 4]);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) { lv[g4 * 4 + u] = a[u]; dl[g4 * 4 + u] = c[u]; }
+            }
+        };
+        auto valu_pair = [&](const float* lv, const float* dl, int i2, const f32x16_t& sv, const f32x16_t& dv, float* p, float* ds) {
+            // values 2*i2 and 2*i2 + 1 (i2 = 0..7)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int i = 2 * i2 + u;
+                p[i] = exp2_raw(fmaf(sv[i], scale_log2, -lv[i]));
+                ds[i] = p[i] * (dv[i] - dl[i]);
+            }
+        };
+        auto dvdk_step = [&](int buf, int mt, int s, int dt, const bf16x8_t& pfr, const bf16x8_t& dsf) {
+            const bf16x8_t dot = tr_operand<STR>(&sdO[buf][tr_lane], mt * 32, s, dt * 32);
+            const bf16x8_t qt = tr_operand<STR>(&sQ[buf][tr_lane], mt * 32, s, dt * 32);
+            dvacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot, pfr, dvacc[dt], 0, 0, 0);
+            dkacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf, dkacc[dt], 0, 0, 0);
+        };
+
+        // prologue: chunk 0 staged, chunk 1 in flight, indices of chunk 2 in flight, S/dP of (0, 0)
+        prefetch_idx(0);
+        prefetch_rows();
+        prefetch_idx(1);
+        stage(0);
+        prefetch_rows();
+        prefetch_idx(2);
+        __syncthreads();
+        f32x16_t s0 = zero16, p0 = zero16, s1 = zero16, p1 = zero16;   // S, dP of half-chunks 0 and 1 of the current chunk
+        if (wave_live) {
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) sdp_step(0, 0, ks, s0, p0);
+        }
+        int buf = 0;
+        for (int c = 0; c < n_chunks; ++c) {
+            const int nbuf = (buf + 1 == NBUF) ? 0 : buf + 1;
+            float pa[16], dsa[16], pb[16], dsb[16];
+            bf16x8_t pf1[2], df1[2];
+            if (wave_live && !(dbg & 16)) {
+                float lv0[16], dl0[16], lv1[16], dl1[16];
+                load_ld(buf, 0, lv0, dl0);
+                load_ld(buf, 1, lv1, dl1);
+                // A: S, dP of (c, 1)  ||  exp / dS of (c, 0)
+#pragma unroll
+                for (int ks = 0; ks < KSTEPS; ++ks) {
+                    sdp_step(buf, 1, ks, s1, p1);
+#pragma unroll
+                    for (int u = 0; u < 8 / KSTEPS; ++u) valu_pair(lv0, dl0, ks * (8 / KSTEPS) + u, s0, p0, pa, dsa);
+                }
+                const bf16x8_t pf0[2] = {pack8(&pa[0]), pack8(&pa[8])};
+                const bf16x8_t df0[2] = {pack8(&dsa[0]), pack8(&dsa[8])};
+                // B: dV, dK of (c, 0)  ||  exp / dS of (c, 1)
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt) {
+                        dvdk_step(buf, 0, s, dt, pf0[s], df0[s]);
+#pragma unroll
+                        for (int u = 0; u < 8 / (2 * DT); ++u)
+                            valu_pair(lv1, dl1, (s * DT + dt) * (8 / (2 * DT)) + u, s1, p1, pb, dsb);
+                    }
+                pf1[0] = pack8(&pb[0]); pf1[1] = pack8(&pb[8]);
+                df1[0] = pack8(&dsb[0]); df1[1] = pack8(&dsb[8]);
+#if VMOBA_DKV_SCHED
+                // requested instruction order for this block: LDS reads run ahead of the matrix
+                // instructions that consume them, vector work fills the gaps between matrix issues
+#define VMOBA_SG_STEP(NDS)                                      \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);          \
+    __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);          \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);          \
+    __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);          \
+    __builtin_amdgcn_sched_group_barrier(0x100, NDS, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 8 + 6, 0);      // LSE/delta + first 3 steps of A
+                if constexpr (D == 128) {
+                    VMOBA_SG_STEP(2) VMOBA_SG_STEP(2) VMOBA_SG_STEP(2) VMOBA_SG_STEP(2)
+                    VMOBA_SG_STEP(2) VMOBA_SG_STEP(4) VMOBA_SG_STEP(4) VMOBA_SG_STEP(4)
+                    VMOBA_SG_STEP(4) VMOBA_SG_STEP(4) VMOBA_SG_STEP(4) VMOBA_SG_STEP(4)
+                    VMOBA_SG_STEP(4) VMOBA_SG_STEP(0) VMOBA_SG_STEP(0) VMOBA_SG_STEP(0)
+                }
+#undef VMOBA_SG_STEP
+#endif
+            }
+            // next chunk into the ring (its rows arrived during this iteration), loads of the one after
+            stage(nbuf);
+            if (!(dbg & 1)) {
+                prefetch_rows();
+                prefetch_idx(c + 3);
+            }
+            __syncthreads();
+            if (wave_live && !(dbg & 16)) {
+                // C: dV, dK of (c, 1)  and  S, dP of (c + 1, 0)
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt) {
+                        dvdk_step(buf, 1, s, dt, pf1[s], df1[s]);
+                        sdp_step(nbuf, 0, s * DT + dt, s0, p0);
+                    }
+            }
+            buf = nbuf;
         }
     }
     if (key_live) {
@@ -522,12 +624,13 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
     }
 }
 
-// dQ[q] = scale * sum over the query's pairs of dQpart[pair].
-template <bool BF16, int D>
+// dQ[q] = scale * sum over the query's pairs of dQpart[pair] (bfloat16 partials when PBF16).
+template <bool BF16, bool PBF16, int D>
 __global__ __launch_bounds__(256) void dq_merge_kernel(const float* __restrict__ dQpart, const int* __restrict__ row_ptr,
                                                        const int* __restrict__ pair_pos, TensorView dQ, int Hh, int S,
                                                        long long cap, float scale) {
-    constexpr int LPQ = D / 4;
+    constexpr int CH = PBF16 ? 8 : 4;
+    constexpr int LPQ = D / CH;
     constexpr int QPW = 256 / LPQ;
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
     const int q = blockIdx.x * QPW + threadIdx.x / LPQ;
@@ -535,20 +638,42 @@ __global__ __launch_bounds__(256) void dq_merge_kernel(const float* __restrict__
     if (q >= S) return;
     const int r0 = row_ptr[(long long)bh * (S + 1) + q], r1 = row_ptr[(long long)bh * (S + 1) + q + 1];
     const long long seg = (long long)bh * cap;
-    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    float acc[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) acc[c] = 0.f;
     for (int r = r0; r < r1; ++r) {
         const long long pair = seg + pair_pos[seg + r];
-        acc += *reinterpret_cast<const f32x4_t*>(dQpart + pair * D + part * 4);
+        if constexpr (PBF16) {
+            const u32x4_t v = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const uint16_t*>(dQpart) + pair * D + part * 8);
+            acc[0] += bf16lo_to_f32(v.x); acc[1] += bf16hi_to_f32(v.x);
+            acc[2] += bf16lo_to_f32(v.y); acc[3] += bf16hi_to_f32(v.y);
+            acc[4] += bf16lo_to_f32(v.z); acc[5] += bf16hi_to_f32(v.z);
+            acc[6] += bf16lo_to_f32(v.w); acc[7] += bf16hi_to_f32(v.w);
+        } else {
+            const f32x4_t v = *reinterpret_cast<const f32x4_t*>(dQpart + pair * D + part * 4);
+            acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
+        }
     }
-    acc *= scale;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) acc[c] *= scale;
     char* dst = dQ.ptr + ((long long)b * dQ.stride_b + (long long)q * dQ.stride_s + (long long)h * dQ.stride_h) * (BF16 ? 2 : 4);
-    if (BF16) {
-        u32x2_t w;
-        w.x = pack_bf16x2(acc.x, acc.y);
-        w.y = pack_bf16x2(acc.z, acc.w);
-        *reinterpret_cast<u32x2_t*>(dst + part * 8) = w;
+    if constexpr (BF16) {
+        uint32_t w[CH / 2];
+#pragma unroll
+        for (int c = 0; c < CH / 2; ++c) w[c] = pack_bf16x2(acc[2 * c], acc[2 * c + 1]);
+        if constexpr (CH == 8) {
+            u32x4_t o = {w[0], w[1], w[2], w[3]};
+            *reinterpret_cast<u32x4_t*>(dst + part * 16) = o;
+        } else {
+            u32x2_t o = {w[0], w[1]};
+            *reinterpret_cast<u32x2_t*>(dst + part * 8) = o;
+        }
     } else {
-        *reinterpret_cast<f32x4_t*>(dst + part * 16) = acc;
+#pragma unroll
+        for (int c = 0; c < CH; c += 4) {
+            f32x4_t o = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
+            *reinterpret_cast<f32x4_t*>(dst + (part * CH + c) * 4) = o;
+        }
     }
 }
 
@@ -557,8 +682,12 @@ struct BwdWs {
     float* delta;      // [BH][S]
     int* tile_start;   // [BH][257]
     int* kb_start;     // [257]
+    int* xcd_work;     // [8 * dkv_max_slots]
     size_t total;
 };
+
+// Upper bound, known on the host, of the key runs (of 128 keys) one XCD can be handed.
+int dkv_max_slots(int64_t S) { return (int)(S / 128 + VMOBA_MAX_BLOCKS / 8 + 2); }
 
 BwdWs carve_bwd(void* base, int BH, int64_t S, int D, int64_t cap) {
     BwdWs w;
@@ -568,6 +697,7 @@ BwdWs carve_bwd(void* base, int BH, int64_t S, int D, int64_t cap) {
     w.delta = (float*)(p + off);     off += align_up((size_t)BH * S * 4, 256);
     w.tile_start = (int*)(p + off);  off += align_up((size_t)BH * (VMOBA_MAX_BLOCKS + 1) * 4, 256);
     w.kb_start = (int*)(p + off);    off += align_up((size_t)(VMOBA_MAX_BLOCKS + 1) * 4, 256);
+    w.xcd_work = (int*)(p + off);    off += align_up((size_t)8 * dkv_max_slots(S) * 4, 256);
     w.total = off;
     return w;
 }
@@ -640,13 +770,16 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
 #undef DQ_ARGS
         VMOBA_PROFILE_END(1, st);
         VMOBA_CHECK_LAUNCH();
-        const int qpw = 256 / (D / 4);
+        const bool pbf16 = !simple;           // the MFMA tile kernel writes bfloat16 partials
+        const int qpw = 256 / (D / (pbf16 ? 8 : 4));
         dim3 mgrid((unsigned)ceil_div64(S, qpw), (unsigned)BH);
 #define MG_ARGS ws.dQpart, row_ptr, pair_pos, dQv, Hh, (int)S, (long long)nnz_capacity, softmax_scale
-        if (bf16 && D == 128) dq_merge_kernel<true, 128><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
-        else if (bf16) dq_merge_kernel<true, 64><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
-        else if (D == 128) dq_merge_kernel<false, 128><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
-        else dq_merge_kernel<false, 64><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
+        if (pbf16 && D == 128) dq_merge_kernel<true, true, 128><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
+        else if (pbf16) dq_merge_kernel<true, true, 64><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
+        else if (bf16 && D == 128) dq_merge_kernel<true, false, 128><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
+        else if (bf16) dq_merge_kernel<true, false, 64><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
+        else if (D == 128) dq_merge_kernel<false, false, 128><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
+        else dq_merge_kernel<false, false, 64><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
 #undef MG_ARGS
         VMOBA_CHECK_LAUNCH();
     }
@@ -654,11 +787,15 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     {
         constexpr int NW = 4;
         const int KPW = simple ? 64 : 32 * NW;
-        key_run_start_kernel<<<dim3(1), dim3(64), 0, st>>>(blk_off, ws.kb_start, n_blocks, KPW);
+        const int max_slots = dkv_max_slots(S);
+        if (simple) key_run_start_kernel<<<dim3(1), dim3(64), 0, st>>>(blk_off, ws.kb_start, n_blocks, KPW);
+        else key_run_xcd_kernel<<<dim3(1), dim3(64), 0, st>>>(blk_off, ws.xcd_work, n_blocks, KPW, max_slots);
         VMOBA_CHECK_LAUNCH();
         // a multiple of 8 so that (workgroup id % 8) is the same for every head; + 8 for the per-XCD rounding
         dim3 grid((unsigned)((S / KPW + n_blocks + 7) / 8 * 8 + 8), (unsigned)BH);
         VMOBA_PROFILE_BEGIN(2, st);
+        const char* de = getenv("VMOBA_BWD_DBG");
+        const int dbg = de ? atoi(de) : 0;
 #define DKV_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.kb_start, dKv, dVv, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
         if (simple) {
             if (bf16 && D == 128) attn_bwd_dkv_simple_kernel<true, 128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
@@ -666,8 +803,11 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
             else if (D == 128) attn_bwd_dkv_simple_kernel<false, 128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
             else attn_bwd_dkv_simple_kernel<false, 64><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
         } else {
-            if (D == 128) attn_bwd_dkv_mfma_kernel<128, NW><<<grid, dim3(64 * NW), 0, st>>>(DKV_ARGS);
-            else attn_bwd_dkv_mfma_kernel<64, NW><<<grid, dim3(64 * NW), 0, st>>>(DKV_ARGS);
+            dim3 xgrid((unsigned)(8 * max_slots), (unsigned)BH);
+#define DKV_XARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.xcd_work, dKv, dVv, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
+            if (D == 128) attn_bwd_dkv_mfma_kernel<128, NW><<<xgrid, dim3(64 * NW), 0, st>>>(DKV_XARGS, dbg);
+            else attn_bwd_dkv_mfma_kernel<64, NW><<<xgrid, dim3(64 * NW), 0, st>>>(DKV_XARGS, dbg);
+#undef DKV_XARGS
         }
 #undef DKV_ARGS
         VMOBA_PROFILE_END(2, st);

@@ -116,7 +116,7 @@ template <int D, int NQ>
 __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void attn_fwd_tile_mfma_kernel(
     TensorView Q, TensorView K, TensorView V, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr,
     const int* __restrict__ q_idx, const int* __restrict__ tile_start, float* __restrict__ Opart,
-    float* __restrict__ lse_part, int Hh, int nb, long long cap, float scale_log2) {
+    float* __restrict__ lse_part, int Hh, int nb, long long cap, float scale_log2, int dbg) {
     constexpr int TM = 128 * NQ;
     constexpr int KC = 64;                  // keys per chunk
     constexpr int STR = D + 8;              // LDS row stride (bf16 elements)
@@ -195,10 +195,11 @@ __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void attn_fwd_tile_mfma_ker
         __syncthreads();                      // everyone is done reading the previous chunk
         stage();
         __syncthreads();
-        if (c + 1 < n_chunks) prefetch(c + 1);
+        if (c + 1 < n_chunks && !(dbg & 1)) prefetch(c + 1);
+        if (dbg & 16) continue;
 
         const int valid = tc.L - c * KC;      // keys of this chunk inside the block (may exceed KC)
-        const int n_mt = valid > 32 ? 2 : 1;  // 32-key groups with at least one valid key
+        const int n_mt = (dbg & 4) ? 0 : (valid > 32 ? 2 : 1);  // 32-key groups with at least one valid key
 
         // ---- S^T = K . Q^T
         f32x16_t sacc[NQ][2];
@@ -233,6 +234,17 @@ __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void attn_fwd_tile_mfma_ker
         bf16x8_t pf[NQ][2][2];
         bool need_rescale = false;
         float alpha[NQ];
+        if (dbg & 2) {
+#pragma unroll
+            for (int nq = 0; nq < NQ; ++nq) {
+                float tmp[32];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) { tmp[v] = sacc[nq][0][v]; tmp[16 + v] = sacc[nq][1][v]; }
+                pf[nq][0][0] = pack8(&tmp[0]); pf[nq][0][1] = pack8(&tmp[8]);
+                pf[nq][1][0] = pack8(&tmp[16]); pf[nq][1][1] = pack8(&tmp[24]);
+                l_run[nq] = 1.f; m_run[nq] = 0.f; alpha[nq] = 1.f;
+            }
+        } else
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq) {
             float mx = sacc[nq][0][0];
@@ -273,7 +285,7 @@ __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void attn_fwd_tile_mfma_ker
         __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
-            if (mt < n_mt) {
+            if (mt < n_mt && !(dbg & 8)) {
 #pragma unroll
                 for (int s = 0; s < 2; ++s) {
 #pragma unroll
@@ -295,14 +307,15 @@ __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void attn_fwd_tile_mfma_ker
         if (my_entry[nq] < tc.count) {
             const long long pair = seg + tc.list0 + tc.t0 + my_entry[nq];
             const float inv = 1.f / l_run[nq];
-            float* dst = Opart + pair * D;
+            uint16_t* dst = reinterpret_cast<uint16_t*>(Opart) + pair * D;      // bf16 partials
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    f32x4_t v = {oacc[nq][dt][4 * g + 0] * inv, oacc[nq][dt][4 * g + 1] * inv,
-                                 oacc[nq][dt][4 * g + 2] * inv, oacc[nq][dt][4 * g + 3] * inv};
-                    *reinterpret_cast<f32x4_t*>(dst + dt * 32 + g * 8 + hf * 4) = v;
+                    u32x2_t v;
+                    v.x = pack_bf16x2(oacc[nq][dt][4 * g + 0] * inv, oacc[nq][dt][4 * g + 1] * inv);
+                    v.y = pack_bf16x2(oacc[nq][dt][4 * g + 2] * inv, oacc[nq][dt][4 * g + 3] * inv);
+                    *reinterpret_cast<u32x2_t*>(dst + dt * 32 + g * 8 + hf * 4) = v;
                 }
             if (hf == 0) lse_part[pair] = (m_run[nq] + log2f(l_run[nq])) * LN2;
         }
@@ -310,13 +323,222 @@ __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void attn_fwd_tile_mfma_ker
 }
 
 // ---------------------------------------------------------------------------------------------
+// bf16 MFMA tile kernel, two-group variant.  8 wavefronts = 2 groups of 4; each group owns 128 of
+// the tile's 256 gathered queries (32 per wavefront) and both walk the same 64-key chunks, so a
+// chunk is staged once for 256 queries.  Time is cut into slots separated by workgroup barriers;
+// in every slot one group runs its matrix phase (S^T of chunk i, O^T += V^T P^T of chunk i-1) while
+// the other runs its soft-max phase, then they swap.  Each SIMD hosts one wavefront of either
+// group, so its matrix pipe and its vector ALU are busy at the same time by construction.
+//   group g: matrix phase of chunk i in slot 2i+g, soft-max of chunk i in slot 2i+g+1.
+// LDS: K and V chunks double-buffered.  K(i) is read in slots 2i, 2i+1 and V(i) in slots 2i+2, 2i+3;
+// at the start of every even slot 2m all threads store K(m+1) and V(m) (fetched two slots earlier
+// into registers) and issue the global loads of K(m+2) and V(m+1).
+template <int D>
+__global__ __launch_bounds__(512, 2) void attn_fwd_tile_pp_kernel(
+    TensorView Q, TensorView K, TensorView V, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr,
+    const int* __restrict__ q_idx, const int* __restrict__ tile_start, float* __restrict__ Opart,
+    float* __restrict__ lse_part, int Hh, int nb, long long cap, float scale_log2, int dbg) {
+    constexpr int TM = 256, KC = 64, STR = D + 8;
+    constexpr int KSTEPS = D / 16, DT = D / 32;
+    constexpr int LOADS = KC * D * 2 / 16 / 512;      // 16-byte pieces per thread per chunk and tensor
+    constexpr float LAZY = 8.f;
+    __shared__ __align__(16) __bf16 sK[2][KC * STR];
+    __shared__ __align__(16) __bf16 sV[2][KC * STR];
+
+    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
+    TileCoord tc;
+    if (!find_tile(tile_start, blk_ptr, blk_off, bh, nb, blockIdx.x, TM, tc)) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int grp = wave >> 2;
+    const int l32 = lane & 31, hf = lane >> 5;
+    const long long seg = (long long)bh * cap;
+
+    const int ent = grp * 128 + (wave & 3) * 32 + l32;
+    bf16x8_t qf[KSTEPS];
+    {
+        const int e = min(ent, tc.count - 1);
+        const int q = q_idx[seg + tc.list0 + tc.t0 + e];
+        const char* src = Q.ptr + ((long long)b * Q.stride_b + (long long)q * Q.stride_s + (long long)h * Q.stride_h) * 2;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8_t*>(src + (ks * 16 + hf * 8) * 2);
+    }
+    f32x16_t oacc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[dt][i] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const char* kbase = K.ptr + ((long long)b * K.stride_b + (long long)h * K.stride_h) * 2;
+    const char* vbase = V.ptr + ((long long)b * V.stride_b + (long long)h * V.stride_h) * 2;
+    const long long kss = K.stride_s * 2, vss = V.stride_s * 2;
+    const int n = (tc.L + KC - 1) / KC;
+
+    u32x4_t kreg[LOADS], vreg[LOADS];
+    auto load_k = [&](int c) {       // chunk index may run past the block: rows are clamped to its last key
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int piece = tid + 512 * i;
+            const int r = piece / (D / 8), pc = piece % (D / 8);
+            const long long row = tc.k0 + min(c * KC + r, tc.L - 1);
+            kreg[i] = *reinterpret_cast<const u32x4_t*>(kbase + row * kss + pc * 16);
+        }
+    };
+    auto load_v = [&](int c) {
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int piece = tid + 512 * i;
+            const int r = piece / (D / 8), pc = piece % (D / 8);
+            const long long row = tc.k0 + min(c * KC + r, tc.L - 1);
+            vreg[i] = *reinterpret_cast<const u32x4_t*>(vbase + row * vss + pc * 16);
+        }
+    };
+    auto store_k = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int piece = tid + 512 * i;
+            const int r = piece / (D / 8), pc = piece % (D / 8);
+            *reinterpret_cast<u32x4_t*>(&sK[buf][r * STR + pc * 8]) = kreg[i];
+        }
+    };
+    auto store_v = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int piece = tid + 512 * i;
+            const int r = piece / (D / 8), pc = piece % (D / 8);
+            *reinterpret_cast<u32x4_t*>(&sV[buf][r * STR + pc * 8]) = vreg[i];
+        }
+    };
+    const int k_lane = rho(l32) * STR + hf * 8;
+    const int v_lane = tr_lane_offset<STR>(lane);
+
+    // prologue: K(0) in place, K(1) and V(0) in flight
+    load_k(0);
+    store_k(0);
+    load_k(1);
+    load_v(0);
+    __syncthreads();
+
+    f32x16_t sacc[2];
+    bf16x8_t pf[2][2];
+    const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const int n_slots = 2 * n + 2;
+    for (int sigma = 0; sigma < n_slots; ++sigma) {
+        if ((sigma & 1) == 0) {
+            const int m = sigma >> 1;
+            store_k((m + 1) & 1);       // K(m+1)
+            store_v(m & 1);             // V(m)
+            if (!(dbg & 1)) {
+                load_k(m + 2);
+                load_v(m + 1);
+            }
+        }
+        const int phase = sigma - grp;
+        const int i = phase >> 1;
+        if (phase >= 0 && (phase & 1) == 0) {
+            // ---- matrix phase: S^T(i) = K(i) . Q^T ;  O^T += V(i-1)^T . P(i-1)^T
+            __builtin_amdgcn_s_setprio(1);
+            if (i < n && !(dbg & 4)) {
+                const __bf16* kt = &sK[i & 1][0] + k_lane;
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int ks = 0; ks < KSTEPS; ++ks) {
+                        const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(kt + mt * 32 * STR + ks * 16);
+                        sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? zero16 : sacc[mt], 0, 0, 0);
+                    }
+            }
+            if (i >= 1 && !(dbg & 8)) {
+                const __bf16* vt = &sV[(i - 1) & 1][0] + v_lane;
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int s = 0; s < 2; ++s)
+#pragma unroll
+                        for (int dt = 0; dt < DT; ++dt) {
+                            const bf16x8_t vf = tr_operand<STR>(vt, mt * 32, s, dt * 32);
+                            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[mt][s], oacc[dt], 0, 0, 0);
+                        }
+            }
+            __builtin_amdgcn_s_setprio(0);
+        } else if (phase >= 0 && i < n && (dbg & 2)) {
+            float tmp[32];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { tmp[v] = sacc[0][v]; tmp[16 + v] = sacc[1][v]; }
+            pf[0][0] = pack8(&tmp[0]); pf[0][1] = pack8(&tmp[8]);
+            pf[1][0] = pack8(&tmp[16]); pf[1][1] = pack8(&tmp[24]);
+            l_run = 1.f; m_run = 0.f;
+        } else if (phase >= 0 && i < n) {
+            // ---- soft-max phase of chunk i (per lane = per query), base-2 units
+            const int valid = tc.L - i * KC;
+            if (valid < KC) {
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        if (mt * 32 + acc_row(v, hf) >= valid) sacc[mt][v] = -INFINITY;
+            }
+            float mx = sacc[0][0];
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[mt][v]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
+            const bool raise = mx > m_run + LAZY;
+            const float m_new = raise ? mx : m_run;
+            const float alpha = raise ? exp2_raw(m_run - m_new) : 1.f;
+            m_run = m_new;
+            float rs = 0.f;
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+                float p[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    p[v] = exp2_raw(fmaf(sacc[mt][v], scale_log2, -m_new));
+                    rs += p[v];
+                }
+                pf[mt][0] = pack8(&p[0]);
+                pf[mt][1] = pack8(&p[8]);
+            }
+            rs += __shfl_xor(rs, 32, 64);
+            l_run = l_run * alpha + rs;
+            if (__any(raise)) {
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+            }
+        }
+        __syncthreads();
+    }
+
+    if (ent < tc.count) {
+        const long long pair = seg + tc.list0 + tc.t0 + ent;
+        const float inv = 1.f / l_run;
+        uint16_t* dst = reinterpret_cast<uint16_t*>(Opart) + pair * D;      // bf16 partials
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                u32x2_t v;
+                v.x = pack_bf16x2(oacc[dt][4 * g + 0] * inv, oacc[dt][4 * g + 1] * inv);
+                v.y = pack_bf16x2(oacc[dt][4 * g + 2] * inv, oacc[dt][4 * g + 3] * inv);
+                *reinterpret_cast<u32x2_t*>(dst + dt * 32 + g * 8 + hf * 4) = v;
+            }
+        if (hf == 0) lse_part[pair] = (m_run + log2f(l_run)) * LN2;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Merge: O[q] = sum_pairs exp(lse_pair - LSE[q]) * Opart[pair], LSE[q] = logsumexp(lse_pair).
-// D/4 lanes per query, each owning 4 channels.
-template <bool BF16, int D>
+// A group of lanes per query, each owning CH consecutive channels (one 16-byte load per partial).
+// Partials are bfloat16 when the MFMA tile kernels wrote them (PBF16), float32 otherwise.
+template <bool BF16, bool PBF16, int D>
 __global__ __launch_bounds__(256) void attn_fwd_merge_kernel(const float* __restrict__ Opart, const float* __restrict__ lse_part,
                                                              const int* __restrict__ row_ptr, const int* __restrict__ pair_pos,
                                                              TensorView O, float* __restrict__ LSE, int Hh, int S, long long cap) {
-    constexpr int LPQ = D / 4;               // lanes per query
+    constexpr int CH = PBF16 ? 8 : 4;
+    constexpr int LPQ = D / CH;              // lanes per query
     constexpr int QPW = 256 / LPQ;           // queries per workgroup
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
     const int q = blockIdx.x * QPW + threadIdx.x / LPQ;
@@ -326,29 +548,50 @@ __global__ __launch_bounds__(256) void attn_fwd_merge_kernel(const float* __rest
     const long long seg = (long long)bh * cap;
     float mx = -INFINITY;
     for (int r = r0; r < r1; ++r) mx = fmaxf(mx, lse_part[seg + pair_pos[seg + r]]);
-    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    float acc[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) acc[c] = 0.f;
     float wsum = 0.f;
     for (int r = r0; r < r1; ++r) {
         const long long pair = seg + pair_pos[seg + r];
         const float w = expf(lse_part[pair] - mx);
         wsum += w;
-        const f32x4_t v = *reinterpret_cast<const f32x4_t*>(Opart + pair * D + part * 4);
-        acc += v * w;
+        if constexpr (PBF16) {
+            const u32x4_t v = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const uint16_t*>(Opart) + pair * D + part * 8);
+            acc[0] += w * bf16lo_to_f32(v.x); acc[1] += w * bf16hi_to_f32(v.x);
+            acc[2] += w * bf16lo_to_f32(v.y); acc[3] += w * bf16hi_to_f32(v.y);
+            acc[4] += w * bf16lo_to_f32(v.z); acc[5] += w * bf16hi_to_f32(v.z);
+            acc[6] += w * bf16lo_to_f32(v.w); acc[7] += w * bf16hi_to_f32(v.w);
+        } else {
+            const f32x4_t v = *reinterpret_cast<const f32x4_t*>(Opart + pair * D + part * 4);
+            acc[0] += w * v.x; acc[1] += w * v.y; acc[2] += w * v.z; acc[3] += w * v.w;
+        }
     }
     float lse = -INFINITY;
     if (r1 > r0) {
         const float inv = 1.f / wsum;
-        acc *= inv;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) acc[c] *= inv;
         lse = mx + logf(wsum);
     }
     char* dst = O.ptr + ((long long)b * O.stride_b + (long long)q * O.stride_s + (long long)h * O.stride_h) * (BF16 ? 2 : 4);
-    if (BF16) {
-        u32x2_t w;
-        w.x = pack_bf16x2(acc.x, acc.y);
-        w.y = pack_bf16x2(acc.z, acc.w);
-        *reinterpret_cast<u32x2_t*>(dst + part * 8) = w;
+    if constexpr (BF16) {
+        uint32_t w[CH / 2];
+#pragma unroll
+        for (int c = 0; c < CH / 2; ++c) w[c] = pack_bf16x2(acc[2 * c], acc[2 * c + 1]);
+        if constexpr (CH == 8) {
+            u32x4_t o = {w[0], w[1], w[2], w[3]};
+            *reinterpret_cast<u32x4_t*>(dst + part * 16) = o;
+        } else {
+            u32x2_t o = {w[0], w[1]};
+            *reinterpret_cast<u32x2_t*>(dst + part * 8) = o;
+        }
     } else {
-        *reinterpret_cast<f32x4_t*>(dst + part * 16) = acc;
+#pragma unroll
+        for (int c = 0; c < CH; c += 4) {
+            f32x4_t o = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
+            *reinterpret_cast<f32x4_t*>(dst + (part * CH + c) * 4) = o;
+        }
     }
     if (part == 0) LSE[(long long)bh * S + q] = lse;
 }
@@ -381,12 +624,9 @@ size_t vmoba_attn_fwd_workspace_bytes(int B, int Hh, int64_t S, int D, int64_t c
 
 // Which MFMA tile width the bf16 path uses (queries per workgroup = 128 * NQ).
 int vmoba_fwd_nq() {
-    static int nq = [] {
-        const char* e = getenv("VMOBA_FWD_NQ");
-        int v = e ? atoi(e) : 1;      // 1: two workgroups per CU (measured faster); 2: wider tile, one per CU
-        return (v == 2) ? 2 : 1;
-    }();
-    return nq;
+    const char* e = getenv("VMOBA_FWD_NQ");
+    int v = e ? atoi(e) : 1;      // 1: two workgroups per CU (measured faster); 2: wider tile, one per CU
+    return (v == 2) ? 2 : 1;
 }
 
 extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
@@ -414,7 +654,9 @@ extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     const float scale_log2 = softmax_scale * LOG2E;
     const bool simple = !bf16 || getenv("VMOBA_FORCE_SIMPLE") != nullptr;
     const int nq = vmoba_fwd_nq();
-    const int TM = simple ? 64 : 128 * nq;
+    const char* ppe = getenv("VMOBA_FWD_PP");
+    const bool two_group = ppe ? atoi(ppe) != 0 : false;
+    const int TM = simple ? 64 : (two_group ? 256 : 128 * nq);
     tile_start_kernel<<<dim3((BH + 63) / 64), dim3(64), 0, st>>>(blk_ptr, ws.tile_start, BH, n_blocks, TM);
     VMOBA_CHECK_LAUNCH();
     // a multiple of 8 so that (workgroup id % 8) is the same for every head; + 8 for the per-XCD rounding
@@ -427,22 +669,32 @@ extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         else if (bf16) attn_fwd_tile_simple_kernel<true, 64><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
         else if (D == 128) attn_fwd_tile_simple_kernel<false, 128><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
         else attn_fwd_tile_simple_kernel<false, 64><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
+    } else if (two_group) {
+        const char* de = getenv("VMOBA_DBG");
+        const int dbg = de ? atoi(de) : 0;
+        if (D == 128) attn_fwd_tile_pp_kernel<128><<<grid, dim3(512), 0, st>>>(TILE_ARGS, dbg);
+        else attn_fwd_tile_pp_kernel<64><<<grid, dim3(512), 0, st>>>(TILE_ARGS, dbg);
     } else {
-        if (D == 128 && nq == 2) attn_fwd_tile_mfma_kernel<128, 2><<<grid, dim3(256), 0, st>>>(TILE_ARGS);
-        else if (D == 128) attn_fwd_tile_mfma_kernel<128, 1><<<grid, dim3(256), 0, st>>>(TILE_ARGS);
-        else if (nq == 2) attn_fwd_tile_mfma_kernel<64, 2><<<grid, dim3(256), 0, st>>>(TILE_ARGS);
-        else attn_fwd_tile_mfma_kernel<64, 1><<<grid, dim3(256), 0, st>>>(TILE_ARGS);
+        const char* de = getenv("VMOBA_DBG");
+        const int dbg = de ? atoi(de) : 0;
+        if (D == 128 && nq == 2) attn_fwd_tile_mfma_kernel<128, 2><<<grid, dim3(256), 0, st>>>(TILE_ARGS, dbg);
+        else if (D == 128) attn_fwd_tile_mfma_kernel<128, 1><<<grid, dim3(256), 0, st>>>(TILE_ARGS, dbg);
+        else if (nq == 2) attn_fwd_tile_mfma_kernel<64, 2><<<grid, dim3(256), 0, st>>>(TILE_ARGS, dbg);
+        else attn_fwd_tile_mfma_kernel<64, 1><<<grid, dim3(256), 0, st>>>(TILE_ARGS, dbg);
     }
 #undef TILE_ARGS
     VMOBA_PROFILE_END(0, st);
     VMOBA_CHECK_LAUNCH();
-    const int qpw = 256 / (D / 4);
+    const bool pbf16 = !simple;               // the MFMA tile kernels write bfloat16 partials
+    const int qpw = 256 / (D / (pbf16 ? 8 : 4));
     dim3 mgrid((unsigned)ceil_div64(S, qpw), (unsigned)BH);
 #define MERGE_ARGS ws.Opart, ws.lse_part, row_ptr, pair_pos, Ov, LSE, Hh, (int)S, (long long)nnz_capacity
-    if (bf16 && D == 128) attn_fwd_merge_kernel<true, 128><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
-    else if (bf16) attn_fwd_merge_kernel<true, 64><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
-    else if (D == 128) attn_fwd_merge_kernel<false, 128><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
-    else attn_fwd_merge_kernel<false, 64><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
+    if (pbf16 && D == 128) attn_fwd_merge_kernel<true, true, 128><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
+    else if (pbf16) attn_fwd_merge_kernel<true, true, 64><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
+    else if (bf16 && D == 128) attn_fwd_merge_kernel<true, false, 128><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
+    else if (bf16) attn_fwd_merge_kernel<true, false, 64><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
+    else if (D == 128) attn_fwd_merge_kernel<false, false, 128><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
+    else attn_fwd_merge_kernel<false, false, 64><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
 #undef MERGE_ARGS
     VMOBA_CHECK_LAUNCH();
     return VMOBA_OK;
