@@ -68,9 +68,19 @@ __global__ __launch_bounds__(64) void key_run_start_kernel(const int* __restrict
 // they should meet in one L2: XCD x gets the blocks j = x, x+8, x+16, ...; entry 8*slot + x of the
 // table is its slot-th (block, run) as j | run << 8, or -1 past its last one.  One thread per XCD.
 __global__ __launch_bounds__(64) void key_run_xcd_kernel(const int* __restrict__ blk_off, int* __restrict__ work,
-                                                         int nb, int KPW, int max_slots) {
+                                                         int nb, int KPW, int max_slots, int linear) {
     const int x = threadIdx.x;
     if (x >= 8 || blockIdx.x != 0) return;
+    if (linear) {               // plain order: run i of the block-major enumeration at entry i
+        if (x != 0) return;
+        int i = 0;
+        for (int j = 0; j < nb; ++j) {
+            const int runs = (blk_off[j + 1] - blk_off[j] + KPW - 1) / KPW;
+            for (int r = 0; r < runs && i < 8 * max_slots; ++r, ++i) work[i] = j | (r << 8);
+        }
+        for (; i < 8 * max_slots; ++i) work[i] = -1;
+        return;
+    }
     int slot = 0;
     for (int j = x; j < nb; j += 8) {
         const int runs = (blk_off[j + 1] - blk_off[j] + KPW - 1) / KPW;
@@ -246,7 +256,8 @@ template <int D>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
-    const int* __restrict__ tile_start, float* __restrict__ dQpart, int Hh, int S, int nb, long long cap, float scale_log2) {
+    const int* __restrict__ tile_start, float* __restrict__ dQpart, int Hh, int S, int nb, long long cap, float scale_log2,
+    int dbg) {
     constexpr int TM = 128, KC = 64;
     constexpr int STR = D + 8;
     constexpr int KSTEPS = D / 16, DT = D / 32;
@@ -318,7 +329,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
         __syncthreads();
         stage();
         __syncthreads();
-        if (c + 1 < n_chunks) prefetch(c + 1);
+        if (c + 1 < n_chunks && !(dbg & 1)) prefetch(c + 1);
+        if (dbg & 16) continue;
         const int valid = tc.L - c * KC;
         const int n_mt = valid > 32 ? 2 : 1;
 #pragma unroll
@@ -490,21 +502,39 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
         const int tr_lane = tr_lane_offset<STR>(lane);
         const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-        // S and dP of half-chunk (buf, mt); optionally interleaved with the vector work of another
-        // half-chunk whose S, dP (sv, dv) are complete: p/ds values 2*ks, 2*ks+1 per k-step.
-        auto sdp_step = [&](int buf, int mt, int ks, f32x16_t& sa, f32x16_t& dp) {
-            const bf16x8_t qa = *reinterpret_cast<const bf16x8_t*>(&sQ[buf][row_lane + mt * 32 * STR + ks * 16]);
-            const bf16x8_t da = *reinterpret_cast<const bf16x8_t*>(&sdO[buf][row_lane + mt * 32 * STR + ks * 16]);
-            sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[ks], ks == 0 ? zero16 : sa, 0, 0, 0);
-            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[ks], ks == 0 ? zero16 : dp, 0, 0, 0);
+        // Operand fetches are written one step ahead of the matrix instructions that use them and
+        // every step ends in a scheduling fence, so an LDS read always has a full step (two matrix
+        // instructions plus vector work) to complete before its data is needed.
+        struct RowOps { bf16x8_t qa, da; };       // A operands of S and dP for one k-step
+        struct TrOps { bf16x8_t dot, qt; };       // A operands of dV and dK for one (s, dt) step
+        auto read_rows = [&](int buf, int mt, int ks) {
+            RowOps o;
+            o.qa = *reinterpret_cast<const bf16x8_t*>(&sQ[buf][row_lane + mt * 32 * STR + ks * 16]);
+            o.da = *reinterpret_cast<const bf16x8_t*>(&sdO[buf][row_lane + mt * 32 * STR + ks * 16]);
+            return o;
+        };
+        auto read_tr = [&](int buf, int mt, int step) {      // step = s * DT + dt
+            TrOps o;
+            o.dot = tr_operand<STR>(&sdO[buf][tr_lane], mt * 32, step / DT, (step % DT) * 32);
+            o.qt = tr_operand<STR>(&sQ[buf][tr_lane], mt * 32, step / DT, (step % DT) * 32);
+            return o;
+        };
+        auto mfma_rows = [&](const RowOps& o, int ks, f32x16_t& sa, f32x16_t& dp) {
+            sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.qa, kf[ks], ks == 0 ? zero16 : sa, 0, 0, 0);
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.da, vf[ks], ks == 0 ? zero16 : dp, 0, 0, 0);
+        };
+        auto mfma_tr = [&](const TrOps& o, int step, const bf16x8_t* pfr, const bf16x8_t* dsf) {
+            const int sidx = step / DT, dt = step % DT;
+            dvacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.dot, pfr[sidx], dvacc[dt], 0, 0, 0);
+            dkacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.qt, dsf[sidx], dkacc[dt], 0, 0, 0);
         };
         auto load_ld = [&](int buf, int mt, float* lv, float* dl) {
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
-                const f32x4_t a = *reinterpret_cast<const f32x4_t*>(&sL[buf][mt * 32 + hf * 16 + g4 * 4]);
-                const f32x4_t c = *reinterpret_cast<const f32x4_t*>(&sDl[buf][mt * 32 + hf * 16 + g4 * 4]);
+                const f32x4_t a4 = *reinterpret_cast<const f32x4_t*>(&sL[buf][mt * 32 + hf * 16 + g4 * 4]);
+                const f32x4_t c4 = *reinterpret_cast<const f32x4_t*>(&sDl[buf][mt * 32 + hf * 16 + g4 * 4]);
 #pragma unroll
-                for (int u = 0; u < 4; ++u) { lv[g4 * 4 + u] = a[u]; dl[g4 * 4 + u] = c[u]; }
+                for (int u = 0; u < 4; ++u) { lv[g4 * 4 + u] = a4[u]; dl[g4 * 4 + u] = c4[u]; }
             }
         };
         auto valu_pair = [&](const float* lv, const float* dl, int i2, const f32x16_t& sv, const f32x16_t& dv, float* p, float* ds) {
@@ -516,12 +546,9 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
                 ds[i] = p[i] * (dv[i] - dl[i]);
             }
         };
-        auto dvdk_step = [&](int buf, int mt, int s, int dt, const bf16x8_t& pfr, const bf16x8_t& dsf) {
-            const bf16x8_t dot = tr_operand<STR>(&sdO[buf][tr_lane], mt * 32, s, dt * 32);
-            const bf16x8_t qt = tr_operand<STR>(&sQ[buf][tr_lane], mt * 32, s, dt * 32);
-            dvacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot, pfr, dvacc[dt], 0, 0, 0);
-            dkacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf, dkacc[dt], 0, 0, 0);
-        };
+        constexpr int TSTEPS = 2 * DT;            // (s, dt) steps of the dV / dK products
+        constexpr int VP_A = 8 / KSTEPS;          // exp/dS value pairs per step of part A
+        constexpr int VP_B = 8 / TSTEPS;          // ... per step of part B
 
         // prologue: chunk 0 staged, chunk 1 in flight, indices of chunk 2 in flight, S/dP of (0, 0)
         prefetch_idx(0);
@@ -534,56 +561,48 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
         f32x16_t s0 = zero16, p0 = zero16, s1 = zero16, p1 = zero16;   // S, dP of half-chunks 0 and 1 of the current chunk
         if (wave_live) {
 #pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) sdp_step(0, 0, ks, s0, p0);
+            for (int ks = 0; ks < KSTEPS; ++ks) mfma_rows(read_rows(0, 0, ks), ks, s0, p0);
         }
         int buf = 0;
         for (int c = 0; c < n_chunks; ++c) {
             const int nbuf = (buf + 1 == NBUF) ? 0 : buf + 1;
             float pa[16], dsa[16], pb[16], dsb[16];
             bf16x8_t pf1[2], df1[2];
+            TrOps tc0;                            // first transposed operands of part C, fetched before the barrier
             if (wave_live && !(dbg & 16)) {
                 float lv0[16], dl0[16], lv1[16], dl1[16];
                 load_ld(buf, 0, lv0, dl0);
                 load_ld(buf, 1, lv1, dl1);
                 // A: S, dP of (c, 1)  ||  exp / dS of (c, 0)
+                RowOps ra = read_rows(buf, 1, 0);
+                TrOps tb;
 #pragma unroll
                 for (int ks = 0; ks < KSTEPS; ++ks) {
-                    sdp_step(buf, 1, ks, s1, p1);
+                    RowOps rn;
+                    if (ks + 1 < KSTEPS) rn = read_rows(buf, 1, ks + 1);
+                    else tb = read_tr(buf, 0, 0);
+                    mfma_rows(ra, ks, s1, p1);
 #pragma unroll
-                    for (int u = 0; u < 8 / KSTEPS; ++u) valu_pair(lv0, dl0, ks * (8 / KSTEPS) + u, s0, p0, pa, dsa);
+                    for (int u = 0; u < VP_A; ++u) valu_pair(lv0, dl0, ks * VP_A + u, s0, p0, pa, dsa);
+                    if (ks + 1 < KSTEPS) ra = rn;
+                    __builtin_amdgcn_sched_barrier(0);
                 }
                 const bf16x8_t pf0[2] = {pack8(&pa[0]), pack8(&pa[8])};
                 const bf16x8_t df0[2] = {pack8(&dsa[0]), pack8(&dsa[8])};
                 // B: dV, dK of (c, 0)  ||  exp / dS of (c, 1)
 #pragma unroll
-                for (int s = 0; s < 2; ++s)
+                for (int st = 0; st < TSTEPS; ++st) {
+                    TrOps tn;
+                    if (st + 1 < TSTEPS) tn = read_tr(buf, 0, st + 1);
+                    else tc0 = read_tr(buf, 1, 0);
+                    mfma_tr(tb, st, pf0, df0);
 #pragma unroll
-                    for (int dt = 0; dt < DT; ++dt) {
-                        dvdk_step(buf, 0, s, dt, pf0[s], df0[s]);
-#pragma unroll
-                        for (int u = 0; u < 8 / (2 * DT); ++u)
-                            valu_pair(lv1, dl1, (s * DT + dt) * (8 / (2 * DT)) + u, s1, p1, pb, dsb);
-                    }
+                    for (int u = 0; u < VP_B; ++u) valu_pair(lv1, dl1, st * VP_B + u, s1, p1, pb, dsb);
+                    if (st + 1 < TSTEPS) tb = tn;
+                    __builtin_amdgcn_sched_barrier(0);
+                }
                 pf1[0] = pack8(&pb[0]); pf1[1] = pack8(&pb[8]);
                 df1[0] = pack8(&dsb[0]); df1[1] = pack8(&dsb[8]);
-#if VMOBA_DKV_SCHED
-                // requested instruction order for this block: LDS reads run ahead of the matrix
-                // instructions that consume them, vector work fills the gaps between matrix issues
-#define VMOBA_SG_STEP(NDS)                                      \
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);          \
-    __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);          \
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);          \
-    __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);          \
-    __builtin_amdgcn_sched_group_barrier(0x100, NDS, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 8 + 6, 0);      // LSE/delta + first 3 steps of A
-                if constexpr (D == 128) {
-                    VMOBA_SG_STEP(2) VMOBA_SG_STEP(2) VMOBA_SG_STEP(2) VMOBA_SG_STEP(2)
-                    VMOBA_SG_STEP(2) VMOBA_SG_STEP(4) VMOBA_SG_STEP(4) VMOBA_SG_STEP(4)
-                    VMOBA_SG_STEP(4) VMOBA_SG_STEP(4) VMOBA_SG_STEP(4) VMOBA_SG_STEP(4)
-                    VMOBA_SG_STEP(4) VMOBA_SG_STEP(0) VMOBA_SG_STEP(0) VMOBA_SG_STEP(0)
-                }
-#undef VMOBA_SG_STEP
-#endif
             }
             // next chunk into the ring (its rows arrived during this iteration), loads of the one after
             stage(nbuf);
@@ -594,13 +613,18 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
             __syncthreads();
             if (wave_live && !(dbg & 16)) {
                 // C: dV, dK of (c, 1)  and  S, dP of (c + 1, 0)
+                RowOps rc = read_rows(nbuf, 0, 0);
+                TrOps tcur = tc0;
 #pragma unroll
-                for (int s = 0; s < 2; ++s)
-#pragma unroll
-                    for (int dt = 0; dt < DT; ++dt) {
-                        dvdk_step(buf, 1, s, dt, pf1[s], df1[s]);
-                        sdp_step(nbuf, 0, s * DT + dt, s0, p0);
-                    }
+                for (int st = 0; st < TSTEPS; ++st) {
+                    TrOps tn;
+                    RowOps rn;
+                    if (st + 1 < TSTEPS) { tn = read_tr(buf, 1, st + 1); rn = read_rows(nbuf, 0, st + 1); }
+                    mfma_tr(tcur, st, pf1, df1);
+                    mfma_rows(rc, st, s0, p0);
+                    if (st + 1 < TSTEPS) { tcur = tn; rc = rn; }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
             buf = nbuf;
         }
@@ -764,8 +788,10 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
             else if (D == 128) attn_bwd_dq_simple_kernel<false, 128><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
             else attn_bwd_dq_simple_kernel<false, 64><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
         } else {
-            if (D == 128) attn_bwd_dq_mfma_kernel<128><<<grid, dim3(256), 0, st>>>(DQ_ARGS);
-            else attn_bwd_dq_mfma_kernel<64><<<grid, dim3(256), 0, st>>>(DQ_ARGS);
+            const char* de = getenv("VMOBA_BWD_DBG");
+            const int dbg = de ? atoi(de) : 0;
+            if (D == 128) attn_bwd_dq_mfma_kernel<128><<<grid, dim3(256), 0, st>>>(DQ_ARGS, dbg);
+            else attn_bwd_dq_mfma_kernel<64><<<grid, dim3(256), 0, st>>>(DQ_ARGS, dbg);
         }
 #undef DQ_ARGS
         VMOBA_PROFILE_END(1, st);
@@ -789,7 +815,10 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         const int KPW = simple ? 64 : 32 * NW;
         const int max_slots = dkv_max_slots(S);
         if (simple) key_run_start_kernel<<<dim3(1), dim3(64), 0, st>>>(blk_off, ws.kb_start, n_blocks, KPW);
-        else key_run_xcd_kernel<<<dim3(1), dim3(64), 0, st>>>(blk_off, ws.xcd_work, n_blocks, KPW, max_slots);
+        else {
+            const char* xe = getenv("VMOBA_DKV_XCD");
+            key_run_xcd_kernel<<<dim3(1), dim3(64), 0, st>>>(blk_off, ws.xcd_work, n_blocks, KPW, max_slots, xe ? atoi(xe) == 0 : 1);     // per-XCD block assignment measured slower (XCD load imbalance): off by default
+        }
         VMOBA_CHECK_LAUNCH();
         // a multiple of 8 so that (workgroup id % 8) is the same for every head; + 8 for the per-XCD rounding
         dim3 grid((unsigned)((S / KPW + n_blocks + 7) / 8 * 8 + 8), (unsigned)BH);
