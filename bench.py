@@ -27,6 +27,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak (published)
+HBM_PEAK_GBS = 8000.0              # MI355X HBM3E peak (published)
+# HBM bytes per launch of the MFMA kernels at the 480p workload (mean over the 1d/2d/3d partitions, tau = 0.25),
+# from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/layer_480p_tau025_hbm_traffic_pmc.md
+# (FETCH_SIZE scaled by 2.000, WRITE_SIZE by 1.000: the factors a plain copy kernel of known size gives).
+MEASURED_TRAFFIC_BYTES_480P = {"attn_fwd_tile": 3.338e9, "attn_bwd_dq_tile": 4.232e9, "attn_bwd_dkv": 5.909e9}
 METRIC = "VMoBA attn fwd+bwd ms/layer + effective TFLOP/s (%MFMA peak), 480p shape"
 
 
@@ -60,7 +65,7 @@ def selected_key_sum(plan):
     return int((cnt * L[None, :]).sum()), int(cnt.sum())
 
 
-def cpu_baseline(Q, K, V, dO, cfg, part, tau, rows=4096):
+def cpu_baseline(Q, K, V, dO, cfg, part, tau, rows=16384):
     """The CPU oracle on head 0: selection over the whole head, masked attention forward and
     backward on every (S/rows)-th query row; time scaled to the whole head."""
     from oracle import vmoba_oracle as vo
@@ -176,8 +181,11 @@ def main():
     dom_flops = sum(kflops[dom] * D * keysum[k] for k in step_kinds)
     dom_ms = sum(ktime[dom])
     achieved = dom_flops / (dom_ms * 1e-3) / 1e12
+    traffic = None
+    if args.config == "480p" and abs(args.tau - 0.25) < 1e-9 and len(kinds) == 3:
+        traffic = MEASURED_TRAFFIC_BYTES_480P.get(SLOTS[dom])
     roofline = {"bound": "mfma", "kernel": SLOTS[dom], "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": None,
+                "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": traffic,
                 "avg_launch_ms": dom_ms / args.steps,
                 "all_kernels": {SLOTS[s]: {"avg_launch_ms": sum(ktime[s]) / args.steps,
                                            "tflops": sum(kflops[s] * D * keysum[k] for k in step_kinds) / (sum(ktime[s]) * 1e-3) / 1e12}
@@ -197,6 +205,18 @@ def main():
         return {n: evs[i].elapsed_time(evs[i + 1]) for i, n in enumerate(names)}
 
     breakdown = {kind: timed_calls(p) for kind, p in plans.items()}
+    # memory-bound steps: algorithmic bytes / time of the call
+    es = 2 if dtype == torch.bfloat16 else 4
+    row_bytes = S * Hh * D * es
+    mem_steps = {}
+    for kind, bd in breakdown.items():
+        nbk = plans[kind].nb
+        sel_bytes = 2 * row_bytes + Hh * S * nbk * 4 + Hh * S * ((nbk + 31) // 32) * 4 + 3 * 4 * pairs[kind]
+        mem_steps[kind] = {
+            "partition_qkv_GBps": 3 * 2 * row_bytes / (bd["partition"] * 1e-3) / 1e9,
+            "unpartition_grads_GBps": 3 * 2 * row_bytes / (bd["unpartition_grads"] * 1e-3) / 1e9,
+            "select_GBps": sel_bytes / (bd["select"] * 1e-3) / 1e9,
+            "select_algorithmic_bytes": sel_bytes}
     per_kind = {kind: {"ms_per_layer": sum(b.values()),
                        "selected_pair_fraction": pairs[kind] / (Hh * S * plans[kind].nb),
                        "token_sparsity": keysum[kind] / (Hh * S * S),
@@ -211,7 +231,10 @@ def main():
                                   f"layer cycle {'/'.join(kinds)}, fwd+bwd per layer", "tokens": S,
                       "input_generation_s": round(t_gen, 1)},
            "frac_of_bf16_mfma_peak": value / BF16_MFMA_PEAK_TFLOPS,
-           "roofline": roofline, "per_kind": per_kind, "breakdown_ms": breakdown}
+           "roofline": roofline, "per_kind": per_kind, "breakdown_ms": breakdown,
+           "memory_bound_steps": dict(mem_steps, hbm_peak_GBps=HBM_PEAK_GBS,
+                                      note="algorithmic bytes (permute: read+write of every row; select: K and Q read once, "
+                                           "P, mask and the three lists written once) over the call's time")}
 
     # ---- dense comparators on the same GPU
     if not args.no_dense:

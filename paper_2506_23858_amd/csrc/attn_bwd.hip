@@ -14,10 +14,6 @@
 #include <algorithm>
 #include <cmath>
 
-#ifndef VMOBA_DKV_SCHED
-#define VMOBA_DKV_SCHED 0
-#endif
-
 namespace {
 
 constexpr float LOG2E = 1.4426950408889634f;
@@ -256,8 +252,7 @@ template <int D>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
-    const int* __restrict__ tile_start, float* __restrict__ dQpart, int Hh, int S, int nb, long long cap, float scale_log2,
-    int dbg) {
+    const int* __restrict__ tile_start, float* __restrict__ dQpart, int Hh, int S, int nb, long long cap, float scale_log2) {
     constexpr int TM = 128, KC = 64;
     constexpr int STR = D + 8;
     constexpr int KSTEPS = D / 16, DT = D / 32;
@@ -329,8 +324,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
         __syncthreads();
         stage();
         __syncthreads();
-        if (c + 1 < n_chunks && !(dbg & 1)) prefetch(c + 1);
-        if (dbg & 16) continue;
+        if (c + 1 < n_chunks) prefetch(c + 1);
         const int valid = tc.L - c * KC;
         const int n_mt = valid > 32 ? 2 : 1;
 #pragma unroll
@@ -398,7 +392,7 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
     const int* __restrict__ kb_start, TensorView dK, TensorView dV, int Hh, int S, int nb, long long cap,
-    float scale_log2, float scale, int dbg) {
+    float scale_log2, float scale) {
     constexpr int NT = 64 * NW;
     constexpr int QC = 64;
     constexpr int STR = D + 8;
@@ -569,7 +563,7 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
             float pa[16], dsa[16], pb[16], dsb[16];
             bf16x8_t pf1[2], df1[2];
             TrOps tc0;                            // first transposed operands of part C, fetched before the barrier
-            if (wave_live && !(dbg & 16)) {
+            if (wave_live) {
                 float lv0[16], dl0[16], lv1[16], dl1[16];
                 load_ld(buf, 0, lv0, dl0);
                 load_ld(buf, 1, lv1, dl1);
@@ -606,12 +600,10 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
             }
             // next chunk into the ring (its rows arrived during this iteration), loads of the one after
             stage(nbuf);
-            if (!(dbg & 1)) {
-                prefetch_rows();
-                prefetch_idx(c + 3);
-            }
+            prefetch_rows();
+            prefetch_idx(c + 3);
             __syncthreads();
-            if (wave_live && !(dbg & 16)) {
+            if (wave_live) {
                 // C: dV, dK of (c, 1)  and  S, dP of (c + 1, 0)
                 RowOps rc = read_rows(nbuf, 0, 0);
                 TrOps tcur = tc0;
@@ -788,10 +780,8 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
             else if (D == 128) attn_bwd_dq_simple_kernel<false, 128><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
             else attn_bwd_dq_simple_kernel<false, 64><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
         } else {
-            const char* de = getenv("VMOBA_BWD_DBG");
-            const int dbg = de ? atoi(de) : 0;
-            if (D == 128) attn_bwd_dq_mfma_kernel<128><<<grid, dim3(256), 0, st>>>(DQ_ARGS, dbg);
-            else attn_bwd_dq_mfma_kernel<64><<<grid, dim3(256), 0, st>>>(DQ_ARGS, dbg);
+            if (D == 128) attn_bwd_dq_mfma_kernel<128><<<grid, dim3(256), 0, st>>>(DQ_ARGS);
+            else attn_bwd_dq_mfma_kernel<64><<<grid, dim3(256), 0, st>>>(DQ_ARGS);
         }
 #undef DQ_ARGS
         VMOBA_PROFILE_END(1, st);
@@ -823,8 +813,6 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         // a multiple of 8 so that (workgroup id % 8) is the same for every head; + 8 for the per-XCD rounding
         dim3 grid((unsigned)((S / KPW + n_blocks + 7) / 8 * 8 + 8), (unsigned)BH);
         VMOBA_PROFILE_BEGIN(2, st);
-        const char* de = getenv("VMOBA_BWD_DBG");
-        const int dbg = de ? atoi(de) : 0;
 #define DKV_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.kb_start, dKv, dVv, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
         if (simple) {
             if (bf16 && D == 128) attn_bwd_dkv_simple_kernel<true, 128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
@@ -834,8 +822,8 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         } else {
             dim3 xgrid((unsigned)(8 * max_slots), (unsigned)BH);
 #define DKV_XARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.xcd_work, dKv, dVv, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
-            if (D == 128) attn_bwd_dkv_mfma_kernel<128, NW><<<xgrid, dim3(64 * NW), 0, st>>>(DKV_XARGS, dbg);
-            else attn_bwd_dkv_mfma_kernel<64, NW><<<xgrid, dim3(64 * NW), 0, st>>>(DKV_XARGS, dbg);
+            if (D == 128) attn_bwd_dkv_mfma_kernel<128, NW><<<xgrid, dim3(64 * NW), 0, st>>>(DKV_XARGS);
+            else attn_bwd_dkv_mfma_kernel<64, NW><<<xgrid, dim3(64 * NW), 0, st>>>(DKV_XARGS);
 #undef DKV_XARGS
         }
 #undef DKV_ARGS

@@ -116,7 +116,7 @@ template <int D, int NQ>
 __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void attn_fwd_tile_mfma_kernel(
     TensorView Q, TensorView K, TensorView V, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr,
     const int* __restrict__ q_idx, const int* __restrict__ tile_start, float* __restrict__ Opart,
-    float* __restrict__ lse_part, int Hh, int nb, long long cap, float scale_log2, int dbg) {
+    float* __restrict__ lse_part, int Hh, int nb, long long cap, float scale_log2) {
     constexpr int TM = 128 * NQ;
     constexpr int KC = 64;                  // keys per chunk
     constexpr int STR = D + 8;              // LDS row stride (bf16 elements)
@@ -195,11 +195,10 @@ __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void attn_fwd_tile_mfma_ker
         __syncthreads();                      // everyone is done reading the previous chunk
         stage();
         __syncthreads();
-        if (c + 1 < n_chunks && !(dbg & 1)) prefetch(c + 1);
-        if (dbg & 16) continue;
+        if (c + 1 < n_chunks) prefetch(c + 1);
 
         const int valid = tc.L - c * KC;      // keys of this chunk inside the block (may exceed KC)
-        const int n_mt = (dbg & 4) ? 0 : (valid > 32 ? 2 : 1);  // 32-key groups with at least one valid key
+        const int n_mt = valid > 32 ? 2 : 1;  // 32-key groups with at least one valid key
 
         // ---- S^T = K . Q^T
         f32x16_t sacc[NQ][2];
@@ -234,17 +233,6 @@ __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void attn_fwd_tile_mfma_ker
         bf16x8_t pf[NQ][2][2];
         bool need_rescale = false;
         float alpha[NQ];
-        if (dbg & 2) {
-#pragma unroll
-            for (int nq = 0; nq < NQ; ++nq) {
-                float tmp[32];
-#pragma unroll
-                for (int v = 0; v < 16; ++v) { tmp[v] = sacc[nq][0][v]; tmp[16 + v] = sacc[nq][1][v]; }
-                pf[nq][0][0] = pack8(&tmp[0]); pf[nq][0][1] = pack8(&tmp[8]);
-                pf[nq][1][0] = pack8(&tmp[16]); pf[nq][1][1] = pack8(&tmp[24]);
-                l_run[nq] = 1.f; m_run[nq] = 0.f; alpha[nq] = 1.f;
-            }
-        } else
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq) {
             float mx = sacc[nq][0][0];
@@ -285,7 +273,7 @@ __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void attn_fwd_tile_mfma_ker
         __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
-            if (mt < n_mt && !(dbg & 8)) {
+            if (mt < n_mt) {
 #pragma unroll
                 for (int s = 0; s < 2; ++s) {
 #pragma unroll
@@ -337,7 +325,7 @@ template <int D>
 __global__ __launch_bounds__(512, 2) void attn_fwd_tile_pp_kernel(
     TensorView Q, TensorView K, TensorView V, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr,
     const int* __restrict__ q_idx, const int* __restrict__ tile_start, float* __restrict__ Opart,
-    float* __restrict__ lse_part, int Hh, int nb, long long cap, float scale_log2, int dbg) {
+    float* __restrict__ lse_part, int Hh, int nb, long long cap, float scale_log2) {
     constexpr int TM = 256, KC = 64, STR = D + 8;
     constexpr int KSTEPS = D / 16, DT = D / 32;
     constexpr int LOADS = KC * D * 2 / 16 / 512;      // 16-byte pieces per thread per chunk and tensor
@@ -428,17 +416,15 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_tile_pp_kernel(
             const int m = sigma >> 1;
             store_k((m + 1) & 1);       // K(m+1)
             store_v(m & 1);             // V(m)
-            if (!(dbg & 1)) {
-                load_k(m + 2);
-                load_v(m + 1);
-            }
+            load_k(m + 2);
+            load_v(m + 1);
         }
         const int phase = sigma - grp;
         const int i = phase >> 1;
         if (phase >= 0 && (phase & 1) == 0) {
             // ---- matrix phase: S^T(i) = K(i) . Q^T ;  O^T += V(i-1)^T . P(i-1)^T
             __builtin_amdgcn_s_setprio(1);
-            if (i < n && !(dbg & 4)) {
+            if (i < n) {
                 const __bf16* kt = &sK[i & 1][0] + k_lane;
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt)
@@ -448,7 +434,7 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_tile_pp_kernel(
                         sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? zero16 : sacc[mt], 0, 0, 0);
                     }
             }
-            if (i >= 1 && !(dbg & 8)) {
+            if (i >= 1) {
                 const __bf16* vt = &sV[(i - 1) & 1][0] + v_lane;
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt)
@@ -461,13 +447,6 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_tile_pp_kernel(
                         }
             }
             __builtin_amdgcn_s_setprio(0);
-        } else if (phase >= 0 && i < n && (dbg & 2)) {
-            float tmp[32];
-#pragma unroll
-            for (int v = 0; v < 16; ++v) { tmp[v] = sacc[0][v]; tmp[16 + v] = sacc[1][v]; }
-            pf[0][0] = pack8(&tmp[0]); pf[0][1] = pack8(&tmp[8]);
-            pf[1][0] = pack8(&tmp[16]); pf[1][1] = pack8(&tmp[24]);
-            l_run = 1.f; m_run = 0.f;
         } else if (phase >= 0 && i < n) {
             // ---- soft-max phase of chunk i (per lane = per query), base-2 units
             const int valid = tc.L - i * KC;
@@ -670,17 +649,13 @@ extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         else if (D == 128) attn_fwd_tile_simple_kernel<false, 128><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
         else attn_fwd_tile_simple_kernel<false, 64><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
     } else if (two_group) {
-        const char* de = getenv("VMOBA_DBG");
-        const int dbg = de ? atoi(de) : 0;
-        if (D == 128) attn_fwd_tile_pp_kernel<128><<<grid, dim3(512), 0, st>>>(TILE_ARGS, dbg);
-        else attn_fwd_tile_pp_kernel<64><<<grid, dim3(512), 0, st>>>(TILE_ARGS, dbg);
+        if (D == 128) attn_fwd_tile_pp_kernel<128><<<grid, dim3(512), 0, st>>>(TILE_ARGS);
+        else attn_fwd_tile_pp_kernel<64><<<grid, dim3(512), 0, st>>>(TILE_ARGS);
     } else {
-        const char* de = getenv("VMOBA_DBG");
-        const int dbg = de ? atoi(de) : 0;
-        if (D == 128 && nq == 2) attn_fwd_tile_mfma_kernel<128, 2><<<grid, dim3(256), 0, st>>>(TILE_ARGS, dbg);
-        else if (D == 128) attn_fwd_tile_mfma_kernel<128, 1><<<grid, dim3(256), 0, st>>>(TILE_ARGS, dbg);
-        else if (nq == 2) attn_fwd_tile_mfma_kernel<64, 2><<<grid, dim3(256), 0, st>>>(TILE_ARGS, dbg);
-        else attn_fwd_tile_mfma_kernel<64, 1><<<grid, dim3(256), 0, st>>>(TILE_ARGS, dbg);
+        if (D == 128 && nq == 2) attn_fwd_tile_mfma_kernel<128, 2><<<grid, dim3(256), 0, st>>>(TILE_ARGS);
+        else if (D == 128) attn_fwd_tile_mfma_kernel<128, 1><<<grid, dim3(256), 0, st>>>(TILE_ARGS);
+        else if (nq == 2) attn_fwd_tile_mfma_kernel<64, 2><<<grid, dim3(256), 0, st>>>(TILE_ARGS);
+        else attn_fwd_tile_mfma_kernel<64, 1><<<grid, dim3(256), 0, st>>>(TILE_ARGS);
     }
 #undef TILE_ARGS
     VMOBA_PROFILE_END(0, st);
