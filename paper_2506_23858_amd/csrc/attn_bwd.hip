@@ -59,32 +59,6 @@ __global__ __launch_bounds__(64) void key_run_start_kernel(const int* __restrict
     kb_start[nb] = run;
 }
 
-// XCD-aware work table of the dK/dV kernel.  Workgroups go to the 8 XCDs round-robin (workgroup
-// id % 8) and every XCD has its own L2.  All key runs of one block gather the same query rows, so
-// they should meet in one L2: XCD x gets the blocks j = x, x+8, x+16, ...; entry 8*slot + x of the
-// table is its slot-th (block, run) as j | run << 8, or -1 past its last one.  One thread per XCD.
-__global__ __launch_bounds__(64) void key_run_xcd_kernel(const int* __restrict__ blk_off, int* __restrict__ work,
-                                                         int nb, int KPW, int max_slots, int linear) {
-    const int x = threadIdx.x;
-    if (x >= 8 || blockIdx.x != 0) return;
-    if (linear) {               // plain order: run i of the block-major enumeration at entry i
-        if (x != 0) return;
-        int i = 0;
-        for (int j = 0; j < nb; ++j) {
-            const int runs = (blk_off[j + 1] - blk_off[j] + KPW - 1) / KPW;
-            for (int r = 0; r < runs && i < 8 * max_slots; ++r, ++i) work[i] = j | (r << 8);
-        }
-        for (; i < 8 * max_slots; ++i) work[i] = -1;
-        return;
-    }
-    int slot = 0;
-    for (int j = x; j < nb; j += 8) {
-        const int runs = (blk_off[j + 1] - blk_off[j] + KPW - 1) / KPW;
-        for (int r = 0; r < runs && slot < max_slots; ++r, ++slot) work[slot * 8 + x] = j | (r << 8);
-    }
-    for (; slot < max_slots; ++slot) work[slot * 8 + x] = -1;
-}
-
 __device__ __forceinline__ float load_elem(const char* p, int d, bool bf16) {
     return bf16 ? bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(p)[d]) : reinterpret_cast<const float*>(p)[d];
 }
@@ -406,9 +380,12 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
     __shared__ __align__(16) float sDl[NBUF][QC];
 
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
-    const int w = kb_start[blockIdx.x];          // XCD-aware work table: block | run << 8, or -1
-    if (w < 0) return;
-    const int j = w & 255, run = w >> 8;
+    // key runs are numbered block-major; kb_start[j] = runs in blocks 0..j-1.  (Handing each XCD whole
+    // blocks, so that the runs of a block share an L2, was measured slower: the XCDs end up unevenly loaded.)
+    if ((int)blockIdx.x >= kb_start[nb]) return;
+    int lo = 0, hi = nb;
+    while (hi - lo > 1) { int mid = (lo + hi) >> 1; if (kb_start[mid] <= (int)blockIdx.x) lo = mid; else hi = mid; }
+    const int j = lo, run = (int)blockIdx.x - kb_start[lo];
     const int k0 = blk_off[j], L = blk_off[j + 1] - k0;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hf = lane >> 5;
@@ -698,12 +675,8 @@ struct BwdWs {
     float* delta;      // [BH][S]
     int* tile_start;   // [BH][257]
     int* kb_start;     // [257]
-    int* xcd_work;     // [8 * dkv_max_slots]
     size_t total;
 };
-
-// Upper bound, known on the host, of the key runs (of 128 keys) one XCD can be handed.
-int dkv_max_slots(int64_t S) { return (int)(S / 128 + VMOBA_MAX_BLOCKS / 8 + 2); }
 
 BwdWs carve_bwd(void* base, int BH, int64_t S, int D, int64_t cap) {
     BwdWs w;
@@ -713,7 +686,6 @@ BwdWs carve_bwd(void* base, int BH, int64_t S, int D, int64_t cap) {
     w.delta = (float*)(p + off);     off += align_up((size_t)BH * S * 4, 256);
     w.tile_start = (int*)(p + off);  off += align_up((size_t)BH * (VMOBA_MAX_BLOCKS + 1) * 4, 256);
     w.kb_start = (int*)(p + off);    off += align_up((size_t)(VMOBA_MAX_BLOCKS + 1) * 4, 256);
-    w.xcd_work = (int*)(p + off);    off += align_up((size_t)8 * dkv_max_slots(S) * 4, 256);
     w.total = off;
     return w;
 }
@@ -803,12 +775,7 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     {
         constexpr int NW = 4;
         const int KPW = simple ? 64 : 32 * NW;
-        const int max_slots = dkv_max_slots(S);
-        if (simple) key_run_start_kernel<<<dim3(1), dim3(64), 0, st>>>(blk_off, ws.kb_start, n_blocks, KPW);
-        else {
-            const char* xe = getenv("VMOBA_DKV_XCD");
-            key_run_xcd_kernel<<<dim3(1), dim3(64), 0, st>>>(blk_off, ws.xcd_work, n_blocks, KPW, max_slots, xe ? atoi(xe) == 0 : 1);     // per-XCD block assignment measured slower (XCD load imbalance): off by default
-        }
+        key_run_start_kernel<<<dim3(1), dim3(64), 0, st>>>(blk_off, ws.kb_start, n_blocks, KPW);
         VMOBA_CHECK_LAUNCH();
         // a multiple of 8 so that (workgroup id % 8) is the same for every head; + 8 for the per-XCD rounding
         dim3 grid((unsigned)((S / KPW + n_blocks + 7) / 8 * 8 + 8), (unsigned)BH);
@@ -820,11 +787,8 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
             else if (D == 128) attn_bwd_dkv_simple_kernel<false, 128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
             else attn_bwd_dkv_simple_kernel<false, 64><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
         } else {
-            dim3 xgrid((unsigned)(8 * max_slots), (unsigned)BH);
-#define DKV_XARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.xcd_work, dKv, dVv, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
-            if (D == 128) attn_bwd_dkv_mfma_kernel<128, NW><<<xgrid, dim3(64 * NW), 0, st>>>(DKV_XARGS);
-            else attn_bwd_dkv_mfma_kernel<64, NW><<<xgrid, dim3(64 * NW), 0, st>>>(DKV_XARGS);
-#undef DKV_XARGS
+            if (D == 128) attn_bwd_dkv_mfma_kernel<128, NW><<<grid, dim3(64 * NW), 0, st>>>(DKV_ARGS);
+            else attn_bwd_dkv_mfma_kernel<64, NW><<<grid, dim3(64 * NW), 0, st>>>(DKV_ARGS);
         }
 #undef DKV_ARGS
         VMOBA_PROFILE_END(2, st);

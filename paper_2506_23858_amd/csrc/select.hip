@@ -209,6 +209,138 @@ __global__ __launch_bounds__(256) void score_kernel(TensorView Q, const float* _
 }
 
 // ---------------------------------------------------------------------------------------------
+// Scores on the matrix cores for bfloat16 queries (same results as score_kernel to float32
+// rounding).  The float32 block means are split exactly into three bfloat16 terms,
+// B = Bh + Bm + Bl (8 + 8 + 8 mantissa bits), so that every product with a bfloat16 query is exact
+// in float32 and only the accumulation rounds -- a bfloat16 copy of the means alone would move P
+// by ~4e-3.  S^T[block, q] = sum over the three terms of Bx[block, :] . Q[q, :], with the query on
+// the MFMA column (= lane % 32), so the soft-max over blocks is a reduction over a lane's own
+// registers plus one exchange with lane ^ 32.  4 wavefronts x 32 queries per tile.
+template <int D>
+__global__ __launch_bounds__(256) void score_mfma_kernel(TensorView Q, const float* __restrict__ Bmean,
+                                                         float* __restrict__ P, unsigned int* __restrict__ hist_cnt,
+                                                         unsigned long long* __restrict__ hist_sum,
+                                                         int Hh, int S, int nb, float score_scale, int fix_shift) {
+    constexpr int STR = D + 8;                 // LDS row stride in bf16 elements
+    constexpr int KSTEPS = D / 16;
+    constexpr int MAX_MT = 4;                  // up to 128 blocks
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int nb_pad = (nb + 31) & ~31;
+    const int n_mt = nb_pad / 32;
+    __bf16* sB = reinterpret_cast<__bf16*>(smem);                                  // [3][nb_pad][STR]
+    unsigned long long* sSum = reinterpret_cast<unsigned long long*>(sB + (size_t)3 * nb_pad * STR);   // [1024]
+    unsigned int* sCnt = reinterpret_cast<unsigned int*>(sSum + HIST_BINS);        // [1024]
+
+    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hf = lane >> 5;
+
+    for (int i = tid; i < nb_pad * D; i += 256) {
+        const int j = i / D, d = i % D;
+        const float x = j < nb ? Bmean[((long long)bh * nb + j) * D + d] : 0.f;
+        const __bf16 xh = (__bf16)x;
+        const float r1 = x - (float)xh;
+        const __bf16 xm = (__bf16)r1;
+        const float r2 = r1 - (float)xm;
+        const __bf16 xl = (__bf16)r2;
+        sB[(0 * nb_pad + j) * STR + d] = xh;
+        sB[(1 * nb_pad + j) * STR + d] = xm;
+        sB[(2 * nb_pad + j) * STR + d] = xl;
+    }
+    for (int i = tid; i < HIST_BINS; i += 256) { sCnt[i] = 0u; sSum[i] = 0ull; }
+    __syncthreads();
+
+    const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const int n_tiles = (S + 127) / 128;
+    const bool vec_ok = (nb & 3) == 0;         // rows of P start 16-byte aligned
+    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int q = tile * 128 + wave * 32 + l32;
+        const int qc = min(q, S - 1);          // rows past the end recompute the last query; never stored
+        bf16x8_t qf[KSTEPS];
+        {
+            const char* src = Q.ptr + ((long long)b * Q.stride_b + (long long)qc * Q.stride_s + (long long)h * Q.stride_h) * 2;
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8_t*>(src + (ks * 16 + hf * 8) * 2);
+        }
+        f32x16_t acc[MAX_MT];
+#pragma unroll
+        for (int mt = 0; mt < MAX_MT; ++mt) {
+            acc[mt] = zero16;
+            if (mt < n_mt) {
+#pragma unroll
+                for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+                    for (int x = 0; x < 3; ++x) {
+                        const bf16x8_t bf = *reinterpret_cast<const bf16x8_t*>(
+                            &sB[((size_t)x * nb_pad + mt * 32 + l32) * STR + ks * 16 + hf * 8]);
+                        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, qf[ks], acc[mt], 0, 0, 0);
+                    }
+            }
+        }
+        // accumulator value v of tile mt <-> block 32*mt + 8*(v>>2) + 4*hf + (v&3)
+        float m = -INFINITY;
+#pragma unroll
+        for (int mt = 0; mt < MAX_MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int j = mt * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+                const float sv = (mt < n_mt && j < nb) ? acc[mt][v] * score_scale : -INFINITY;
+                acc[mt][v] = sv;
+                m = fmaxf(m, sv);
+            }
+        m = fmaxf(m, __shfl_xor(m, 32, 64));
+        float den = 0.f;
+#pragma unroll
+        for (int mt = 0; mt < MAX_MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float e = (mt < n_mt) ? expf(acc[mt][v] - m) : 0.f;     // exp(-inf) = 0 on padding blocks
+                acc[mt][v] = e;
+                den += e;
+            }
+        den += __shfl_xor(den, 32, 64);
+        if (q < S) {
+            float* dst = P + ((long long)bh * S + q) * nb;
+#pragma unroll
+            for (int mt = 0; mt < MAX_MT; ++mt) {
+                if (mt < n_mt) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int j0 = mt * 32 + 8 * g + 4 * hf;
+                        float pv[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) pv[r] = acc[mt][4 * g + r] / den;
+                        if (vec_ok && j0 + 3 < nb) {
+                            f32x4_t o = {pv[0], pv[1], pv[2], pv[3]};
+                            *reinterpret_cast<f32x4_t*>(dst + j0) = o;
+                        } else {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) if (j0 + r < nb) dst[j0 + r] = pv[r];
+                        }
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            if (j0 + r < nb) {
+                                const unsigned int bin = min(__float_as_uint(pv[r]) >> 20, (unsigned)(HIST_BINS - 1));
+                                atomicAdd(&sCnt[bin], 1u);
+                                atomicAdd(&sSum[bin], to_fixed(pv[r], fix_shift));
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < HIST_BINS; i += 256) {
+        const unsigned int c = sCnt[i];
+        if (c) {
+            atomicAdd(&hist_cnt[(long long)bh * HIST_BINS + i], c);
+            atomicAdd(&hist_sum[(long long)bh * HIST_BINS + i], sSum[i]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Descending scan of one radix level.  One workgroup of 1024 threads per head; thread t owns
 // bin 1023 - t, so an inclusive prefix sum over t is the descending cumulative sum.
 template <int LEVEL>
@@ -644,7 +776,22 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
         kfn<<<sgrid, dim3(256), lds, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks,  \
                                            score_scale, fix_shift);                                       \
     } while (0)
-    if (bf16 && D == 128) LAUNCH_SCORE(true, 128);
+    // bfloat16 queries and at most 128 blocks: scores on the matrix cores
+    const int nb_pad = (n_blocks + 31) & ~31;
+    const size_t lds_mfma = (size_t)3 * nb_pad * (D + 8) * 2 + HIST_BINS * 12;
+    const bool score_mfma = bf16 && n_blocks <= 128 && lds_mfma <= 160 * 1024 && getenv("VMOBA_SCORE_FMA") == nullptr;
+    if (score_mfma) {
+        dim3 mgrid((unsigned)ceil_div64(ceil_div64(S, 128), 4), (unsigned)BH);
+        if (D == 128) {
+            auto kfn = score_mfma_kernel<128>;
+            if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_mfma) != hipSuccess) return VMOBA_ERR_HIP;
+            kfn<<<mgrid, dim3(256), lds_mfma, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks, score_scale, fix_shift);
+        } else {
+            auto kfn = score_mfma_kernel<64>;
+            if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_mfma) != hipSuccess) return VMOBA_ERR_HIP;
+            kfn<<<mgrid, dim3(256), lds_mfma, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks, score_scale, fix_shift);
+        }
+    } else if (bf16 && D == 128) LAUNCH_SCORE(true, 128);
     else if (bf16 && D == 64) LAUNCH_SCORE(true, 64);
     else if (D == 128) LAUNCH_SCORE(false, 128);
     else LAUNCH_SCORE(false, 64);
