@@ -14,6 +14,8 @@
 #include <algorithm>
 #include <cmath>
 
+int64_t vmoba_max_tiles(int64_t cap, int TM);
+
 namespace {
 
 constexpr float LOG2E = 1.4426950408889634f;
@@ -69,14 +71,14 @@ template <bool BF16, int D>
 __global__ __launch_bounds__(64) void attn_bwd_dq_simple_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
-    const int* __restrict__ tile_start, float* __restrict__ dQpart, int Hh, int S, int nb, long long cap, float scale_log2) {
+    const int4* __restrict__ tile_desc, int tiles_per_head, float* __restrict__ dQpart, int Hh, int S, int nb, long long cap, float scale_log2) {
     constexpr int TM = 64, KC = 32;
     constexpr int ES = BF16 ? 2 : 4;
     __shared__ float sK[KC][D];
     __shared__ float sV[KC][D];
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
     TileCoord tc;
-    if (!find_tile(tile_start, blk_ptr, blk_off, bh, nb, blockIdx.x, TM, tc)) return;
+    if (!find_tile(tile_desc, tiles_per_head, bh, blockIdx.x, tc)) return;
     const int lane = threadIdx.x;
     const long long seg = (long long)bh * cap;
     const int e = min(lane, tc.count - 1);
@@ -226,7 +228,7 @@ template <int D>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
-    const int* __restrict__ tile_start, float* __restrict__ dQpart, int Hh, int S, int nb, long long cap, float scale_log2) {
+    const int4* __restrict__ tile_desc, int tiles_per_head, float* __restrict__ dQpart, int Hh, int S, int nb, long long cap, float scale_log2) {
     constexpr int TM = 128, KC = 64;
     constexpr int STR = D + 8;
     constexpr int KSTEPS = D / 16, DT = D / 32;
@@ -236,7 +238,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
 
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
     TileCoord tc;
-    if (!find_tile(tile_start, blk_ptr, blk_off, bh, nb, blockIdx.x, TM, tc)) return;
+    if (!find_tile(tile_desc, tiles_per_head, bh, blockIdx.x, tc)) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hf = lane >> 5;
     const long long seg = (long long)bh * cap;
@@ -674,6 +676,7 @@ struct BwdWs {
     float* dQpart;     // [BH * cap][D]
     float* delta;      // [BH][S]
     int* tile_start;   // [BH][257]
+    int4* tile_desc;   // [BH][tiles_per_head]
     int* kb_start;     // [257]
     size_t total;
 };
@@ -685,6 +688,7 @@ BwdWs carve_bwd(void* base, int BH, int64_t S, int D, int64_t cap) {
     w.dQpart = (float*)(p + off);    off += align_up((size_t)BH * cap * D * 4, 256);
     w.delta = (float*)(p + off);     off += align_up((size_t)BH * S * 4, 256);
     w.tile_start = (int*)(p + off);  off += align_up((size_t)BH * (VMOBA_MAX_BLOCKS + 1) * 4, 256);
+    w.tile_desc = (int4*)(p + off);  off += align_up((size_t)BH * vmoba_max_tiles(cap, 64) * 16, 256);
     w.kb_start = (int*)(p + off);    off += align_up((size_t)(VMOBA_MAX_BLOCKS + 1) * 4, 256);
     w.total = off;
     return w;
@@ -742,10 +746,14 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     const int TM = simple ? 64 : 128;
     tile_start_kernel<<<dim3((BH + 63) / 64), dim3(64), 0, st>>>(blk_ptr, ws.tile_start, BH, n_blocks, TM);
     VMOBA_CHECK_LAUNCH();
+    const int64_t max_tiles = std::min<int64_t>(vmoba_max_tiles(nnz_capacity, TM), (nnz_capacity / TM + n_blocks + 7) / 8 * 8);
+    tile_desc_kernel<<<dim3((unsigned)ceil_div64(max_tiles, 256), (unsigned)BH), dim3(256), 0, st>>>(
+        ws.tile_start, blk_ptr, blk_off, ws.tile_desc, n_blocks, TM, (int)max_tiles);
+    VMOBA_CHECK_LAUNCH();
     {
-        dim3 grid((unsigned)((nnz_capacity / TM + n_blocks + 7) / 8 * 8 + 8), (unsigned)BH);
+        dim3 grid((unsigned)max_tiles, (unsigned)BH);
         VMOBA_PROFILE_BEGIN(1, st);
-#define DQ_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.tile_start, ws.dQpart, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2
+#define DQ_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.tile_desc, (int)max_tiles, ws.dQpart, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2
         if (simple) {
             if (bf16 && D == 128) attn_bwd_dq_simple_kernel<true, 128><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
             else if (bf16) attn_bwd_dq_simple_kernel<true, 64><<<grid, dim3(64), 0, st>>>(DQ_ARGS);

@@ -64,37 +64,33 @@ __device__ __forceinline__ bf16x8_t pack8(const float* p) {
 }
 
 struct TileCoord {
-    int j;        // key block
-    int t0;       // first list entry of the tile, relative to blk_ptr[j]
     int count;    // valid entries in the tile (1..TM)
-    int list0;    // blk_ptr[j]: first list entry of the block, relative to the head's segment
-    int k0, L;    // first key position and number of keys of block j
+    int list0;    // first list entry of the tile, relative to the head's segment
+    int t0;       // always 0 (the tile's offset is folded into list0)
+    int k0, L;    // first key position and number of keys of the tile's key block
 };
 
-// Locate tile `tile` of head `bh`.  Returns false if the tile does not exist.
-__device__ __forceinline__ bool find_tile(const int* __restrict__ tile_start, const int* __restrict__ blk_ptr,
-                                          const int* __restrict__ blk_off, int bh, int nb, int tile, int TM,
+// Tile descriptors: one int4 {first list entry, count, k0, L} per (head, tile), written by
+// tile_desc_kernel so that a tile kernel learns its work with a single 16-byte load instead of a
+// binary search over dependent loads.  count = 0 marks a tile that does not exist.
+__device__ __forceinline__ bool find_tile(const int4* __restrict__ tile_desc, int tiles_per_head, int bh, int tile,
                                           TileCoord& tc) {
-    const int* ts = tile_start + (long long)bh * (nb + 1);
-    if (tile >= ts[nb]) return false;
-    int lo = 0, hi = nb;           // largest j with ts[j] <= tile
-    while (hi - lo > 1) {
-        int mid = (lo + hi) >> 1;
-        if (ts[mid] <= tile) lo = mid; else hi = mid;
-    }
-    const int* bp = blk_ptr + (long long)bh * (nb + 1);
-    tc.j = lo;
-    tc.list0 = bp[lo];
-    const int cnt = bp[lo + 1] - bp[lo];
-    tc.t0 = (tile - ts[lo]) * TM;
-    tc.count = min(TM, cnt - tc.t0);
-    tc.k0 = blk_off[lo];
-    tc.L = blk_off[lo + 1] - blk_off[lo];
+    const int4 d = tile_desc[(long long)bh * tiles_per_head + tile];
+    if (d.y <= 0) return false;
+    tc.list0 = d.x;
+    tc.t0 = 0;
+    tc.count = d.y;
+    tc.k0 = d.z;
+    tc.L = d.w;
     return true;
 }
 
-// tile_start for all heads.  One thread per head (n_blocks <= 256).
+// tile_start[bh][j] = number of tiles (of TM list entries) in blocks 0..j-1.  One thread per head.
 __global__ __launch_bounds__(64) void tile_start_kernel(const int* __restrict__ blk_ptr, int* __restrict__ tile_start,
                                                         int BH, int nb, int TM);
+// Descriptor of every tile id below tiles_per_head (one thread per id; ids past the head's last tile get count 0).
+__global__ __launch_bounds__(256) void tile_desc_kernel(const int* __restrict__ tile_start, const int* __restrict__ blk_ptr,
+                                                        const int* __restrict__ blk_off, int4* __restrict__ tile_desc,
+                                                        int nb, int TM, int tiles_per_head);
 
 inline __device__ float exp2_raw(float x) { return __builtin_amdgcn_exp2f(x); }

@@ -26,6 +26,30 @@ __global__ __launch_bounds__(64) void tile_start_kernel(const int* __restrict__ 
     ts[nb] = run;
 }
 
+__global__ __launch_bounds__(256) void tile_desc_kernel(const int* __restrict__ tile_start, const int* __restrict__ blk_ptr,
+                                                        const int* __restrict__ blk_off, int4* __restrict__ tile_desc,
+                                                        int nb, int TM, int tiles_per_head) {
+    const int bh = blockIdx.y;
+    const int tile = blockIdx.x * 256 + threadIdx.x;
+    if (tile >= tiles_per_head) return;
+    const int* ts = tile_start + (long long)bh * (nb + 1);
+    int4 d = {0, 0, 0, 0};
+    if (tile < ts[nb]) {
+        int lo = 0, hi = nb;           // largest j with ts[j] <= tile
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (ts[mid] <= tile) lo = mid; else hi = mid;
+        }
+        const int* bp = blk_ptr + (long long)bh * (nb + 1);
+        const int t0 = (tile - ts[lo]) * TM;
+        d.x = bp[lo] + t0;
+        d.y = min(TM, bp[lo + 1] - bp[lo] - t0);
+        d.z = blk_off[lo];
+        d.w = blk_off[lo + 1] - blk_off[lo];
+    }
+    tile_desc[(long long)bh * tiles_per_head + tile] = d;
+}
+
 namespace {
 
 constexpr float LOG2E = 1.4426950408889634f;
@@ -38,7 +62,7 @@ constexpr float LN2 = 0.6931471805599453f;
 template <bool BF16, int D>
 __global__ __launch_bounds__(64) void attn_fwd_tile_simple_kernel(
     TensorView Q, TensorView K, TensorView V, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr,
-    const int* __restrict__ q_idx, const int* __restrict__ tile_start, float* __restrict__ Opart,
+    const int* __restrict__ q_idx, const int4* __restrict__ tile_desc, int tiles_per_head, float* __restrict__ Opart,
     float* __restrict__ lse_part, int Hh, int nb, long long cap, float scale_log2) {
     constexpr int TM = 64, KC = 32;
     constexpr int ES = BF16 ? 2 : 4;
@@ -46,7 +70,7 @@ __global__ __launch_bounds__(64) void attn_fwd_tile_simple_kernel(
     __shared__ float sV[KC][D];
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
     TileCoord tc;
-    if (!find_tile(tile_start, blk_ptr, blk_off, bh, nb, blockIdx.x, TM, tc)) return;
+    if (!find_tile(tile_desc, tiles_per_head, bh, blockIdx.x, tc)) return;
     const int lane = threadIdx.x;
     const long long seg = (long long)bh * cap;
     const int e = min(lane, tc.count - 1);
@@ -115,7 +139,7 @@ __global__ __launch_bounds__(64) void attn_fwd_tile_simple_kernel(
 template <int D, int NQ>
 __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void attn_fwd_tile_mfma_kernel(
     TensorView Q, TensorView K, TensorView V, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr,
-    const int* __restrict__ q_idx, const int* __restrict__ tile_start, float* __restrict__ Opart,
+    const int* __restrict__ q_idx, const int4* __restrict__ tile_desc, int tiles_per_head, float* __restrict__ Opart,
     float* __restrict__ lse_part, int Hh, int nb, long long cap, float scale_log2) {
     constexpr int TM = 128 * NQ;
     constexpr int KC = 64;                  // keys per chunk
@@ -129,7 +153,7 @@ __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void attn_fwd_tile_mfma_ker
 
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
     TileCoord tc;
-    if (!find_tile(tile_start, blk_ptr, blk_off, bh, nb, blockIdx.x, TM, tc)) return;
+    if (!find_tile(tile_desc, tiles_per_head, bh, blockIdx.x, tc)) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hf = lane >> 5;
     const long long seg = (long long)bh * cap;
@@ -324,7 +348,7 @@ __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void attn_fwd_tile_mfma_ker
 template <int D>
 __global__ __launch_bounds__(512, 2) void attn_fwd_tile_pp_kernel(
     TensorView Q, TensorView K, TensorView V, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr,
-    const int* __restrict__ q_idx, const int* __restrict__ tile_start, float* __restrict__ Opart,
+    const int* __restrict__ q_idx, const int4* __restrict__ tile_desc, int tiles_per_head, float* __restrict__ Opart,
     float* __restrict__ lse_part, int Hh, int nb, long long cap, float scale_log2) {
     constexpr int TM = 256, KC = 64, STR = D + 8;
     constexpr int KSTEPS = D / 16, DT = D / 32;
@@ -335,7 +359,7 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_tile_pp_kernel(
 
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
     TileCoord tc;
-    if (!find_tile(tile_start, blk_ptr, blk_off, bh, nb, blockIdx.x, TM, tc)) return;
+    if (!find_tile(tile_desc, tiles_per_head, bh, blockIdx.x, tc)) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int grp = wave >> 2;
     const int l32 = lane & 31, hf = lane >> 5;
@@ -579,8 +603,14 @@ struct FwdWs {
     float* Opart;      // [BH * cap][D]
     float* lse_part;   // [BH * cap]
     int* tile_start;   // [BH][nb + 1]
+    int4* tile_desc;   // [BH][tiles_per_head]
     size_t total;
 };
+
+}  // namespace
+// Grid width (tiles per head) for tiles of TM list entries: a host-side bound on sum_j ceil(cnt_j / TM).
+int64_t vmoba_max_tiles(int64_t cap, int TM) { return (cap / TM + VMOBA_MAX_BLOCKS + 7) / 8 * 8; }
+namespace {
 
 FwdWs carve_fwd(void* base, int BH, int D, int64_t cap, int nb) {
     FwdWs w;
@@ -589,6 +619,7 @@ FwdWs carve_fwd(void* base, int BH, int D, int64_t cap, int nb) {
     w.Opart = (float*)(p + off);     off += align_up((size_t)BH * cap * D * 4, 256);
     w.lse_part = (float*)(p + off);  off += align_up((size_t)BH * cap * 4, 256);
     w.tile_start = (int*)(p + off);  off += align_up((size_t)BH * (VMOBA_MAX_BLOCKS + 1) * 4, 256);
+    w.tile_desc = (int4*)(p + off);  off += align_up((size_t)BH * vmoba_max_tiles(cap, 64) * 16, 256);
     (void)nb;
     w.total = off;
     return w;
@@ -638,11 +669,13 @@ extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     const int TM = simple ? 64 : (two_group ? 256 : 128 * nq);
     tile_start_kernel<<<dim3((BH + 63) / 64), dim3(64), 0, st>>>(blk_ptr, ws.tile_start, BH, n_blocks, TM);
     VMOBA_CHECK_LAUNCH();
-    // a multiple of 8 so that (workgroup id % 8) is the same for every head; + 8 for the per-XCD rounding
-    const int64_t max_tiles = (nnz_capacity / TM + n_blocks + 7) / 8 * 8 + 8;
+    const int64_t max_tiles = std::min<int64_t>(vmoba_max_tiles(nnz_capacity, TM), (nnz_capacity / TM + n_blocks + 7) / 8 * 8);
+    tile_desc_kernel<<<dim3((unsigned)ceil_div64(max_tiles, 256), (unsigned)BH), dim3(256), 0, st>>>(
+        ws.tile_start, blk_ptr, blk_off, ws.tile_desc, n_blocks, TM, (int)max_tiles);
+    VMOBA_CHECK_LAUNCH();
     dim3 grid((unsigned)max_tiles, (unsigned)BH);
     VMOBA_PROFILE_BEGIN(0, st);
-#define TILE_ARGS Qv, Kv, Vv, blk_off, blk_ptr, q_idx, ws.tile_start, ws.Opart, ws.lse_part, Hh, n_blocks, (long long)nnz_capacity, scale_log2
+#define TILE_ARGS Qv, Kv, Vv, blk_off, blk_ptr, q_idx, ws.tile_desc, (int)max_tiles, ws.Opart, ws.lse_part, Hh, n_blocks, (long long)nnz_capacity, scale_log2
     if (simple) {
         if (bf16 && D == 128) attn_fwd_tile_simple_kernel<true, 128><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
         else if (bf16) attn_fwd_tile_simple_kernel<true, 64><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
