@@ -636,17 +636,23 @@ __global__ __launch_bounds__(256) void dq_merge_kernel(const float* __restrict__
     float acc[CH];
 #pragma unroll
     for (int c = 0; c < CH; ++c) acc[c] = 0.f;
-    for (int r = r0; r < r1; ++r) {
-        const long long pair = seg + pair_pos[seg + r];
-        if constexpr (PBF16) {
-            const u32x4_t v = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const uint16_t*>(dQpart) + pair * D + part * 8);
-            acc[0] += bf16lo_to_f32(v.x); acc[1] += bf16hi_to_f32(v.x);
-            acc[2] += bf16lo_to_f32(v.y); acc[3] += bf16hi_to_f32(v.y);
-            acc[4] += bf16lo_to_f32(v.z); acc[5] += bf16hi_to_f32(v.z);
-            acc[6] += bf16lo_to_f32(v.w); acc[7] += bf16hi_to_f32(v.w);
-        } else {
-            const f32x4_t v = *reinterpret_cast<const f32x4_t*>(dQpart + pair * D + part * 4);
-            acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
+    for (int r = r0; r < r1; r += 4) {               // four partial rows in flight per step
+        long long pair[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) pair[u] = seg + pair_pos[seg + min(r + u, r1 - 1)];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float keep = (r + u < r1) ? 1.f : 0.f;
+            if constexpr (PBF16) {
+                const u32x4_t v = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const uint16_t*>(dQpart) + pair[u] * D + part * 8);
+                acc[0] += keep * bf16lo_to_f32(v.x); acc[1] += keep * bf16hi_to_f32(v.x);
+                acc[2] += keep * bf16lo_to_f32(v.y); acc[3] += keep * bf16hi_to_f32(v.y);
+                acc[4 % CH] += keep * bf16lo_to_f32(v.z); acc[5 % CH] += keep * bf16hi_to_f32(v.z);
+                acc[6 % CH] += keep * bf16lo_to_f32(v.w); acc[7 % CH] += keep * bf16hi_to_f32(v.w);
+            } else {
+                const f32x4_t v = *reinterpret_cast<const f32x4_t*>(dQpart + pair[u] * D + part * 4);
+                acc[0] += keep * v.x; acc[1] += keep * v.y; acc[2] += keep * v.z; acc[3] += keep * v.w;
+            }
         }
     }
 #pragma unroll

@@ -549,26 +549,45 @@ __global__ __launch_bounds__(256) void attn_fwd_merge_kernel(const float* __rest
     if (q >= S) return;
     const int r0 = row_ptr[(long long)bh * (S + 1) + q], r1 = row_ptr[(long long)bh * (S + 1) + q + 1];
     const long long seg = (long long)bh * cap;
+    // one pass with a running maximum; four partials in flight per step (index -> lse and row loads)
     float mx = -INFINITY;
-    for (int r = r0; r < r1; ++r) mx = fmaxf(mx, lse_part[seg + pair_pos[seg + r]]);
     float acc[CH];
 #pragma unroll
     for (int c = 0; c < CH; ++c) acc[c] = 0.f;
     float wsum = 0.f;
-    for (int r = r0; r < r1; ++r) {
-        const long long pair = seg + pair_pos[seg + r];
-        const float w = expf(lse_part[pair] - mx);
-        wsum += w;
-        if constexpr (PBF16) {
-            const u32x4_t v = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const uint16_t*>(Opart) + pair * D + part * 8);
-            acc[0] += w * bf16lo_to_f32(v.x); acc[1] += w * bf16hi_to_f32(v.x);
-            acc[2] += w * bf16lo_to_f32(v.y); acc[3] += w * bf16hi_to_f32(v.y);
-            acc[4] += w * bf16lo_to_f32(v.z); acc[5] += w * bf16hi_to_f32(v.z);
-            acc[6] += w * bf16lo_to_f32(v.w); acc[7] += w * bf16hi_to_f32(v.w);
-        } else {
-            const f32x4_t v = *reinterpret_cast<const f32x4_t*>(Opart + pair * D + part * 4);
-            acc[0] += w * v.x; acc[1] += w * v.y; acc[2] += w * v.z; acc[3] += w * v.w;
+    for (int r = r0; r < r1; r += 4) {
+        long long pair[4];
+        float l[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) pair[u] = seg + pair_pos[seg + min(r + u, r1 - 1)];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) l[u] = (r + u < r1) ? lse_part[pair[u]] : -INFINITY;
+        float v[4][CH];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if constexpr (PBF16) {
+                const u32x4_t x = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const uint16_t*>(Opart) + pair[u] * D + part * 8);
+                v[u][0] = bf16lo_to_f32(x.x); v[u][1] = bf16hi_to_f32(x.x); v[u][2] = bf16lo_to_f32(x.y); v[u][3] = bf16hi_to_f32(x.y);
+                v[u][4 % CH] = bf16lo_to_f32(x.z); v[u][5 % CH] = bf16hi_to_f32(x.z);
+                v[u][6 % CH] = bf16lo_to_f32(x.w); v[u][7 % CH] = bf16hi_to_f32(x.w);
+            } else {
+                const f32x4_t x = *reinterpret_cast<const f32x4_t*>(Opart + pair[u] * D + part * 4);
+                v[u][0] = x.x; v[u][1] = x.y; v[u][2] = x.z; v[u][3] = x.w;
+            }
         }
+        const float m_new = fmaxf(fmaxf(mx, fmaxf(l[0], l[1])), fmaxf(l[2], l[3]));
+        const float alpha = expf(mx - m_new);          // exp(-inf) = 0 on the first step (m_new is finite: l[0] is)
+        wsum *= alpha;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) acc[c] *= alpha;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float w = expf(l[u] - m_new);        // 0 for the padding entries
+            wsum += w;
+#pragma unroll
+            for (int c = 0; c < CH; ++c) acc[c] += w * v[u][c];
+        }
+        mx = m_new;
     }
     float lse = -INFINITY;
     if (r1 > r0) {
