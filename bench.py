@@ -217,8 +217,10 @@ def main():
             "unpartition_grads_GBps": 3 * 2 * row_bytes / (bd["unpartition_grads"] * 1e-3) / 1e9,
             "select_GBps": sel_bytes / (bd["select"] * 1e-3) / 1e9,
             "select_algorithmic_bytes": sel_bytes}
+    empty_rows = {kind: float((p.row_ptr[:, 1:] == p.row_ptr[:, :-1]).float().mean().item()) for kind, p in plans.items()}
     per_kind = {kind: {"ms_per_layer": sum(b.values()),
                        "selected_pair_fraction": pairs[kind] / (Hh * S * plans[kind].nb),
+                       "empty_row_fraction": empty_rows[kind],
                        "token_sparsity": keysum[kind] / (Hh * S * S),
                        "n_blocks": plans[kind].nb,
                        "attn_fwd_bwd_tflops": 14.0 * D * keysum[kind] / ((b["attn_fwd"] + b["attn_bwd"]) * 1e-3) / 1e12}
@@ -235,6 +237,41 @@ def main():
            "memory_bound_steps": dict(mem_steps, hbm_peak_GBps=HBM_PEAK_GBS,
                                       note="algorithmic bytes (permute: read+write of every row; select: K and Q read once, "
                                            "P, mask and the three lists written once) over the call's time")}
+
+    # ---- measured copy ceiling (plain device-to-device copy of 1 GiB, read + write counted)
+    try:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["memory_bound_steps"]["measured_copy_GBps"] = 2 * 5 * (1 << 30) / (time.perf_counter() - t) / 1e9
+        del src, dst
+    except Exception as e:
+        out["memory_bound_steps"]["measured_copy_error"] = repr(e)[:100]
+
+    # ---- the second threshold of the workload (tau = 0.5), 3D partition, a few steps
+    if abs(args.tau - 0.5) > 1e-9 and "3d" in cfg["partitions"]:
+        try:
+            bt, bh, bw, chunk = cfg["partitions"]["3d"]
+            p5 = vb.LayerPlan(1, Hh, D, cfg["grid"], (bt, bh, bw), chunk, 0.5, dtype)
+            p5.forward(Q, K, V); p5.backward(dO)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(3):
+                p5.forward(Q, K, V); p5.backward(dO)
+            torch.cuda.synchronize()
+            ms5 = (time.perf_counter() - t) * 1e3 / 3
+            ks5, pr5 = selected_key_sum(p5)
+            out["tau_0.5_3d"] = {"ms_per_layer": ms5, "effective_tflops": 14.0 * D * ks5 / (ms5 * 1e-3) / 1e12,
+                                 "selected_pair_fraction": pr5 / (Hh * S * p5.nb)}
+            del p5
+            torch.cuda.empty_cache()
+        except Exception as e:
+            out["tau_0.5_3d"] = {"error": repr(e)[:200]}
 
     # ---- dense comparators on the same GPU
     if not args.no_dense:

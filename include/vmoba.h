@@ -52,6 +52,16 @@ typedef enum { VMOBA_F32 = 0, VMOBA_BF16 = 1 } vmoba_dtype;
 /* Operations that need a workspace (argument `op` of vmoba_workspace_bytes). */
 typedef enum { VMOBA_OP_SELECT = 1, VMOBA_OP_ATTN_FWD = 2, VMOBA_OP_ATTN_BWD = 3 } vmoba_op;
 
+/* Block-choice designs (argument `mode` of vmoba_select).  Sec. 3.3-3.4 define global + threshold, the
+ * paper's training setting; the other three are the variants of its block-choice ablation (Sec. 4.3) --
+ * local + top-k, the option of the original MoBA, is what its training-free runs use (App. A). */
+typedef enum {
+    VMOBA_GLOBAL_THRESHOLD = 0, /* head's whole pool, descending cumulative similarity until tau * S (Eq. 4) */
+    VMOBA_LOCAL_TOPK = 1,       /* every query keeps its `topk` most similar blocks                          */
+    VMOBA_LOCAL_THRESHOLD = 2,  /* every query keeps the shortest descending prefix of its row reaching tau  */
+    VMOBA_GLOBAL_TOPK = 3       /* head's whole pool, the topk * S most similar pairs (Eq. 3 with a fixed k)  */
+} vmoba_select_mode;
+
 /* Latent grid and key-block shape (Sec. 3.2, Eq. 1).  A block is a box of bt x bh x bw
  * latent positions: the paper's 1D partition is (s^T, H, W), its 2D partition (T, s^H, s^W),
  * its 3D partition (s^T, s^H, s^W).  If chunk > 0 the box is ignored and a block is `chunk`
@@ -116,7 +126,9 @@ int vmoba_partition(const vmoba_grid* g, int inverse, int B, int Hh, int D, int 
  *  Qp, Kp      block-order tensors (b, s, h, d) with the strides given
  *  tau         threshold in (0, 1]; tau >= 1 keeps every pair
  *  score_scale factor applied to <q, b> before the soft-max (1/sqrt(D) by convention)
- *  mode        0 = global pool + threshold (the paper's training setting); others reserved
+ *  mode        a vmoba_select_mode; tau is used by the threshold modes, topk (>= 1) by the top-k modes.
+ *              Ties rank by ascending block index (local modes) or ascending (query, block) (global modes).
+ *              In the local modes k_out is the number of kept pairs and theta_out is 0
  *  Bmean  out  [B, Hh, n_blocks, D] float32 block means
  *  P      out  [B, Hh, S, n_blocks] float32 normalised similarities (each row sums to 1)
  *  mask   out  [B, Hh, S, ceil(n_blocks/32)] uint32, bit j of a row = query keeps block j
@@ -132,14 +144,15 @@ int vmoba_partition(const vmoba_grid* g, int inverse, int B, int Hh, int D, int 
  *    col_idx  [B*Hh * nnz_capacity] int32 blocks (ascending) kept by query q
  *    pair_pos [B*Hh * nnz_capacity] int32 for each (q, block) in query-major order, its offset
  *                                         in the block-major list
- *  k <= ceil(tau*S*n_blocks) always holds, so nnz_capacity = min(S*n_blocks,
- *  ceil(tau*S*n_blocks)) suffices.  If a head would still exceed it, nothing is written out of
+ *  In mode 0, k <= ceil(tau*S*n_blocks) always holds, so nnz_capacity = min(S*n_blocks,
+ *  ceil(tau*S*n_blocks)) suffices; the top-k modes keep exactly min(topk, n_blocks)*S pairs; the local
+ *  threshold mode can keep up to S*n_blocks.  If a head would still exceed it, nothing is written out of
  *  bounds, its lists are left incomplete and *dev_status is set to VMOBA_ERR_CAPACITY
  *  (dev_status is a device int32 the caller zeroes and reads after its own synchronisation).
  */
 int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
                  const vmoba_tensor* Qp, const vmoba_tensor* Kp, float tau, float score_scale,
-                 int mode, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
+                 int mode, int32_t topk, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
                  int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
                  int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
                  void* workspace, size_t workspace_bytes, void* stream);

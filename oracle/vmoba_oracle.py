@@ -55,6 +55,7 @@ import numpy as np
 __all__ = [
     "layer_kind", "partition_dims", "partition_index", "gather_rows", "scatter_rows",
     "block_means", "block_scores", "normalise_rows", "threshold_topk", "select_blocks",
+    "local_topk", "local_threshold", "global_topk",
     "csr_from_mask", "masked_attention_fwd", "masked_attention_bwd", "vmoba_layer",
 ]
 
@@ -199,12 +200,68 @@ def threshold_topk(P, tau):
     return k, theta, mask.reshape(S, nb)
 
 
-def select_blocks(Qp, Kp, blk_off, tau, score_scale):
+# Selection variants of the paper's ablation ("block choice design": top-k or threshold, chosen
+# per query -- "local" -- or from the head's whole pool -- "global"; the training-free runs use
+# local + top-k, the option of the original MoBA).  Ties are ordered by ascending block / (q, j).
+MODE_GLOBAL_THRESHOLD, MODE_LOCAL_TOPK, MODE_LOCAL_THRESHOLD, MODE_GLOBAL_TOPK = 0, 1, 2, 3
+
+
+def local_topk(P, topk):
+    """Every query keeps its `topk` most similar blocks (all of them if topk >= N_b).
+    [App. A, "Local + TopK"; Sec. 4.3 block choice ablation.]"""
+    S, nb = P.shape
+    k = min(int(topk), nb)
+    order = np.argsort(-P.astype(np.float32), axis=1, kind="stable")
+    mask = np.zeros((S, nb), dtype=bool)
+    np.put_along_axis(mask, order[:, :k], True, axis=1)
+    return mask
+
+
+def local_threshold(P, tau):
+    """Every query keeps the shortest descending prefix of its own blocks whose normalised
+    similarities sum to >= tau (float64 running sum; tau in single precision).
+    [Sec. 4.3 block choice ablation, "threshold + local": Eq. 4 applied per query.]"""
+    S, nb = P.shape
+    P32 = P.astype(np.float32)
+    order = np.argsort(-P32, axis=1, kind="stable")
+    sorted_vals = np.take_along_axis(P32, order, axis=1).astype(np.float64)
+    before = np.cumsum(sorted_vals, axis=1) - sorted_vals        # mass ranked strictly before each entry
+    tau32 = float(np.float32(tau))
+    keep_sorted = before < tau32 if tau32 < 1.0 else np.ones_like(before, dtype=bool)
+    mask = np.zeros((S, nb), dtype=bool)
+    np.put_along_axis(mask, order, keep_sorted, axis=1)
+    return mask
+
+
+def global_topk(P, k_total):
+    """The k_total most similar (query, block) pairs of the head's pool.
+    [Sec. 3.3, Eq. 3 with a fixed k: "topk + global" of the ablation.]"""
+    S, nb = P.shape
+    k = max(1, min(int(k_total), S * nb))
+    flat = P.astype(np.float32).reshape(-1)
+    order = np.argsort(-flat, kind="stable")
+    mask = np.zeros(S * nb, dtype=bool)
+    mask[order[:k]] = True
+    return k, np.float32(flat[order[k - 1]]), mask.reshape(S, nb)
+
+
+def select_blocks(Qp, Kp, blk_off, tau, score_scale, mode=MODE_GLOBAL_THRESHOLD, topk=0):
     """Steps 2-6 for one head.  Returns dict(Bmean, S_hat, P, k, theta, mask)."""
     Bm = block_means(Kp, blk_off)
     S_hat = block_scores(Qp, Bm, score_scale)
     P = normalise_rows(S_hat)
-    k, theta, mask = threshold_topk(P, tau)
+    if mode == MODE_GLOBAL_THRESHOLD:
+        k, theta, mask = threshold_topk(P, tau)
+    elif mode == MODE_LOCAL_TOPK:
+        mask = local_topk(P, topk)
+        k, theta = int(mask.sum()), np.float32(0)
+    elif mode == MODE_LOCAL_THRESHOLD:
+        mask = local_threshold(P, tau)
+        k, theta = int(mask.sum()), np.float32(0)
+    elif mode == MODE_GLOBAL_TOPK:
+        k, theta, mask = global_topk(P, topk * P.shape[0])
+    else:
+        raise ValueError(mode)
     return dict(Bmean=Bm, S_hat=S_hat, P=P, k=k, theta=theta, mask=mask)
 
 
@@ -298,7 +355,7 @@ def masked_attention_bwd(Qp, Kp, Vp, mask, blk_off, softmax_scale, dO, rows_per_
 
 # --------------------------------------------------------------------------- whole layer
 def vmoba_layer(Q, K, V, grid, block, tau, dO=None, score_scale=None, softmax_scale=None,
-                chunk=0):
+                chunk=0, mode=MODE_GLOBAL_THRESHOLD, topk=0):
     """One VMoBA attention layer on caller-layout tensors [B, S, Hh, D].  [Sec. 3.1-3.4.]
 
     grid = (T, H, W); block = (bt, bh, bw) (ignored when chunk > 0).
@@ -328,7 +385,7 @@ def vmoba_layer(Q, K, V, grid, block, tau, dO=None, score_scale=None, softmax_sc
         grads = [np.zeros((B, Hh, S, D), dtype=np.float64) for _ in range(3)]
     for b in range(B):
         for h in range(Hh):
-            sel = select_blocks(Qp[b, h], Kp[b, h], blk_off, tau, score_scale)
+            sel = select_blocks(Qp[b, h], Kp[b, h], blk_off, tau, score_scale, mode, topk)
             masks[b, h], ks[b, h], thetas[b, h] = sel["mask"], sel["k"], sel["theta"]
             Ps[b, h], Bms[b, h] = sel["P"], sel["Bmean"]
             Op[b, h], LSE[b, h] = masked_attention_fwd(Qp[b, h], Kp[b, h], Vp[b, h],

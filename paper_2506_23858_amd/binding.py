@@ -65,7 +65,7 @@ def lib():
     L.vmoba_partition.restype = C.c_int
     L.vmoba_select.argtypes = [C.c_int, C.c_int, C.c_int64, C.c_int, C.c_int32, P,
                                C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor), C.c_float, C.c_float, C.c_int,
-                               P, P, P, P, P, P, P, P, C.c_int64, P, P, P, P, C.c_size_t, P]
+                               C.c_int32, P, P, P, P, P, P, P, P, C.c_int64, P, P, P, P, C.c_size_t, P]
     L.vmoba_select.restype = C.c_int
     L.vmoba_attn_fwd.argtypes = [C.c_int, C.c_int, C.c_int64, C.c_int, C.c_int32, P,
                                  C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor),
@@ -160,12 +160,15 @@ def vmoba_partition(g, inverse, B, Hh, D, ins, outs, perm, inv_perm, blk_off, st
     _check("vmoba_partition", rc)
 
 
-def vmoba_select(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode, Bmean, P, mask,
+GLOBAL_THRESHOLD, LOCAL_TOPK, LOCAL_THRESHOLD, GLOBAL_TOPK = 0, 1, 2, 3
+
+
+def vmoba_select(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode, topk, Bmean, P, mask,
                  blk_ptr, q_idx, row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status,
                  workspace, stream=None):
     q, k = tensor_desc(Qp), tensor_desc(Kp)
     rc = lib().vmoba_select(B, Hh, S, D, n_blocks, _ptr(blk_off), C.byref(q), C.byref(k),
-                            float(tau), float(score_scale), int(mode), _ptr(Bmean), _ptr(P), _ptr(mask),
+                            float(tau), float(score_scale), int(mode), int(topk), _ptr(Bmean), _ptr(P), _ptr(mask),
                             _ptr(blk_ptr), _ptr(q_idx), _ptr(row_ptr), _ptr(col_idx), _ptr(pair_pos),
                             int(nnz_capacity), _ptr(k_out), _ptr(theta_out), _ptr(dev_status),
                             _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
@@ -200,14 +203,20 @@ class LayerPlan:
     inverse partition and allocate nothing."""
 
     def __init__(self, B, Hh, D, grid, block=(0, 0, 0), chunk=0, tau=0.25, dtype=torch.bfloat16,
-                 device="cuda", score_scale=None, softmax_scale=None, need_bwd=True):
+                 device="cuda", score_scale=None, softmax_scale=None, need_bwd=True, mode=GLOBAL_THRESHOLD, topk=0):
         T, H, W = grid
         self.g = make_grid(T, H, W, *block, chunk)
         self.B, self.Hh, self.D, self.tau, self.dtype, self.dev = B, Hh, D, float(tau), dtype, device
         self.S, self.nb = vmoba_partition_dims(self.g)
         self.score_scale = score_scale if score_scale is not None else 1.0 / math.sqrt(D)
         self.softmax_scale = softmax_scale if softmax_scale is not None else 1.0 / math.sqrt(D)
-        self.cap = nnz_capacity_for(self.S, self.nb, tau)
+        self.mode, self.topk = int(mode), int(topk)
+        if mode == GLOBAL_THRESHOLD:
+            self.cap = nnz_capacity_for(self.S, self.nb, tau)
+        elif mode == LOCAL_THRESHOLD:
+            self.cap = self.S * self.nb
+        else:
+            self.cap = self.S * min(self.topk, self.nb)
         S, nb, BH, cap = self.S, self.nb, B * Hh, self.cap
         dc = VMOBA_BF16 if dtype == torch.bfloat16 else VMOBA_F32
         i32 = dict(dtype=torch.int32, device=device)
@@ -251,7 +260,7 @@ class LayerPlan:
 
     def select(self):
         vmoba_select(self.B, self.Hh, self.S, self.D, self.nb, self.blk_off, self.Qp, self.Kp, self.tau,
-                     self.score_scale, 0, self.Bmean, self.P, self.mask, self.blk_ptr, self.q_idx,
+                     self.score_scale, self.mode, self.topk, self.Bmean, self.P, self.mask, self.blk_ptr, self.q_idx,
                      self.row_ptr, self.col_idx, self.pair_pos, self.cap, self.k_out, self.theta,
                      self.dev_status, self.ws_select)
 

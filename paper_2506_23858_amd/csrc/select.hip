@@ -343,7 +343,9 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(TensorView Q, const flo
 // ---------------------------------------------------------------------------------------------
 // Descending scan of one radix level.  One workgroup of 1024 threads per head; thread t owns
 // bin 1023 - t, so an inclusive prefix sum over t is the descending cumulative sum.
-template <int LEVEL>
+// BYCOUNT = false: the cut is where the descending cumulative SUM reaches `target` (threshold selection,
+// Eq. 4); BYCOUNT = true: where the descending cumulative COUNT reaches it (a fixed global k).
+template <int LEVEL, bool BYCOUNT>
 __global__ __launch_bounds__(HIST_BINS) void scan_level_kernel(const unsigned int* __restrict__ hist_cnt,
                                                                const unsigned long long* __restrict__ hist_sum,
                                                                HeadState* __restrict__ state,
@@ -373,8 +375,9 @@ __global__ __launch_bounds__(HIST_BINS) void scan_level_kernel(const unsigned in
         __syncthreads();
     }
     const unsigned long long need = (LEVEL == 0) ? target : st.need;
-    const unsigned long long incl = sS[t], excl = incl - my_s;
     const unsigned long long cexcl = sC[t] - my_c;
+    const unsigned long long incl = BYCOUNT ? sC[t] : sS[t];
+    const unsigned long long excl = BYCOUNT ? cexcl : incl - my_s;
     if (LEVEL == 0 && t == HIST_BINS - 1 && incl < need) {
         // the whole pool does not reach the target (tau >= 1, or rounding): keep everything
         HeadState ns = st;
@@ -391,8 +394,13 @@ __global__ __launch_bounds__(HIST_BINS) void scan_level_kernel(const unsigned in
         if (LEVEL == 2) {
             ns.prefix = st.prefix | (unsigned)bin;
             const float theta = __uint_as_float(ns.prefix);
-            const unsigned long long each = to_fixed(theta, fix_shift);   // > 0: this bin has mass
-            unsigned long long take = (ns.need + each - 1) / each;
+            unsigned long long take;
+            if (BYCOUNT) {
+                take = ns.need;                                            // entries still missing
+            } else {
+                const unsigned long long each = to_fixed(theta, fix_shift);   // > 0: this bin has mass
+                take = (ns.need + each - 1) / each;
+            }
             if (take > my_c) take = my_c;
             if (take < 1) take = 1;
             ns.n_tie = (unsigned)my_c;
@@ -613,6 +621,96 @@ __global__ __launch_bounds__(256) void mask_kernel(const float* __restrict__ P, 
     }
 }
 
+// Per-query ("local") selection, the block-choice variants of the paper's ablation and of its
+// training-free runs.  LOCAL_TOPK: a query keeps its `topk` most similar blocks; otherwise it keeps the
+// shortest descending prefix of its own row whose sum reaches tau.  Entry j' ranks before j when it is
+// larger, or equal with a lower block index.  One wavefront per 64 queries; a row is spread over the
+// lanes (up to 4 columns each) and every lane counts, or sums, what ranks before its own entries.
+// Same outputs as mask_kernel.
+template <bool LOCAL_TOPK>
+__global__ __launch_bounds__(256) void local_mask_kernel(const float* __restrict__ P, unsigned int* __restrict__ mask,
+                                                         int* __restrict__ rowcnt, int* __restrict__ wcnt,
+                                                         int S, int nb, int n_waves, int topk, float tau) {
+    constexpr int MAXC = VMOBA_MAX_BLOCKS / 64;
+    __shared__ float sRow[4][VMOBA_MAX_BLOCKS];
+    __shared__ unsigned int sKeep[4][64][VMOBA_MAX_MASK_WORDS + 1];
+    const int bh = blockIdx.y;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int w = blockIdx.x * 4 + wv;
+    const bool active = w < n_waves;
+    const int q0 = active ? w * 64 : 0;
+    const int words = (nb + 31) / 32;
+    const int rows = active ? min(64, S - q0) : 0;
+    const int ncol = (nb + 63) / 64;
+    for (int r = 0; r < 64; ++r) {
+        const bool live = r < rows;
+        const float* row = P + ((long long)bh * S + q0 + (live ? r : 0)) * nb;
+        float v[MAXC];
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) {
+            const int j = c * 64 + lane;
+            v[c] = (c < ncol && j < nb) ? row[j] : -1.f;
+            if (c < ncol && j < nb) sRow[wv][j] = v[c];
+        }
+        __syncthreads();
+        float before[MAXC];
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) before[c] = 0.f;
+        for (int jp = 0; jp < nb; ++jp) {
+            const float x = sRow[wv][jp];
+#pragma unroll
+            for (int c = 0; c < MAXC; ++c) {
+                const int j = c * 64 + lane;
+                const bool first = (x > v[c]) || (x == v[c] && jp < j);
+                before[c] += first ? (LOCAL_TOPK ? 1.f : x) : 0.f;
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) {
+            const int j = c * 64 + lane;
+            const bool keep = live && c < ncol && j < nb && (LOCAL_TOPK ? before[c] < (float)topk : (tau >= 1.f || before[c] < tau));
+            const unsigned long long bal = __ballot(keep);
+            if (lane == 0 && c < ncol) {
+                sKeep[wv][r][2 * c] = (unsigned)bal;
+                if (2 * c + 1 <= VMOBA_MAX_MASK_WORDS) sKeep[wv][r][2 * c + 1] = (unsigned)(bal >> 32);
+            }
+        }
+        __syncthreads();
+    }
+    // lane = row
+    unsigned int mw[VMOBA_MAX_MASK_WORDS];
+    const int q = q0 + lane;
+    const bool live = lane < rows;
+    int cnt = 0;
+#pragma unroll
+    for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) {
+        unsigned int g = 0;
+        if (live && wd < words) {
+            g = sKeep[wv][lane][wd];
+            mask[((long long)bh * S + q) * words + wd] = g;
+            cnt += __popc(g);
+        }
+        mw[wd] = g;
+    }
+    if (live) rowcnt[(long long)bh * S + q] = cnt;
+    for (int j = 0; j < nb; ++j) {
+        unsigned int word = 0;
+#pragma unroll
+        for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) if (wd == (j >> 5)) word = mw[wd];
+        const unsigned long long bal = __ballot((word >> (j & 31)) & 1u);
+        if (lane == 0 && active) wcnt[((long long)bh * nb + j) * n_waves + w] = __popcll(bal);
+    }
+}
+
+// k_out / theta_out of the per-query modes: the number of kept pairs is the end of row_ptr.
+__global__ __launch_bounds__(64) void local_k_kernel(const int* __restrict__ row_ptr, long long* __restrict__ k_out,
+                                                     float* __restrict__ theta_out, int BH, int S) {
+    const int bh = blockIdx.x * 64 + threadIdx.x;
+    if (bh >= BH) return;
+    k_out[bh] = row_ptr[(long long)bh * (S + 1) + S];
+    theta_out[bh] = 0.f;
+}
+
 // Exclusive scan of wcnt over the wavefront index for every (head, block) (in place) and the
 // per-block totals.  One workgroup of 256 threads per (block, head).
 __global__ __launch_bounds__(256) void wave_scan_kernel(int* __restrict__ wcnt, int* __restrict__ blk_cnt,
@@ -718,7 +816,7 @@ size_t vmoba_select_workspace_bytes(int B, int Hh, int64_t S, int nb) {
 
 extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
                             const vmoba_tensor* Qp, const vmoba_tensor* Kp, float tau, float score_scale,
-                            int mode, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
+                            int mode, int32_t topk, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
                             int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
                             int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
                             void* workspace, size_t workspace_bytes, void* stream) {
@@ -727,8 +825,11 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
         !k_out || !theta_out || !dev_status || !workspace)
         return VMOBA_ERR_INVALID_ARG;
     if (!tensor_ok(Qp) || !tensor_ok(Kp)) return VMOBA_ERR_INVALID_ARG;
-    if (!(tau > 0.f) || !(tau <= 1.f) || !std::isfinite(score_scale)) return VMOBA_ERR_INVALID_ARG;
-    if (mode != 0) return VMOBA_ERR_UNSUPPORTED;
+    if (!std::isfinite(score_scale)) return VMOBA_ERR_INVALID_ARG;
+    if (mode < VMOBA_GLOBAL_THRESHOLD || mode > VMOBA_GLOBAL_TOPK) return VMOBA_ERR_UNSUPPORTED;
+    const bool uses_tau = mode == VMOBA_GLOBAL_THRESHOLD || mode == VMOBA_LOCAL_THRESHOLD;
+    if (uses_tau && (!(tau > 0.f) || !(tau <= 1.f))) return VMOBA_ERR_INVALID_ARG;
+    if (!uses_tau && topk < 1) return VMOBA_ERR_INVALID_ARG;
     if (D != 64 && D != 128) return VMOBA_ERR_UNSUPPORTED;
     if (Qp->dtype != Kp->dtype) return VMOBA_ERR_UNSUPPORTED;
     if (n_blocks > VMOBA_MAX_BLOCKS || S > ((int64_t)1 << 30) || S * n_blocks > (int64_t)INT32_MAX)
@@ -744,9 +845,12 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
     const int n_waves = (int)ceil_div64(S, 64);
     const long long pool = (long long)S * n_blocks;
     const int fix_shift = fix_shift_for(S);
-    // target mass tau * S in fixed point (rounded up); tau >= 1 asks for more than the pool can hold
+    // target of the head-global cut: mass tau * S in fixed point (rounded up; tau >= 1 asks for more than the
+    // pool can hold), or, for a fixed global k, the number of pairs topk * S
     unsigned long long target;
-    if (tau >= 1.f) {
+    if (mode == VMOBA_GLOBAL_TOPK) {
+        target = (unsigned long long)std::min<long long>((long long)topk * S, pool);
+    } else if (tau >= 1.f) {
         target = ~0ull;
     } else {
         target = (unsigned long long)std::ceil((double)tau * (double)S * (double)(1ull << fix_shift));
@@ -804,31 +908,48 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
     unsigned long long* hs2 = ws.hist_sum + (size_t)2 * BH * HIST_BINS;
     const unsigned refine_gx = (unsigned)std::max<int64_t>(1, std::min<int64_t>(ceil_div64(pool / 4, 256 * 8), 2048));
 
-    scan_level_kernel<0><<<dim3(BH), dim3(HIST_BINS), 0, st>>>(ws.hist_cnt, ws.hist_sum, ws.state, target, fix_shift,
-                                                              pool, (long long*)k_out, theta_out);
-    VMOBA_CHECK_LAUNCH();
-    refine_hist_kernel<1><<<dim3(refine_gx, BH), dim3(256), 0, st>>>(P, ws.state, hc1, hs1, pool, fix_shift);
-    VMOBA_CHECK_LAUNCH();
-    scan_level_kernel<1><<<dim3(BH), dim3(HIST_BINS), 0, st>>>(hc1, hs1, ws.state, target, fix_shift, pool,
-                                                              (long long*)k_out, theta_out);
-    VMOBA_CHECK_LAUNCH();
-    refine_hist_kernel<2><<<dim3(refine_gx, BH), dim3(256), 0, st>>>(P, ws.state, hc2, hs2, pool, fix_shift);
-    VMOBA_CHECK_LAUNCH();
-    scan_level_kernel<2><<<dim3(BH), dim3(HIST_BINS), 0, st>>>(hc2, hs2, ws.state, target, fix_shift, pool,
-                                                              (long long*)k_out, theta_out);
-    VMOBA_CHECK_LAUNCH();
-
-    const unsigned row_gx = (unsigned)std::min<int64_t>(ceil_div64(S, 4 * 8), 4096);
-    tie_count_kernel<<<dim3(row_gx, BH), dim3(256), 0, st>>>(P, ws.state, ws.ties, (int)S, n_blocks);
-    VMOBA_CHECK_LAUNCH();
-    row_scan_kernel<<<dim3(BH), dim3(SCAN_THREADS), 0, st>>>(ws.ties, ws.tie_base, ws.state, 1, (int)S);
-    VMOBA_CHECK_LAUNCH();
     const unsigned wave_gx = (unsigned)ceil_div64(n_waves, 4);
-    mask_kernel<<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, ws.state, ws.tie_base, mask, ws.rowcnt, ws.wcnt,
-                                                        (int)S, n_blocks, n_waves);
-    VMOBA_CHECK_LAUNCH();
+    const bool local = mode == VMOBA_LOCAL_TOPK || mode == VMOBA_LOCAL_THRESHOLD;
+    if (local) {
+        if (mode == VMOBA_LOCAL_TOPK)
+            local_mask_kernel<true><<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, mask, ws.rowcnt, ws.wcnt, (int)S, n_blocks, n_waves, topk, tau);
+        else
+            local_mask_kernel<false><<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, mask, ws.rowcnt, ws.wcnt, (int)S, n_blocks, n_waves, topk, tau);
+        VMOBA_CHECK_LAUNCH();
+    } else {
+#define SCAN_LEVEL(LV, HC, HS)                                                                                        \
+    do {                                                                                                              \
+        if (mode == VMOBA_GLOBAL_TOPK)                                                                                \
+            scan_level_kernel<LV, true><<<dim3(BH), dim3(HIST_BINS), 0, st>>>(HC, HS, ws.state, target, fix_shift, pool, (long long*)k_out, theta_out); \
+        else                                                                                                          \
+            scan_level_kernel<LV, false><<<dim3(BH), dim3(HIST_BINS), 0, st>>>(HC, HS, ws.state, target, fix_shift, pool, (long long*)k_out, theta_out); \
+    } while (0)
+        SCAN_LEVEL(0, ws.hist_cnt, ws.hist_sum);
+        VMOBA_CHECK_LAUNCH();
+        refine_hist_kernel<1><<<dim3(refine_gx, BH), dim3(256), 0, st>>>(P, ws.state, hc1, hs1, pool, fix_shift);
+        VMOBA_CHECK_LAUNCH();
+        SCAN_LEVEL(1, hc1, hs1);
+        VMOBA_CHECK_LAUNCH();
+        refine_hist_kernel<2><<<dim3(refine_gx, BH), dim3(256), 0, st>>>(P, ws.state, hc2, hs2, pool, fix_shift);
+        VMOBA_CHECK_LAUNCH();
+        SCAN_LEVEL(2, hc2, hs2);
+        VMOBA_CHECK_LAUNCH();
+#undef SCAN_LEVEL
+        const unsigned row_gx = (unsigned)std::min<int64_t>(ceil_div64(S, 4 * 8), 4096);
+        tie_count_kernel<<<dim3(row_gx, BH), dim3(256), 0, st>>>(P, ws.state, ws.ties, (int)S, n_blocks);
+        VMOBA_CHECK_LAUNCH();
+        row_scan_kernel<<<dim3(BH), dim3(SCAN_THREADS), 0, st>>>(ws.ties, ws.tie_base, ws.state, 1, (int)S);
+        VMOBA_CHECK_LAUNCH();
+        mask_kernel<<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, ws.state, ws.tie_base, mask, ws.rowcnt, ws.wcnt,
+                                                            (int)S, n_blocks, n_waves);
+        VMOBA_CHECK_LAUNCH();
+    }
     row_scan_kernel<<<dim3(BH), dim3(SCAN_THREADS), 0, st>>>(ws.rowcnt, row_ptr, ws.state, 0, (int)S);
     VMOBA_CHECK_LAUNCH();
+    if (local) {
+        local_k_kernel<<<dim3((BH + 63) / 64), dim3(64), 0, st>>>(row_ptr, (long long*)k_out, theta_out, BH, (int)S);
+        VMOBA_CHECK_LAUNCH();
+    }
     wave_scan_kernel<<<dim3(n_blocks, BH), dim3(256), 0, st>>>(ws.wcnt, ws.blk_cnt, n_blocks, n_waves);
     VMOBA_CHECK_LAUNCH();
     blk_ptr_kernel<<<dim3(BH), dim3(64), 0, st>>>(ws.blk_cnt, blk_ptr, n_blocks, (long long)nnz_capacity, dev_status);

@@ -22,7 +22,10 @@ CONFIGS = {
     "mid": dict(grid=(9, 30, 52), heads=12, D=128, dtype="bf16", sigma=2.0, seed=2000,
                 partitions={"3d": (3, 10, 13, 0)}),
     "480p": dict(grid=(21, 30, 52), heads=12, D=128, dtype="bf16", sigma=2.0, seed=3000,
-                 partitions={"1d": (0, 0, 0, 1560), "2d": (1, 15, 26, 0), "3d": (3, 15, 13, 0)}),
+                 # the *_tf entries are the block sizes of the paper's training-free runs at this
+                 # resolution (App. A, hyperparameter table): 7 | 24 | 72 blocks
+                 partitions={"1d": (0, 0, 0, 1560), "2d": (1, 15, 26, 0), "3d": (3, 15, 13, 0),
+                             "1d_tf": (3, 30, 52, 0), "2d_tf": (21, 5, 13, 0), "3d_tf": (7, 5, 13, 0)}),
     "720p": dict(grid=(21, 45, 80), heads=12, D=128, dtype="bf16", sigma=2.0, seed=4000,
                  partitions={"1d": (0, 0, 0, 2100), "2d": (1, 30, 40, 0), "2d_half": (1, 45, 40, 0),
                              "3d": (3, 15, 40, 0)}),

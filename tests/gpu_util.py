@@ -25,11 +25,11 @@ def unpack_mask(words: np.ndarray, nb: int) -> np.ndarray:
 
 
 def run_gpu(Q, K, V, dO, grid, block=(0, 0, 0), chunk=0, tau=0.25, dtype=torch.float32,
-            score_scale=None, softmax_scale=None):
+            score_scale=None, softmax_scale=None, mode=0, topk=0):
     """Whole layer on the GPU.  Q, K, V, dO: numpy [B, S, Hh, D] float32 (dO may be None)."""
     B, S, Hh, D = Q.shape
     plan = vb.LayerPlan(B, Hh, D, grid, block, chunk, tau, dtype, score_scale=score_scale,
-                        softmax_scale=softmax_scale, need_bwd=dO is not None)
+                        softmax_scale=softmax_scale, need_bwd=dO is not None, mode=mode, topk=topk)
     assert plan.S == S
     q, k, v = (to_dev(x, dtype) for x in (Q, K, V))
     plan.forward(q, k, v)
@@ -77,11 +77,41 @@ def check_lists(g, b, h):
     assert np.array_equal(blk_of_entry[pp], col_idx)
 
 
-def check_selection(g, o, b, h, band_tol=1e-6):
+def undecided_local_threshold(P, tau, eps=1e-6, chunk=2048):
+    """Per-query threshold selection: the entries whose membership the rounding of P (eps per
+    entry) can change.  Entry j is certainly kept when even the mass of everything that could
+    rank before it (values >= P_j - eps) stays below tau, certainly dropped when the mass of what
+    must rank before it (values > P_j + eps) already reaches tau; the rest is undecided."""
+    S, nb = P.shape
+    und = np.zeros((S, nb), dtype=bool)
+    P64 = P.astype(np.float64)
+    slack = nb * eps
+    for a in range(0, S, chunk):
+        x = P64[a:a + chunk]
+        ge = x[:, None, :] >= x[:, :, None] - eps          # [row, j, j']: j' could rank before j
+        gt = x[:, None, :] > x[:, :, None] + eps           # j' must rank before j
+        idx = np.arange(nb)
+        ge[:, idx, idx] = False
+        hi = (ge * x[:, None, :]).sum(-1)
+        lo = (gt * x[:, None, :]).sum(-1)
+        und[a:a + chunk] = ~((hi + slack < tau) | (lo - slack >= tau))
+    return und
+
+
+def check_selection(g, o, b, h, band_tol=1e-6, mode=0, tau=None):
     """Selection of head (b, h): GPU (g) against oracle (o).  Pairs whose oracle P lies within
-    band_tol of the oracle threshold are exempt (they flip with summation order)."""
-    P_or, th_or = o["P"][b, h], o["theta"][b, h]
-    band = np.abs(P_or - th_or) <= band_tol
+    band_tol of the deciding value are exempt (they flip with the rounding of P): the head's
+    threshold for the global modes, the row's last kept value for per-query top-k; for the
+    per-query threshold see undecided_local_threshold."""
+    P_or, m_or = o["P"][b, h], o["mask"][b, h]
+    if mode in (0, 3):
+        band = np.abs(P_or - o["theta"][b, h]) <= band_tol
+    elif mode == 1:
+        kth = np.where(m_or, P_or, np.inf).min(axis=1, keepdims=True)
+        band = np.abs(P_or - kth) <= band_tol
+        assert np.all(g["mask"][b, h].sum(1) == m_or.sum(1))           # every query keeps exactly k blocks
+    else:
+        band = undecided_local_threshold(P_or, float(np.float32(tau)), band_tol)
     diff = g["mask"][b, h] != o["mask"][b, h]
     assert not (diff & ~band).any(), f"{(diff & ~band).sum()} mask bits differ outside the band"
     assert abs(int(g["k"][b, h]) - int(o["k"][b, h])) <= int(band.sum())

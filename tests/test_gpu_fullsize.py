@@ -36,14 +36,16 @@ def gu_rel(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
 
 
-def check_layer_sampled(name, kind, tau, heads=None, bwd=True, sel_heads=None, groups=2, max_rows=20000):
+def check_layer_sampled(name, kind, tau, heads=None, bwd=True, sel_heads=None, groups=2, max_rows=20000,
+                        mode=0, topk=0):
     Q, K, V, dO = get_inputs(name, heads)
     c = synth.CONFIGS[name]
     bt, bh, bw, chunk = c["partitions"][kind]
     D, Hh = c["D"], Q.shape[2]
     scale = 1.0 / math.sqrt(D)
     print(f"[fullsize] {name} {kind} tau={tau} heads={Hh} bwd={bwd}: GPU layer", flush=True)
-    plan = vb.LayerPlan(1, Hh, D, c["grid"], (bt, bh, bw), chunk, tau, torch.bfloat16, need_bwd=bwd)
+    plan = vb.LayerPlan(1, Hh, D, c["grid"], (bt, bh, bw), chunk, tau, torch.bfloat16, need_bwd=bwd,
+                        mode=mode, topk=topk)
     dev = [gu.to_dev(x, torch.bfloat16) for x in ((Q, K, V, dO) if bwd else (Q, K, V))]
     plan.forward(*dev[:3])
     if bwd:
@@ -78,11 +80,11 @@ def check_layer_sampled(name, kind, tau, heads=None, bwd=True, sel_heads=None, g
              row_ptr=row_ptr.reshape(1, Hh, S + 1), q_idx=q_idx[None], col_idx=col_idx[None], pair_pos=pair_pos[None])
     P_gpu = plan.P.cpu().numpy()[0]
     for h in (range(Hh) if sel_heads is None else sel_heads):
-        sel = vo.select_blocks(Qp_all[h], Kp_all[h], off, tau, scale)
+        sel = vo.select_blocks(Qp_all[h], Kp_all[h], off, tau, scale, mode, topk)
         o = dict(P=sel["P"][None, None], theta=np.array([[sel["theta"]]]), mask=sel["mask"][None, None],
                  k=np.array([[sel["k"]]]))
         gh = dict(mask=mask_gpu[None, h:h + 1], k=k_gpu[h:h + 1].reshape(1, 1))
-        nband, ndiff = gu.check_selection(gh, o, 0, 0)
+        nband, ndiff = gu.check_selection(gh, o, 0, 0, mode=mode, tau=tau)
         assert np.abs(P_gpu[h] - sel["P"]).max() <= 5e-7
         gu.check_lists(g, 0, h)
         print(f"   head {h}: k_gpu={k_gpu[h]} k_oracle={sel['k']} band={nband} flipped={ndiff} "
@@ -136,6 +138,21 @@ def test_480p_layer_sampled(kind):
 
 def test_480p_tau_half():
     check_layer_sampled("480p", "3d", 0.5, sel_heads=[0, 5, 11])
+
+
+@pytest.mark.parametrize("kind,topk,n_blocks", [("1d_tf", 2, 7), ("2d_tf", 6, 24), ("3d_tf", 18, 72)])
+def test_480p_local_topk(kind, topk, n_blocks):
+    """The training-free setting (App. A, hyperparameter table): per-query top-k with k = 2 | 6 | 18 of
+    7 | 24 | 72 blocks for the 1D | 2D | 3D layers at 480p; forward only, as in inference."""
+    c = synth.CONFIGS["480p"]
+    assert len(vo.partition_index(*c["grid"], *c["partitions"][kind])[2]) - 1 == n_blocks
+    check_layer_sampled("480p", kind, 0.25, bwd=False, sel_heads=[0, 6], mode=vb.LOCAL_TOPK, topk=topk, max_rows=12000)
+
+
+def test_480p_other_variants():
+    """Per-query threshold and global top-k at full size, forward and backward."""
+    check_layer_sampled("480p", "3d", 0.25, sel_heads=[3], groups=1, mode=vb.LOCAL_THRESHOLD)
+    check_layer_sampled("480p", "3d", 0.25, sel_heads=[9], groups=1, mode=vb.GLOBAL_TOPK, topk=18)
 
 
 @pytest.mark.parametrize("kind", ["2d", "3d"])

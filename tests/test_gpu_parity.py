@@ -11,7 +11,7 @@ import pytest
 import torch
 
 from oracle import vmoba_oracle as vo
-from paper_2506_23858_amd import synth
+from paper_2506_23858_amd import binding as vb, synth
 from tests import gpu_util as gu
 
 pytestmark = pytest.mark.gpu
@@ -44,11 +44,11 @@ def oracle_with_gpu_mask(g, Q, K, V, dO, softmax_scale):
     return res
 
 
-def compare_layer(Q, K, V, dO, grid, block, chunk, tau, dtype, label=""):
+def compare_layer(Q, K, V, dO, grid, block, chunk, tau, dtype, label="", mode=0, topk=0):
     B, S, Hh, D = Q.shape
     print(f"[parity] {label} S={S} Hh={Hh} D={D} grid={grid} block={block} chunk={chunk} tau={tau} {dtype}", flush=True)
-    g = gu.run_gpu(Q, K, V, dO, grid, block, chunk, tau, dtype)
-    o = vo.vmoba_layer(Q, K, V, grid, block, tau, dO=None, chunk=chunk)   # selection + its own attention
+    g = gu.run_gpu(Q, K, V, dO, grid, block, chunk, tau, dtype, mode=mode, topk=topk)
+    o = vo.vmoba_layer(Q, K, V, grid, block, tau, dO=None, chunk=chunk, mode=mode, topk=topk)   # selection + its own attention
     # --- partition: bit exact
     assert np.array_equal(g["perm"], o["perm"])
     assert np.array_equal(g["inv_perm"], o["inv_perm"])
@@ -62,9 +62,11 @@ def compare_layer(Q, K, V, dO, grid, block, chunk, tau, dtype, label=""):
     np.testing.assert_allclose(g["P"].sum(-1, dtype=np.float64), 1.0, atol=2e-6)
     for b in range(B):
         for h in range(Hh):
-            nband, ndiff = gu.check_selection(g, o, b, h)
+            nband, ndiff = gu.check_selection(g, o, b, h, mode=mode, tau=tau)
             gu.check_lists(g, b, h)
-            if int(g["k"][b, h]) < S * g["nb"]:      # theta is reported as 0 when every pair is kept
+            if mode in (1, 2):
+                assert g["theta"][b, h] == 0
+            elif int(g["k"][b, h]) < S * g["nb"]:      # theta is reported as 0 when every pair is kept
                 np.testing.assert_allclose(g["theta"][b, h], o["theta"][b, h], atol=1e-6)
             print(f"   head {h}: k_gpu={g['k'][b, h]} k_oracle={o['k'][b, h]} band={nband} flipped={ndiff}", flush=True)
     # --- attention under the GPU's own mask
@@ -114,6 +116,58 @@ def test_ragged_grids_fp32(grid, block, chunk, D):
     S = grid[0] * grid[1] * grid[2]
     Q, K, V, dO = (synth.iid_normal(70 + i, (1, S, 2, D)) for i in range(4))
     compare_layer(Q, K, V, dO, grid, block, chunk, 0.3, torch.float32, "ragged")
+
+
+# ------------------------------------------------------------ block-choice variants (Sec. 4.3, App. A)
+@pytest.mark.parametrize("kind,topk", [("1d", 1), ("2d", 2), ("3d", 4), ("3d", 16), ("3d", 99)])
+def test_local_topk_fp32(kind, topk):
+    """Per-query top-k, the setting of the training-free runs; k = 16 and 99 keep every block."""
+    c = synth.CONFIGS["tiny"]
+    Q, K, V, dO = synth.make_qkv("tiny")
+    bt, bh, bw, chunk = c["partitions"][kind]
+    g, o = compare_layer(Q, K, V, dO, c["grid"], (bt, bh, bw), chunk, 0.25, torch.float32, f"local-topk-{kind}",
+                         mode=vb.LOCAL_TOPK, topk=topk)
+    assert np.all(g["mask"].sum(-1) == min(topk, g["nb"]))
+
+
+@pytest.mark.parametrize("tau", [0.25, 0.6, 1.0])
+def test_local_threshold_fp32(tau):
+    c = synth.CONFIGS["tiny"]
+    Q, K, V, dO = synth.make_qkv("tiny")
+    g, o = compare_layer(Q, K, V, dO, c["grid"], (2, 4, 4), 0, tau, torch.float32, "local-threshold",
+                         mode=vb.LOCAL_THRESHOLD)
+    assert np.all(g["mask"].sum(-1) >= 1)           # a query always keeps its best block
+
+
+@pytest.mark.parametrize("topk", [1, 3, 16])
+def test_global_topk_fp32(topk):
+    c = synth.CONFIGS["tiny"]
+    Q, K, V, dO = synth.make_qkv("tiny")
+    g, o = compare_layer(Q, K, V, dO, c["grid"], (2, 4, 4), 0, 0.25, torch.float32, "global-topk",
+                         mode=vb.GLOBAL_TOPK, topk=topk)
+    assert np.all(g["k"] == min(topk, g["nb"]) * 512)
+
+
+def test_variants_ragged_bf16():
+    """The three variants on a ragged grid (blocks of 1..24 tokens, 70 blocks > one mask word) in bfloat16."""
+    grid, block = (5, 7, 9), (1, 2, 3)
+    S = grid[0] * grid[1] * grid[2]
+    Q, K, V, dO = (synth.to_bf16_grid(synth.iid_normal(90 + i, (1, S, 2, 64))) for i in range(4))
+    for mode, topk, tau in ((vb.LOCAL_TOPK, 5, 0.25), (vb.LOCAL_THRESHOLD, 0, 0.3), (vb.GLOBAL_TOPK, 7, 0.25)):
+        compare_layer(Q, K, V, dO, grid, block, 0, tau, torch.bfloat16, f"ragged-mode{mode}", mode=mode, topk=topk)
+
+
+def test_local_topk_with_equal_scores_takes_lowest_indices():
+    """All keys equal -> every block scores the same for every query; ties go to the lower block index."""
+    S, D = 512, 64
+    Q = synth.iid_normal(5, (1, S, 1, D))
+    K = np.ones((1, S, 1, D), dtype=np.float32)
+    V = synth.iid_normal(6, (1, S, 1, D))
+    g = gu.run_gpu(Q, K, V, None, (8, 8, 8), (2, 4, 4), 0, 0.25, torch.float32, mode=vb.LOCAL_TOPK, topk=3)
+    assert g["mask"][0, 0][:, :3].all() and not g["mask"][0, 0][:, 3:].any()
+    g = gu.run_gpu(Q, K, V, None, (8, 8, 8), (2, 4, 4), 0, 0.25, torch.float32, mode=vb.GLOBAL_TOPK, topk=3)
+    m = g["mask"][0, 0].reshape(-1)
+    assert m[:3 * S].all() and not m[3 * S:].any()           # pool order: ascending (query, block)
 
 
 def test_tau_one_is_dense_attention():

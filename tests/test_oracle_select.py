@@ -149,3 +149,66 @@ def test_csr_views_are_consistent():
         rebuilt2[q, cs] = True
     assert np.array_equal(rebuilt2, mask)
     assert row_ptr[5] == row_ptr[6]
+
+
+# ----------------------------------------------------------------- selection variants (ablation)
+def _rank_before(row, j):
+    """Brute force: entries of `row` ranked before entry j (larger value, or equal and lower index)."""
+    return [i for i in range(len(row)) if row[i] > row[j] or (row[i] == row[j] and i < j)]
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_local_topk_brute_force(seed):
+    rng = np.random.default_rng(200 + seed)
+    S, nb, k = 9, 7, int(rng.integers(1, 7))
+    P = vo.normalise_rows((rng.standard_normal((S, nb)) * 2).astype(np.float32))
+    P[3] = np.float32(1.0 / nb)                       # a row of ties: lowest block indices win
+    mask = vo.local_topk(P, k)
+    assert np.all(mask.sum(1) == k)
+    for q in range(S):
+        for j in range(nb):
+            assert mask[q, j] == (len(_rank_before(P[q], j)) < k)
+    assert mask[3, :k].all() and not mask[3, k:].any()
+    assert vo.local_topk(P, nb + 5).all()
+
+
+@pytest.mark.parametrize("tau", [0.2, 0.5, 0.9])
+def test_local_threshold_brute_force(tau):
+    rng = np.random.default_rng(300)
+    P = vo.normalise_rows((rng.standard_normal((12, 6)) * 2).astype(np.float32))
+    mask = vo.local_threshold(P, tau)
+    t32 = float(np.float32(tau))
+    for q in range(12):
+        for j in range(6):
+            before = math.fsum(float(P[q, i]) for i in _rank_before(P[q], j))
+            if abs(before - t32) > 1e-9:
+                assert mask[q, j] == (before < t32)
+        # the kept mass reaches tau, and dropping the weakest kept block would fall short
+        kept = np.sort(P[q][mask[q]].astype(np.float64))[::-1]
+        assert kept.sum() >= t32 - 1e-7 and kept[:-1].sum() < t32 + 1e-7
+    assert np.all(mask.sum(1) >= 1)
+    assert vo.local_threshold(P, 1.0).all()
+
+
+def test_global_topk_matches_threshold_machinery():
+    rng = np.random.default_rng(301)
+    P = vo.normalise_rows((rng.standard_normal((20, 5)) * 2).astype(np.float32))
+    k, theta, mask = vo.global_topk(P, 37)
+    assert k == 37 and mask.sum() == 37
+    flat = np.sort(P.reshape(-1))[::-1]
+    assert theta == flat[36] and P[mask].min() >= P[~mask].max()
+    # the threshold rule with the mass of those 37 pairs as tau picks the same set
+    tau = float(flat[:37].astype(np.float64).sum() / 20)
+    k2, _, mask2 = vo.threshold_topk(P, np.nextafter(np.float32(tau), np.float32(0)))
+    assert k2 == 37 and np.array_equal(mask2, mask)
+    k_all, _, m_all = vo.global_topk(P, 10 ** 6)
+    assert k_all == 100 and m_all.all()
+
+
+def test_select_blocks_modes_feed_the_layer():
+    from paper_2506_23858_amd import synth
+    Q, K, V, dO = synth.make_qkv("tiny")
+    out = vo.vmoba_layer(Q, K, V, (4, 8, 16), (2, 4, 4), tau=0.25, mode=vo.MODE_LOCAL_TOPK, topk=3)
+    assert np.all(out["mask"].sum(-1) == 3)
+    out = vo.vmoba_layer(Q, K, V, (4, 8, 16), (2, 4, 4), tau=0.25, mode=vo.MODE_GLOBAL_TOPK, topk=3)
+    assert np.all(out["mask"].sum((-1, -2)) == 3 * 512)
