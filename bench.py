@@ -100,6 +100,75 @@ def cpu_baseline(Q, K, V, dO, cfg, part, tau, rows=16384):
             "seconds_per_head_est": est}
 
 
+def sweep(args):
+    """Sequence-length sweep in the shape of the paper's latency-vs-length figure (Fig. 1b): the 480p frame
+    (30 x 52 latent tokens) with 9..72 latent frames, 12 heads x 128, the three partitions of the 480p
+    workload, tau = 0.25, sparse layer fwd+bwd (all steps) next to PyTorch's dense attention fwd+bwd."""
+    import numpy as np
+    import torch
+    from paper_2506_23858_amd import binding as vb, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    Hh, D, dtype = 12, 128, torch.bfloat16
+    frames = [int(x) for x in args.sweep_frames.split(",")]
+    points = []
+    for T in frames:
+        grid = (T, 30, 52)
+        S = T * 30 * 52
+        t_gen = time.perf_counter()
+        ts = [torch.from_numpy(synth.to_bf16_grid(synth.blurred_noise(7000 + 10 * T + i, grid, Hh, D, 2.0))).to("cuda").to(dtype)
+              for i in range(4)]
+        Q, K, V, dO = ts
+        print(f"[sweep] T={T} S={S}: inputs in {time.perf_counter() - t_gen:.1f} s", file=sys.stderr, flush=True)
+        pt = {"frames": T, "tokens": S, "kinds": {}}
+        for kind, (block, chunk) in {"1d": ((0, 0, 0), 1560), "2d": ((1, 15, 26), 0), "3d": ((3, 15, 13), 0)}.items():
+            nb = S // 1560 if chunk else -(-T // block[0]) * 2 * (52 // block[2])
+            if nb > 256:
+                pt["kinds"][kind] = None          # more key blocks than the library's mask words hold
+                continue
+            p = vb.LayerPlan(1, Hh, D, grid, block, chunk, args.tau, dtype)
+            p.forward(Q, K, V); p.backward(dO)
+            torch.cuda.synchronize()
+            assert int(p.dev_status.item()) == 0
+            reps = 4
+            t = time.perf_counter()
+            for _ in range(reps):
+                p.forward(Q, K, V); p.backward(dO)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t) * 1e3 / reps
+            keysum, pairs = selected_key_sum(p)
+            pt["kinds"][kind] = {"ms_per_layer": ms, "n_blocks": p.nb, "selected_pair_fraction": pairs / (Hh * S * p.nb),
+                                 "effective_tflops": 14.0 * D * keysum / (ms * 1e-3) / 1e12}
+            del p
+            torch.cuda.empty_cache()
+        done = [v["ms_per_layer"] for v in pt["kinds"].values() if v]
+        pt["sparse_ms_mean_over_kinds"] = sum(done) / len(done)
+        q, k, v = (x.permute(0, 2, 1, 3).detach().clone().requires_grad_(True) for x in (Q, K, V))
+        g = dO.permute(0, 2, 1, 3).contiguous()
+        def sdpa():
+            torch.nn.functional.scaled_dot_product_attention(q, k, v).backward(g)
+            q.grad = k.grad = v.grad = None
+        sdpa()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(2):
+            sdpa()
+        torch.cuda.synchronize()
+        pt["torch_sdpa_fwd_bwd_ms"] = (time.perf_counter() - t) * 1e3 / 2
+        pt["speedup_vs_torch_sdpa"] = pt["torch_sdpa_fwd_bwd_ms"] / pt["sparse_ms_mean_over_kinds"]
+        points.append(pt)
+        print(f"[sweep] {json.dumps(pt)}", file=sys.stderr, flush=True)
+        del q, k, v, g, Q, K, V, dO, ts
+        torch.cuda.empty_cache()
+    lt = np.log([p["tokens"] for p in points])
+    fit = {"dense_exponent": float(np.polyfit(lt, np.log([p["torch_sdpa_fwd_bwd_ms"] for p in points]), 1)[0]),
+           "sparse_exponent": float(np.polyfit(lt, np.log([p["sparse_ms_mean_over_kinds"] for p in points]), 1)[0])}
+    print(json.dumps({"metric": "sequence-length sweep: VMoBA layer fwd+bwd ms vs dense (torch SDPA) ms", "tau": args.tau,
+                      "heads": Hh, "D": D, "dtype": "bf16", "data": "synthetic", "points": points,
+                      "log_log_slope": fit}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -110,11 +179,16 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense comparators")
     ap.add_argument("--kinds", default="1d,2d,3d")
+    ap.add_argument("--sweep", action="store_true", help="sequence-length sweep instead of the benchmark line")
+    ap.add_argument("--sweep-frames", default="9,15,21,36,48,72")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; --gpus must be 1 (the path shards by head, see DESIGN.md)",
               file=sys.stderr)
         sys.exit(2)
+
+    if args.sweep:
+        return sweep(args)
 
     import torch
     from paper_2506_23858_amd import binding as vb, synth
