@@ -127,7 +127,7 @@ def sweep(args):
             if nb > 256:
                 pt["kinds"][kind] = None          # more key blocks than the library's mask words hold
                 continue
-            p = vb.LayerPlan(1, Hh, D, grid, block, chunk, args.tau, dtype)
+            p = vb.LayerPlan(1, Hh, D, grid, block, chunk, args.tau, dtype, fused_io=True)
             p.forward(Q, K, V); p.backward(dO)
             torch.cuda.synchronize()
             assert int(p.dev_status.item()) == 0
@@ -211,7 +211,7 @@ def main():
     plans = {}
     for kind in kinds:
         bt, bh, bw, chunk = cfg["partitions"][kind]
-        plans[kind] = vb.LayerPlan(1, Hh, D, cfg["grid"], (bt, bh, bw), chunk, args.tau, dtype)
+        plans[kind] = vb.LayerPlan(1, Hh, D, cfg["grid"], (bt, bh, bw), chunk, args.tau, dtype, fused_io=True)
 
     def step(i):
         p = plans[kinds[i % len(kinds)]]
@@ -267,9 +267,9 @@ def main():
 
     # ---- per-call breakdown (outside the timed region), per kind
     def timed_calls(p):
-        names = ["partition", "select", "attn_fwd", "unpartition_O", "partition_dO", "attn_bwd", "unpartition_grads"]
-        fns = [lambda: p.partition(Q, K, V), p.select, p.attn_fwd, p.unpartition_out,
-               lambda: p.partition_dO(dO), p.attn_bwd, p.unpartition_grads]
+        # the attention calls read dO and write O, dQ, dK, dV in the caller's token order (row map = perm)
+        names = ["partition", "select", "attn_fwd", "attn_bwd"]
+        fns = [lambda: p.partition(Q, K, V), p.select, p.attn_fwd, lambda: p.attn_bwd(dO)]
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(fns) + 1)]
         evs[0].record()
         for f, e in zip(fns, evs[1:]):
@@ -288,7 +288,6 @@ def main():
         sel_bytes = 2 * row_bytes + Hh * S * nbk * 4 + Hh * S * ((nbk + 31) // 32) * 4 + 3 * 4 * pairs[kind]
         mem_steps[kind] = {
             "partition_qkv_GBps": 3 * 2 * row_bytes / (bd["partition"] * 1e-3) / 1e9,
-            "unpartition_grads_GBps": 3 * 2 * row_bytes / (bd["unpartition_grads"] * 1e-3) / 1e9,
             "select_GBps": sel_bytes / (bd["select"] * 1e-3) / 1e9,
             "select_algorithmic_bytes": sel_bytes}
     empty_rows = {kind: float((p.row_ptr[:, 1:] == p.row_ptr[:, :-1]).float().mean().item()) for kind, p in plans.items()}
@@ -331,7 +330,7 @@ def main():
     if abs(args.tau - 0.5) > 1e-9 and "3d" in cfg["partitions"]:
         try:
             bt, bh, bw, chunk = cfg["partitions"]["3d"]
-            p5 = vb.LayerPlan(1, Hh, D, cfg["grid"], (bt, bh, bw), chunk, 0.5, dtype)
+            p5 = vb.LayerPlan(1, Hh, D, cfg["grid"], (bt, bh, bw), chunk, 0.5, dtype, fused_io=True)
             p5.forward(Q, K, V); p5.backward(dO)
             torch.cuda.synchronize()
             t = time.perf_counter()
@@ -373,7 +372,7 @@ def main():
             for p in plans.values():
                 p.ws_attn = None
             torch.cuda.empty_cache()
-            pd = vb.LayerPlan(1, Hh, D, cfg["grid"], (bt, bh, bw), chunk, 1.0, dtype)
+            pd = vb.LayerPlan(1, Hh, D, cfg["grid"], (bt, bh, bw), chunk, 1.0, dtype, fused_io=True)
             pd.forward(Q, K, V); pd.backward(dO)
             torch.cuda.synchronize()
             t = time.perf_counter()

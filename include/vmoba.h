@@ -163,23 +163,30 @@ int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_
  * the selected blocks; LSE [B, Hh, S] float32 is the natural-log-sum-exp of the scaled scores.
  * A query that selected nothing gets O = 0 and LSE = -inf.
  * Inputs: block-order Q', K', V', blk_off, and the lists written by vmoba_select with the same
- * nnz_capacity.  O is written in block order.  Accumulation and soft-max are float32; bfloat16
- * inputs are multiplied on the matrix cores.
+ * nnz_capacity.  Accumulation and soft-max are float32; bfloat16 inputs are multiplied on the
+ * matrix cores.
+ *  out_rows  optional int32 [S].  Null: O is written in block order.  Otherwise block-order row q
+ *            goes to row out_rows[q] of O: pass the partition's perm and a tensor in the caller's
+ *            token order to skip the inverse partition of O.  LSE stays in block order either way.
  */
 int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
                    const vmoba_tensor* Qp, const vmoba_tensor* Kp, const vmoba_tensor* Vp,
                    const int32_t* blk_ptr, const int32_t* q_idx, const int32_t* row_ptr,
                    const int32_t* pair_pos, int64_t nnz_capacity, float softmax_scale,
-                   const vmoba_tensor* O, float* LSE, void* workspace, size_t workspace_bytes,
-                   void* stream);
+                   const vmoba_tensor* O, float* LSE, const int32_t* out_rows, void* workspace,
+                   size_t workspace_bytes, void* stream);
 
 /*
  * vmoba_attn_bwd -- gradient of vmoba_attn_fwd with the selection held fixed (the paper trains
  * through Step 3; the hard selection of Step 2 passes no gradient).  With A the attention
  * weights over the selected keys: delta = rowsum(dO * O), dV = A^T dO, dP = dO V^T,
  * dS = A * (dP - delta), dQ = softmax_scale * dS K, dK = softmax_scale * dS^T Q.
- * O and LSE are the forward results; all tensors in block order; dQ, dK, dV are written
- * (not accumulated into).  Rows that selected nothing get dQ = 0 and contribute nothing.
+ * O and LSE are the forward results; dQ, dK, dV are written (not accumulated into).  Rows that
+ * selected nothing get dQ = 0 and contribute nothing.
+ *  rows  optional int32 [S].  Null: all tensors are in block order.  Otherwise O, dO, dQ, dK and dV
+ *        (not Q', K', V', LSE) are addressed through it -- block-order row r is row rows[r] of each:
+ *        pass the partition's perm and tensors in the caller's token order to skip the partition
+ *        of dO and the inverse partition of the three gradients.
  */
 int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
                    const vmoba_tensor* Qp, const vmoba_tensor* Kp, const vmoba_tensor* Vp,
@@ -187,7 +194,7 @@ int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int3
                    const int32_t* blk_ptr, const int32_t* q_idx, const int32_t* row_ptr,
                    const int32_t* pair_pos, int64_t nnz_capacity, float softmax_scale,
                    const vmoba_tensor* dQ, const vmoba_tensor* dK, const vmoba_tensor* dV,
-                   void* workspace, size_t workspace_bytes, void* stream);
+                   const int32_t* rows, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * vmoba_profile_events -- measurement aid, not part of the method.  Asks the library to record

@@ -69,14 +69,14 @@ def lib():
     L.vmoba_select.restype = C.c_int
     L.vmoba_attn_fwd.argtypes = [C.c_int, C.c_int, C.c_int64, C.c_int, C.c_int32, P,
                                  C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor),
-                                 P, P, P, P, C.c_int64, C.c_float, C.POINTER(vmoba_tensor), P, P, C.c_size_t, P]
+                                 P, P, P, P, C.c_int64, C.c_float, C.POINTER(vmoba_tensor), P, P, P, C.c_size_t, P]
     L.vmoba_attn_fwd.restype = C.c_int
     L.vmoba_attn_bwd.argtypes = [C.c_int, C.c_int, C.c_int64, C.c_int, C.c_int32, P,
                                  C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor),
                                  C.POINTER(vmoba_tensor), P, C.POINTER(vmoba_tensor),
                                  P, P, P, P, C.c_int64, C.c_float,
                                  C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor),
-                                 P, C.c_size_t, P]
+                                 P, P, C.c_size_t, P]
     L.vmoba_attn_bwd.restype = C.c_int
     L.vmoba_profile_events.argtypes = [C.c_int, P, P]
     L.vmoba_profile_events.restype = C.c_int
@@ -176,22 +176,22 @@ def vmoba_select(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode,
 
 
 def vmoba_attn_fwd(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, Vp, blk_ptr, q_idx, row_ptr, pair_pos,
-                   nnz_capacity, softmax_scale, O, LSE, workspace, stream=None):
+                   nnz_capacity, softmax_scale, O, LSE, workspace, stream=None, out_rows=None):
     q, k, v, o = tensor_desc(Qp), tensor_desc(Kp), tensor_desc(Vp), tensor_desc(O)
     rc = lib().vmoba_attn_fwd(B, Hh, S, D, n_blocks, _ptr(blk_off), C.byref(q), C.byref(k), C.byref(v),
                               _ptr(blk_ptr), _ptr(q_idx), _ptr(row_ptr), _ptr(pair_pos), int(nnz_capacity),
-                              float(softmax_scale), C.byref(o), _ptr(LSE), _ptr(workspace),
+                              float(softmax_scale), C.byref(o), _ptr(LSE), _ptr(out_rows), _ptr(workspace),
                               workspace.numel() * workspace.element_size(), _stream(stream))
     _check("vmoba_attn_fwd", rc)
 
 
 def vmoba_attn_bwd(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, Vp, O, LSE, dO, blk_ptr, q_idx, row_ptr,
-                   pair_pos, nnz_capacity, softmax_scale, dQ, dK, dV, workspace, stream=None):
+                   pair_pos, nnz_capacity, softmax_scale, dQ, dK, dV, workspace, stream=None, rows=None):
     d = [tensor_desc(t) for t in (Qp, Kp, Vp, O, dO, dQ, dK, dV)]
     rc = lib().vmoba_attn_bwd(B, Hh, S, D, n_blocks, _ptr(blk_off), C.byref(d[0]), C.byref(d[1]), C.byref(d[2]),
                               C.byref(d[3]), _ptr(LSE), C.byref(d[4]), _ptr(blk_ptr), _ptr(q_idx),
                               _ptr(row_ptr), _ptr(pair_pos), int(nnz_capacity), float(softmax_scale),
-                              C.byref(d[5]), C.byref(d[6]), C.byref(d[7]), _ptr(workspace),
+                              C.byref(d[5]), C.byref(d[6]), C.byref(d[7]), _ptr(rows), _ptr(workspace),
                               workspace.numel() * workspace.element_size(), _stream(stream))
     _check("vmoba_attn_bwd", rc)
 
@@ -200,11 +200,15 @@ def vmoba_attn_bwd(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, Vp, O, LSE, dO, blk_p
 class LayerPlan:
     """All device buffers of one layer geometry, allocated once (PyTorch is only the allocator).
     The methods call the C ABI in the order partition -> select -> attn_fwd -> attn_bwd ->
-    inverse partition and allocate nothing."""
+    inverse partition and allocate nothing.  With fused_io the attention calls read dO and write O,
+    dQ, dK, dV in the caller's token order themselves (row map = perm): no partition of dO, no
+    inverse partitions, and the block-order copies Op, dOp, dQp, dKp, dVp do not exist."""
 
     def __init__(self, B, Hh, D, grid, block=(0, 0, 0), chunk=0, tau=0.25, dtype=torch.bfloat16,
-                 device="cuda", score_scale=None, softmax_scale=None, need_bwd=True, mode=GLOBAL_THRESHOLD, topk=0):
+                 device="cuda", score_scale=None, softmax_scale=None, need_bwd=True, mode=GLOBAL_THRESHOLD, topk=0,
+                 fused_io=False):
         T, H, W = grid
+        self.fused_io = bool(fused_io)
         self.g = make_grid(T, H, W, *block, chunk)
         self.B, self.Hh, self.D, self.tau, self.dtype, self.dev = B, Hh, D, float(tau), dtype, device
         self.S, self.nb = vmoba_partition_dims(self.g)
@@ -228,7 +232,8 @@ class LayerPlan:
         def blk_tensor(dt=dtype):   # block-order storage [B, Hh, S, D], handed out as a (b, s, h, d) view
             return torch.empty(B, Hh, S, D, dtype=dt, device=device).permute(0, 2, 1, 3)
 
-        self.Qp, self.Kp, self.Vp, self.Op = (blk_tensor() for _ in range(4))
+        self.Qp, self.Kp, self.Vp = (blk_tensor() for _ in range(3))
+        self.Op = None if fused_io else blk_tensor()
         self.LSE = torch.empty(B, Hh, S, **f32)
         self.Bmean = torch.empty(B, Hh, nb, D, **f32)
         self.P = torch.empty(B, Hh, S, nb, **f32)
@@ -250,7 +255,8 @@ class LayerPlan:
         self.ws_attn = torch.empty(max(n_fwd, n_bwd), dtype=torch.uint8, device=device)
         self.O = torch.empty(B, S, Hh, D, dtype=dtype, device=device)
         if need_bwd:
-            self.dOp, self.dQp, self.dKp, self.dVp = (blk_tensor() for _ in range(4))
+            if not fused_io:
+                self.dOp, self.dQp, self.dKp, self.dVp = (blk_tensor() for _ in range(4))
             self.dQ, self.dK, self.dV = (torch.empty(B, S, Hh, D, dtype=dtype, device=device) for _ in range(3))
 
     # -- the hot path, one method per C-ABI call -------------------------------------------
@@ -267,7 +273,8 @@ class LayerPlan:
     def attn_fwd(self):
         vmoba_attn_fwd(self.B, self.Hh, self.S, self.D, self.nb, self.blk_off, self.Qp, self.Kp, self.Vp,
                        self.blk_ptr, self.q_idx, self.row_ptr, self.pair_pos, self.cap, self.softmax_scale,
-                       self.Op, self.LSE, self.ws_attn)
+                       self.O if self.fused_io else self.Op, self.LSE, self.ws_attn,
+                       out_rows=self.perm if self.fused_io else None)
 
     def unpartition_out(self):
         vmoba_partition(self.g, 1, self.B, self.Hh, self.D, [self.Op], [self.O], self.perm, None, None)
@@ -275,7 +282,13 @@ class LayerPlan:
     def partition_dO(self, dO):
         vmoba_partition(self.g, 0, self.B, self.Hh, self.D, [dO], [self.dOp], self.perm, None, None)
 
-    def attn_bwd(self):
+    def attn_bwd(self, dO=None):
+        """dO: the caller-layout gradient (fused_io only; otherwise partition_dO() has run)."""
+        if self.fused_io:
+            vmoba_attn_bwd(self.B, self.Hh, self.S, self.D, self.nb, self.blk_off, self.Qp, self.Kp, self.Vp,
+                           self.O, self.LSE, dO, self.blk_ptr, self.q_idx, self.row_ptr, self.pair_pos,
+                           self.cap, self.softmax_scale, self.dQ, self.dK, self.dV, self.ws_attn, rows=self.perm)
+            return
         vmoba_attn_bwd(self.B, self.Hh, self.S, self.D, self.nb, self.blk_off, self.Qp, self.Kp, self.Vp,
                        self.Op, self.LSE, self.dOp, self.blk_ptr, self.q_idx, self.row_ptr, self.pair_pos,
                        self.cap, self.softmax_scale, self.dQp, self.dKp, self.dVp, self.ws_attn)
@@ -288,10 +301,14 @@ class LayerPlan:
         self.partition(Q, K, V)
         self.select()
         self.attn_fwd()
-        self.unpartition_out()
+        if not self.fused_io:
+            self.unpartition_out()
         return self.O
 
     def backward(self, dO):
+        if self.fused_io:
+            self.attn_bwd(dO)
+            return self.dQ, self.dK, self.dV
         self.partition_dO(dO)
         self.attn_bwd()
         self.unpartition_grads()

@@ -22,7 +22,8 @@ constexpr float LOG2E = 1.4426950408889634f;
 
 // ---------------------------------------------------------------------------------------------
 template <bool BF16, int D>
-__global__ __launch_bounds__(256) void delta_kernel(TensorView O, TensorView dO, float* __restrict__ delta, int Hh, int S) {
+__global__ __launch_bounds__(256) void delta_kernel(TensorView O, TensorView dO, float* __restrict__ delta,
+                                                    const int* __restrict__ rows, char* __restrict__ dO_copy, int Hh, int S) {
     constexpr int EPP = BF16 ? 8 : 4;
     constexpr int LPQ = D / EPP;
     constexpr int QPW = 256 / LPQ;
@@ -31,10 +32,13 @@ __global__ __launch_bounds__(256) void delta_kernel(TensorView O, TensorView dO,
     const int part = threadIdx.x % LPQ;
     float acc = 0.f;
     if (q < S) {
-        const char* po = O.ptr + ((long long)b * O.stride_b + (long long)q * O.stride_s + (long long)h * O.stride_h) * (BF16 ? 2 : 4) + part * 16;
-        const char* pd = dO.ptr + ((long long)b * dO.stride_b + (long long)q * dO.stride_s + (long long)h * dO.stride_h) * (BF16 ? 2 : 4) + part * 16;
+        // with a row map, O and dO are in the caller's token order and dO is also copied to block order
+        const int qs = rows ? rows[q] : q;
+        const char* po = O.ptr + ((long long)b * O.stride_b + (long long)qs * O.stride_s + (long long)h * O.stride_h) * (BF16 ? 2 : 4) + part * 16;
+        const char* pd = dO.ptr + ((long long)b * dO.stride_b + (long long)qs * dO.stride_s + (long long)h * dO.stride_h) * (BF16 ? 2 : 4) + part * 16;
         const u32x4_t a = *reinterpret_cast<const u32x4_t*>(po);
         const u32x4_t c = *reinterpret_cast<const u32x4_t*>(pd);
+        if (rows) *reinterpret_cast<u32x4_t*>(dO_copy + ((long long)bh * S + q) * D * (BF16 ? 2 : 4) + part * 16) = c;
         if constexpr (BF16) {
             acc = bf16lo_to_f32(a.x) * bf16lo_to_f32(c.x) + bf16hi_to_f32(a.x) * bf16hi_to_f32(c.x) +
                   bf16lo_to_f32(a.y) * bf16lo_to_f32(c.y) + bf16hi_to_f32(a.y) * bf16hi_to_f32(c.y) +
@@ -134,7 +138,7 @@ template <bool BF16, int D>
 __global__ __launch_bounds__(64) void attn_bwd_dkv_simple_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
-    const int* __restrict__ kb_start, TensorView dK, TensorView dV, int Hh, int S, int nb, long long cap,
+    const int* __restrict__ kb_start, TensorView dK, TensorView dV, const int* __restrict__ rows, int Hh, int S, int nb, long long cap,
     float scale_log2, float scale) {
     constexpr int KPW = 64, QC = 16;
     constexpr int ES = BF16 ? 2 : 4;
@@ -200,8 +204,9 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_simple_kernel(
         }
     }
     if (live) {
-        char* pk = dK.ptr + ((long long)b * dK.stride_b + (long long)krow * dK.stride_s + (long long)h * dK.stride_h) * ES;
-        char* pv = dV.ptr + ((long long)b * dV.stride_b + (long long)krow * dV.stride_s + (long long)h * dV.stride_h) * ES;
+        const int kout = rows ? rows[krow] : krow;
+        char* pk = dK.ptr + ((long long)b * dK.stride_b + (long long)kout * dK.stride_s + (long long)h * dK.stride_h) * ES;
+        char* pv = dV.ptr + ((long long)b * dV.stride_b + (long long)kout * dV.stride_s + (long long)h * dV.stride_h) * ES;
 #pragma unroll
         for (int d = 0; d < D; d += 2) {
             if (BF16) {
@@ -367,7 +372,7 @@ template <int D, int NW>
 __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
-    const int* __restrict__ kb_start, TensorView dK, TensorView dV, int Hh, int S, int nb, long long cap,
+    const int* __restrict__ kb_start, TensorView dK, TensorView dV, const int* __restrict__ rows, int Hh, int S, int nb, long long cap,
     float scale_log2, float scale) {
     constexpr int NT = 64 * NW;
     constexpr int QC = 64;
@@ -601,8 +606,9 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
         }
     }
     if (key_live) {
-        char* pk = dK.ptr + ((long long)b * dK.stride_b + (long long)krow * dK.stride_s + (long long)h * dK.stride_h) * 2;
-        char* pv = dV.ptr + ((long long)b * dV.stride_b + (long long)krow * dV.stride_s + (long long)h * dV.stride_h) * 2;
+        const int kout = rows ? rows[krow] : krow;
+        char* pk = dK.ptr + ((long long)b * dK.stride_b + (long long)kout * dK.stride_s + (long long)h * dK.stride_h) * 2;
+        char* pv = dV.ptr + ((long long)b * dV.stride_b + (long long)kout * dV.stride_s + (long long)h * dV.stride_h) * 2;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -622,7 +628,7 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
 // dQ[q] = scale * sum over the query's pairs of dQpart[pair] (bfloat16 partials when PBF16).
 template <bool BF16, bool PBF16, int D>
 __global__ __launch_bounds__(256) void dq_merge_kernel(const float* __restrict__ dQpart, const int* __restrict__ row_ptr,
-                                                       const int* __restrict__ pair_pos, TensorView dQ, int Hh, int S,
+                                                       const int* __restrict__ pair_pos, TensorView dQ, const int* __restrict__ rows, int Hh, int S,
                                                        long long cap, float scale) {
     constexpr int CH = PBF16 ? 8 : 4;
     constexpr int LPQ = D / CH;
@@ -657,7 +663,8 @@ __global__ __launch_bounds__(256) void dq_merge_kernel(const float* __restrict__
     }
 #pragma unroll
     for (int c = 0; c < CH; ++c) acc[c] *= scale;
-    char* dst = dQ.ptr + ((long long)b * dQ.stride_b + (long long)q * dQ.stride_s + (long long)h * dQ.stride_h) * (BF16 ? 2 : 4);
+    const int qo = rows ? rows[q] : q;
+    char* dst = dQ.ptr + ((long long)b * dQ.stride_b + (long long)qo * dQ.stride_s + (long long)h * dQ.stride_h) * (BF16 ? 2 : 4);
     if constexpr (BF16) {
         uint32_t w[CH / 2];
 #pragma unroll
@@ -684,10 +691,11 @@ struct BwdWs {
     int* tile_start;   // [BH][257]
     int4* tile_desc;   // [BH][tiles_per_head]
     int* kb_start;     // [257]
+    char* dO_copy;     // [BH, S, D] block-order copy of dO (used with a row map)
     size_t total;
 };
 
-BwdWs carve_bwd(void* base, int BH, int64_t S, int D, int64_t cap) {
+BwdWs carve_bwd(void* base, int BH, int64_t S, int D, int64_t cap, int es) {
     BwdWs w;
     char* p = (char*)base;
     size_t off = 0;
@@ -696,6 +704,7 @@ BwdWs carve_bwd(void* base, int BH, int64_t S, int D, int64_t cap) {
     w.tile_start = (int*)(p + off);  off += align_up((size_t)BH * (VMOBA_MAX_BLOCKS + 1) * 4, 256);
     w.tile_desc = (int4*)(p + off);  off += align_up((size_t)BH * vmoba_max_tiles(cap, 64) * 16, 256);
     w.kb_start = (int*)(p + off);    off += align_up((size_t)(VMOBA_MAX_BLOCKS + 1) * 4, 256);
+    w.dO_copy = p + off;             off += align_up((size_t)BH * S * D * es, 256);
     w.total = off;
     return w;
 }
@@ -703,8 +712,7 @@ BwdWs carve_bwd(void* base, int BH, int64_t S, int D, int64_t cap) {
 }  // namespace
 
 size_t vmoba_attn_bwd_workspace_bytes(int B, int Hh, int64_t S, int D, int64_t cap, int dtype) {
-    (void)dtype;
-    return carve_bwd(nullptr, B * Hh, S, D, cap).total;
+    return carve_bwd(nullptr, B * Hh, S, D, cap, dtype == VMOBA_BF16 ? 2 : 4).total;
 }
 
 extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
@@ -713,7 +721,7 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
                               const int32_t* blk_ptr, const int32_t* q_idx, const int32_t* row_ptr,
                               const int32_t* pair_pos, int64_t nnz_capacity, float softmax_scale,
                               const vmoba_tensor* dQ, const vmoba_tensor* dK, const vmoba_tensor* dV,
-                              void* workspace, size_t workspace_bytes, void* stream) {
+                              const int32_t* rows, void* workspace, size_t workspace_bytes, void* stream) {
     if (B <= 0 || Hh <= 0 || S <= 0 || n_blocks <= 0 || nnz_capacity <= 0) return VMOBA_ERR_INVALID_ARG;
     if (!blk_off || !blk_ptr || !q_idx || !row_ptr || !pair_pos || !LSE || !workspace) return VMOBA_ERR_INVALID_ARG;
     if (!tensor_ok(Qp) || !tensor_ok(Kp) || !tensor_ok(Vp) || !tensor_ok(O) || !tensor_ok(dO) || !tensor_ok(dQ) ||
@@ -728,13 +736,14 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         return VMOBA_ERR_UNSUPPORTED;
     const int BH = B * Hh;
     if (nnz_capacity > INT32_MAX) return VMOBA_ERR_UNSUPPORTED;
-    BwdWs ws = carve_bwd(workspace, BH, S, D, nnz_capacity);
+    BwdWs ws = carve_bwd(workspace, BH, S, D, nnz_capacity, dt == VMOBA_BF16 ? 2 : 4);
     if (workspace_bytes < ws.total) return VMOBA_ERR_WORKSPACE;
     if (((uintptr_t)workspace) & 255) return VMOBA_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
     const bool bf16 = dt == VMOBA_BF16;
-    const TensorView Qv = make_view(Qp), Kv = make_view(Kp), Vv = make_view(Vp), Ov = make_view(O), dOv = make_view(dO);
+    const TensorView Qv = make_view(Qp), Kv = make_view(Kp), Vv = make_view(Vp), Ov = make_view(O);
     const TensorView dQv = make_view(dQ), dKv = make_view(dK), dVv = make_view(dV);
+    TensorView dOv = make_view(dO);
     const float scale_log2 = softmax_scale * LOG2E;
     const bool simple = !bf16 || getenv("VMOBA_FORCE_SIMPLE") != nullptr;
 
@@ -742,11 +751,17 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         const int epp = bf16 ? 8 : 4;
         const int qpw = 256 / (D / epp);
         dim3 grid((unsigned)ceil_div64(S, qpw), (unsigned)BH);
-        if (bf16 && D == 128) delta_kernel<true, 128><<<grid, dim3(256), 0, st>>>(Ov, dOv, ws.delta, Hh, (int)S);
-        else if (bf16) delta_kernel<true, 64><<<grid, dim3(256), 0, st>>>(Ov, dOv, ws.delta, Hh, (int)S);
-        else if (D == 128) delta_kernel<false, 128><<<grid, dim3(256), 0, st>>>(Ov, dOv, ws.delta, Hh, (int)S);
-        else delta_kernel<false, 64><<<grid, dim3(256), 0, st>>>(Ov, dOv, ws.delta, Hh, (int)S);
+        if (bf16 && D == 128) delta_kernel<true, 128><<<grid, dim3(256), 0, st>>>(Ov, dOv, ws.delta, rows, ws.dO_copy, Hh, (int)S);
+        else if (bf16) delta_kernel<true, 64><<<grid, dim3(256), 0, st>>>(Ov, dOv, ws.delta, rows, ws.dO_copy, Hh, (int)S);
+        else if (D == 128) delta_kernel<false, 128><<<grid, dim3(256), 0, st>>>(Ov, dOv, ws.delta, rows, ws.dO_copy, Hh, (int)S);
+        else delta_kernel<false, 64><<<grid, dim3(256), 0, st>>>(Ov, dOv, ws.delta, rows, ws.dO_copy, Hh, (int)S);
         VMOBA_CHECK_LAUNCH();
+    }
+    if (rows) {   // from here on dO is the block-order copy [B, Hh, S, D] the delta kernel wrote
+        dOv.ptr = ws.dO_copy;
+        dOv.stride_b = (int64_t)Hh * S * D;
+        dOv.stride_h = S * D;
+        dOv.stride_s = D;
     }
     // ---- dQ
     const int TM = simple ? 64 : 128;
@@ -775,7 +790,7 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         const bool pbf16 = !simple;           // the MFMA tile kernel writes bfloat16 partials
         const int qpw = 256 / (D / (pbf16 ? 8 : 4));
         dim3 mgrid((unsigned)ceil_div64(S, qpw), (unsigned)BH);
-#define MG_ARGS ws.dQpart, row_ptr, pair_pos, dQv, Hh, (int)S, (long long)nnz_capacity, softmax_scale
+#define MG_ARGS ws.dQpart, row_ptr, pair_pos, dQv, rows, Hh, (int)S, (long long)nnz_capacity, softmax_scale
         if (pbf16 && D == 128) dq_merge_kernel<true, true, 128><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
         else if (pbf16) dq_merge_kernel<true, true, 64><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
         else if (bf16 && D == 128) dq_merge_kernel<true, false, 128><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
@@ -794,7 +809,7 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         // a multiple of 8 so that (workgroup id % 8) is the same for every head; + 8 for the per-XCD rounding
         dim3 grid((unsigned)((S / KPW + n_blocks + 7) / 8 * 8 + 8), (unsigned)BH);
         VMOBA_PROFILE_BEGIN(2, st);
-#define DKV_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.kb_start, dKv, dVv, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
+#define DKV_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.kb_start, dKv, dVv, rows, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
         if (simple) {
             if (bf16 && D == 128) attn_bwd_dkv_simple_kernel<true, 128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
             else if (bf16) attn_bwd_dkv_simple_kernel<true, 64><<<grid, dim3(64), 0, st>>>(DKV_ARGS);

@@ -539,7 +539,8 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_tile_pp_kernel(
 template <bool BF16, bool PBF16, int D>
 __global__ __launch_bounds__(256) void attn_fwd_merge_kernel(const float* __restrict__ Opart, const float* __restrict__ lse_part,
                                                              const int* __restrict__ row_ptr, const int* __restrict__ pair_pos,
-                                                             TensorView O, float* __restrict__ LSE, int Hh, int S, long long cap) {
+                                                             TensorView O, float* __restrict__ LSE,
+                                                             const int* __restrict__ out_rows, int Hh, int S, long long cap) {
     constexpr int CH = PBF16 ? 8 : 4;
     constexpr int LPQ = D / CH;              // lanes per query
     constexpr int QPW = 256 / LPQ;           // queries per workgroup
@@ -596,7 +597,8 @@ __global__ __launch_bounds__(256) void attn_fwd_merge_kernel(const float* __rest
         for (int c = 0; c < CH; ++c) acc[c] *= inv;
         lse = mx + logf(wsum);
     }
-    char* dst = O.ptr + ((long long)b * O.stride_b + (long long)q * O.stride_s + (long long)h * O.stride_h) * (BF16 ? 2 : 4);
+    const int qo = out_rows ? out_rows[q] : q;       // row of O that block-order row q is written to
+    char* dst = O.ptr + ((long long)b * O.stride_b + (long long)qo * O.stride_s + (long long)h * O.stride_h) * (BF16 ? 2 : 4);
     if constexpr (BF16) {
         uint32_t w[CH / 2];
 #pragma unroll
@@ -662,8 +664,8 @@ extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
                               const vmoba_tensor* Qp, const vmoba_tensor* Kp, const vmoba_tensor* Vp,
                               const int32_t* blk_ptr, const int32_t* q_idx, const int32_t* row_ptr,
                               const int32_t* pair_pos, int64_t nnz_capacity, float softmax_scale,
-                              const vmoba_tensor* O, float* LSE, void* workspace, size_t workspace_bytes,
-                              void* stream) {
+                              const vmoba_tensor* O, float* LSE, const int32_t* out_rows, void* workspace,
+                              size_t workspace_bytes, void* stream) {
     if (B <= 0 || Hh <= 0 || S <= 0 || n_blocks <= 0 || nnz_capacity <= 0) return VMOBA_ERR_INVALID_ARG;
     if (!blk_off || !blk_ptr || !q_idx || !row_ptr || !pair_pos || !LSE || !workspace) return VMOBA_ERR_INVALID_ARG;
     if (!tensor_ok(Qp) || !tensor_ok(Kp) || !tensor_ok(Vp) || !tensor_ok(O)) return VMOBA_ERR_INVALID_ARG;
@@ -715,7 +717,7 @@ extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     const bool pbf16 = !simple;               // the MFMA tile kernels write bfloat16 partials
     const int qpw = 256 / (D / (pbf16 ? 8 : 4));
     dim3 mgrid((unsigned)ceil_div64(S, qpw), (unsigned)BH);
-#define MERGE_ARGS ws.Opart, ws.lse_part, row_ptr, pair_pos, Ov, LSE, Hh, (int)S, (long long)nnz_capacity
+#define MERGE_ARGS ws.Opart, ws.lse_part, row_ptr, pair_pos, Ov, LSE, out_rows, Hh, (int)S, (long long)nnz_capacity
     if (pbf16 && D == 128) attn_fwd_merge_kernel<true, true, 128><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
     else if (pbf16) attn_fwd_merge_kernel<true, true, 64><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
     else if (bf16 && D == 128) attn_fwd_merge_kernel<true, false, 128><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);

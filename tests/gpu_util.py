@@ -25,11 +25,13 @@ def unpack_mask(words: np.ndarray, nb: int) -> np.ndarray:
 
 
 def run_gpu(Q, K, V, dO, grid, block=(0, 0, 0), chunk=0, tau=0.25, dtype=torch.float32,
-            score_scale=None, softmax_scale=None, mode=0, topk=0):
-    """Whole layer on the GPU.  Q, K, V, dO: numpy [B, S, Hh, D] float32 (dO may be None)."""
+            score_scale=None, softmax_scale=None, mode=0, topk=0, fused_io=False):
+    """Whole layer on the GPU.  Q, K, V, dO: numpy [B, S, Hh, D] float32 (dO may be None).
+    With fused_io the attention calls write O and the gradients in the caller's token order
+    themselves; their block-order views (Op, dQp, ...) are then gathered here on the host."""
     B, S, Hh, D = Q.shape
     plan = vb.LayerPlan(B, Hh, D, grid, block, chunk, tau, dtype, score_scale=score_scale,
-                        softmax_scale=softmax_scale, need_bwd=dO is not None, mode=mode, topk=topk)
+                        softmax_scale=softmax_scale, need_bwd=dO is not None, mode=mode, topk=topk, fused_io=fused_io)
     assert plan.S == S
     q, k, v = (to_dev(x, dtype) for x in (Q, K, V))
     plan.forward(q, k, v)
@@ -43,7 +45,7 @@ def run_gpu(Q, K, V, dO, grid, block=(0, 0, 0), chunk=0, tau=0.25, dtype=torch.f
                perm=plan.perm.cpu().numpy(), inv_perm=plan.inv_perm.cpu().numpy(),
                blk_off=plan.blk_off.cpu().numpy(),
                Qp=np32(plan.Qp.permute(0, 2, 1, 3)), Kp=np32(plan.Kp.permute(0, 2, 1, 3)),
-               Vp=np32(plan.Vp.permute(0, 2, 1, 3)), Op=np32(plan.Op.permute(0, 2, 1, 3)),
+               Vp=np32(plan.Vp.permute(0, 2, 1, 3)),
                O=np32(plan.O), LSE=plan.LSE.cpu().numpy(), Bmean=plan.Bmean.cpu().numpy(),
                P=plan.P.cpu().numpy(), mask=unpack_mask(plan.mask.cpu().numpy(), nb),
                k=plan.k_out.cpu().numpy().reshape(B, Hh), theta=plan.theta.cpu().numpy().reshape(B, Hh),
@@ -52,10 +54,14 @@ def run_gpu(Q, K, V, dO, grid, block=(0, 0, 0), chunk=0, tau=0.25, dtype=torch.f
                q_idx=plan.q_idx.cpu().numpy().reshape(B, Hh, plan.cap),
                col_idx=plan.col_idx.cpu().numpy().reshape(B, Hh, plan.cap),
                pair_pos=plan.pair_pos.cpu().numpy().reshape(B, Hh, plan.cap))
+    def block_order(x):      # caller layout [B, S, Hh, D] -> [B, Hh, S, D] in block order
+        return np.ascontiguousarray(x[:, out["perm"]].transpose(0, 2, 1, 3))
+
+    out["Op"] = block_order(out["O"]) if fused_io else np32(plan.Op.permute(0, 2, 1, 3))
     if dO is not None:
-        out.update(dQ=np32(plan.dQ), dK=np32(plan.dK), dV=np32(plan.dV),
-                   dQp=np32(plan.dQp.permute(0, 2, 1, 3)), dKp=np32(plan.dKp.permute(0, 2, 1, 3)),
-                   dVp=np32(plan.dVp.permute(0, 2, 1, 3)))
+        out.update(dQ=np32(plan.dQ), dK=np32(plan.dK), dV=np32(plan.dV))
+        for n in ("dQ", "dK", "dV"):
+            out[n + "p"] = block_order(out[n]) if fused_io else np32(getattr(plan, n + "p").permute(0, 2, 1, 3))
     return out
 
 

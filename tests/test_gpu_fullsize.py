@@ -37,7 +37,7 @@ def gu_rel(a, b):
 
 
 def check_layer_sampled(name, kind, tau, heads=None, bwd=True, sel_heads=None, groups=2, max_rows=20000,
-                        mode=0, topk=0):
+                        mode=0, topk=0, fused_io=False):
     Q, K, V, dO = get_inputs(name, heads)
     c = synth.CONFIGS[name]
     bt, bh, bw, chunk = c["partitions"][kind]
@@ -45,7 +45,7 @@ def check_layer_sampled(name, kind, tau, heads=None, bwd=True, sel_heads=None, g
     scale = 1.0 / math.sqrt(D)
     print(f"[fullsize] {name} {kind} tau={tau} heads={Hh} bwd={bwd}: GPU layer", flush=True)
     plan = vb.LayerPlan(1, Hh, D, c["grid"], (bt, bh, bw), chunk, tau, torch.bfloat16, need_bwd=bwd,
-                        mode=mode, topk=topk)
+                        mode=mode, topk=topk, fused_io=fused_io)
     dev = [gu.to_dev(x, torch.bfloat16) for x in ((Q, K, V, dO) if bwd else (Q, K, V))]
     plan.forward(*dev[:3])
     if bwd:
@@ -66,14 +66,24 @@ def check_layer_sampled(name, kind, tau, heads=None, bwd=True, sel_heads=None, g
     Qp_all = gu.np32(plan.Qp.permute(0, 2, 1, 3))[0]
     assert np.array_equal(Qp_all, vo.gather_rows(Q, perm)[0])          # permutation bit-exact
     Kp_all, Vp_all = (vo.gather_rows(x, perm)[0] for x in (K, V))
-    Op = gu.np32(plan.Op.permute(0, 2, 1, 3))[0]
     LSE = plan.LSE.cpu().numpy()[0]
-    assert np.array_equal(gu.np32(plan.O)[0][perm].transpose(1, 0, 2), Op)      # inverse permutation exact
+
+    def block_order(t):          # caller layout [1, S, Hh, D] on the device -> [Hh, S, D] in block order
+        return np.ascontiguousarray(gu.np32(t)[0][perm].transpose(1, 0, 2))
+
+    if fused_io:                 # the attention kernels wrote the caller's layout themselves
+        Op = block_order(plan.O)
+    else:
+        Op = gu.np32(plan.Op.permute(0, 2, 1, 3))[0]
+        assert np.array_equal(block_order(plan.O), Op)                          # inverse permutation exact
     if bwd:
         dOp_all = vo.gather_rows(dO, perm)[0]
-        assert np.array_equal(gu.np32(plan.dOp.permute(0, 2, 1, 3))[0], dOp_all)
-        dQp, dKp, dVp = (gu.np32(t.permute(0, 2, 1, 3))[0] for t in (plan.dQp, plan.dKp, plan.dVp))
-        assert np.array_equal(gu.np32(plan.dK)[0][perm].transpose(1, 0, 2), dKp)
+        if fused_io:
+            dQp, dKp, dVp = (block_order(t) for t in (plan.dQ, plan.dK, plan.dV))
+        else:
+            assert np.array_equal(gu.np32(plan.dOp.permute(0, 2, 1, 3))[0], dOp_all)
+            dQp, dKp, dVp = (gu.np32(t.permute(0, 2, 1, 3))[0] for t in (plan.dQp, plan.dKp, plan.dVp))
+            assert np.array_equal(block_order(plan.dK), dKp)
 
     # ---- selection, in full, for the chosen heads; list consistency for every head
     g = dict(mask=mask_gpu[None], k=k_gpu.reshape(1, Hh), blk_ptr=blk_ptr.reshape(1, Hh, nb + 1),
@@ -133,7 +143,12 @@ def check_layer_sampled(name, kind, tau, heads=None, bwd=True, sel_heads=None, g
 
 @pytest.mark.parametrize("kind", ["3d", "2d", "1d"])
 def test_480p_layer_sampled(kind):
-    check_layer_sampled("480p", kind, 0.25)
+    """The configuration bench.py times (outputs written in the caller's order by the attention calls)."""
+    check_layer_sampled("480p", kind, 0.25, fused_io=True)
+
+
+def test_480p_separate_partition_calls():
+    check_layer_sampled("480p", "3d", 0.25, sel_heads=[4], groups=1)
 
 
 def test_480p_tau_half():

@@ -44,10 +44,10 @@ def oracle_with_gpu_mask(g, Q, K, V, dO, softmax_scale):
     return res
 
 
-def compare_layer(Q, K, V, dO, grid, block, chunk, tau, dtype, label="", mode=0, topk=0):
+def compare_layer(Q, K, V, dO, grid, block, chunk, tau, dtype, label="", mode=0, topk=0, fused_io=False):
     B, S, Hh, D = Q.shape
     print(f"[parity] {label} S={S} Hh={Hh} D={D} grid={grid} block={block} chunk={chunk} tau={tau} {dtype}", flush=True)
-    g = gu.run_gpu(Q, K, V, dO, grid, block, chunk, tau, dtype, mode=mode, topk=topk)
+    g = gu.run_gpu(Q, K, V, dO, grid, block, chunk, tau, dtype, mode=mode, topk=topk, fused_io=fused_io)
     o = vo.vmoba_layer(Q, K, V, grid, block, tau, dO=None, chunk=chunk, mode=mode, topk=topk)   # selection + its own attention
     # --- partition: bit exact
     assert np.array_equal(g["perm"], o["perm"])
@@ -168,6 +168,20 @@ def test_local_topk_with_equal_scores_takes_lowest_indices():
     g = gu.run_gpu(Q, K, V, None, (8, 8, 8), (2, 4, 4), 0, 0.25, torch.float32, mode=vb.GLOBAL_TOPK, topk=3)
     m = g["mask"][0, 0].reshape(-1)
     assert m[:3 * S].all() and not m[3 * S:].any()           # pool order: ascending (query, block)
+
+
+# ------------------------------------------- outputs written in the caller's token order by the kernels
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_fused_io_matches_oracle_and_unfused(dtype):
+    """attn_fwd / attn_bwd with a row map (O, dO, dQ, dK, dV in the caller's order): against the oracle,
+    and bit-identical to the path through the separate partition calls (same arithmetic, other addresses)."""
+    grid, block = (5, 7, 9), (2, 3, 4)
+    S = grid[0] * grid[1] * grid[2]
+    Q, K, V, dO = (synth.to_bf16_grid(synth.iid_normal(120 + i, (2, S, 3, 64))) for i in range(4))
+    g, o = compare_layer(Q, K, V, dO, grid, block, 0, 0.3, dtype, "fused-io", fused_io=True)
+    u = gu.run_gpu(Q, K, V, dO, grid, block, 0, 0.3, dtype)
+    for n in ("O", "dQ", "dK", "dV", "LSE"):
+        assert np.array_equal(g[n], u[n]), n
 
 
 def test_tau_one_is_dense_attention():
