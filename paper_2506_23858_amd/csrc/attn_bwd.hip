@@ -10,6 +10,7 @@
 // no atomics anywhere, results are reproducible.  The attention weights are recomputed from
 // Q, K and the forward's LSE in both (2) and (3).
 #include "attn_common.h"
+#include <type_traits>
 
 #include <algorithm>
 #include <cmath>
@@ -379,7 +380,7 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
     constexpr int STR = D + 8;
     constexpr int KSTEPS = D / 16, DT = D / 32;
     constexpr int LOADS = QC * D * 2 / 16 / NT;     // 16-byte pieces per thread per chunk and tensor
-    constexpr int NBUF = 3;
+    constexpr int NBUF = 4;                         // power of two: ring index = chunk & (NBUF - 1)
     static_assert(QC * D * 2 / 16 % NT == 0, "chunk must divide evenly over the threads");
     __shared__ __align__(16) __bf16 sQ[NBUF][QC * STR];
     __shared__ __align__(16) __bf16 sdO[NBUF][QC * STR];
@@ -428,6 +429,7 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
         const float* lse_h = LSE + (long long)bh * S;
         const float* dl_h = delta + (long long)bh * S;
         const int n_chunks = (cnt + QC - 1) / QC;
+        const int H = 2 * n_chunks;               // half-chunks of 32 queries
 
         u32x4_t qreg[LOADS], doreg[LOADS];
         float lreg = 0.f, dreg = 0.f;
@@ -441,168 +443,189 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
                 const int r = (tid + NT * i) / (D / 8);
                 qn[i] = list[min(c0 + r, cnt - 1)];
             }
-            if (tid < QC) {
-                ql = list[min(c0 + tid, cnt - 1)];
-                ql_live = c0 + tid < cnt;
-            }
         };
-        auto prefetch_rows = [&]() {
-#pragma unroll
-            for (int i = 0; i < LOADS; ++i) {
+        // the gathered rows travel in 2 * LOADS sixteen-byte pieces per thread: Q pieces, then dO pieces
+        auto load_piece = [&](int i) {
+            if (i < LOADS) {
                 const int pc = (tid + NT * i) % (D / 8);
                 qreg[i] = *reinterpret_cast<const u32x4_t*>(qbase + (long long)qn[i] * qss + pc * 16);
-                doreg[i] = *reinterpret_cast<const u32x4_t*>(dobase + (long long)qn[i] * doss + pc * 16);
-            }
-            if (tid < QC) {
-                lreg = lse_h[ql];            // used only at the next stage(): no wait on these loads here
-                dreg = dl_h[ql];
-                rows_live = ql_live;
+            } else {
+                const int k = i - LOADS;
+                const int pc = (tid + NT * k) % (D / 8);
+                doreg[k] = *reinterpret_cast<const u32x4_t*>(dobase + (long long)qn[k] * doss + pc * 16);
             }
         };
-        auto stage = [&](int buf) {
-#pragma unroll
-            for (int i = 0; i < LOADS; ++i) {
-                const int piece = tid + NT * i;
-                const int r = piece / (D / 8), pc = piece % (D / 8);
-                *reinterpret_cast<u32x4_t*>(&sQ[buf][r * STR + pc * 8]) = qreg[i];
-                *reinterpret_cast<u32x4_t*>(&sdO[buf][r * STR + pc * 8]) = doreg[i];
-            }
-            if (tid < QC) {
-                // accumulator order: the 16 values a lane half needs per 32-query group are contiguous
-                const int r = tid & 31;
-                const int pos = (tid & 32) + ((r & 1) << 4) + ((r >> 4) << 3) + (((r >> 1) & 1) << 2) + ((r >> 2) & 3);
-                // rows past the end of the list get LSE = +inf (weight 0) and delta = 0
-                sL[buf][pos] = rows_live ? lreg * LOG2E : INFINITY;
-                sDl[buf][pos] = rows_live ? dreg : 0.f;
-            }
+        // LSE and delta of the chunk's 64 rows: every wavefront fetches and stores all 64 (same values to the
+        // same places), which keeps these few accesses free of branches inside the pipelined loop
+        const int r64 = lane;
+        auto prefetch_ld_idx = [&](int c) {
+            ql = list[min(c * QC + r64, cnt - 1)];
+            ql_live = c * QC + r64 < cnt;
+        };
+        auto load_ld_regs = [&]() {
+            lreg = lse_h[ql];
+            dreg = dl_h[ql];
+            rows_live = ql_live;
+        };
+        auto stage_piece = [&](int buf, int i) {
+            const int k = i < LOADS ? i : i - LOADS;
+            const int piece = tid + NT * k;
+            const int r = piece / (D / 8), pc = piece % (D / 8);
+            if (i < LOADS) *reinterpret_cast<u32x4_t*>(&sQ[buf][r * STR + pc * 8]) = qreg[k];
+            else *reinterpret_cast<u32x4_t*>(&sdO[buf][r * STR + pc * 8]) = doreg[k];
+        };
+        // accumulator order: the 16 values a lane half needs per 32-query group are contiguous
+        const int ld_pos = (r64 & 32) + ((r64 & 1) << 4) + (((r64 & 31) >> 4) << 3) + (((r64 >> 1) & 1) << 2) + ((r64 >> 2) & 3);
+        auto stage_ld = [&](int buf) {
+            // rows past the end of the list get LSE = +inf (weight 0) and delta = 0
+            sL[buf][ld_pos] = rows_live ? lreg * LOG2E : INFINITY;
+            sDl[buf][ld_pos] = rows_live ? dreg : 0.f;
         };
         const int row_lane = rho(l32) * STR + hf * 8;
         const int tr_lane = tr_lane_offset<STR>(lane);
         const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-        // Operand fetches are written one step ahead of the matrix instructions that use them and
-        // every step ends in a scheduling fence, so an LDS read always has a full step (two matrix
-        // instructions plus vector work) to complete before its data is needed.
         struct RowOps { bf16x8_t qa, da; };       // A operands of S and dP for one k-step
         struct TrOps { bf16x8_t dot, qt; };       // A operands of dV and dK for one (s, dt) step
-        auto read_rows = [&](int buf, int mt, int ks) {
-            RowOps o;
-            o.qa = *reinterpret_cast<const bf16x8_t*>(&sQ[buf][row_lane + mt * 32 * STR + ks * 16]);
-            o.da = *reinterpret_cast<const bf16x8_t*>(&sdO[buf][row_lane + mt * 32 * STR + ks * 16]);
-            return o;
+        // `half` = half-chunk index: chunk half / 2 sits in ring buffer (half / 2) % NBUF, rows 32 * (half % 2)
+        auto read_rows = [&](int half, int ks) {
+            const int o = ((half >> 1) & (NBUF - 1)) * (QC * STR) + (half & 1) * 32 * STR + row_lane + ks * 16;
+            RowOps r;
+            r.qa = *reinterpret_cast<const bf16x8_t*>(&sQ[0][o]);
+            r.da = *reinterpret_cast<const bf16x8_t*>(&sdO[0][o]);
+            return r;
         };
-        auto read_tr = [&](int buf, int mt, int step) {      // step = s * DT + dt
-            TrOps o;
-            o.dot = tr_operand<STR>(&sdO[buf][tr_lane], mt * 32, step / DT, (step % DT) * 32);
-            o.qt = tr_operand<STR>(&sQ[buf][tr_lane], mt * 32, step / DT, (step % DT) * 32);
-            return o;
+        auto read_tr = [&](int half, int step) {  // step = s * DT + dt
+            const int o = ((half >> 1) & (NBUF - 1)) * (QC * STR) + tr_lane;
+            TrOps t;
+            t.dot = tr_operand<STR>(&sdO[0][o], (half & 1) * 32, step / DT, (step % DT) * 32);
+            t.qt = tr_operand<STR>(&sQ[0][o], (half & 1) * 32, step / DT, (step % DT) * 32);
+            return t;
         };
-        auto mfma_rows = [&](const RowOps& o, int ks, f32x16_t& sa, f32x16_t& dp) {
-            sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.qa, kf[ks], ks == 0 ? zero16 : sa, 0, 0, 0);
-            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.da, vf[ks], ks == 0 ? zero16 : dp, 0, 0, 0);
-        };
-        auto mfma_tr = [&](const TrOps& o, int step, const bf16x8_t* pfr, const bf16x8_t* dsf) {
-            const int sidx = step / DT, dt = step % DT;
-            dvacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.dot, pfr[sidx], dvacc[dt], 0, 0, 0);
-            dkacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.qt, dsf[sidx], dkacc[dt], 0, 0, 0);
-        };
-        auto load_ld = [&](int buf, int mt, float* lv, float* dl) {
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                const f32x4_t a4 = *reinterpret_cast<const f32x4_t*>(&sL[buf][mt * 32 + hf * 16 + g4 * 4]);
-                const f32x4_t c4 = *reinterpret_cast<const f32x4_t*>(&sDl[buf][mt * 32 + hf * 16 + g4 * 4]);
-#pragma unroll
-                for (int u = 0; u < 4; ++u) { lv[g4 * 4 + u] = a4[u]; dl[g4 * 4 + u] = c4[u]; }
-            }
-        };
-        auto valu_pair = [&](const float* lv, const float* dl, int i2, const f32x16_t& sv, const f32x16_t& dv, float* p, float* ds) {
-            // values 2*i2 and 2*i2 + 1 (i2 = 0..7)
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int i = 2 * i2 + u;
-                p[i] = exp2_raw(fmaf(sv[i], scale_log2, -lv[i]));
-                ds[i] = p[i] * (dv[i] - dl[i]);
-            }
-        };
-        constexpr int TSTEPS = 2 * DT;            // (s, dt) steps of the dV / dK products
-        constexpr int VP_A = 8 / KSTEPS;          // exp/dS value pairs per step of part A
-        constexpr int VP_B = 8 / TSTEPS;          // ... per step of part B
+        constexpr int NST = KSTEPS;               // steps of a half-chunk: k-steps of S / dP = (s, dt) steps of dV / dK
+        static_assert(NST == 2 * DT && NST == 2 * LOADS, "one row piece, one k-step and one (s, dt) step per step");
+        constexpr int VP = 8 / NST;               // exp / dS value pairs per step
 
-        // prologue: chunk 0 staged, chunk 1 in flight, indices of chunk 2 in flight, S/dP of (0, 0)
-        prefetch_idx(0);
-        prefetch_rows();
-        prefetch_idx(1);
-        stage(0);
-        prefetch_rows();
-        prefetch_idx(2);
-        __syncthreads();
-        f32x16_t s0 = zero16, p0 = zero16, s1 = zero16, p1 = zero16;   // S, dP of half-chunks 0 and 1 of the current chunk
+        // prologue: chunks 0 and 1 staged, rows of chunk 2 in flight, indices of chunk 3 in flight
+        auto load_all = [&]() {
+#pragma unroll
+            for (int i = 0; i < 2 * LOADS; ++i) load_piece(i);
+            load_ld_regs();
+        };
+        auto stage_all = [&](int buf) {
+#pragma unroll
+            for (int i = 0; i < 2 * LOADS; ++i) stage_piece(buf, i);
+            stage_ld(buf);
+        };
+        prefetch_idx(0); prefetch_ld_idx(0);
+        load_all();
+        prefetch_idx(1); prefetch_ld_idx(1);
+        stage_all(0);
+        load_all();
+        prefetch_idx(2); prefetch_ld_idx(2);
+        stage_all(1);
+        load_all();
+        prefetch_idx(3); prefetch_ld_idx(3);
+
         if (wave_live) {
-#pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) mfma_rows(read_rows(0, 0, ks), ks, s0, p0);
-        }
-        int buf = 0;
-        for (int c = 0; c < n_chunks; ++c) {
-            const int nbuf = (buf + 1 == NBUF) ? 0 : buf + 1;
-            float pa[16], dsa[16], pb[16], dsb[16];
-            bf16x8_t pf1[2], df1[2];
-            TrOps tc0;                            // first transposed operands of part C, fetched before the barrier
-            if (wave_live) {
-                float lv0[16], dl0[16], lv1[16], dl1[16];
-                load_ld(buf, 0, lv0, dl0);
-                load_ld(buf, 1, lv1, dl1);
-                // A: S, dP of (c, 1)  ||  exp / dS of (c, 0)
-                RowOps ra = read_rows(buf, 1, 0);
-                TrOps tb;
-#pragma unroll
-                for (int ks = 0; ks < KSTEPS; ++ks) {
-                    RowOps rn;
-                    if (ks + 1 < KSTEPS) rn = read_rows(buf, 1, ks + 1);
-                    else tb = read_tr(buf, 0, 0);
-                    mfma_rows(ra, ks, s1, p1);
-#pragma unroll
-                    for (int u = 0; u < VP_A; ++u) valu_pair(lv0, dl0, ks * VP_A + u, s0, p0, pa, dsa);
-                    if (ks + 1 < KSTEPS) ra = rn;
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                const bf16x8_t pf0[2] = {pack8(&pa[0]), pack8(&pa[8])};
-                const bf16x8_t df0[2] = {pack8(&dsa[0]), pack8(&dsa[8])};
-                // B: dV, dK of (c, 0)  ||  exp / dS of (c, 1)
-#pragma unroll
-                for (int st = 0; st < TSTEPS; ++st) {
-                    TrOps tn;
-                    if (st + 1 < TSTEPS) tn = read_tr(buf, 0, st + 1);
-                    else tc0 = read_tr(buf, 1, 0);
-                    mfma_tr(tb, st, pf0, df0);
-#pragma unroll
-                    for (int u = 0; u < VP_B; ++u) valu_pair(lv1, dl1, st * VP_B + u, s1, p1, pb, dsb);
-                    if (st + 1 < TSTEPS) tb = tn;
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                pf1[0] = pack8(&pb[0]); pf1[1] = pack8(&pb[8]);
-                df1[0] = pack8(&dsb[0]); df1[1] = pack8(&dsb[8]);
+            // Software pipeline over half-chunks.  Step hc runs, interleaved instruction by instruction,
+            //   matrix:  S, dP of half-chunk hc + 1     and     dV, dK += of half-chunk hc - 1
+            //   vector:  P = exp(S - LSE), dS = P * (dP - delta) of half-chunk hc
+            //   memory (even steps): rows of chunk hc/2 + 2 from registers into the ring, loads of chunk hc/2 + 3
+            // so every step carries the same mix and the vector work hides under the matrix work of its
+            // neighbours.  One barrier per chunk, before the even step: the buffer written during steps
+            // 2c, 2c + 1 (chunk c + 2) was last read in step 2c - 2 and is first read in step 2c + 3.
+            f32x16_t s_cur = zero16, p_cur = zero16;
+            bf16x8_t pf_prev[2], df_prev[2];
+            {
+                const f32x4_t z4 = {0.f, 0.f, 0.f, 0.f};
+                const bf16x4_t zb = __builtin_convertvector(z4, bf16x4_t);
+                const bf16x8_t z8 = __builtin_shufflevector(zb, zb, 0, 1, 2, 3, 4, 5, 6, 7);
+                pf_prev[0] = pf_prev[1] = df_prev[0] = df_prev[1] = z8;
             }
-            // next chunk into the ring (its rows arrived during this iteration), loads of the one after
-            stage(nbuf);
-            prefetch_rows();
-            prefetch_idx(c + 3);
             __syncthreads();
-            if (wave_live) {
-                // C: dV, dK of (c, 1)  and  S, dP of (c + 1, 0)
-                RowOps rc = read_rows(nbuf, 0, 0);
-                TrOps tcur = tc0;
 #pragma unroll
-                for (int st = 0; st < TSTEPS; ++st) {
-                    TrOps tn;
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                const RowOps r = read_rows(0, ks);
+                s_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(r.qa, kf[ks], ks == 0 ? zero16 : s_cur, 0, 0, 0);
+                p_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(r.da, vf[ks], ks == 0 ? zero16 : p_cur, 0, 0, 0);
+            }
+            RowOps rcur = read_rows(1, 0);
+            TrOps tcur = read_tr(0, 0);               // step 0 multiplies it by P = dS = 0
+            auto half_step = [&](int hc, auto even_tag) {
+                constexpr bool EVEN = decltype(even_tag)::value;
+                const int wbuf = ((hc >> 1) + 2) & (NBUF - 1);
+                float lv[16], dl[16], pv[16], dsv[16];
+                {
+                    const int o = ((hc >> 1) & (NBUF - 1)) * QC + (EVEN ? 0 : 32) + hf * 16;
+#pragma unroll
+                    for (int g4 = 0; g4 < 4; ++g4) {
+                        const f32x4_t a4 = *reinterpret_cast<const f32x4_t*>(&sL[0][o + g4 * 4]);
+                        const f32x4_t c4 = *reinterpret_cast<const f32x4_t*>(&sDl[0][o + g4 * 4]);
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) { lv[g4 * 4 + u] = a4[u]; dl[g4 * 4 + u] = c4[u]; }
+                    }
+                }
+                f32x16_t s_nxt = zero16, p_nxt = zero16;
+                const int th = hc > 0 ? hc - 1 : 0;
+#pragma unroll
+                for (int st = 0; st < NST; ++st) {
                     RowOps rn;
-                    if (st + 1 < TSTEPS) { tn = read_tr(buf, 1, st + 1); rn = read_rows(nbuf, 0, st + 1); }
-                    mfma_tr(tcur, st, pf1, df1);
-                    mfma_rows(rc, st, s0, p0);
-                    if (st + 1 < TSTEPS) { tcur = tn; rc = rn; }
+                    TrOps tn;
+                    if (st + 1 < NST) { rn = read_rows(hc + 1, st + 1); tn = read_tr(th, st + 1); }
+                    else { rn = read_rows(hc + 2, 0); tn = read_tr(hc, 0); }
+                    s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rcur.qa, kf[st], st == 0 ? zero16 : s_nxt, 0, 0, 0);
+                    p_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rcur.da, vf[st], st == 0 ? zero16 : p_nxt, 0, 0, 0);
+                    dvacc[st % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tcur.dot, pf_prev[st / DT], dvacc[st % DT], 0, 0, 0);
+                    dkacc[st % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tcur.qt, df_prev[st / DT], dkacc[st % DT], 0, 0, 0);
+#pragma unroll
+                    for (int u = 0; u < 2 * VP; ++u) {
+                        const int i = 2 * VP * st + u;
+                        pv[i] = exp2_raw(fmaf(s_cur[i], scale_log2, -lv[i]));
+                        dsv[i] = pv[i] * (p_cur[i] - dl[i]);
+                    }
+                    // the packed operands are replaced as soon as their last reader of this step has issued
+                    if (st == NST / 2 - 1) { pf_prev[0] = pack8(&pv[0]); df_prev[0] = pack8(&dsv[0]); }
+                    if (st == NST - 1) { pf_prev[1] = pack8(&pv[8]); df_prev[1] = pack8(&dsv[8]); }
+                    if constexpr (EVEN) {
+                        stage_piece(wbuf, st);
+                        load_piece(st);
+                        if (st == 0) { stage_ld(wbuf); load_ld_regs(); }
+                    } else {
+                        // indices of the chunk after that: a whole step ahead of the row loads that use them
+                        if (st == 0) { prefetch_idx((hc >> 1) + 4); prefetch_ld_idx((hc >> 1) + 4); }
+                    }
+                    rcur = rn;
+                    tcur = tn;
                     __builtin_amdgcn_sched_barrier(0);
                 }
+                s_cur = s_nxt;
+                p_cur = p_nxt;
+            };
+            for (int c = 0; c < n_chunks; ++c) {
+                if (c > 0) __syncthreads();
+                half_step(2 * c, std::true_type{});
+                half_step(2 * c + 1, std::false_type{});
             }
-            buf = nbuf;
+            // drain: dV, dK of the last half-chunk
+#pragma unroll
+            for (int st = 0; st < NST; ++st) {
+                TrOps tn;
+                if (st + 1 < NST) tn = read_tr(H - 1, st + 1);
+                dvacc[st % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tcur.dot, pf_prev[st / DT], dvacc[st % DT], 0, 0, 0);
+                dkacc[st % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tcur.qt, df_prev[st / DT], dkacc[st % DT], 0, 0, 0);
+                if (st + 1 < NST) tcur = tn;
+            }
+        } else {
+            // a wavefront whose keys lie past the end of the block only helps to move rows
+            __syncthreads();
+            for (int c = 0; c < n_chunks; ++c) {
+                if (c > 0) __syncthreads();
+                stage_all((c + 2) & (NBUF - 1));
+                load_all();
+                prefetch_idx(c + 4);
+                prefetch_ld_idx(c + 4);
+            }
         }
     }
     if (key_live) {
