@@ -356,6 +356,339 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
+// bf16 MFMA dK/dV kernel, wavefront-pair variant.  The limiter of the kernel above is the LDS
+// issue rate (one operand fetch per matrix instruction, two for a transposed operand), not the
+// matrix pipe.  Here a workgroup still owns 128 keys of one block, but as two PAIRS of wavefronts
+// with 64 keys (two 32-key groups) each, and the two wavefronts of a pair split the products:
+//   wavefront 0 of the pair:  S  = Q  . K^T  ->  P = exp(S - LSE)  ->  dV^T += dO^T . P
+//   wavefront 1 of the pair:  dP = dO . V^T  ->  dS = P * (dP - delta)  ->  dK^T += Q^T . dS
+// so every operand fetched from LDS feeds two matrix instructions (one per key group), and each
+// wavefront keeps only one set of fragments (K or V) and one accumulator tile (dV^T or dK^T).
+// P travels from wavefront 0 to wavefront 1 as packed bf16 through a small LDS buffer (same lane,
+// same accumulator layout on both sides); wavefront 1 therefore runs the same pipeline one
+// half-chunk later, and the steps are separated by one workgroup barrier per half-chunk.
+// Step hc of the workgroup, local step t = hc - (wavefront % 2), all interleaved:
+//   matrix:  S or dP of half-chunk t + 1,  dV or dK of half-chunk t - 1      vector: P or dS of t
+//   memory (even hc): rows of chunk hc/2 + 2 from registers into the ring, loads of chunk hc/2 + 3.
+// The ring buffer written during steps 2c, 2c + 1 was last read in step 2c - 1 and is first read in 2c + 3.
+template <int D>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_pair_kernel(
+    TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
+    const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
+    const int* __restrict__ kb_start, TensorView dK, TensorView dV, const int* __restrict__ rows, int Hh, int S, int nb, long long cap,
+    float scale_log2, float scale) {
+    constexpr int NT = 256;
+    constexpr int QC = 64;
+    constexpr int STR = D + 8;
+    constexpr int KSTEPS = D / 16, DT = D / 32;
+    constexpr int LOADS = QC * D * 2 / 16 / NT;
+    constexpr int NBUF = 4;
+    constexpr int NST = KSTEPS;
+    static_assert(NST == 2 * DT && NST == 2 * LOADS, "one row piece, one k-step and one (s, dt) step per step");
+    constexpr int VP = 8 / NST;               // value pairs per key group and step
+    __shared__ __align__(16) __bf16 sQ[NBUF][QC * STR];
+    __shared__ __align__(16) __bf16 sdO[NBUF][QC * STR];
+    __shared__ __align__(16) float sL[NBUF][QC];
+    __shared__ __align__(16) float sDl[NBUF][QC];
+    __shared__ __align__(16) u32x4_t sX[2][2][4][64];     // [pair][step parity][kg * 2 + s][lane]: packed P
+
+    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
+    if ((int)blockIdx.x >= kb_start[nb]) return;
+    int lo = 0, hi = nb;
+    while (hi - lo > 1) { int mid = (lo + hi) >> 1; if (kb_start[mid] <= (int)blockIdx.x) lo = mid; else hi = mid; }
+    const int j = lo, run = (int)blockIdx.x - kb_start[lo];
+    const int k0 = blk_off[j], L = blk_off[j + 1] - k0;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int pair = wave >> 1, role = wave & 1;
+    const int l32 = lane & 31, hf = lane >> 5;
+    const int kbase = run * 128 + pair * 64;            // first key of the pair inside the block
+    const bool pair_live = kbase < L;
+    const long long seg = (long long)bh * cap;
+    const int list0 = blk_ptr[(long long)bh * (nb + 1) + j];
+    const int cnt = blk_ptr[(long long)bh * (nb + 1) + j + 1] - list0;
+
+    // fragments of the pair's keys: K rows for wavefront 0, V rows for wavefront 1 (B operands, key = lane % 32)
+    bf16x8_t frag[2][KSTEPS];
+    int krow[2];
+    bool key_live[2];
+    {
+        const TensorView& src = role == 0 ? K : V;
+#pragma unroll
+        for (int kg = 0; kg < 2; ++kg) {
+            const int kk = kbase + kg * 32 + l32;
+            key_live[kg] = kk < L;
+            krow[kg] = k0 + min(kk, L - 1);
+            const char* sp = src.ptr + ((long long)b * src.stride_b + (long long)krow[kg] * src.stride_s + (long long)h * src.stride_h) * 2;
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) frag[kg][ks] = *reinterpret_cast<const bf16x8_t*>(sp + (ks * 16 + hf * 8) * 2);
+        }
+    }
+    f32x16_t acc[2][DT];                       // dV^T (wavefront 0) or dK^T (wavefront 1), [key group][channel tile]
+#pragma unroll
+    for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[kg][dt][i] = 0.f;
+
+    if (cnt > 0) {
+        const char* qbase = Q.ptr + ((long long)b * Q.stride_b + (long long)h * Q.stride_h) * 2;
+        const char* dobase = dO.ptr + ((long long)b * dO.stride_b + (long long)h * dO.stride_h) * 2;
+        const long long qss = Q.stride_s * 2, doss = dO.stride_s * 2;
+        const int* list = q_idx + seg + list0;
+        const float* lse_h = LSE + (long long)bh * S;
+        const float* dl_h = delta + (long long)bh * S;
+        const int n_chunks = (cnt + QC - 1) / QC;
+        const int H = 2 * n_chunks;
+
+        u32x4_t qreg[LOADS], doreg[LOADS];
+        float lreg = 0.f, dreg = 0.f;
+        int qn[LOADS], ql = 0;
+        bool ql_live = false, rows_live = false;
+        auto prefetch_idx = [&](int c) {       // chunks past the list: indices clamp, rows count as dead
+            const int c0 = c * QC;
+#pragma unroll
+            for (int i = 0; i < LOADS; ++i) {
+                const int r = (tid + NT * i) / (D / 8);
+                qn[i] = list[min(c0 + r, cnt - 1)];
+            }
+            ql = list[min(c0 + lane, cnt - 1)];
+            ql_live = c0 + lane < cnt;
+        };
+        auto load_piece = [&](int i) {
+            if (i < LOADS) {
+                const int pc = (tid + NT * i) % (D / 8);
+                qreg[i] = *reinterpret_cast<const u32x4_t*>(qbase + (long long)qn[i] * qss + pc * 16);
+            } else {
+                const int k = i - LOADS;
+                const int pc = (tid + NT * k) % (D / 8);
+                doreg[k] = *reinterpret_cast<const u32x4_t*>(dobase + (long long)qn[k] * doss + pc * 16);
+            }
+        };
+        // LSE and delta of the chunk's 64 rows: every wavefront fetches and stores all 64 (same values,
+        // same places), which keeps these accesses free of branches inside the pipelined loop
+        auto load_ld_regs = [&]() {
+            lreg = lse_h[ql];
+            dreg = dl_h[ql];
+            rows_live = ql_live;
+        };
+        auto stage_piece = [&](int buf, int i) {
+            const int k = i < LOADS ? i : i - LOADS;
+            const int piece = tid + NT * k;
+            const int r = piece / (D / 8), pc = piece % (D / 8);
+            if (i < LOADS) *reinterpret_cast<u32x4_t*>(&sQ[buf][r * STR + pc * 8]) = qreg[k];
+            else *reinterpret_cast<u32x4_t*>(&sdO[buf][r * STR + pc * 8]) = doreg[k];
+        };
+        // accumulator order: the 16 values a lane half needs per 32-query group are contiguous
+        const int ld_pos = (lane & 32) + ((lane & 1) << 4) + (((lane & 31) >> 4) << 3) + (((lane >> 1) & 1) << 2) + ((lane >> 2) & 3);
+        auto stage_ld = [&](int buf) {         // rows past the end of the list: LSE = +inf (weight 0), delta = 0
+            sL[buf][ld_pos] = rows_live ? lreg * LOG2E : INFINITY;
+            sDl[buf][ld_pos] = rows_live ? dreg : 0.f;
+        };
+        auto load_all = [&]() {
+#pragma unroll
+            for (int i = 0; i < 2 * LOADS; ++i) load_piece(i);
+            load_ld_regs();
+        };
+        auto stage_all = [&](int buf) {
+#pragma unroll
+            for (int i = 0; i < 2 * LOADS; ++i) stage_piece(buf, i);
+            stage_ld(buf);
+        };
+        // prologue: chunks 0 and 1 staged, rows of chunk 2 in flight, indices of chunk 3 in flight
+        prefetch_idx(0);
+        load_all();
+        prefetch_idx(1);
+        stage_all(0);
+        load_all();
+        prefetch_idx(2);
+        stage_all(1);
+        load_all();
+        prefetch_idx(3);
+
+        const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        // row operands come from the Q tile for wavefront 0 (S) and from the dO tile for wavefront 1 (dP);
+        // transposed operands from the dO tile for wavefront 0 (dV) and from the Q tile for wavefront 1 (dK)
+        const __bf16* rows_tile = role == 0 ? &sQ[0][0] : &sdO[0][0];
+        const __bf16* tr_tile = role == 0 ? &sdO[0][0] : &sQ[0][0];
+        const float* ld_tile = role == 0 ? &sL[0][0] : &sDl[0][0];
+        const int row_lane = rho(l32) * STR + hf * 8;
+        const int tr_lane = tr_lane_offset<STR>(lane);
+        auto half_off = [&](int half) { return ((half >> 1) & (NBUF - 1)) * (QC * STR) + (half & 1) * 32 * STR; };
+        auto read_rows = [&](int half, int ks) {
+            return *reinterpret_cast<const bf16x8_t*>(rows_tile + half_off(half) + row_lane + ks * 16);
+        };
+        auto read_tr = [&](int half, int step) {
+            return tr_operand<STR>(tr_tile + half_off(half) + tr_lane, 0, step / DT, (step % DT) * 32);
+        };
+
+        if (pair_live) {
+            f32x16_t x_cur[2] = {zero16, zero16};          // S or dP of local half-chunk t
+            bf16x8_t w_prev[2][2];                          // packed P or dS of local half-chunk t - 1, [kg][s]
+            {
+                const f32x4_t z4 = {0.f, 0.f, 0.f, 0.f};
+                const bf16x4_t zb = __builtin_convertvector(z4, bf16x4_t);
+                const bf16x8_t z8 = __builtin_shufflevector(zb, zb, 0, 1, 2, 3, 4, 5, 6, 7);
+                w_prev[0][0] = w_prev[0][1] = w_prev[1][0] = w_prev[1][1] = z8;
+            }
+            __syncthreads();
+            // S / dP of half-chunk 0
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                const bf16x8_t a = read_rows(0, ks);
+#pragma unroll
+                for (int kg = 0; kg < 2; ++kg)
+                    x_cur[kg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, frag[kg][ks], ks == 0 ? zero16 : x_cur[kg], 0, 0, 0);
+            }
+            bf16x8_t rcur = read_rows(1, 0);
+            bf16x8_t tcur = read_tr(0, 0);                  // local step 0 multiplies it by zeros
+            u32x4_t* xbuf = &sX[pair][0][0][lane];          // + parity * 256 + slot * 64
+
+            // one local step; ROLE and EVEN (parity of the workgroup step hc = t + ROLE) are compile-time
+            auto local_step = [&](int t, auto role_tag, auto even_tag) {
+                constexpr int ROLE = decltype(role_tag)::value;
+                constexpr bool EVEN = decltype(even_tag)::value;
+                const int hc = t + ROLE;
+                const int wbuf = ((hc >> 1) + 2) & (NBUF - 1);
+                float ld[16];
+                {
+                    const float* lp = ld_tile + ((t >> 1) & (NBUF - 1)) * QC + (t & 1) * 32 + hf * 16;
+#pragma unroll
+                    for (int g4 = 0; g4 < 4; ++g4) {
+                        const f32x4_t a4 = *reinterpret_cast<const f32x4_t*>(lp + g4 * 4);
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) ld[g4 * 4 + u] = a4[u];
+                    }
+                }
+                u32x4_t pin[4];
+                if constexpr (ROLE == 1) {
+#pragma unroll
+                    for (int sl = 0; sl < 4; ++sl) pin[sl] = xbuf[(t & 1) * 256 + sl * 64];
+                }
+                f32x16_t x_nxt[2] = {zero16, zero16};
+                float w[2][16];
+                const int th = t > 0 ? t - 1 : 0;
+#pragma unroll
+                for (int st = 0; st < NST; ++st) {
+                    bf16x8_t rn, tn;
+                    if (st + 1 < NST) { rn = read_rows(t + 1, st + 1); tn = read_tr(th, st + 1); }
+                    else { rn = read_rows(t + 2, 0); tn = read_tr(t, 0); }
+#pragma unroll
+                    for (int kg = 0; kg < 2; ++kg)
+                        x_nxt[kg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rcur, frag[kg][st], st == 0 ? zero16 : x_nxt[kg], 0, 0, 0);
+#pragma unroll
+                    for (int kg = 0; kg < 2; ++kg)
+                        acc[kg][st % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tcur, w_prev[kg][st / DT], acc[kg][st % DT], 0, 0, 0);
+#pragma unroll
+                    for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+                        for (int u = 0; u < 2 * VP; ++u) {
+                            const int i = 2 * VP * st + u;
+                            if constexpr (ROLE == 0) {
+                                w[kg][i] = exp2_raw(fmaf(x_cur[kg][i], scale_log2, -ld[i]));
+                            } else {
+                                const u32x4_t pk = pin[kg * 2 + i / 8];
+                                const uint32_t word = (i % 8) / 2 == 0 ? pk.x : (i % 8) / 2 == 1 ? pk.y : (i % 8) / 2 == 2 ? pk.z : pk.w;
+                                const float pval = (i & 1) ? bf16hi_to_f32(word) : bf16lo_to_f32(word);
+                                w[kg][i] = pval * (x_cur[kg][i] - ld[i]);
+                            }
+                        }
+                    // packed operands are replaced as soon as their last reader of this step has issued
+                    if (st == NST / 2 - 1 || st == NST - 1) {
+                        const int sidx = st == NST - 1 ? 1 : 0;
+#pragma unroll
+                        for (int kg = 0; kg < 2; ++kg) {
+                            w_prev[kg][sidx] = pack8(&w[kg][8 * sidx]);
+                            if constexpr (ROLE == 0) {
+                                u32x4_t o;
+                                __builtin_memcpy(&o, &w_prev[kg][sidx], 16);
+                                xbuf[(t & 1) * 256 + (kg * 2 + sidx) * 64] = o;
+                            }
+                        }
+                    }
+                    if constexpr (EVEN) {
+                        stage_piece(wbuf, st);
+                        load_piece(st);
+                        if (st == 0) { stage_ld(wbuf); load_ld_regs(); }
+                    } else {
+                        if (st == 0) prefetch_idx((hc >> 1) + 4);
+                    }
+                    rcur = rn;
+                    tcur = tn;
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                x_cur[0] = x_nxt[0];
+                x_cur[1] = x_nxt[1];
+            };
+            // a step in which this wavefront has no local step (hc = 0 for wavefront 1, hc = H + 1 for
+            // wavefront 0) still moves its share of the rows
+            auto idle_step = [&](int hc, auto even_tag) {
+                constexpr bool EVEN = decltype(even_tag)::value;
+                if constexpr (EVEN) {
+                    stage_all(((hc >> 1) + 2) & (NBUF - 1));
+                    load_all();
+                } else {
+                    prefetch_idx((hc >> 1) + 4);
+                }
+            };
+            if (role == 0) {
+                for (int c = 0; c < n_chunks; ++c) {
+                    if (c > 0) __syncthreads();
+                    local_step(2 * c, std::integral_constant<int, 0>{}, std::true_type{});
+                    __syncthreads();
+                    local_step(2 * c + 1, std::integral_constant<int, 0>{}, std::false_type{});
+                }
+                __syncthreads();
+                local_step(H, std::integral_constant<int, 0>{}, std::true_type{});       // drain: dV of the last half-chunk
+                __syncthreads();
+                idle_step(H + 1, std::false_type{});
+            } else {
+                idle_step(0, std::true_type{});
+                for (int c = 0; c < n_chunks; ++c) {
+                    __syncthreads();
+                    local_step(2 * c, std::integral_constant<int, 1>{}, std::false_type{});
+                    __syncthreads();
+                    local_step(2 * c + 1, std::integral_constant<int, 1>{}, std::true_type{});
+                }
+                __syncthreads();
+                local_step(H, std::integral_constant<int, 1>{}, std::false_type{});      // drain: dK of the last half-chunk
+            }
+        } else {
+            // a pair whose keys lie past the end of the block only helps to move rows
+            __syncthreads();
+            for (int c = 0; c <= n_chunks; ++c) {
+                if (c > 0) __syncthreads();
+                stage_all((c + 2) & (NBUF - 1));
+                load_all();
+                __syncthreads();
+                prefetch_idx(c + 4);
+            }
+        }
+    }
+    {
+        const TensorView& dst = role == 0 ? dV : dK;
+        const float f = role == 0 ? 1.f : scale;
+#pragma unroll
+        for (int kg = 0; kg < 2; ++kg) {
+            if (pair_live && key_live[kg]) {
+                const int kout = rows ? rows[krow[kg]] : krow[kg];
+                char* pd = dst.ptr + ((long long)b * dst.stride_b + (long long)kout * dst.stride_s + (long long)h * dst.stride_h) * 2;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int d = dt * 32 + g * 8 + hf * 4;
+                        u32x2_t wv;
+                        wv.x = pack_bf16x2(acc[kg][dt][4 * g + 0] * f, acc[kg][dt][4 * g + 1] * f);
+                        wv.y = pack_bf16x2(acc[kg][dt][4 * g + 2] * f, acc[kg][dt][4 * g + 3] * f);
+                        *reinterpret_cast<u32x2_t*>(pd + d * 2) = wv;
+                    }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // bf16 MFMA dK/dV kernel.  A workgroup of NW wavefronts owns 32*NW consecutive keys of one
 // block (wavefront w: 32 keys, key = MFMA column = lane % 32) and walks the block's query list
 // in chunks of 64 gathered queries (two half-chunks of 32):
@@ -838,9 +1171,12 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
             else if (bf16) attn_bwd_dkv_simple_kernel<true, 64><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
             else if (D == 128) attn_bwd_dkv_simple_kernel<false, 128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
             else attn_bwd_dkv_simple_kernel<false, 64><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
-        } else {
+        } else if (getenv("VMOBA_DKV_OLD") != nullptr) {
             if (D == 128) attn_bwd_dkv_mfma_kernel<128, NW><<<grid, dim3(64 * NW), 0, st>>>(DKV_ARGS);
             else attn_bwd_dkv_mfma_kernel<64, NW><<<grid, dim3(64 * NW), 0, st>>>(DKV_ARGS);
+        } else {
+            if (D == 128) attn_bwd_dkv_pair_kernel<128><<<grid, dim3(256), 0, st>>>(DKV_ARGS);
+            else attn_bwd_dkv_pair_kernel<64><<<grid, dim3(256), 0, st>>>(DKV_ARGS);
         }
 #undef DKV_ARGS
         VMOBA_PROFILE_END(2, st);
