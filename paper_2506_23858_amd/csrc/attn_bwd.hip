@@ -356,10 +356,17 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// bf16 MFMA dK/dV kernel, wavefront-pair variant.  The limiter of the kernel above is the LDS
-// issue rate (one operand fetch per matrix instruction, two for a transposed operand), not the
-// matrix pipe.  Here a workgroup still owns 128 keys of one block, but as two PAIRS of wavefronts
-// with 64 keys (two 32-key groups) each, and the two wavefronts of a pair split the products:
+// bf16 MFMA dK/dV kernel.  A workgroup owns 128 consecutive keys of one block (key = MFMA column
+// = lane % 32) and walks the block's query list in chunks of 64 gathered queries (two half-chunks
+// of 32), which pass through a ring of four LDS buffers; the gathered rows are prefetched into
+// registers one chunk ahead of the ring and their indices one more chunk ahead.
+//   S   = Q . K^T      A = Q rows (LDS),   B = K^T (registers, loaded once)
+//   dP  = dO . V^T     A = dO rows (LDS),  B = V^T (registers, loaded once)
+//   dV^T += dO^T . P   A = dO^T by transpose reads of the dO tile,  B = P packed from S
+//   dK^T += Q^T . dS   A = Q^T  by transpose reads of the Q tile,   B = dS
+// What limits such a kernel is the LDS issue rate (one operand fetch per matrix instruction, two
+// for a transposed operand), not the matrix pipe.  So the 128 keys are held by two PAIRS of
+// wavefronts with 64 keys (two 32-key groups) each, and the two wavefronts of a pair split the products:
 //   wavefront 0 of the pair:  S  = Q  . K^T  ->  P = exp(S - LSE)  ->  dV^T += dO^T . P
 //   wavefront 1 of the pair:  dP = dO . V^T  ->  dS = P * (dP - delta)  ->  dK^T += Q^T . dS
 // so every operand fetched from LDS feeds two matrix instructions (one per key group), and each
@@ -688,299 +695,6 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_pair_kernel(
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// bf16 MFMA dK/dV kernel.  A workgroup of NW wavefronts owns 32*NW consecutive keys of one
-// block (wavefront w: 32 keys, key = MFMA column = lane % 32) and walks the block's query list
-// in chunks of 64 gathered queries (two half-chunks of 32):
-//   S   = Q . K^T                     A = Q rows (LDS),   B = K^T (registers, loaded once)
-//   dP  = dO . V^T                    A = dO rows (LDS),  B = V^T (registers, loaded once)
-//   P = exp(S - LSE), dS = P * (dP - delta)        packed to bf16 as B operands
-//   dV^T += dO^T . P                  A = dO^T by transpose reads of the dO tile
-//   dK^T += Q^T . dS                  A = Q^T  by transpose reads of the Q tile
-// One wavefront per SIMD, so the overlap of matrix and vector work is arranged in the program
-// order: the exp/dS arithmetic of one half-chunk is interleaved with the S, dP products of the next
-// half-chunk or the dV, dK products of the previous one, which do not depend on it.
-// Chunks pass through a ring of three LDS buffers with one barrier per chunk; the gathered rows are
-// prefetched into registers one chunk ahead and the query indices two chunks ahead.
-template <int D, int NW>
-__global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_mfma_kernel(
-    TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
-    const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
-    const int* __restrict__ kb_start, TensorView dK, TensorView dV, const int* __restrict__ rows, int Hh, int S, int nb, long long cap,
-    float scale_log2, float scale) {
-    constexpr int NT = 64 * NW;
-    constexpr int QC = 64;
-    constexpr int STR = D + 8;
-    constexpr int KSTEPS = D / 16, DT = D / 32;
-    constexpr int LOADS = QC * D * 2 / 16 / NT;     // 16-byte pieces per thread per chunk and tensor
-    constexpr int NBUF = 4;                         // power of two: ring index = chunk & (NBUF - 1)
-    static_assert(QC * D * 2 / 16 % NT == 0, "chunk must divide evenly over the threads");
-    __shared__ __align__(16) __bf16 sQ[NBUF][QC * STR];
-    __shared__ __align__(16) __bf16 sdO[NBUF][QC * STR];
-    __shared__ __align__(16) float sL[NBUF][QC];
-    __shared__ __align__(16) float sDl[NBUF][QC];
-
-    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
-    // key runs are numbered block-major; kb_start[j] = runs in blocks 0..j-1.  (Handing each XCD whole
-    // blocks, so that the runs of a block share an L2, was measured slower: the XCDs end up unevenly loaded.)
-    if ((int)blockIdx.x >= kb_start[nb]) return;
-    int lo = 0, hi = nb;
-    while (hi - lo > 1) { int mid = (lo + hi) >> 1; if (kb_start[mid] <= (int)blockIdx.x) lo = mid; else hi = mid; }
-    const int j = lo, run = (int)blockIdx.x - kb_start[lo];
-    const int k0 = blk_off[j], L = blk_off[j + 1] - k0;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int l32 = lane & 31, hf = lane >> 5;
-    const int kk = run * (32 * NW) + wave * 32 + l32;   // key inside the block
-    const bool key_live = kk < L;
-    const bool wave_live = run * (32 * NW) + wave * 32 < L;
-    const int krow = k0 + min(kk, L - 1);
-    const long long seg = (long long)bh * cap;
-    const int list0 = blk_ptr[(long long)bh * (nb + 1) + j];
-    const int cnt = blk_ptr[(long long)bh * (nb + 1) + j + 1] - list0;
-
-    bf16x8_t kf[KSTEPS], vf[KSTEPS];
-    {
-        const char* sk = K.ptr + ((long long)b * K.stride_b + (long long)krow * K.stride_s + (long long)h * K.stride_h) * 2;
-        const char* sv = V.ptr + ((long long)b * V.stride_b + (long long)krow * V.stride_s + (long long)h * V.stride_h) * 2;
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-            kf[ks] = *reinterpret_cast<const bf16x8_t*>(sk + (ks * 16 + hf * 8) * 2);
-            vf[ks] = *reinterpret_cast<const bf16x8_t*>(sv + (ks * 16 + hf * 8) * 2);
-        }
-    }
-    f32x16_t dkacc[DT], dvacc[DT];
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { dkacc[dt][i] = 0.f; dvacc[dt][i] = 0.f; }
-
-    if (cnt > 0) {
-        const char* qbase = Q.ptr + ((long long)b * Q.stride_b + (long long)h * Q.stride_h) * 2;
-        const char* dobase = dO.ptr + ((long long)b * dO.stride_b + (long long)h * dO.stride_h) * 2;
-        const long long qss = Q.stride_s * 2, doss = dO.stride_s * 2;
-        const int* list = q_idx + seg + list0;
-        const float* lse_h = LSE + (long long)bh * S;
-        const float* dl_h = delta + (long long)bh * S;
-        const int n_chunks = (cnt + QC - 1) / QC;
-        const int H = 2 * n_chunks;               // half-chunks of 32 queries
-
-        u32x4_t qreg[LOADS], doreg[LOADS];
-        float lreg = 0.f, dreg = 0.f;
-        int qn[LOADS], ql = 0;
-        bool ql_live = false, rows_live = false;
-        // chunk indices past the list behave as chunks without live rows (indices clamp, LSE = +inf)
-        auto prefetch_idx = [&](int c) {
-            const int c0 = c * QC;
-#pragma unroll
-            for (int i = 0; i < LOADS; ++i) {
-                const int r = (tid + NT * i) / (D / 8);
-                qn[i] = list[min(c0 + r, cnt - 1)];
-            }
-        };
-        // the gathered rows travel in 2 * LOADS sixteen-byte pieces per thread: Q pieces, then dO pieces
-        auto load_piece = [&](int i) {
-            if (i < LOADS) {
-                const int pc = (tid + NT * i) % (D / 8);
-                qreg[i] = *reinterpret_cast<const u32x4_t*>(qbase + (long long)qn[i] * qss + pc * 16);
-            } else {
-                const int k = i - LOADS;
-                const int pc = (tid + NT * k) % (D / 8);
-                doreg[k] = *reinterpret_cast<const u32x4_t*>(dobase + (long long)qn[k] * doss + pc * 16);
-            }
-        };
-        // LSE and delta of the chunk's 64 rows: every wavefront fetches and stores all 64 (same values to the
-        // same places), which keeps these few accesses free of branches inside the pipelined loop
-        const int r64 = lane;
-        auto prefetch_ld_idx = [&](int c) {
-            ql = list[min(c * QC + r64, cnt - 1)];
-            ql_live = c * QC + r64 < cnt;
-        };
-        auto load_ld_regs = [&]() {
-            lreg = lse_h[ql];
-            dreg = dl_h[ql];
-            rows_live = ql_live;
-        };
-        auto stage_piece = [&](int buf, int i) {
-            const int k = i < LOADS ? i : i - LOADS;
-            const int piece = tid + NT * k;
-            const int r = piece / (D / 8), pc = piece % (D / 8);
-            if (i < LOADS) *reinterpret_cast<u32x4_t*>(&sQ[buf][r * STR + pc * 8]) = qreg[k];
-            else *reinterpret_cast<u32x4_t*>(&sdO[buf][r * STR + pc * 8]) = doreg[k];
-        };
-        // accumulator order: the 16 values a lane half needs per 32-query group are contiguous
-        const int ld_pos = (r64 & 32) + ((r64 & 1) << 4) + (((r64 & 31) >> 4) << 3) + (((r64 >> 1) & 1) << 2) + ((r64 >> 2) & 3);
-        auto stage_ld = [&](int buf) {
-            // rows past the end of the list get LSE = +inf (weight 0) and delta = 0
-            sL[buf][ld_pos] = rows_live ? lreg * LOG2E : INFINITY;
-            sDl[buf][ld_pos] = rows_live ? dreg : 0.f;
-        };
-        const int row_lane = rho(l32) * STR + hf * 8;
-        const int tr_lane = tr_lane_offset<STR>(lane);
-        const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-
-        struct RowOps { bf16x8_t qa, da; };       // A operands of S and dP for one k-step
-        struct TrOps { bf16x8_t dot, qt; };       // A operands of dV and dK for one (s, dt) step
-        // `half` = half-chunk index: chunk half / 2 sits in ring buffer (half / 2) % NBUF, rows 32 * (half % 2)
-        auto read_rows = [&](int half, int ks) {
-            const int o = ((half >> 1) & (NBUF - 1)) * (QC * STR) + (half & 1) * 32 * STR + row_lane + ks * 16;
-            RowOps r;
-            r.qa = *reinterpret_cast<const bf16x8_t*>(&sQ[0][o]);
-            r.da = *reinterpret_cast<const bf16x8_t*>(&sdO[0][o]);
-            return r;
-        };
-        auto read_tr = [&](int half, int step) {  // step = s * DT + dt
-            const int o = ((half >> 1) & (NBUF - 1)) * (QC * STR) + tr_lane;
-            TrOps t;
-            t.dot = tr_operand<STR>(&sdO[0][o], (half & 1) * 32, step / DT, (step % DT) * 32);
-            t.qt = tr_operand<STR>(&sQ[0][o], (half & 1) * 32, step / DT, (step % DT) * 32);
-            return t;
-        };
-        constexpr int NST = KSTEPS;               // steps of a half-chunk: k-steps of S / dP = (s, dt) steps of dV / dK
-        static_assert(NST == 2 * DT && NST == 2 * LOADS, "one row piece, one k-step and one (s, dt) step per step");
-        constexpr int VP = 8 / NST;               // exp / dS value pairs per step
-
-        // prologue: chunks 0 and 1 staged, rows of chunk 2 in flight, indices of chunk 3 in flight
-        auto load_all = [&]() {
-#pragma unroll
-            for (int i = 0; i < 2 * LOADS; ++i) load_piece(i);
-            load_ld_regs();
-        };
-        auto stage_all = [&](int buf) {
-#pragma unroll
-            for (int i = 0; i < 2 * LOADS; ++i) stage_piece(buf, i);
-            stage_ld(buf);
-        };
-        prefetch_idx(0); prefetch_ld_idx(0);
-        load_all();
-        prefetch_idx(1); prefetch_ld_idx(1);
-        stage_all(0);
-        load_all();
-        prefetch_idx(2); prefetch_ld_idx(2);
-        stage_all(1);
-        load_all();
-        prefetch_idx(3); prefetch_ld_idx(3);
-
-        if (wave_live) {
-            // Software pipeline over half-chunks.  Step hc runs, interleaved instruction by instruction,
-            //   matrix:  S, dP of half-chunk hc + 1     and     dV, dK += of half-chunk hc - 1
-            //   vector:  P = exp(S - LSE), dS = P * (dP - delta) of half-chunk hc
-            //   memory (even steps): rows of chunk hc/2 + 2 from registers into the ring, loads of chunk hc/2 + 3
-            // so every step carries the same mix and the vector work hides under the matrix work of its
-            // neighbours.  One barrier per chunk, before the even step: the buffer written during steps
-            // 2c, 2c + 1 (chunk c + 2) was last read in step 2c - 2 and is first read in step 2c + 3.
-            f32x16_t s_cur = zero16, p_cur = zero16;
-            bf16x8_t pf_prev[2], df_prev[2];
-            {
-                const f32x4_t z4 = {0.f, 0.f, 0.f, 0.f};
-                const bf16x4_t zb = __builtin_convertvector(z4, bf16x4_t);
-                const bf16x8_t z8 = __builtin_shufflevector(zb, zb, 0, 1, 2, 3, 4, 5, 6, 7);
-                pf_prev[0] = pf_prev[1] = df_prev[0] = df_prev[1] = z8;
-            }
-            __syncthreads();
-#pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) {
-                const RowOps r = read_rows(0, ks);
-                s_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(r.qa, kf[ks], ks == 0 ? zero16 : s_cur, 0, 0, 0);
-                p_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(r.da, vf[ks], ks == 0 ? zero16 : p_cur, 0, 0, 0);
-            }
-            RowOps rcur = read_rows(1, 0);
-            TrOps tcur = read_tr(0, 0);               // step 0 multiplies it by P = dS = 0
-            auto half_step = [&](int hc, auto even_tag) {
-                constexpr bool EVEN = decltype(even_tag)::value;
-                const int wbuf = ((hc >> 1) + 2) & (NBUF - 1);
-                float lv[16], dl[16], pv[16], dsv[16];
-                {
-                    const int o = ((hc >> 1) & (NBUF - 1)) * QC + (EVEN ? 0 : 32) + hf * 16;
-#pragma unroll
-                    for (int g4 = 0; g4 < 4; ++g4) {
-                        const f32x4_t a4 = *reinterpret_cast<const f32x4_t*>(&sL[0][o + g4 * 4]);
-                        const f32x4_t c4 = *reinterpret_cast<const f32x4_t*>(&sDl[0][o + g4 * 4]);
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) { lv[g4 * 4 + u] = a4[u]; dl[g4 * 4 + u] = c4[u]; }
-                    }
-                }
-                f32x16_t s_nxt = zero16, p_nxt = zero16;
-                const int th = hc > 0 ? hc - 1 : 0;
-#pragma unroll
-                for (int st = 0; st < NST; ++st) {
-                    RowOps rn;
-                    TrOps tn;
-                    if (st + 1 < NST) { rn = read_rows(hc + 1, st + 1); tn = read_tr(th, st + 1); }
-                    else { rn = read_rows(hc + 2, 0); tn = read_tr(hc, 0); }
-                    s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rcur.qa, kf[st], st == 0 ? zero16 : s_nxt, 0, 0, 0);
-                    p_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rcur.da, vf[st], st == 0 ? zero16 : p_nxt, 0, 0, 0);
-                    dvacc[st % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tcur.dot, pf_prev[st / DT], dvacc[st % DT], 0, 0, 0);
-                    dkacc[st % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tcur.qt, df_prev[st / DT], dkacc[st % DT], 0, 0, 0);
-#pragma unroll
-                    for (int u = 0; u < 2 * VP; ++u) {
-                        const int i = 2 * VP * st + u;
-                        pv[i] = exp2_raw(fmaf(s_cur[i], scale_log2, -lv[i]));
-                        dsv[i] = pv[i] * (p_cur[i] - dl[i]);
-                    }
-                    // the packed operands are replaced as soon as their last reader of this step has issued
-                    if (st == NST / 2 - 1) { pf_prev[0] = pack8(&pv[0]); df_prev[0] = pack8(&dsv[0]); }
-                    if (st == NST - 1) { pf_prev[1] = pack8(&pv[8]); df_prev[1] = pack8(&dsv[8]); }
-                    if constexpr (EVEN) {
-                        stage_piece(wbuf, st);
-                        load_piece(st);
-                        if (st == 0) { stage_ld(wbuf); load_ld_regs(); }
-                    } else {
-                        // indices of the chunk after that: a whole step ahead of the row loads that use them
-                        if (st == 0) { prefetch_idx((hc >> 1) + 4); prefetch_ld_idx((hc >> 1) + 4); }
-                    }
-                    rcur = rn;
-                    tcur = tn;
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                s_cur = s_nxt;
-                p_cur = p_nxt;
-            };
-            for (int c = 0; c < n_chunks; ++c) {
-                if (c > 0) __syncthreads();
-                half_step(2 * c, std::true_type{});
-                half_step(2 * c + 1, std::false_type{});
-            }
-            // drain: dV, dK of the last half-chunk
-#pragma unroll
-            for (int st = 0; st < NST; ++st) {
-                TrOps tn;
-                if (st + 1 < NST) tn = read_tr(H - 1, st + 1);
-                dvacc[st % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tcur.dot, pf_prev[st / DT], dvacc[st % DT], 0, 0, 0);
-                dkacc[st % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tcur.qt, df_prev[st / DT], dkacc[st % DT], 0, 0, 0);
-                if (st + 1 < NST) tcur = tn;
-            }
-        } else {
-            // a wavefront whose keys lie past the end of the block only helps to move rows
-            __syncthreads();
-            for (int c = 0; c < n_chunks; ++c) {
-                if (c > 0) __syncthreads();
-                stage_all((c + 2) & (NBUF - 1));
-                load_all();
-                prefetch_idx(c + 4);
-                prefetch_ld_idx(c + 4);
-            }
-        }
-    }
-    if (key_live) {
-        const int kout = rows ? rows[krow] : krow;
-        char* pk = dK.ptr + ((long long)b * dK.stride_b + (long long)kout * dK.stride_s + (long long)h * dK.stride_h) * 2;
-        char* pv = dV.ptr + ((long long)b * dV.stride_b + (long long)kout * dV.stride_s + (long long)h * dV.stride_h) * 2;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int d = dt * 32 + g * 8 + hf * 4;
-                u32x2_t wk, wv;
-                wk.x = pack_bf16x2(dkacc[dt][4 * g + 0] * scale, dkacc[dt][4 * g + 1] * scale);
-                wk.y = pack_bf16x2(dkacc[dt][4 * g + 2] * scale, dkacc[dt][4 * g + 3] * scale);
-                wv.x = pack_bf16x2(dvacc[dt][4 * g + 0], dvacc[dt][4 * g + 1]);
-                wv.y = pack_bf16x2(dvacc[dt][4 * g + 2], dvacc[dt][4 * g + 3]);
-                *reinterpret_cast<u32x2_t*>(pk + d * 2) = wk;
-                *reinterpret_cast<u32x2_t*>(pv + d * 2) = wv;
-            }
-    }
-}
-
 // dQ[q] = scale * sum over the query's pairs of dQpart[pair] (bfloat16 partials when PBF16).
 template <bool BF16, bool PBF16, int D>
 __global__ __launch_bounds__(256) void dq_merge_kernel(const float* __restrict__ dQpart, const int* __restrict__ row_ptr,
@@ -1158,8 +872,7 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     }
     // ---- dK, dV
     {
-        constexpr int NW = 4;
-        const int KPW = simple ? 64 : 32 * NW;
+        const int KPW = simple ? 64 : 128;      // keys per workgroup
         key_run_start_kernel<<<dim3(1), dim3(64), 0, st>>>(blk_off, ws.kb_start, n_blocks, KPW);
         VMOBA_CHECK_LAUNCH();
         // a multiple of 8 so that (workgroup id % 8) is the same for every head; + 8 for the per-XCD rounding
@@ -1171,9 +884,6 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
             else if (bf16) attn_bwd_dkv_simple_kernel<true, 64><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
             else if (D == 128) attn_bwd_dkv_simple_kernel<false, 128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
             else attn_bwd_dkv_simple_kernel<false, 64><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
-        } else if (getenv("VMOBA_DKV_OLD") != nullptr) {
-            if (D == 128) attn_bwd_dkv_mfma_kernel<128, NW><<<grid, dim3(64 * NW), 0, st>>>(DKV_ARGS);
-            else attn_bwd_dkv_mfma_kernel<64, NW><<<grid, dim3(64 * NW), 0, st>>>(DKV_ARGS);
         } else {
             if (D == 128) attn_bwd_dkv_pair_kernel<128><<<grid, dim3(256), 0, st>>>(DKV_ARGS);
             else attn_bwd_dkv_pair_kernel<64><<<grid, dim3(256), 0, st>>>(DKV_ARGS);
