@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0              # MI355X HBM3E peak (published)
 # HBM bytes per launch of the MFMA kernels at the 480p workload (mean over the 1d/2d/3d partitions, tau = 0.25),
 # from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/layer_480p_tau025_hbm_traffic_pmc.md
 # (FETCH_SIZE scaled by 2.000, WRITE_SIZE by 1.000: the factors a plain copy kernel of known size gives).
-MEASURED_TRAFFIC_BYTES_480P = {"attn_fwd_tile": 3.338e9, "attn_bwd_dq_tile": 4.232e9, "attn_bwd_dkv": 5.909e9}
+MEASURED_TRAFFIC_BYTES_480P = {"attn_fwd_tile": 3.334e9, "attn_bwd_dq_tile": 4.224e9, "attn_bwd_dkv": 5.873e9}
 METRIC = "VMoBA attn fwd+bwd ms/layer + effective TFLOP/s (%MFMA peak), 480p shape"
 
 
@@ -179,6 +179,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense comparators")
     ap.add_argument("--kinds", default="1d,2d,3d")
+    ap.add_argument("--no-extras", action="store_true", help="skip the copy-rate probe and the tau = 0.5 run (profiling runs)")
     ap.add_argument("--sweep", action="store_true", help="sequence-length sweep instead of the benchmark line")
     ap.add_argument("--sweep-frames", default="9,15,21,36,48,72")
     args = ap.parse_args()
@@ -313,6 +314,8 @@ def main():
 
     # ---- measured copy ceiling (plain device-to-device copy of 1 GiB, read + write counted)
     try:
+        if args.no_extras:
+            raise RuntimeError("skipped (--no-extras)")
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
         dst.copy_(src)
@@ -327,7 +330,7 @@ def main():
         out["memory_bound_steps"]["measured_copy_error"] = repr(e)[:100]
 
     # ---- the second threshold of the workload (tau = 0.5), 3D partition, a few steps
-    if abs(args.tau - 0.5) > 1e-9 and "3d" in cfg["partitions"]:
+    if abs(args.tau - 0.5) > 1e-9 and "3d" in cfg["partitions"] and not args.no_extras:
         try:
             bt, bh, bw, chunk = cfg["partitions"]["3d"]
             p5 = vb.LayerPlan(1, Hh, D, cfg["grid"], (bt, bh, bw), chunk, 0.5, dtype, fused_io=True)
