@@ -59,7 +59,16 @@ typedef enum {
     VMOBA_GLOBAL_THRESHOLD = 0, /* head's whole pool, descending cumulative similarity until tau * S (Eq. 4) */
     VMOBA_LOCAL_TOPK = 1,       /* every query keeps its `topk` most similar blocks                          */
     VMOBA_LOCAL_THRESHOLD = 2,  /* every query keeps the shortest descending prefix of its row reaching tau  */
-    VMOBA_GLOBAL_TOPK = 3       /* head's whole pool, the topk * S most similar pairs (Eq. 3 with a fixed k)  */
+    VMOBA_GLOBAL_TOPK = 3,      /* head's whole pool, the topk * S most similar pairs (Eq. 3 with a fixed k)  */
+    /* The other reading of "normalised similarity" in Sec. 3.4: ONE soft-max over the head's whole pool of
+     * S * n_blocks scores instead of one per query.  The pool then sums to 1, the cut is the shortest
+     * descending prefix that reaches tau, and P holds the pool-normalised values (its rows no longer sum to 1). */
+    VMOBA_POOL_SOFTMAX_THRESHOLD = 4,
+    /* Flag, OR-ed into any of the above: every query also keeps the block it lies in itself, so no query is
+     * left without keys (under global selection some are, Sec. 3.3; the original MoBA always keeps the
+     * current chunk).  The cut (k of the pool, theta) is taken as without the flag; k_out then reports the
+     * number of kept pairs, which can exceed it by up to S. */
+    VMOBA_SELECT_OWN_BLOCK = 0x100
 } vmoba_select_mode;
 
 /* Latent grid and key-block shape (Sec. 3.2, Eq. 1).  A block is a box of bt x bh x bw
@@ -126,7 +135,8 @@ int vmoba_partition(const vmoba_grid* g, int inverse, int B, int Hh, int D, int 
  *  Qp, Kp      block-order tensors (b, s, h, d) with the strides given
  *  tau         threshold in (0, 1]; tau >= 1 keeps every pair
  *  score_scale factor applied to <q, b> before the soft-max (1/sqrt(D) by convention)
- *  mode        a vmoba_select_mode; tau is used by the threshold modes, topk (>= 1) by the top-k modes.
+ *  mode        a vmoba_select_mode, optionally | VMOBA_SELECT_OWN_BLOCK (then allow S more pairs in
+ *              nnz_capacity); tau is used by the threshold modes, topk (>= 1) by the top-k modes.
  *              Ties rank by ascending block index (local modes) or ascending (query, block) (global modes).
  *              In the local modes k_out is the number of kept pairs and theta_out is 0
  *  Bmean  out  [B, Hh, n_blocks, D] float32 block means

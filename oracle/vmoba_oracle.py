@@ -170,14 +170,24 @@ def normalise_rows(S_hat):
     return (e / den).astype(np.float32)
 
 
+def normalise_pool(S_hat):
+    """The other reading of "normalised": ONE soft-max over the head's whole pool,
+    G[q, j] = exp(S_hat[q, j] - max) / sum over all (q, j), accumulated in float64 and rounded
+    once to float32.  The pool then sums to 1.  [Sec. 3.4, text before Eq. 4.]"""
+    x = S_hat.astype(np.float64)
+    e = np.exp(x - x.max())
+    return (e / e.sum()).astype(np.float32)
+
+
 # --------------------------------------------------------------------------- steps 5-6
-def threshold_topk(P, tau):
+def threshold_topk(P, tau, total=None):
     """Head-global threshold selection.  [Sec. 3.4, Eq. 4 and Sec. 3.3, Eq. 3.]
 
     The pool is every entry of P (shape [S, N_b], rows sum to one, so the pool sums
     to S).  Sort it descending (equal values: ascending (q, j)), accumulate in float64,
     k = the first prefix length whose sum is >= tau * S; the k best pairs form the mask.
     tau is taken in single precision (that is how it crosses the library boundary).
+    total: what the pool sums to when it is not S (1 for the pool soft-max of normalise_pool).
     Returns (k, theta, mask) with theta = the k-th largest value and mask bool [S, N_b].
     """
     S, nb = P.shape
@@ -190,7 +200,7 @@ def threshold_topk(P, tau):
         k = N
     else:
         csum = np.cumsum(sorted_vals.astype(np.float64))
-        target = tau32 * float(S)
+        target = tau32 * (float(S) if total is None else float(total))
         k = int(np.searchsorted(csum, target, side="left")) + 1
         if k > N:            # rounding kept the total just below tau * S
             k = N
@@ -203,7 +213,8 @@ def threshold_topk(P, tau):
 # Selection variants of the paper's ablation ("block choice design": top-k or threshold, chosen
 # per query -- "local" -- or from the head's whole pool -- "global"; the training-free runs use
 # local + top-k, the option of the original MoBA).  Ties are ordered by ascending block / (q, j).
-MODE_GLOBAL_THRESHOLD, MODE_LOCAL_TOPK, MODE_LOCAL_THRESHOLD, MODE_GLOBAL_TOPK = 0, 1, 2, 3
+MODE_GLOBAL_THRESHOLD, MODE_LOCAL_TOPK, MODE_LOCAL_THRESHOLD, MODE_GLOBAL_TOPK, MODE_POOL_SOFTMAX = 0, 1, 2, 3, 4
+MODE_OWN_BLOCK = 0x100      # flag: every query also keeps the block it lies in
 
 
 def local_topk(P, topk):
@@ -246,7 +257,13 @@ def global_topk(P, k_total):
 
 
 def select_blocks(Qp, Kp, blk_off, tau, score_scale, mode=MODE_GLOBAL_THRESHOLD, topk=0):
-    """Steps 2-6 for one head.  Returns dict(Bmean, S_hat, P, k, theta, mask)."""
+    """Steps 2-6 for one head.  Returns dict(Bmean, S_hat, P, k, theta, mask).
+    mode may carry MODE_OWN_BLOCK: after the selection every query also keeps the block that
+    holds its own position (no query is left without keys; the cut itself, theta, is unchanged
+    and k becomes the number of kept pairs).  [Sec. 3.3 leaves queries without blocks possible;
+    keeping the current block is the original MoBA's rule.]"""
+    own = bool(mode & MODE_OWN_BLOCK)
+    mode &= ~MODE_OWN_BLOCK
     Bm = block_means(Kp, blk_off)
     S_hat = block_scores(Qp, Bm, score_scale)
     P = normalise_rows(S_hat)
@@ -260,8 +277,16 @@ def select_blocks(Qp, Kp, blk_off, tau, score_scale, mode=MODE_GLOBAL_THRESHOLD,
         k, theta = int(mask.sum()), np.float32(0)
     elif mode == MODE_GLOBAL_TOPK:
         k, theta, mask = global_topk(P, topk * P.shape[0])
+    elif mode == MODE_POOL_SOFTMAX:
+        P = normalise_pool(S_hat)
+        k, theta, mask = threshold_topk(P, tau, total=1.0)
     else:
         raise ValueError(mode)
+    if own:
+        sizes = np.diff(np.asarray(blk_off, dtype=np.int64))
+        mask = mask.copy()
+        mask[np.arange(P.shape[0]), np.repeat(np.arange(len(sizes)), sizes)] = True
+        k = int(mask.sum())
     return dict(Bmean=Bm, S_hat=S_hat, P=P, k=k, theta=theta, mask=mask)
 
 

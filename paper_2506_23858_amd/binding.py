@@ -160,7 +160,8 @@ def vmoba_partition(g, inverse, B, Hh, D, ins, outs, perm, inv_perm, blk_off, st
     _check("vmoba_partition", rc)
 
 
-GLOBAL_THRESHOLD, LOCAL_TOPK, LOCAL_THRESHOLD, GLOBAL_TOPK = 0, 1, 2, 3
+GLOBAL_THRESHOLD, LOCAL_TOPK, LOCAL_THRESHOLD, GLOBAL_TOPK, POOL_SOFTMAX_THRESHOLD = 0, 1, 2, 3, 4
+SELECT_OWN_BLOCK = 0x100
 
 
 def vmoba_select(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode, topk, Bmean, P, mask,
@@ -215,12 +216,15 @@ class LayerPlan:
         self.score_scale = score_scale if score_scale is not None else 1.0 / math.sqrt(D)
         self.softmax_scale = softmax_scale if softmax_scale is not None else 1.0 / math.sqrt(D)
         self.mode, self.topk = int(mode), int(topk)
-        if mode == GLOBAL_THRESHOLD:
+        base_mode = self.mode & ~SELECT_OWN_BLOCK
+        if base_mode == GLOBAL_THRESHOLD:
             self.cap = nnz_capacity_for(self.S, self.nb, tau)
-        elif mode == LOCAL_THRESHOLD:
+        elif base_mode in (LOCAL_THRESHOLD, POOL_SOFTMAX_THRESHOLD):   # no bound below the whole pool
             self.cap = self.S * self.nb
         else:
             self.cap = self.S * min(self.topk, self.nb)
+        if self.mode & SELECT_OWN_BLOCK:
+            self.cap = min(self.cap + self.S, self.S * self.nb)
         S, nb, BH, cap = self.S, self.nb, B * Hh, self.cap
         dc = VMOBA_BF16 if dtype == torch.bfloat16 else VMOBA_F32
         i32 = dict(dtype=torch.int32, device=device)

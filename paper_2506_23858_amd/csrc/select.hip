@@ -38,6 +38,8 @@ struct SelectWs {               // workspace carve-up (device pointers)
     int* wcnt;                      // [BH][n_blocks][n_waves]
     int* blk_cnt;                   // [BH][n_blocks]
     size_t zero_bytes;              // leading bytes (hist + state) cleared on every call
+    float2* row_stat;   // [BH * S] {row maximum, row denominator} of the score soft-max (pool soft-max mode)
+    float2* pool_stat;  // [BH] {pool maximum, 1 / pool denominator}
     size_t total;
 };
 
@@ -55,6 +57,8 @@ SelectWs carve(void* base, int BH, int64_t S, int nb) {
     int64_t n_waves = ceil_div64(S, 64);
     w.wcnt = (int*)(p + off);                     off += align_up((size_t)BH * nb * n_waves * 4, 256);
     w.blk_cnt = (int*)(p + off);                  off += align_up((size_t)BH * nb * 4, 256);
+    w.row_stat = (float2*)(p + off);              off += align_up((size_t)BH * S * 8, 256);
+    w.pool_stat = (float2*)(p + off);             off += align_up((size_t)BH * 8, 256);
     w.total = off;
     return w;
 }
@@ -118,7 +122,8 @@ template <bool BF16, int D>
 __global__ __launch_bounds__(256) void score_kernel(TensorView Q, const float* __restrict__ Bmean,
                                                     float* __restrict__ P, unsigned int* __restrict__ hist_cnt,
                                                     unsigned long long* __restrict__ hist_sum,
-                                                    int Hh, int S, int nb, float score_scale, int fix_shift) {
+                                                    int Hh, int S, int nb, float score_scale, int fix_shift,
+                                                    float2* __restrict__ row_stat) {
     extern __shared__ __align__(16) unsigned char smem[];
     float* sB = reinterpret_cast<float*>(smem);                       // [nb][D]
     const int pstride = nb | 1;
@@ -182,6 +187,7 @@ __global__ __launch_bounds__(256) void score_kernel(TensorView Q, const float* _
         for (int j = 0; j < nb; ++j) m = fmaxf(m, sP[ql * pstride + j]);
         float den = 0.f;
         for (int j = 0; j < nb; ++j) den += expf(sP[ql * pstride + j] - m);
+        if (row_stat && wave == 0 && q0 + ql < S) row_stat[(long long)bh * S + q0 + ql] = make_float2(m, den);
         __syncthreads();
         for (int j = wave; j < nb; j += 4) sP[ql * pstride + j] = expf(sP[ql * pstride + j] - m) / den;
         __syncthreads();
@@ -220,7 +226,8 @@ template <int D>
 __global__ __launch_bounds__(256) void score_mfma_kernel(TensorView Q, const float* __restrict__ Bmean,
                                                          float* __restrict__ P, unsigned int* __restrict__ hist_cnt,
                                                          unsigned long long* __restrict__ hist_sum,
-                                                         int Hh, int S, int nb, float score_scale, int fix_shift) {
+                                                         int Hh, int S, int nb, float score_scale, int fix_shift,
+                                                         float2* __restrict__ row_stat) {
     constexpr int STR = D + 8;                 // LDS row stride in bf16 elements
     constexpr int KSTEPS = D / 16;
     constexpr int MAX_MT = 4;                  // up to 128 blocks
@@ -299,6 +306,7 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(TensorView Q, const flo
                 den += e;
             }
         den += __shfl_xor(den, 32, 64);
+        if (row_stat && q < S && hf == 0) row_stat[(long long)bh * S + q] = make_float2(m, den);
         if (q < S) {
             float* dst = P + ((long long)bh * S + q) * nb;
 #pragma unroll
@@ -409,6 +417,72 @@ __global__ __launch_bounds__(HIST_BINS) void scan_level_kernel(const unsigned in
             theta_out[bh] = theta;
         }
         state[bh] = ns;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Pool soft-max mode: "normalised" read as ONE soft-max over the head's whole pool of S * N_b scores.
+// With the row soft-max P[q, j] = exp(s_qj - m_q) / d_q already written, the pool value is
+//   G[q, j] = exp(s_qj - M) / Z = P[q, j] * w_q,   w_q = d_q exp(m_q - M) / Z,
+//   M = max_q m_q,   Z = sum_q d_q exp(m_q - M).
+// pool_stat_kernel: one workgroup per head, fixed summation order (double), so Z is reproducible.
+__global__ __launch_bounds__(1024) void pool_stat_kernel(const float2* __restrict__ row_stat, float2* __restrict__ pool_stat, int S) {
+    __shared__ float sM[1024];
+    __shared__ double sZ[1024];
+    const int bh = blockIdx.x, t = threadIdx.x;
+    const float2* rs = row_stat + (long long)bh * S;
+    float m = -INFINITY;
+    for (int q = t; q < S; q += 1024) m = fmaxf(m, rs[q].x);
+    sM[t] = m;
+    __syncthreads();
+    for (int off = 512; off >= 1; off >>= 1) {
+        if (t < off) sM[t] = fmaxf(sM[t], sM[t + off]);
+        __syncthreads();
+    }
+    const float M = sM[0];
+    double z = 0.0;
+    for (int q = t; q < S; q += 1024) z += (double)rs[q].y * (double)expf(rs[q].x - M);
+    sZ[t] = z;
+    __syncthreads();
+    for (int off = 512; off >= 1; off >>= 1) {
+        if (t < off) sZ[t] += sZ[t + off];
+        __syncthreads();
+    }
+    if (t == 0) pool_stat[bh] = make_float2(M, (float)(1.0 / sZ[0]));
+}
+
+// P <- G in place, and the first radix level (count + fixed-point sum per bin) of the new values.
+__global__ __launch_bounds__(256) void pool_rescale_kernel(float* __restrict__ P, const float2* __restrict__ row_stat,
+                                                           const float2* __restrict__ pool_stat,
+                                                           unsigned int* __restrict__ hist_cnt,
+                                                           unsigned long long* __restrict__ hist_sum,
+                                                           int S, int nb, int fix_shift) {
+    __shared__ unsigned int sCnt[HIST_BINS];
+    __shared__ unsigned long long sSum[HIST_BINS];
+    const int bh = blockIdx.y;
+    for (int i = threadIdx.x; i < HIST_BINS; i += 256) { sCnt[i] = 0u; sSum[i] = 0ull; }
+    __syncthreads();
+    const float2 ps = pool_stat[bh];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    for (int q = blockIdx.x * 4 + wv; q < S; q += gridDim.x * 4) {      // one wavefront per row
+        const float2 rs = row_stat[(long long)bh * S + q];
+        const float w = rs.y * expf(rs.x - ps.x) * ps.y;
+        float* row = P + ((long long)bh * S + q) * nb;
+        for (int j = lane; j < nb; j += 64) {
+            const float g = row[j] * w;
+            row[j] = g;
+            const unsigned int bin = min(__float_as_uint(g) >> 20, (unsigned)(HIST_BINS - 1));
+            atomicAdd(&sCnt[bin], 1u);
+            atomicAdd(&sSum[bin], to_fixed(g, fix_shift));
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < HIST_BINS; i += 256) {
+        const unsigned int c = sCnt[i];
+        if (c) {
+            atomicAdd(&hist_cnt[(long long)bh * HIST_BINS + i], c);
+            atomicAdd(&hist_sum[(long long)bh * HIST_BINS + i], sSum[i]);
+        }
     }
 }
 
@@ -542,10 +616,21 @@ __global__ __launch_bounds__(SCAN_THREADS) void row_scan_kernel(const int* __res
 // TopkMask (Eq. 3): bit (q, j) = P[q, j] is among the k best of the head.  One wavefront per
 // 64 consecutive queries.  Also counts, per wavefront, how many of its queries keep each block
 // (the raw material of the block-major list).
+// Block that holds block-order position q (blk_off ascending, blk_off[0] = 0, blk_off[nb] = S).
+__device__ __forceinline__ int block_of_position(const int* __restrict__ blk_off, int nb, int q) {
+    int lo = 0, hi = nb;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (blk_off[mid] <= q) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// own_blk_off: null, or blk_off when every query also keeps the block it lies in itself.
 __global__ __launch_bounds__(256) void mask_kernel(const float* __restrict__ P, const HeadState* __restrict__ state,
                                                    const int* __restrict__ tie_base, unsigned int* __restrict__ mask,
                                                    int* __restrict__ rowcnt, int* __restrict__ wcnt,
-                                                   int S, int nb, int n_waves) {
+                                                   int S, int nb, int n_waves, const int* __restrict__ own_blk_off) {
     __shared__ unsigned int sGt[4][64][VMOBA_MAX_MASK_WORDS + 1];
     __shared__ unsigned int sTie[4][64][VMOBA_MAX_MASK_WORDS + 1];
     const int bh = blockIdx.y;
@@ -585,11 +670,13 @@ __global__ __launch_bounds__(256) void mask_kernel(const float* __restrict__ P, 
     if (live) {
         const bool all_ties = (st.take == st.n_tie);
         int rank = all_ties ? 0 : tie_base[(long long)bh * (S + 1) + q];
+        const int own = own_blk_off ? block_of_position(own_blk_off, nb, q) : -1;
 #pragma unroll
         for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) {
             unsigned int g = 0;
             if (wd < words) {
                 g = sGt[wv][lane][wd];
+                if (wd == (own >> 5)) g |= 1u << (own & 31);       // own = -1: no word matches
                 unsigned int t = sTie[wv][lane][wd];
                 if (all_ties) {
                     g |= t;
@@ -630,7 +717,8 @@ __global__ __launch_bounds__(256) void mask_kernel(const float* __restrict__ P, 
 template <bool LOCAL_TOPK>
 __global__ __launch_bounds__(256) void local_mask_kernel(const float* __restrict__ P, unsigned int* __restrict__ mask,
                                                          int* __restrict__ rowcnt, int* __restrict__ wcnt,
-                                                         int S, int nb, int n_waves, int topk, float tau) {
+                                                         int S, int nb, int n_waves, int topk, float tau,
+                                                         const int* __restrict__ own_blk_off) {
     constexpr int MAXC = VMOBA_MAX_BLOCKS / 64;
     __shared__ float sRow[4][VMOBA_MAX_BLOCKS];
     __shared__ unsigned int sKeep[4][64][VMOBA_MAX_MASK_WORDS + 1];
@@ -682,11 +770,13 @@ __global__ __launch_bounds__(256) void local_mask_kernel(const float* __restrict
     const int q = q0 + lane;
     const bool live = lane < rows;
     int cnt = 0;
+    const int own = (own_blk_off && live) ? block_of_position(own_blk_off, nb, q) : -1;
 #pragma unroll
     for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) {
         unsigned int g = 0;
         if (live && wd < words) {
             g = sKeep[wv][lane][wd];
+            if (wd == (own >> 5)) g |= 1u << (own & 31);
             mask[((long long)bh * S + q) * words + wd] = g;
             cnt += __popc(g);
         }
@@ -704,11 +794,11 @@ __global__ __launch_bounds__(256) void local_mask_kernel(const float* __restrict
 
 // k_out / theta_out of the per-query modes: the number of kept pairs is the end of row_ptr.
 __global__ __launch_bounds__(64) void local_k_kernel(const int* __restrict__ row_ptr, long long* __restrict__ k_out,
-                                                     float* __restrict__ theta_out, int BH, int S) {
+                                                     float* __restrict__ theta_out, int BH, int S, int zero_theta) {
     const int bh = blockIdx.x * 64 + threadIdx.x;
     if (bh >= BH) return;
     k_out[bh] = row_ptr[(long long)bh * (S + 1) + S];
-    theta_out[bh] = 0.f;
+    if (zero_theta) theta_out[bh] = 0.f;
 }
 
 // Exclusive scan of wcnt over the wavefront index for every (head, block) (in place) and the
@@ -826,8 +916,12 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
         return VMOBA_ERR_INVALID_ARG;
     if (!tensor_ok(Qp) || !tensor_ok(Kp)) return VMOBA_ERR_INVALID_ARG;
     if (!std::isfinite(score_scale)) return VMOBA_ERR_INVALID_ARG;
-    if (mode < VMOBA_GLOBAL_THRESHOLD || mode > VMOBA_GLOBAL_TOPK) return VMOBA_ERR_UNSUPPORTED;
-    const bool uses_tau = mode == VMOBA_GLOBAL_THRESHOLD || mode == VMOBA_LOCAL_THRESHOLD;
+    const bool own_block = (mode & VMOBA_SELECT_OWN_BLOCK) != 0;
+    mode &= ~VMOBA_SELECT_OWN_BLOCK;
+    if (mode < VMOBA_GLOBAL_THRESHOLD || mode > VMOBA_POOL_SOFTMAX_THRESHOLD) return VMOBA_ERR_UNSUPPORTED;
+    const int* own_off = own_block ? blk_off : nullptr;
+    const bool pool_softmax = mode == VMOBA_POOL_SOFTMAX_THRESHOLD;
+    const bool uses_tau = mode == VMOBA_GLOBAL_THRESHOLD || mode == VMOBA_LOCAL_THRESHOLD || pool_softmax;
     if (uses_tau && (!(tau > 0.f) || !(tau <= 1.f))) return VMOBA_ERR_INVALID_ARG;
     if (!uses_tau && topk < 1) return VMOBA_ERR_INVALID_ARG;
     if (D != 64 && D != 128) return VMOBA_ERR_UNSUPPORTED;
@@ -844,7 +938,9 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
     const bool bf16 = Qp->dtype == VMOBA_BF16;
     const int n_waves = (int)ceil_div64(S, 64);
     const long long pool = (long long)S * n_blocks;
-    const int fix_shift = fix_shift_for(S);
+    // the pool sums to S (row soft-max) or to 1 (pool soft-max); the fixed-point scale leaves headroom for either
+    const int fix_shift = pool_softmax ? fix_shift_for(2) : fix_shift_for(S);
+    const double pool_total = pool_softmax ? 1.0 : (double)S;
     // target of the head-global cut: mass tau * S in fixed point (rounded up; tau >= 1 asks for more than the
     // pool can hold), or, for a fixed global k, the number of pairs topk * S
     unsigned long long target;
@@ -853,7 +949,7 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
     } else if (tau >= 1.f) {
         target = ~0ull;
     } else {
-        target = (unsigned long long)std::ceil((double)tau * (double)S * (double)(1ull << fix_shift));
+        target = (unsigned long long)std::ceil((double)tau * pool_total * (double)(1ull << fix_shift));
         if (target == 0) target = 1;
     }
     const TensorView Qv = make_view(Qp), Kv = make_view(Kp);
@@ -869,6 +965,7 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
 #undef LAUNCH_MEAN
     VMOBA_CHECK_LAUNCH();
 
+    float2* row_stat = pool_softmax ? ws.row_stat : nullptr;
     const int n_tiles = (int)ceil_div64(S, QT);
     const int tiles_per_wg = 4;
     dim3 sgrid((unsigned)ceil_div64(n_tiles, tiles_per_wg), (unsigned)BH);
@@ -878,7 +975,7 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
         if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
             return VMOBA_ERR_HIP;                                                                         \
         kfn<<<sgrid, dim3(256), lds, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks,  \
-                                           score_scale, fix_shift);                                       \
+                                           score_scale, fix_shift, row_stat);                             \
     } while (0)
     // bfloat16 queries and at most 128 blocks: scores on the matrix cores
     const int nb_pad = (n_blocks + 31) & ~31;
@@ -889,11 +986,11 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
         if (D == 128) {
             auto kfn = score_mfma_kernel<128>;
             if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_mfma) != hipSuccess) return VMOBA_ERR_HIP;
-            kfn<<<mgrid, dim3(256), lds_mfma, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks, score_scale, fix_shift);
+            kfn<<<mgrid, dim3(256), lds_mfma, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks, score_scale, fix_shift, row_stat);
         } else {
             auto kfn = score_mfma_kernel<64>;
             if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_mfma) != hipSuccess) return VMOBA_ERR_HIP;
-            kfn<<<mgrid, dim3(256), lds_mfma, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks, score_scale, fix_shift);
+            kfn<<<mgrid, dim3(256), lds_mfma, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks, score_scale, fix_shift, row_stat);
         }
     } else if (bf16 && D == 128) LAUNCH_SCORE(true, 128);
     else if (bf16 && D == 64) LAUNCH_SCORE(true, 64);
@@ -901,6 +998,16 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
     else LAUNCH_SCORE(false, 64);
 #undef LAUNCH_SCORE
     VMOBA_CHECK_LAUNCH();
+    if (pool_softmax) {
+        // the score kernel's first radix level was taken over the row soft-max: start it again over G
+        zero_words_kernel<<<dim3(64), dim3(256), 0, st>>>((unsigned int*)workspace, ws.zero_bytes / 4);
+        VMOBA_CHECK_LAUNCH();
+        pool_stat_kernel<<<dim3(BH), dim3(1024), 0, st>>>(ws.row_stat, ws.pool_stat, (int)S);
+        VMOBA_CHECK_LAUNCH();
+        pool_rescale_kernel<<<dim3((unsigned)std::min<int64_t>(ceil_div64(S, 4 * 8), 1024), (unsigned)BH), dim3(256), 0, st>>>(
+            P, ws.row_stat, ws.pool_stat, ws.hist_cnt, ws.hist_sum, (int)S, n_blocks, fix_shift);
+        VMOBA_CHECK_LAUNCH();
+    }
 
     unsigned int* hc1 = ws.hist_cnt + (size_t)BH * HIST_BINS;
     unsigned int* hc2 = ws.hist_cnt + (size_t)2 * BH * HIST_BINS;
@@ -912,9 +1019,9 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
     const bool local = mode == VMOBA_LOCAL_TOPK || mode == VMOBA_LOCAL_THRESHOLD;
     if (local) {
         if (mode == VMOBA_LOCAL_TOPK)
-            local_mask_kernel<true><<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, mask, ws.rowcnt, ws.wcnt, (int)S, n_blocks, n_waves, topk, tau);
+            local_mask_kernel<true><<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, mask, ws.rowcnt, ws.wcnt, (int)S, n_blocks, n_waves, topk, tau, own_off);
         else
-            local_mask_kernel<false><<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, mask, ws.rowcnt, ws.wcnt, (int)S, n_blocks, n_waves, topk, tau);
+            local_mask_kernel<false><<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, mask, ws.rowcnt, ws.wcnt, (int)S, n_blocks, n_waves, topk, tau, own_off);
         VMOBA_CHECK_LAUNCH();
     } else {
 #define SCAN_LEVEL(LV, HC, HS)                                                                                        \
@@ -941,13 +1048,13 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
         row_scan_kernel<<<dim3(BH), dim3(SCAN_THREADS), 0, st>>>(ws.ties, ws.tie_base, ws.state, 1, (int)S);
         VMOBA_CHECK_LAUNCH();
         mask_kernel<<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, ws.state, ws.tie_base, mask, ws.rowcnt, ws.wcnt,
-                                                            (int)S, n_blocks, n_waves);
+                                                            (int)S, n_blocks, n_waves, own_off);
         VMOBA_CHECK_LAUNCH();
     }
     row_scan_kernel<<<dim3(BH), dim3(SCAN_THREADS), 0, st>>>(ws.rowcnt, row_ptr, ws.state, 0, (int)S);
     VMOBA_CHECK_LAUNCH();
-    if (local) {
-        local_k_kernel<<<dim3((BH + 63) / 64), dim3(64), 0, st>>>(row_ptr, (long long*)k_out, theta_out, BH, (int)S);
+    if (local || own_off) {     // the number of kept pairs is not the k of the cut: take it from the lists
+        local_k_kernel<<<dim3((BH + 63) / 64), dim3(64), 0, st>>>(row_ptr, (long long*)k_out, theta_out, BH, (int)S, local ? 1 : 0);
         VMOBA_CHECK_LAUNCH();
     }
     wave_scan_kernel<<<dim3(n_blocks, BH), dim3(256), 0, st>>>(ws.wcnt, ws.blk_cnt, n_blocks, n_waves);

@@ -104,18 +104,24 @@ def undecided_local_threshold(P, tau, eps=1e-6, chunk=2048):
     return und
 
 
-def check_selection(g, o, b, h, band_tol=1e-6, mode=0, tau=None):
+def check_selection(g, o, b, h, band_tol=1e-6, mode=0, tau=None, topk=0):
     """Selection of head (b, h): GPU (g) against oracle (o).  Pairs whose oracle P lies within
     band_tol of the deciding value are exempt (they flip with the rounding of P): the head's
     threshold for the global modes, the row's last kept value for per-query top-k; for the
     per-query threshold see undecided_local_threshold."""
     P_or, m_or = o["P"][b, h], o["mask"][b, h]
+    own_flag = bool(mode & 0x100)   # a keep-own-block flag adds the same pairs on both sides
+    mode &= 0xff
     if mode in (0, 3):
         band = np.abs(P_or - o["theta"][b, h]) <= band_tol
+    elif mode == 4:     # pool soft-max: values are ~1 / (S N_b), so the band is relative to the threshold
+        band = np.abs(P_or - o["theta"][b, h]) <= 2e-5 * o["theta"][b, h]
     elif mode == 1:
-        kth = np.where(m_or, P_or, np.inf).min(axis=1, keepdims=True)
+        kk = min(int(topk), P_or.shape[1])
+        kth = -np.partition(-P_or, kk - 1, axis=1)[:, kk - 1:kk]          # the row's k-th largest value
         band = np.abs(P_or - kth) <= band_tol
-        assert np.all(g["mask"][b, h].sum(1) == m_or.sum(1))           # every query keeps exactly k blocks
+        if not own_flag:
+            assert np.all(g["mask"][b, h].sum(1) == m_or.sum(1))       # every query keeps exactly k blocks
     else:
         band = undecided_local_threshold(P_or, float(np.float32(tau)), band_tol)
     diff = g["mask"][b, h] != o["mask"][b, h]

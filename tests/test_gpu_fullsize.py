@@ -94,7 +94,7 @@ def check_layer_sampled(name, kind, tau, heads=None, bwd=True, sel_heads=None, g
         o = dict(P=sel["P"][None, None], theta=np.array([[sel["theta"]]]), mask=sel["mask"][None, None],
                  k=np.array([[sel["k"]]]))
         gh = dict(mask=mask_gpu[None, h:h + 1], k=k_gpu[h:h + 1].reshape(1, 1))
-        nband, ndiff = gu.check_selection(gh, o, 0, 0, mode=mode, tau=tau)
+        nband, ndiff = gu.check_selection(gh, o, 0, 0, mode=mode, tau=tau, topk=topk)
         assert np.abs(P_gpu[h] - sel["P"]).max() <= 5e-7
         gu.check_lists(g, 0, h)
         print(f"   head {h}: k_gpu={k_gpu[h]} k_oracle={sel['k']} band={nband} flipped={ndiff} "

@@ -212,3 +212,66 @@ def test_select_blocks_modes_feed_the_layer():
     assert np.all(out["mask"].sum(-1) == 3)
     out = vo.vmoba_layer(Q, K, V, (4, 8, 16), (2, 4, 4), tau=0.25, mode=vo.MODE_GLOBAL_TOPK, topk=3)
     assert np.all(out["mask"].sum((-1, -2)) == 3 * 512)
+
+
+def test_own_block_flag_adds_exactly_the_diagonal_blocks():
+    """MODE_OWN_BLOCK: the mask is the plain selection OR the (query, own block) pairs -- brute force over
+    positions -- so no row is empty, the cut (theta) is unchanged and k counts the kept pairs.  On the
+    hand-worked example at tau = 0.5 the query that kept nothing (q1, block 0) gets its own block."""
+    rng = np.random.default_rng(31)
+    blk_off = np.array([0, 5, 6, 14, 20])
+    S, D = 20, 8
+    Q, K = rng.standard_normal((S, D)).astype(np.float32), rng.standard_normal((S, D)).astype(np.float32)
+    for mode, topk in ((vo.MODE_GLOBAL_THRESHOLD, 0), (vo.MODE_LOCAL_TOPK, 1), (vo.MODE_GLOBAL_TOPK, 1)):
+        plain = vo.select_blocks(Q, K, blk_off, 0.2, 0.35, mode, topk)
+        own = vo.select_blocks(Q, K, blk_off, 0.2, 0.35, mode | vo.MODE_OWN_BLOCK, topk)
+        expect = plain["mask"].copy()
+        for q in range(S):
+            j = max(j for j in range(4) if blk_off[j] <= q)
+            expect[q, j] = True
+        assert np.array_equal(own["mask"], expect)
+        assert own["mask"].any(axis=1).all()
+        assert own["k"] == expect.sum() and own["theta"] == plain["theta"]
+    # the golden two-block example: q1 is empty at tau = 0.5 without the flag
+    keys = np.array([[1.0], [1.0], [-1.0], [-1.0]], dtype=np.float32)
+    qs = np.array([[0.5 * np.log(3)], [0.5 * np.log(1.5)], [-np.log(2)], [-0.5 * np.log(7 / 3)]], dtype=np.float32)
+    off = np.array([0, 2, 4])
+    plain = vo.select_blocks(qs, keys, off, 0.5, 1.0)
+    own = vo.select_blocks(qs, keys, off, 0.5, 1.0, vo.MODE_OWN_BLOCK)
+    assert not plain["mask"][1].any()
+    assert own["mask"].tolist() == [[True, False], [True, False], [False, True], [False, True]]
+    assert own["k"] == 4
+
+
+def test_pool_softmax_reading():
+    """normalise_pool / MODE_POOL_SOFTMAX: closed forms and the relation to the per-query soft-max."""
+    # worked by hand: scores [[ln 4, 0], [0, 0]] -> exp = [[4, 1], [1, 1]], sum 7
+    s = np.array([[np.log(4.0), 0.0], [0.0, 0.0]], dtype=np.float32)
+    G = vo.normalise_pool(s)
+    np.testing.assert_allclose(G, np.array([[4, 1], [1, 1]]) / 7.0, rtol=1e-6)
+    assert vo.threshold_topk(G, 0.5, total=1.0)[0] == 1                     # 4/7 >= 0.5
+    k, theta, mask = vo.threshold_topk(G, 0.6, total=1.0)                   # 5/7: ties enter in (q, j) order
+    assert k == 2 and mask.tolist() == [[True, True], [False, False]]
+    assert vo.threshold_topk(G, 0.75, total=1.0)[0] == 3                    # 6/7
+    assert vo.threshold_topk(G, 0.9, total=1.0)[0] == 4
+    # invariants on random scores: sums to one, shift invariance, rows renormalise to the row soft-max
+    rng = np.random.default_rng(8)
+    x = (3 * rng.standard_normal((40, 7))).astype(np.float32)
+    G = vo.normalise_pool(x)
+    assert abs(G.sum(dtype=np.float64) - 1.0) < 1e-6
+    np.testing.assert_allclose(vo.normalise_pool(x + np.float32(2.5)), G, rtol=2e-6)
+    np.testing.assert_allclose(G / G.sum(1, keepdims=True), vo.normalise_rows(x), rtol=2e-6)
+    # brute force of the cut
+    flat = np.sort(G.astype(np.float64).reshape(-1))[::-1]
+    for tau in (0.1, 0.37, 0.8):
+        k = vo.threshold_topk(G, tau, total=1.0)[0]
+        kk = next(i + 1 for i in range(flat.size) if flat[:i + 1].sum() >= float(np.float32(tau)))
+        assert k == kk
+    # the two readings differ: a query with one large score takes the pool's mass
+    Q = np.array([[10.0], [0.0]], dtype=np.float32)
+    K = np.array([[1.0], [0.0]], dtype=np.float32)
+    off = np.array([0, 1, 2])
+    pool = vo.select_blocks(Q, K, off, 0.5, 1.0, vo.MODE_POOL_SOFTMAX)
+    rows = vo.select_blocks(Q, K, off, 0.5, 1.0)
+    assert pool["mask"].tolist() == [[True, False], [False, False]] and pool["k"] == 1
+    assert rows["k"] == 2 and rows["mask"][1].any()
