@@ -55,15 +55,35 @@ __global__ __launch_bounds__(256) void delta_kernel(TensorView O, TensorView dO,
     if (q < S && part == 0) delta[(long long)bh * S + q] = acc;
 }
 
-// key-run table: kb_start[j] = number of key runs (of KPW keys) in blocks 0..j-1
-__global__ __launch_bounds__(64) void key_run_start_kernel(const int* __restrict__ blk_off, int* __restrict__ kb_start, int nb, int KPW) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    int run = 0;
-    for (int j = 0; j < nb; ++j) {
-        kb_start[j] = run;
-        run += (blk_off[j + 1] - blk_off[j] + KPW - 1) / KPW;
+// Key-run table of one head.  A "run" is KPW consecutive keys of one block, the share of one dK/dV
+// workgroup, and costs time in proportion to the length of the block's query list.  Workgroups are
+// dispatched in index order, so the blocks are numbered longest list first (a longest-processing-time
+// order: the short ones fill the tail of the launch): kb_order[r] = block at rank r,
+// kb_start[r] = number of runs of the blocks at ranks 0..r-1.  One workgroup per head.
+__global__ __launch_bounds__(256) void key_run_order_kernel(const int* __restrict__ blk_off, const int* __restrict__ blk_ptr,
+                                                            int* __restrict__ kb_start, int* __restrict__ kb_order, int nb, int KPW) {
+    __shared__ int sCnt[VMOBA_MAX_BLOCKS];
+    __shared__ int sRuns[VMOBA_MAX_BLOCKS];
+    const int bh = blockIdx.x, j = threadIdx.x;
+    const int* bp = blk_ptr + (long long)bh * (nb + 1);
+    const int cnt = j < nb ? bp[j + 1] - bp[j] : -1;
+    if (j < nb) sCnt[j] = cnt;
+    __syncthreads();
+    if (j < nb) {
+        int rank = 0;
+        for (int i = 0; i < nb; ++i) rank += (sCnt[i] > cnt || (sCnt[i] == cnt && i < j)) ? 1 : 0;
+        kb_order[(long long)bh * nb + rank] = j;
+        sRuns[rank] = (blk_off[j + 1] - blk_off[j] + KPW - 1) / KPW;
     }
-    kb_start[nb] = run;
+    __syncthreads();
+    if (j == 0) {
+        int run = 0;
+        for (int r = 0; r < nb; ++r) {
+            kb_start[(long long)bh * (nb + 1) + r] = run;
+            run += sRuns[r];
+        }
+        kb_start[(long long)bh * (nb + 1) + nb] = run;
+    }
 }
 
 __device__ __forceinline__ float load_elem(const char* p, int d, bool bf16) {
@@ -139,7 +159,7 @@ template <bool BF16, int D>
 __global__ __launch_bounds__(64) void attn_bwd_dkv_simple_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
-    const int* __restrict__ kb_start, TensorView dK, TensorView dV, const int* __restrict__ rows, int Hh, int S, int nb, long long cap,
+    const int* __restrict__ kb_start, const int* __restrict__ kb_order, TensorView dK, TensorView dV, const int* __restrict__ rows, int Hh, int S, int nb, long long cap,
     float scale_log2, float scale) {
     constexpr int KPW = 64, QC = 16;
     constexpr int ES = BF16 ? 2 : 4;
@@ -147,12 +167,13 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_simple_kernel(
     __shared__ float sdO[QC][D];
     __shared__ float sL[QC], sDl[QC];
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
-    if ((int)blockIdx.x >= kb_start[nb]) return;
+    const int* ks = kb_start + (long long)bh * (nb + 1);
+    if ((int)blockIdx.x >= ks[nb]) return;
     int lo = 0, hi = nb;
-    while (hi - lo > 1) { int mid = (lo + hi) >> 1; if (kb_start[mid] <= (int)blockIdx.x) lo = mid; else hi = mid; }
-    const int j = lo;
+    while (hi - lo > 1) { int mid = (lo + hi) >> 1; if (ks[mid] <= (int)blockIdx.x) lo = mid; else hi = mid; }
+    const int j = kb_order[(long long)bh * nb + lo];
     const int k0 = blk_off[j], L = blk_off[j + 1] - k0;
-    const int kk0 = ((int)blockIdx.x - kb_start[j]) * KPW;       // first key of this run inside the block
+    const int kk0 = ((int)blockIdx.x - ks[lo]) * KPW;            // first key of this run inside the block
     const int lane = threadIdx.x;
     const bool live = kk0 + lane < L;
     const int krow = k0 + min(kk0 + lane, L - 1);
@@ -382,7 +403,7 @@ template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_pair_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
-    const int* __restrict__ kb_start, TensorView dK, TensorView dV, const int* __restrict__ rows, int Hh, int S, int nb, long long cap,
+    const int* __restrict__ kb_start, const int* __restrict__ kb_order, TensorView dK, TensorView dV, const int* __restrict__ rows, int Hh, int S, int nb, long long cap,
     float scale_log2, float scale) {
     constexpr int NT = 256;
     constexpr int QC = 64;
@@ -400,10 +421,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_pair_kernel(
     __shared__ __align__(16) u32x4_t sX[2][2][4][64];     // [pair][step parity][kg * 2 + s][lane]: packed P
 
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
-    if ((int)blockIdx.x >= kb_start[nb]) return;
+    const int* ks = kb_start + (long long)bh * (nb + 1);
+    if ((int)blockIdx.x >= ks[nb]) return;
     int lo = 0, hi = nb;
-    while (hi - lo > 1) { int mid = (lo + hi) >> 1; if (kb_start[mid] <= (int)blockIdx.x) lo = mid; else hi = mid; }
-    const int j = lo, run = (int)blockIdx.x - kb_start[lo];
+    while (hi - lo > 1) { int mid = (lo + hi) >> 1; if (ks[mid] <= (int)blockIdx.x) lo = mid; else hi = mid; }
+    const int j = kb_order[(long long)bh * nb + lo], run = (int)blockIdx.x - ks[lo];
     const int k0 = blk_off[j], L = blk_off[j + 1] - k0;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int pair = wave >> 1, role = wave & 1;
@@ -760,7 +782,8 @@ struct BwdWs {
     float* delta;      // [BH][S]
     int* tile_start;   // [BH][257]
     int4* tile_desc;   // [BH][tiles_per_head]
-    int* kb_start;     // [257]
+    int* kb_start;     // [BH][257]
+    int* kb_order;     // [BH][256]
     char* dO_copy;     // [BH, S, D] block-order copy of dO (used with a row map)
     size_t total;
 };
@@ -773,7 +796,8 @@ BwdWs carve_bwd(void* base, int BH, int64_t S, int D, int64_t cap, int es) {
     w.delta = (float*)(p + off);     off += align_up((size_t)BH * S * 4, 256);
     w.tile_start = (int*)(p + off);  off += align_up((size_t)BH * (VMOBA_MAX_BLOCKS + 1) * 4, 256);
     w.tile_desc = (int4*)(p + off);  off += align_up((size_t)BH * vmoba_max_tiles(cap, 64) * 16, 256);
-    w.kb_start = (int*)(p + off);    off += align_up((size_t)(VMOBA_MAX_BLOCKS + 1) * 4, 256);
+    w.kb_start = (int*)(p + off);    off += align_up((size_t)BH * (VMOBA_MAX_BLOCKS + 1) * 4, 256);
+    w.kb_order = (int*)(p + off);    off += align_up((size_t)BH * VMOBA_MAX_BLOCKS * 4, 256);
     w.dO_copy = p + off;             off += align_up((size_t)BH * S * D * es, 256);
     w.total = off;
     return w;
@@ -873,12 +897,12 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     // ---- dK, dV
     {
         const int KPW = simple ? 64 : 128;      // keys per workgroup
-        key_run_start_kernel<<<dim3(1), dim3(64), 0, st>>>(blk_off, ws.kb_start, n_blocks, KPW);
+        key_run_order_kernel<<<dim3(BH), dim3(256), 0, st>>>(blk_off, blk_ptr, ws.kb_start, ws.kb_order, n_blocks, KPW);
         VMOBA_CHECK_LAUNCH();
         // a multiple of 8 so that (workgroup id % 8) is the same for every head; + 8 for the per-XCD rounding
         dim3 grid((unsigned)((S / KPW + n_blocks + 7) / 8 * 8 + 8), (unsigned)BH);
         VMOBA_PROFILE_BEGIN(2, st);
-#define DKV_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.kb_start, dKv, dVv, rows, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
+#define DKV_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.kb_start, ws.kb_order, dKv, dVv, rows, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
         if (simple) {
             if (bf16 && D == 128) attn_bwd_dkv_simple_kernel<true, 128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
             else if (bf16) attn_bwd_dkv_simple_kernel<true, 64><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
