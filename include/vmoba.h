@@ -178,6 +178,8 @@ int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_
  *  out_rows  optional int32 [S].  Null: O is written in block order.  Otherwise block-order row q
  *            goes to row out_rows[q] of O: pass the partition's perm and a tensor in the caller's
  *            token order to skip the inverse partition of O.  LSE stays in block order either way.
+ *  Limit (bfloat16): one (batch, head) slice of K' and of V' must span less than 4 GiB, i.e.
+ *  (S + 256) * stride_s * 2 < 2^32 with a positive stride_s; otherwise VMOBA_ERR_UNSUPPORTED.
  */
 int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
                    const vmoba_tensor* Qp, const vmoba_tensor* Kp, const vmoba_tensor* Vp,

@@ -11,6 +11,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <type_traits>
 
 __global__ __launch_bounds__(64) void tile_start_kernel(const int* __restrict__ blk_ptr, int* __restrict__ tile_start,
                                                         int BH, int nb, int TM) {
@@ -125,411 +126,402 @@ __global__ __launch_bounds__(64) void attn_fwd_tile_simple_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// bf16 MFMA tile kernel.  4 wavefronts; wavefront w owns NQ groups of 32 gathered queries
-// (TM = 128 * NQ per workgroup) and walks the block's keys in chunks of 64.
+// bf16 MFMA tile kernel.  NW wavefronts; wavefront w owns 32 gathered queries (a tile is 32 * NW list
+// entries of one key block) and the block's keys are walked in groups of 32.
 //
-// All products are computed transposed so that the query index is the MFMA column (= lane % 32):
+// Operand orientation.  All products are computed transposed so that the query index is the MFMA
+// column (= lane % 32):
 //   S^T[key, q] = K[key, :] . Q[q, :]          A = K rows from LDS, B = Q^T held in registers
 //   O^T[d, q]  += V^T[d, key] . P^T[key, q]    A = V^T by transpose reads, B = P^T packed from S^T
 // With the query on the lane, the row maximum and row sum of the online soft-max are reductions
-// over a lane's own registers plus one exchange with lane ^ 32.  The running maximum is only
-// raised when a chunk exceeds it by more than 2^8 (the probabilities then stay below 2^8, well
-// inside float32/bf16 range), so the accumulator rescale is rare; the final division by the row
-// sum makes the result independent of which maximum was used.
-template <int D, int NQ>
-__global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void attn_fwd_tile_mfma_kernel(
-    TensorView Q, TensorView K, TensorView V, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr,
-    const int* __restrict__ q_idx, const int4* __restrict__ tile_desc, int tiles_per_head, float* __restrict__ Opart,
-    float* __restrict__ lse_part, int Hh, int nb, long long cap, float scale_log2) {
-    constexpr int TM = 128 * NQ;
-    constexpr int KC = 64;                  // keys per chunk
-    constexpr int STR = D + 8;              // LDS row stride (bf16 elements)
-    constexpr int KSTEPS = D / 16;          // MFMA k-steps of the first product
-    constexpr int DT = D / 32;              // 32-row tiles of O^T
-    constexpr int LOADS = KC * D * 2 / 16 / 256;   // 16-byte pieces per thread per chunk and tensor
+// over a lane's own registers plus one exchange between the lane halves (v_permlane32_swap).  The
+// running maximum is only raised when a group exceeds it by more than 2^8 (the probabilities then
+// stay below 2^8, well inside float32 / bf16 range), so the accumulator rescale is rare; the final
+// division by the row sum makes the result independent of which maximum was used.  The row sum is
+// kept per lane half and the halves are added once at the end (they always agree on the maximum).
+//
+// Pipeline.  A wavefront's instruction stream is a three-stage software pipeline: step g issues
+//     S^T(g+1) = K(g+1) . Q^T               (matrix)
+//     P(g)     = soft-max piece of S^T(g)   (vector)
+//     O^T     += V(g-1)^T . P(g-1)^T        (matrix)
+// interleaved unit by unit (unit u = k-step u of the first product and (s, dt) = (u / DT, u % DT)
+// of the second), with the LDS operands of unit u + 2 fetched during unit u, so neither LDS
+// latency nor the soft-max sits between dependent matrix instructions.  S^T and P live in two
+// register sets that swap roles every step.
+//
+// Rows.  K and V groups are loaded straight from global memory into rings of four LDS slots each
+// (global_load_lds_dwordx4: 64 lanes x 16 bytes land in 1024 consecutive LDS bytes), so no
+// registers hold rows in flight and a group is requested two steps before it is first read.  A
+// slot is 32 rows of 2*D bytes without padding; 16-byte piece p of row r is stored at piece
+// position p ^ f(r), f(r) = (r >> SH) & (pieces per row - 1), which keeps both the row reads of
+// the first product and the transposed reads of the second free of bank conflicts (D = 128; for
+// D = 64 the transposed reads take two-way conflicts).  The swizzle is applied on the global side
+// (the lane that fills piece position p' fetches piece p' ^ f(r)) and undone on the read side
+// with one XOR of the per-lane address.  Rows past the end of the block repeat its last key; the
+// surplus keys of the last group are masked to -inf in the soft-max.
+//
+// Ordering.  The loads are issued by inline assembly, so their waits are written by hand: every
+// step that requests rows starts with s_waitcnt vmcnt(loads of one step) -- the wavefront's own
+// loads of two steps ago have landed -- followed by the workgroup barrier, which makes every
+// wavefront's loads of two steps ago visible.  Step g requests K(g+4) into the slot of K(g) (last
+// read in step g-1) and V(g+2) into the slot of V(g-2) (last read in step g-1); K(g+2) and V(g)
+// are first read at the end of step g.
+//
+// Persistence.  Workgroup w takes tiles w, w + gridDim.x, ... of the flat tile list (all heads, see
+// flat_tile_desc_kernel) and overlaps the start of its next tile with the end of the current one:
+// the next descriptor is fetched early in the tile, the next tile's query index during the last
+// soft-max step, and its query rows (into the Q^T registers, the first product is done by then)
+// and K(0..3), V(0..1) during the final step, into slots nobody reads any more (the rings are
+// indexed by running group counters, so the next tile's first V slots differ from the slot of the
+// group the final step reads).
+__device__ __forceinline__ float swap_halves_max(float x) {
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
+    const u2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+}
+__device__ __forceinline__ float swap_halves_sum(float x) {
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
+    const u2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r.x) + __uint_as_float(r.y);
+}
+// 64 lanes x 16 bytes from base + byte_off (per lane) to LDS: lane i writes lds_addr + 16 * i (lds_addr is
+// wave-uniform).  Counts in vmcnt like any vector load; the compiler does not know about it.
+__device__ __forceinline__ void dma16(const char* base, uint32_t byte_off, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr)
+                 : "memory", "m0");
+}
+#define VMOBA_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
+    TensorView Q, TensorView K, TensorView V, const int* __restrict__ q_idx, const int4* __restrict__ flat_desc,
+    const int* __restrict__ head_base, int BH, float* __restrict__ Opart, float* __restrict__ lse_part, int Hh,
+    long long cap, float scale_log2) {
+    constexpr int G = 32;                   // keys per group
+    constexpr int RB = 2 * D;               // bytes per LDS row
+    constexpr int PPR = D / 8;              // 16-byte pieces per row
+    constexpr int SH = PPR == 16 ? 0 : 1;   // swizzle f(r) = (r >> SH) & (PPR - 1)
+    constexpr int SLOT = G * RB;            // bytes per ring slot
+    constexpr int NR = 4;                   // ring slots per tensor
+    constexpr int KSTEPS = D / 16, DT = D / 32, UNITS = KSTEPS;
+    constexpr int IPW = SLOT / 1024 / NW;   // load instructions per wavefront per group
+    constexpr int RPI = 1024 / RB;          // rows per load instruction
+    constexpr int NDMA = 2 * IPW;           // loads a wavefront issues per step (one K group, one V group)
     constexpr float LAZY = 8.f;
-    __shared__ __align__(16) __bf16 sK[KC * STR];
-    __shared__ __align__(16) __bf16 sV[KC * STR];
+    static_assert(UNITS % 4 == 0 && UNITS == 2 * DT && IPW >= 1 && IPW * NW * 1024 == SLOT && (D == 64 || D == 128), "unit bookkeeping");
+    __shared__ __align__(1024) char sK[NR * SLOT];
+    __shared__ __align__(1024) char sV[NR * SLOT];
 
-    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
-    TileCoord tc;
-    if (!find_tile(tile_desc, tiles_per_head, bh, blockIdx.x, tc)) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int total = head_base[BH];
+    int f = blockIdx.x;
+    if (f >= total) return;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hf = lane >> 5;
-    const long long seg = (long long)bh * cap;
+    const int ent = wave * 32 + l32;
+    const uint32_t sK0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)sK;
+    const uint32_t sV0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)sV;
 
-    // ---- Q^T operand: lane holds, for each of its NQ queries, 8 channels per k-step
-    bf16x8_t qf[NQ][KSTEPS];
-    int my_entry[NQ];
-#pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) {
-        const int ent = (wave * NQ + nq) * 32 + l32;          // entry inside the tile
-        my_entry[nq] = ent;
-        const int e = min(ent, tc.count - 1);                 // surplus rows repeat the last query
-        const int q = q_idx[seg + tc.list0 + tc.t0 + e];
+    // ---- per-tile state.  Descriptor: {first list entry, count | head << 10, first key, block length}
+    struct Tile {
+        int list0, count, bh, k0, L;
+        const char* kbase;
+        const char* vbase;
+        long long seg;
+    };
+    auto decode = [&](const int4 d) {
+        Tile t;
+        t.list0 = d.x;
+        t.count = d.y & 1023;
+        t.bh = d.y >> 10;
+        t.k0 = d.z;
+        t.L = d.w;
+        const int b = t.bh / Hh, h = t.bh % Hh;
+        t.kbase = K.ptr + ((long long)b * K.stride_b + (long long)h * K.stride_h) * 2;
+        t.vbase = V.ptr + ((long long)b * V.stride_b + (long long)h * V.stride_h) * 2;
+        t.seg = (long long)t.bh * cap;
+        return t;
+    };
+    auto query_of = [&](const Tile& t) {                          // surplus rows repeat the tile's last query
+        return q_idx[t.seg + t.list0 + min(ent, t.count - 1)];
+    };
+    bf16x8_t qf[KSTEPS];
+    auto load_q = [&](const Tile& t, int q) {
+        const int b = t.bh / Hh, h = t.bh % Hh;
         const char* src = Q.ptr + ((long long)b * Q.stride_b + (long long)q * Q.stride_s + (long long)h * Q.stride_h) * 2;
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks)
-            qf[nq][ks] = *reinterpret_cast<const bf16x8_t*>(src + (ks * 16 + hf * 8) * 2);
-    }
+        for (int ks = 0; ks < KSTEPS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8_t*>(src + (ks * 16 + hf * 8) * 2);
+    };
+    const uint32_t kss = (uint32_t)(K.stride_s * 2), vss = (uint32_t)(V.stride_s * 2);
+    const uint32_t k_adv = G * kss, v_adv = G * vss;
 
-    f32x16_t oacc[NQ][DT];
-    float m_run[NQ], l_run[NQ];
+    // Load instruction i of this wavefront fills LDS bytes [(wave * IPW + i) * 1024, + 1024) of a slot: lane -> row
+    // dr[i] of the group, piece position lane % PPR, i.e. piece (lane % PPR) ^ f(dr[i]) of the global row.  Byte offsets
+    // from the head's base are 32-bit (checked on the host); an offset past the block's last row is clamped to it.
+    uint32_t k_off[IPW], v_off[IPW], k_last[IPW], v_last[IPW];
+    auto first_offsets = [&](const Tile& t) {
 #pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) {
-        m_run[nq] = -INFINITY;
-        l_run[nq] = 0.f;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) oacc[nq][dt][i] = 0.f;
-    }
-
-    const char* kbase = K.ptr + ((long long)b * K.stride_b + (long long)h * K.stride_h) * 2;
-    const char* vbase = V.ptr + ((long long)b * V.stride_b + (long long)h * V.stride_h) * 2;
-    const long long kss = K.stride_s * 2, vss = V.stride_s * 2;
-    const int n_chunks = (tc.L + KC - 1) / KC;
-
-    u32x4_t kreg[LOADS], vreg[LOADS];
-    auto prefetch = [&](int c) {
-        const int c0 = c * KC;
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int piece = tid + 256 * i;
-            const int r = piece / (D / 8), pc = piece % (D / 8);
-            const long long row = tc.k0 + min(c0 + r, tc.L - 1);   // rows past the block repeat its last key
-            kreg[i] = *reinterpret_cast<const u32x4_t*>(kbase + row * kss + pc * 16);
-            vreg[i] = *reinterpret_cast<const u32x4_t*>(vbase + row * vss + pc * 16);
+        for (int i = 0; i < IPW; ++i) {
+            const int dr = (wave * IPW + i) * RPI + lane / PPR;
+            const uint32_t pc16 = (uint32_t)((lane % PPR) ^ ((dr >> SH) & (PPR - 1))) * 16;
+            k_off[i] = (uint32_t)(t.k0 + dr) * kss + pc16;
+            v_off[i] = (uint32_t)(t.k0 + dr) * vss + pc16;
+            k_last[i] = (uint32_t)(t.k0 + t.L - 1) * kss + pc16;
+            v_last[i] = (uint32_t)(t.k0 + t.L - 1) * vss + pc16;
         }
     };
-    auto stage = [&]() {
+    // request the next group of a tensor into ring slot `slot`; every call advances the offsets by one group
+    auto request = [&](const char* base, uint32_t* off, const uint32_t* last, uint32_t adv, uint32_t ring0, int slot) {
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int piece = tid + 256 * i;
-            const int r = piece / (D / 8), pc = piece % (D / 8);
-            *reinterpret_cast<u32x4_t*>(&sK[r * STR + pc * 8]) = kreg[i];
-            *reinterpret_cast<u32x4_t*>(&sV[r * STR + pc * 8]) = vreg[i];
+        for (int i = 0; i < IPW; ++i) {
+            dma16(base, min(off[i], last[i]), ring0 + (uint32_t)(slot & (NR - 1)) * SLOT + (uint32_t)(wave * IPW + i) * 1024);
+            off[i] += adv;
         }
     };
-    const __bf16* sK_lane = sK + rho(l32) * STR + hf * 8;
-    const __bf16* sV_lane = sV + tr_lane_offset<STR>(lane);
-
-    prefetch(0);
-    for (int c = 0; c < n_chunks; ++c) {
-        __syncthreads();                      // everyone is done reading the previous chunk
-        stage();
-        __syncthreads();
-        if (c + 1 < n_chunks) prefetch(c + 1);
-
-        const int valid = tc.L - c * KC;      // keys of this chunk inside the block (may exceed KC)
-        const int n_mt = valid > 32 ? 2 : 1;  // 32-key groups with at least one valid key
-
-        // ---- S^T = K . Q^T
-        f32x16_t sacc[NQ][2];
-        const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        __builtin_amdgcn_s_setprio(1);
+    int kb = 0, vb = 0;                    // running group counters: group x of the current tile uses slot (kb + x) & 3 / (vb + x) & 3
+    auto request_first_groups = [&](const Tile& t, int kb_t, int vb_t) {     // K(0..3), V(0..1) of tile t
+        first_offsets(t);
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-            if (mt < n_mt) {
+        for (int x = 0; x < 4; ++x) request(t.kbase, k_off, k_last, k_adv, sK0, kb_t + x);
 #pragma unroll
-                for (int ks = 0; ks < KSTEPS; ++ks) {
-                    const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sK_lane + mt * 32 * STR + ks * 16);
+        for (int x = 0; x < 2; ++x) request(t.vbase, v_off, v_last, v_adv, sV0, vb_t + x);
+    };
+
+    // read side: per-lane byte offsets inside a slot, completed by XOR with the k-step / channel-tile bits
+    const int kr = rho(l32);
+    const uint32_t a_lane = (uint32_t)kr * RB + (uint32_t)((hf ^ (kr >> SH)) & (PPR - 1)) * 16;
+    uint32_t c_lane[2];
+    {
+        const int g4 = lane >> 4, e = (lane >> 2) & 3, a = lane & 3;
 #pragma unroll
-                    for (int nq = 0; nq < NQ; ++nq)
-                        sacc[nq][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nq][ks], ks == 0 ? zero16 : sacc[nq][mt], 0, 0, 0);
+        for (int t = 0; t < 2; ++t) {
+            const int r = 4 * e + hf + 2 * t;
+            const int p0 = 2 * (g4 & 1) + (a >> 1);
+            c_lane[t] = (uint32_t)r * RB + (uint32_t)((p0 ^ (r >> SH)) & (PPR - 1)) * 16 + (a & 1) * 8;
+        }
+    }
+    auto readK = [&](int x, int ks) {
+        const uint32_t off = (a_lane ^ (uint32_t)(ks << 5)) + (uint32_t)((kb + x) & (NR - 1)) * SLOT;
+        return *reinterpret_cast<const bf16x8_t*>(sK + off);
+    };
+    auto readV = [&](int x, int u) {       // transposed operand: channel tile dt = u % DT, 16-row step s = u / DT
+        const uint32_t sl = (uint32_t)((vb + x) & (NR - 1)) * SLOT + (uint32_t)(u / DT) * 16 * RB;
+        const uint32_t x6 = (uint32_t)(u % DT) << 6;
+        const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_t*)(sV + ((c_lane[0] ^ x6) + sl)));
+        const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_t*)(sV + ((c_lane[1] ^ x6) + sl)));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+    const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    Tile cur = decode(flat_desc[f]);
+    load_q(cur, query_of(cur));
+    request_first_groups(cur, kb, vb);
+
+    for (;;) {
+        const int fn = f + (int)gridDim.x;
+        const bool has_next = fn < total;
+        const int4 nd = flat_desc[has_next ? fn : f];   // without a next tile the look-ahead repeats this one (loads only)
+        const int L = cur.L;
+        const int Gt = (L + G - 1) / G;
+        // A tile has Ge >= 2 steps with a soft-max (a block of one group gets a second, fully masked one) and
+        // Ge - 2 of them are "middle" steps.  The two register sets swap roles every step; the set that starts is
+        // chosen so that the last soft-max step always finds S^T in sB and P(g-1) in pA.
+        const int Ge = max(Gt, 2);
+        const int n_mid = Ge - 2;
+        const bool odd = n_mid & 1;
+
+        f32x16_t oacc[DT];
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) oacc[dt] = zero16;
+        float m_run = -INFINITY, l_run = 0.f;      // l_run: this lane half's share of the row sum
+        bf16x8_t opK[4], opV[4];                    // operands of units u .. u + 2, slot = unit % 4
+        f32x16_t sA = zero16, sB = zero16;
+        bf16x8_t pA[2], pB[2];
+
+        VMOBA_WAIT_VMCNT(0);                       // this wavefront's K(0..3), V(0..1) (and Q rows) have landed
+        __syncthreads();                           // ... and everybody else's
+        // S^T(0), and the operands of the first two units of step 0
+        if (odd) {
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(readK(0, ks), qf[ks], sB, 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(readK(0, ks), qf[ks], sA, 0, 0, 0);
+        }
+        opK[0] = readK(1, 0);
+        opK[1] = readK(1, 1);
+        opV[0] = opK[0];
+        opV[1] = opK[1];
+        const Tile nxt = decode(nd);
+        int nq = 0;
+
+        // one pipeline step; the flags are compile-time: QK / PV = the step has a first / second product, SM = it has a
+        // soft-max (MASK: with the keys past the block's end masked), NEXTPV = the next step has a second product,
+        // STAGE = it requests rows
+        auto step = [&](int g, auto qk_t, auto pv_t, auto sm_t, auto mask_t, auto nextpv_t, auto stage_t, f32x16_t& s_cur,
+                        f32x16_t& s_nxt, bf16x8_t(&p_new)[2], bf16x8_t(&p_prev)[2]) {
+            constexpr bool QK = decltype(qk_t)::value, PV = decltype(pv_t)::value, SM = decltype(sm_t)::value;
+            constexpr bool MASK = decltype(mask_t)::value, NEXTPV = decltype(nextpv_t)::value, STAGE = decltype(stage_t)::value;
+            constexpr bool LAST_SM = SM && !QK;       // the first product is complete: Q^T may be replaced
+            constexpr bool FINAL = !SM;               // the tile's final step
+            if constexpr (STAGE) { VMOBA_WAIT_VMCNT(NDMA); __syncthreads(); }
+            if constexpr (LAST_SM) { VMOBA_WAIT_VMCNT(0); __syncthreads(); }
+            uint32_t w[8];                            // P of this step as packed bf16 pairs (accumulator values 2j, 2j + 1)
+            float m_new = m_run, alpha = 1.f;
+            bool raise = false;
+#pragma unroll
+            for (int u = 0; u < UNITS; ++u) {
+                const int u2 = u + 2;
+                bf16x8_t nk = opK[u2 & 3], nv = opV[u2 & 3];
+                if (u2 < UNITS) {
+                    if constexpr (QK) nk = readK(g + 1, u2);
+                    if constexpr (PV) nv = readV(g - 1, u2);
+                } else {
+                    if constexpr (QK) nk = readK(g + 2, u2 - UNITS);
+                    if constexpr (NEXTPV) nv = readV(g, u2 - UNITS);
                 }
-            } else {
+                if constexpr (QK) s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opK[u & 3], qf[u], u == 0 ? zero16 : s_nxt, 0, 0, 0);
+                if constexpr (PV) oacc[u % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opV[u & 3], p_prev[u / DT], oacc[u % DT], 0, 0, 0);
+                if constexpr (SM) {
+                    if (u == 0) {
+                        if constexpr (MASK) {
+                            const int vh = L - g * G - hf;          // accumulator value i is key row acc_row(i, 0) + hf
 #pragma unroll
-                for (int nq = 0; nq < NQ; ++nq) sacc[nq][mt] = zero16;   // masked to -inf below
-            }
-        }
-        __builtin_amdgcn_s_setprio(0);
-        if (valid < KC) {                     // last chunk: keys past the block get -inf
+                            for (int i = 0; i < 16; ++i)
+                                if (acc_row(i, 0) >= vh) s_cur[i] = -INFINITY;
+                        }
+                        float mx = fmaxf(s_cur[0], s_cur[1]);
 #pragma unroll
-            for (int nq = 0; nq < NQ; ++nq)
+                        for (int i = 2; i < 16; i += 2) mx = fmaxf(fmaxf(mx, s_cur[i]), s_cur[i + 1]);
+                        mx = swap_halves_max(mx * scale_log2);            // scale_log2 > 0
+                        raise = mx > m_run + LAZY;
+                        m_new = raise ? mx : m_run;
+                        alpha = raise ? exp2_raw(m_run - m_new) : 1.f;
+                        m_run = m_new;
+                        l_run *= alpha;
+                    } else {
+                        // the 8 value pairs are spread over units 1 .. UNITS - 1; a pair is packed as soon as it exists
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        if (mt * 32 + acc_row(i, hf) >= valid) sacc[nq][mt][i] = -INFINITY;
-        }
-        // ---- online soft-max (per lane = per query), in base-2 units
-        bf16x8_t pf[NQ][2][2];
-        bool need_rescale = false;
-        float alpha[NQ];
-#pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) {
-            float mx = sacc[nq][0][0];
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[nq][mt][i]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;       // scale_log2 > 0
-            const bool raise = mx > m_run[nq] + LAZY;
-            const float m_new = raise ? mx : m_run[nq];
-            alpha[nq] = raise ? exp2_raw(m_run[nq] - m_new) : 1.f;
-            need_rescale |= raise;
-            m_run[nq] = m_new;
-            float rs = 0.f;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                float p[16];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    p[i] = exp2_raw(fmaf(sacc[nq][mt][i], scale_log2, -m_new));
-                    rs += p[i];
-                }
-                pf[nq][mt][0] = pack8(&p[0]);
-                pf[nq][mt][1] = pack8(&p[8]);
-            }
-            rs += __shfl_xor(rs, 32, 64);
-            l_run[nq] = l_run[nq] * alpha[nq] + rs;
-        }
-        if (__any(need_rescale)) {
-#pragma unroll
-            for (int nq = 0; nq < NQ; ++nq)
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) oacc[nq][dt][i] *= alpha[nq];
-        }
-        // ---- O^T += V^T . P^T
-        __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-            if (mt < n_mt) {
-#pragma unroll
-                for (int s = 0; s < 2; ++s) {
-#pragma unroll
-                    for (int dt = 0; dt < DT; ++dt) {
-                        const bf16x8_t vf = tr_operand<STR>(sV_lane, mt * 32, s, dt * 32);
-#pragma unroll
-                        for (int nq = 0; nq < NQ; ++nq)
-                            oacc[nq][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nq][mt][s], oacc[nq][dt], 0, 0, 0);
+                        for (int j = 0; j < 8; ++j) {
+                            if (1 + (j * (UNITS - 1)) / 8 == u) {
+                                const float p0 = exp2_raw(fmaf(s_cur[2 * j], scale_log2, -m_new));
+                                const float p1 = exp2_raw(fmaf(s_cur[2 * j + 1], scale_log2, -m_new));
+                                l_run += p0 + p1;
+                                w[j] = pack_bf16x2(p0, p1);
+                                asm volatile("" : "+v"(w[j]));     // keeps the pair in this unit (it is only read a step later)
+                            }
+                        }
+                        asm volatile("" : "+v"(l_run));
+                        if (u == UNITS - 1) {
+                            const u32x4_t lo = {w[0], w[1], w[2], w[3]}, hi = {w[4], w[5], w[6], w[7]};
+                            __builtin_memcpy(&p_new[0], &lo, 16);
+                            __builtin_memcpy(&p_new[1], &hi, 16);
+                        }
                     }
                 }
+                if constexpr (STAGE) {
+                    if (u == 1) {
+                        request(cur.kbase, k_off, k_last, k_adv, sK0, kb + g + 4);
+                        request(cur.vbase, v_off, v_last, v_adv, sV0, vb + g + 2);
+                    }
+                }
+                if constexpr (LAST_SM) { if (u == 1) nq = query_of(nxt); }
+                if constexpr (FINAL) {
+                    if (u == 1) {          // the next tile: query rows first (the wait for nq must not cover the requests below)
+                        load_q(nxt, nq);
+                        request_first_groups(nxt, kb + g, vb + g);
+                    }
+                }
+                opK[u2 & 3] = nk;
+                opV[u2 & 3] = nv;
+                __builtin_amdgcn_sched_barrier(0);
             }
-        }
-        __builtin_amdgcn_s_setprio(0);
-    }
-
-    // ---- partial output: O^T value i of tile dt <-> channel 32*dt + 8*(i>>2) + 4*hf + (i&3)
+            if constexpr (PV && SM) {                 // the accumulator holds groups <= g - 1, all relative to the old maximum
+                if (__builtin_amdgcn_ballot_w64(raise)) {
 #pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) {
-        if (my_entry[nq] < tc.count) {
-            const long long pair = seg + tc.list0 + tc.t0 + my_entry[nq];
-            const float inv = 1.f / l_run[nq];
+                    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) oacc[dt][i] *= alpha;
+                }
+            }
+        };
+        using T = std::true_type;
+        using F = std::false_type;
+        //   (g,  QK,  PV,  SM,  MASK, NEXTPV, STAGE, S^T(g), S^T(g+1), P(g), P(g-1))
+        int g = 1;
+        if (odd) {
+            step(0, T{}, F{}, T{}, T{}, T{}, T{}, sB, sA, pB, pA);
+            step(1, T{}, T{}, T{}, F{}, T{}, T{}, sA, sB, pA, pB);
+            g = 2;
+        } else {
+            step(0, T{}, F{}, T{}, T{}, T{}, T{}, sA, sB, pA, pB);
+        }
+        for (int it = 0; it < (n_mid >> 1); ++it) {
+            step(g, T{}, T{}, T{}, F{}, T{}, T{}, sB, sA, pB, pA);
+            step(g + 1, T{}, T{}, T{}, F{}, T{}, T{}, sA, sB, pA, pB);
+            g += 2;
+        }
+        step(g, F{}, T{}, T{}, T{}, T{}, F{}, sB, sA, pB, pA);          // g = Ge - 1: last soft-max
+        step(g + 1, F{}, T{}, F{}, F{}, F{}, F{}, sA, sB, pA, pB);      // final step (g + 1 = Ge): second product of group Ge - 1
+
+        // ---- partial output: O^T value i of tile dt <-> channel 32*dt + 8*(i>>2) + 4*hf + (i&3)
+        const float l_tot = swap_halves_sum(l_run);
+        if (ent < cur.count) {
+            const long long pair = cur.seg + cur.list0 + ent;
+            const float inv = 1.f / l_tot;
             uint16_t* dst = reinterpret_cast<uint16_t*>(Opart) + pair * D;      // bf16 partials
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
+                for (int gq = 0; gq < 4; ++gq) {
                     u32x2_t v;
-                    v.x = pack_bf16x2(oacc[nq][dt][4 * g + 0] * inv, oacc[nq][dt][4 * g + 1] * inv);
-                    v.y = pack_bf16x2(oacc[nq][dt][4 * g + 2] * inv, oacc[nq][dt][4 * g + 3] * inv);
-                    *reinterpret_cast<u32x2_t*>(dst + dt * 32 + g * 8 + hf * 4) = v;
+                    v.x = pack_bf16x2(oacc[dt][4 * gq + 0] * inv, oacc[dt][4 * gq + 1] * inv);
+                    v.y = pack_bf16x2(oacc[dt][4 * gq + 2] * inv, oacc[dt][4 * gq + 3] * inv);
+                    *reinterpret_cast<u32x2_t*>(dst + dt * 32 + gq * 8 + hf * 4) = v;
                 }
-            if (hf == 0) lse_part[pair] = (m_run[nq] + log2f(l_run[nq])) * LN2;
+            if (hf == 0) lse_part[pair] = (m_run + log2f(l_tot)) * LN2;
         }
+        if (!has_next) break;
+        f = fn;
+        cur = nxt;
+        kb += Ge;
+        vb += Ge;
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// bf16 MFMA tile kernel, two-group variant.  8 wavefronts = 2 groups of 4; each group owns 128 of
-// the tile's 256 gathered queries (32 per wavefront) and both walk the same 64-key chunks, so a
-// chunk is staged once for 256 queries.  Time is cut into slots separated by workgroup barriers;
-// in every slot one group runs its matrix phase (S^T of chunk i, O^T += V^T P^T of chunk i-1) while
-// the other runs its soft-max phase, then they swap.  Each SIMD hosts one wavefront of either
-// group, so its matrix pipe and its vector ALU are busy at the same time by construction.
-//   group g: matrix phase of chunk i in slot 2i+g, soft-max of chunk i in slot 2i+g+1.
-// LDS: K and V chunks double-buffered.  K(i) is read in slots 2i, 2i+1 and V(i) in slots 2i+2, 2i+3;
-// at the start of every even slot 2m all threads store K(m+1) and V(m) (fetched two slots earlier
-// into registers) and issue the global loads of K(m+2) and V(m+1).
-template <int D>
-__global__ __launch_bounds__(512, 2) void attn_fwd_tile_pp_kernel(
-    TensorView Q, TensorView K, TensorView V, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr,
-    const int* __restrict__ q_idx, const int4* __restrict__ tile_desc, int tiles_per_head, float* __restrict__ Opart,
-    float* __restrict__ lse_part, int Hh, int nb, long long cap, float scale_log2) {
-    constexpr int TM = 256, KC = 64, STR = D + 8;
-    constexpr int KSTEPS = D / 16, DT = D / 32;
-    constexpr int LOADS = KC * D * 2 / 16 / 512;      // 16-byte pieces per thread per chunk and tensor
-    constexpr float LAZY = 8.f;
-    __shared__ __align__(16) __bf16 sK[2][KC * STR];
-    __shared__ __align__(16) __bf16 sV[2][KC * STR];
-
-    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
-    TileCoord tc;
-    if (!find_tile(tile_desc, tiles_per_head, bh, blockIdx.x, tc)) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int grp = wave >> 2;
-    const int l32 = lane & 31, hf = lane >> 5;
-    const long long seg = (long long)bh * cap;
-
-    const int ent = grp * 128 + (wave & 3) * 32 + l32;
-    bf16x8_t qf[KSTEPS];
-    {
-        const int e = min(ent, tc.count - 1);
-        const int q = q_idx[seg + tc.list0 + tc.t0 + e];
-        const char* src = Q.ptr + ((long long)b * Q.stride_b + (long long)q * Q.stride_s + (long long)h * Q.stride_h) * 2;
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8_t*>(src + (ks * 16 + hf * 8) * 2);
+// Flat tile list over all heads for the persistent tile kernels.  head_base[bh] = number of tiles of the heads
+// before bh (head_base[BH] = total); one thread.
+__global__ void head_base_kernel(const int* __restrict__ tile_start, int* __restrict__ head_base, int BH, int nb) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    int run = 0;
+    for (int bh = 0; bh < BH; ++bh) {
+        head_base[bh] = run;
+        run += tile_start[(long long)bh * (nb + 1) + nb];
     }
-    f32x16_t oacc[DT];
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) oacc[dt][i] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
-
-    const char* kbase = K.ptr + ((long long)b * K.stride_b + (long long)h * K.stride_h) * 2;
-    const char* vbase = V.ptr + ((long long)b * V.stride_b + (long long)h * V.stride_h) * 2;
-    const long long kss = K.stride_s * 2, vss = V.stride_s * 2;
-    const int n = (tc.L + KC - 1) / KC;
-
-    u32x4_t kreg[LOADS], vreg[LOADS];
-    auto load_k = [&](int c) {       // chunk index may run past the block: rows are clamped to its last key
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int piece = tid + 512 * i;
-            const int r = piece / (D / 8), pc = piece % (D / 8);
-            const long long row = tc.k0 + min(c * KC + r, tc.L - 1);
-            kreg[i] = *reinterpret_cast<const u32x4_t*>(kbase + row * kss + pc * 16);
-        }
-    };
-    auto load_v = [&](int c) {
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int piece = tid + 512 * i;
-            const int r = piece / (D / 8), pc = piece % (D / 8);
-            const long long row = tc.k0 + min(c * KC + r, tc.L - 1);
-            vreg[i] = *reinterpret_cast<const u32x4_t*>(vbase + row * vss + pc * 16);
-        }
-    };
-    auto store_k = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int piece = tid + 512 * i;
-            const int r = piece / (D / 8), pc = piece % (D / 8);
-            *reinterpret_cast<u32x4_t*>(&sK[buf][r * STR + pc * 8]) = kreg[i];
-        }
-    };
-    auto store_v = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int piece = tid + 512 * i;
-            const int r = piece / (D / 8), pc = piece % (D / 8);
-            *reinterpret_cast<u32x4_t*>(&sV[buf][r * STR + pc * 8]) = vreg[i];
-        }
-    };
-    const int k_lane = rho(l32) * STR + hf * 8;
-    const int v_lane = tr_lane_offset<STR>(lane);
-
-    // prologue: K(0) in place, K(1) and V(0) in flight
-    load_k(0);
-    store_k(0);
-    load_k(1);
-    load_v(0);
-    __syncthreads();
-
-    f32x16_t sacc[2];
-    bf16x8_t pf[2][2];
-    const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    const int n_slots = 2 * n + 2;
-    for (int sigma = 0; sigma < n_slots; ++sigma) {
-        if ((sigma & 1) == 0) {
-            const int m = sigma >> 1;
-            store_k((m + 1) & 1);       // K(m+1)
-            store_v(m & 1);             // V(m)
-            load_k(m + 2);
-            load_v(m + 1);
-        }
-        const int phase = sigma - grp;
-        const int i = phase >> 1;
-        if (phase >= 0 && (phase & 1) == 0) {
-            // ---- matrix phase: S^T(i) = K(i) . Q^T ;  O^T += V(i-1)^T . P(i-1)^T
-            __builtin_amdgcn_s_setprio(1);
-            if (i < n) {
-                const __bf16* kt = &sK[i & 1][0] + k_lane;
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int ks = 0; ks < KSTEPS; ++ks) {
-                        const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(kt + mt * 32 * STR + ks * 16);
-                        sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? zero16 : sacc[mt], 0, 0, 0);
-                    }
-            }
-            if (i >= 1) {
-                const __bf16* vt = &sV[(i - 1) & 1][0] + v_lane;
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int s = 0; s < 2; ++s)
-#pragma unroll
-                        for (int dt = 0; dt < DT; ++dt) {
-                            const bf16x8_t vf = tr_operand<STR>(vt, mt * 32, s, dt * 32);
-                            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[mt][s], oacc[dt], 0, 0, 0);
-                        }
-            }
-            __builtin_amdgcn_s_setprio(0);
-        } else if (phase >= 0 && i < n) {
-            // ---- soft-max phase of chunk i (per lane = per query), base-2 units
-            const int valid = tc.L - i * KC;
-            if (valid < KC) {
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        if (mt * 32 + acc_row(v, hf) >= valid) sacc[mt][v] = -INFINITY;
-            }
-            float mx = sacc[0][0];
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[mt][v]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
-            const bool raise = mx > m_run + LAZY;
-            const float m_new = raise ? mx : m_run;
-            const float alpha = raise ? exp2_raw(m_run - m_new) : 1.f;
-            m_run = m_new;
-            float rs = 0.f;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                float p[16];
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    p[v] = exp2_raw(fmaf(sacc[mt][v], scale_log2, -m_new));
-                    rs += p[v];
-                }
-                pf[mt][0] = pack8(&p[0]);
-                pf[mt][1] = pack8(&p[8]);
-            }
-            rs += __shfl_xor(rs, 32, 64);
-            l_run = l_run * alpha + rs;
-            if (__any(raise)) {
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
-            }
-        }
-        __syncthreads();
+    head_base[BH] = run;
+}
+// flat_desc[head_base[bh] + tile] = {first list entry, count | bh << 10, first key, block length}; one thread per
+// (head, tile id below tiles_per_head).
+__global__ __launch_bounds__(256) void flat_tile_desc_kernel(const int* __restrict__ tile_start, const int* __restrict__ blk_ptr,
+                                                             const int* __restrict__ blk_off, const int* __restrict__ head_base,
+                                                             int4* __restrict__ flat_desc, int nb, int TM, int tiles_per_head) {
+    const int bh = blockIdx.y;
+    const int tile = blockIdx.x * 256 + threadIdx.x;
+    const int* ts = tile_start + (long long)bh * (nb + 1);
+    if (tile >= tiles_per_head || tile >= ts[nb]) return;
+    int lo = 0, hi = nb;           // largest j with ts[j] <= tile
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (ts[mid] <= tile) lo = mid; else hi = mid;
     }
-
-    if (ent < tc.count) {
-        const long long pair = seg + tc.list0 + tc.t0 + ent;
-        const float inv = 1.f / l_run;
-        uint16_t* dst = reinterpret_cast<uint16_t*>(Opart) + pair * D;      // bf16 partials
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                u32x2_t v;
-                v.x = pack_bf16x2(oacc[dt][4 * g + 0] * inv, oacc[dt][4 * g + 1] * inv);
-                v.y = pack_bf16x2(oacc[dt][4 * g + 2] * inv, oacc[dt][4 * g + 3] * inv);
-                *reinterpret_cast<u32x2_t*>(dst + dt * 32 + g * 8 + hf * 4) = v;
-            }
-        if (hf == 0) lse_part[pair] = (m_run + log2f(l_run)) * LN2;
-    }
+    const int* bp = blk_ptr + (long long)bh * (nb + 1);
+    const int t0 = (tile - ts[lo]) * TM;
+    int4 d;
+    d.x = bp[lo] + t0;
+    d.y = min(TM, bp[lo + 1] - bp[lo] - t0) | (bh << 10);
+    d.z = blk_off[lo];
+    d.w = blk_off[lo + 1] - blk_off[lo];
+    flat_desc[head_base[bh] + tile] = d;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -624,7 +616,8 @@ struct FwdWs {
     float* Opart;      // [BH * cap][D]
     float* lse_part;   // [BH * cap]
     int* tile_start;   // [BH][nb + 1]
-    int4* tile_desc;   // [BH][tiles_per_head]
+    int4* tile_desc;   // [BH][tiles_per_head], or the flat list of all heads' tiles
+    int* head_base;    // [BH + 1]
     size_t total;
 };
 
@@ -641,6 +634,7 @@ FwdWs carve_fwd(void* base, int BH, int D, int64_t cap, int nb) {
     w.lse_part = (float*)(p + off);  off += align_up((size_t)BH * cap * 4, 256);
     w.tile_start = (int*)(p + off);  off += align_up((size_t)BH * (VMOBA_MAX_BLOCKS + 1) * 4, 256);
     w.tile_desc = (int4*)(p + off);  off += align_up((size_t)BH * vmoba_max_tiles(cap, 64) * 16, 256);
+    w.head_base = (int*)(p + off);   off += align_up((size_t)(BH + 1) * 4, 256);
     (void)nb;
     w.total = off;
     return w;
@@ -653,11 +647,18 @@ size_t vmoba_attn_fwd_workspace_bytes(int B, int Hh, int64_t S, int D, int64_t c
     return carve_fwd(nullptr, B * Hh, D, cap, 0).total;
 }
 
-// Which MFMA tile width the bf16 path uses (queries per workgroup = 128 * NQ).
-int vmoba_fwd_nq() {
-    const char* e = getenv("VMOBA_FWD_NQ");
-    int v = e ? atoi(e) : 1;      // 1: two workgroups per CU (measured faster); 2: wider tile, one per CU
-    return (v == 2) ? 2 : 1;
+// Compute units of the current device (queried once).
+int vmoba_num_cus() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            n = v;
+        else
+            n = 256;
+    }
+    return n;
 }
 
 extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
@@ -684,34 +685,44 @@ extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     const TensorView Qv = make_view(Qp), Kv = make_view(Kp), Vv = make_view(Vp), Ov = make_view(O);
     const float scale_log2 = softmax_scale * LOG2E;
     const bool simple = !bf16 || getenv("VMOBA_FORCE_SIMPLE") != nullptr;
-    const int nq = vmoba_fwd_nq();
-    const char* ppe = getenv("VMOBA_FWD_PP");
-    const bool two_group = ppe ? atoi(ppe) != 0 : false;
-    const int TM = simple ? 64 : (two_group ? 256 : 128 * nq);
+    // the MFMA kernel addresses the rows of one (batch, head) slice of K and V with 32-bit byte offsets
+    if (!simple && (Kp->stride_s <= 0 || Vp->stride_s <= 0 ||
+                    (uint64_t)(S + 256) * (uint64_t)Kp->stride_s * 2 >= ((uint64_t)1 << 32) ||
+                    (uint64_t)(S + 256) * (uint64_t)Vp->stride_s * 2 >= ((uint64_t)1 << 32)))
+        return VMOBA_ERR_UNSUPPORTED;
+    // bf16, D = 128: 256-query tiles, one persistent workgroup of 8 wavefronts per compute unit (a tile's K and V
+    // rows are fetched once per 256 queries); D = 64: 128-query tiles, two workgroups of 4 wavefronts per compute unit
+    const bool wide = !simple && D == 128;
+    const int TM = simple ? 64 : (wide ? 256 : 128);
     tile_start_kernel<<<dim3((BH + 63) / 64), dim3(64), 0, st>>>(blk_ptr, ws.tile_start, BH, n_blocks, TM);
     VMOBA_CHECK_LAUNCH();
     const int64_t max_tiles = std::min<int64_t>(vmoba_max_tiles(nnz_capacity, TM), (nnz_capacity / TM + n_blocks + 7) / 8 * 8);
-    tile_desc_kernel<<<dim3((unsigned)ceil_div64(max_tiles, 256), (unsigned)BH), dim3(256), 0, st>>>(
-        ws.tile_start, blk_ptr, blk_off, ws.tile_desc, n_blocks, TM, (int)max_tiles);
-    VMOBA_CHECK_LAUNCH();
-    dim3 grid((unsigned)max_tiles, (unsigned)BH);
-    VMOBA_PROFILE_BEGIN(0, st);
-#define TILE_ARGS Qv, Kv, Vv, blk_off, blk_ptr, q_idx, ws.tile_desc, (int)max_tiles, ws.Opart, ws.lse_part, Hh, n_blocks, (long long)nnz_capacity, scale_log2
     if (simple) {
+        tile_desc_kernel<<<dim3((unsigned)ceil_div64(max_tiles, 256), (unsigned)BH), dim3(256), 0, st>>>(
+            ws.tile_start, blk_ptr, blk_off, ws.tile_desc, n_blocks, TM, (int)max_tiles);
+    } else {
+        head_base_kernel<<<dim3(1), dim3(64), 0, st>>>(ws.tile_start, ws.head_base, BH, n_blocks);
+        VMOBA_CHECK_LAUNCH();
+        flat_tile_desc_kernel<<<dim3((unsigned)ceil_div64(max_tiles, 256), (unsigned)BH), dim3(256), 0, st>>>(
+            ws.tile_start, blk_ptr, blk_off, ws.head_base, ws.tile_desc, n_blocks, TM, (int)max_tiles);
+    }
+    VMOBA_CHECK_LAUNCH();
+    VMOBA_PROFILE_BEGIN(0, st);
+    if (simple) {
+        dim3 grid((unsigned)max_tiles, (unsigned)BH);
+#define TILE_ARGS Qv, Kv, Vv, blk_off, blk_ptr, q_idx, ws.tile_desc, (int)max_tiles, ws.Opart, ws.lse_part, Hh, n_blocks, (long long)nnz_capacity, scale_log2
         if (bf16 && D == 128) attn_fwd_tile_simple_kernel<true, 128><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
         else if (bf16) attn_fwd_tile_simple_kernel<true, 64><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
         else if (D == 128) attn_fwd_tile_simple_kernel<false, 128><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
         else attn_fwd_tile_simple_kernel<false, 64><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
-    } else if (two_group) {
-        if (D == 128) attn_fwd_tile_pp_kernel<128><<<grid, dim3(512), 0, st>>>(TILE_ARGS);
-        else attn_fwd_tile_pp_kernel<64><<<grid, dim3(512), 0, st>>>(TILE_ARGS);
-    } else {
-        if (D == 128 && nq == 2) attn_fwd_tile_mfma_kernel<128, 2><<<grid, dim3(256), 0, st>>>(TILE_ARGS);
-        else if (D == 128) attn_fwd_tile_mfma_kernel<128, 1><<<grid, dim3(256), 0, st>>>(TILE_ARGS);
-        else if (nq == 2) attn_fwd_tile_mfma_kernel<64, 2><<<grid, dim3(256), 0, st>>>(TILE_ARGS);
-        else attn_fwd_tile_mfma_kernel<64, 1><<<grid, dim3(256), 0, st>>>(TILE_ARGS);
-    }
 #undef TILE_ARGS
+    } else {
+        const dim3 pgrid((unsigned)std::min<int64_t>((wide ? 1 : 2) * (int64_t)vmoba_num_cus(), (int64_t)BH * max_tiles));
+#define MFMA_ARGS Qv, Kv, Vv, q_idx, ws.tile_desc, ws.head_base, BH, ws.Opart, ws.lse_part, Hh, (long long)nnz_capacity, scale_log2
+        if (wide) attn_fwd_tile_mfma_kernel<128, 8><<<pgrid, dim3(512), 0, st>>>(MFMA_ARGS);
+        else attn_fwd_tile_mfma_kernel<64, 4><<<pgrid, dim3(256), 0, st>>>(MFMA_ARGS);
+#undef MFMA_ARGS
+    }
     VMOBA_PROFILE_END(0, st);
     VMOBA_CHECK_LAUNCH();
     const bool pbf16 = !simple;               // the MFMA tile kernels write bfloat16 partials
