@@ -167,7 +167,7 @@ __global__ __launch_bounds__(64) void attn_fwd_tile_simple_kernel(
 // read in step g-1) and V(g+2) into the slot of V(g-2) (last read in step g-1); K(g+2) and V(g)
 // are first read at the end of step g.
 //
-// Persistence.  Workgroup w takes tiles w, w + gridDim.x, ... of the flat tile list (all heads, see
+// Persistence.  A workgroup strides through its XCD's share of the flat tile list (all heads, see
 // flat_tile_desc_kernel) and overlaps the start of its next tile with the end of the current one:
 // the next descriptor is fetched early in the tile, the next tile's query index during the last
 // soft-max step, and its query rows (into the Q^T registers, the first product is done by then)
@@ -212,9 +212,16 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
     __shared__ __align__(1024) char sK[NR * SLOT];
     __shared__ __align__(1024) char sV[NR * SLOT];
 
+    // Workgroup ids go round the 8 XCDs (each with its own L2), so XCD x = id % 8 takes the x-th eighth of the tile
+    // list and its workgroups stride through it: a key block's tiles then share one L2 instead of eight.
     const int total = head_base[BH];
-    int f = blockIdx.x;
-    if (f >= total) return;
+    const bool by_xcd = (gridDim.x & 7) == 0;
+    const int xcd = by_xcd ? (int)(blockIdx.x & 7) : 0;
+    const int f_step = by_xcd ? (int)(gridDim.x >> 3) : (int)gridDim.x;
+    const int per_xcd = by_xcd ? (total + 7) >> 3 : total;
+    const int f_end = min(total, (xcd + 1) * per_xcd);
+    int f = xcd * per_xcd + (by_xcd ? (int)(blockIdx.x >> 3) : (int)blockIdx.x);
+    if (f >= f_end) return;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hf = lane >> 5;
@@ -318,8 +325,8 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
     request_first_groups(cur, kb, vb);
 
     for (;;) {
-        const int fn = f + (int)gridDim.x;
-        const bool has_next = fn < total;
+        const int fn = f + f_step;
+        const bool has_next = fn < f_end;
         const int4 nd = flat_desc[has_next ? fn : f];   // without a next tile the look-ahead repeats this one (loads only)
         const int L = cur.L;
         const int Gt = (L + G - 1) / G;
