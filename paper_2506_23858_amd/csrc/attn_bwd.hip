@@ -60,8 +60,10 @@ __global__ __launch_bounds__(256) void delta_kernel(TensorView O, TensorView dO,
 // dispatched in index order, so the blocks are numbered longest list first (a longest-processing-time
 // order: the short ones fill the tail of the launch): kb_order[r] = block at rank r,
 // kb_start[r] = number of runs of the blocks at ranks 0..r-1.  One workgroup per head.
+// A last run of at most tail_max keys is not counted: the tail kernel takes those keys.
 __global__ __launch_bounds__(256) void key_run_order_kernel(const int* __restrict__ blk_off, const int* __restrict__ blk_ptr,
-                                                            int* __restrict__ kb_start, int* __restrict__ kb_order, int nb, int KPW) {
+                                                            int* __restrict__ kb_start, int* __restrict__ kb_order, int nb, int KPW,
+                                                            int tail_max) {
     __shared__ int sCnt[VMOBA_MAX_BLOCKS];
     __shared__ int sRuns[VMOBA_MAX_BLOCKS];
     const int bh = blockIdx.x, j = threadIdx.x;
@@ -73,7 +75,9 @@ __global__ __launch_bounds__(256) void key_run_order_kernel(const int* __restric
         int rank = 0;
         for (int i = 0; i < nb; ++i) rank += (sCnt[i] > cnt || (sCnt[i] == cnt && i < j)) ? 1 : 0;
         kb_order[(long long)bh * nb + rank] = j;
-        sRuns[rank] = (blk_off[j + 1] - blk_off[j] + KPW - 1) / KPW;
+        const int L = blk_off[j + 1] - blk_off[j];
+        const int tail = L % KPW;
+        sRuns[rank] = (tail > 0 && tail <= tail_max) ? L / KPW : (L + KPW - 1) / KPW;
     }
     __syncthreads();
     if (j == 0) {
@@ -717,6 +721,207 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_pair_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// bf16 MFMA dK/dV kernel for a block's last L % 128 keys when they are at most 32.  The pair kernel above
+// spends a whole walk of the block's query list on every 128-key run, however few of its keys exist; here
+// the cost follows the keys: one workgroup per (head, block), its four wavefronts hold the same <= 32 keys
+// and split the query list (wavefront w takes the 32-query chunks w, w + 4, ...), each computing all four
+// products for its chunks (same operand orientation as above, key = MFMA column) from its own LDS tiles,
+// without workgroup barriers; the four partial dK^T / dV^T are added through LDS at the end.
+template <int D>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_tail_kernel(
+    TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
+    const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
+    const int* __restrict__ kb_order, TensorView dK, TensorView dV, const int* __restrict__ rows, int Hh, int S, int nb, long long cap,
+    float scale_log2, float scale) {
+    constexpr int QC = 32;                       // queries per chunk
+    constexpr int STR = D + 8;
+    constexpr int KSTEPS = D / 16, DT = D / 32;
+    constexpr int LOADS = QC * (D / 8) / 64;     // 16-byte pieces per lane per chunk and tensor
+    __shared__ __align__(16) __bf16 sT[2][4][QC * STR];      // Q tiles, then dO tiles, one of each per wavefront
+    __shared__ __align__(16) float sL[4][QC];
+    __shared__ __align__(16) float sDl[4][QC];
+    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
+    const int j = kb_order[(long long)bh * nb + blockIdx.x];      // longest query list first
+    const int k0 = blk_off[j], L = blk_off[j + 1] - k0;
+    const int tail = L % 128;
+    if (tail == 0 || tail > 32) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hf = lane >> 5;
+    const long long seg = (long long)bh * cap;
+    const int list0 = blk_ptr[(long long)bh * (nb + 1) + j];
+    const int cnt = blk_ptr[(long long)bh * (nb + 1) + j + 1] - list0;
+    const int* list = q_idx + seg + list0;
+    const float* lse_h = LSE + (long long)bh * S;
+    const float* dl_h = delta + (long long)bh * S;
+
+    // the tail keys: B operands (key = lane % 32); columns past the tail repeat the block's last key and are not written
+    const bool key_live = l32 < tail;
+    const int krow = k0 + min(L - tail + l32, L - 1);
+    bf16x8_t kf[KSTEPS], vf[KSTEPS];
+    {
+        const char* pk = K.ptr + ((long long)b * K.stride_b + (long long)krow * K.stride_s + (long long)h * K.stride_h) * 2;
+        const char* pv = V.ptr + ((long long)b * V.stride_b + (long long)krow * V.stride_s + (long long)h * V.stride_h) * 2;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            kf[ks] = *reinterpret_cast<const bf16x8_t*>(pk + (ks * 16 + hf * 8) * 2);
+            vf[ks] = *reinterpret_cast<const bf16x8_t*>(pv + (ks * 16 + hf * 8) * 2);
+        }
+    }
+    const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16_t dvacc[DT], dkacc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) { dvacc[dt] = zero16; dkacc[dt] = zero16; }
+
+    const char* qbase = Q.ptr + ((long long)b * Q.stride_b + (long long)h * Q.stride_h) * 2;
+    const char* dobase = dO.ptr + ((long long)b * dO.stride_b + (long long)h * dO.stride_h) * 2;
+    const long long qss = Q.stride_s * 2, doss = dO.stride_s * 2;
+    const int n_chunks = (cnt + QC - 1) / QC;
+    __bf16* tQ = &sT[0][wave][0];
+    __bf16* tdO = &sT[1][wave][0];
+    float* tL = &sL[wave][0];
+    float* tDl = &sDl[wave][0];
+    // LSE / delta of row r are stored at the place where the accumulator layout wants them: a lane half reads its 16 rows
+    // (acc_row(i, hf), i = 0..15) as 16 consecutive floats
+    const int ld_pos = ((l32 & 1) << 4) + ((l32 >> 4) << 3) + (((l32 >> 1) & 1) << 2) + ((l32 >> 2) & 3);
+    const int row_lane = rho(l32) * STR + hf * 8;
+    const int tr_lane = tr_lane_offset<STR>(lane);
+
+    // Gathered rows travel list index -> row address -> registers -> LDS; a wavefront keeps the rows of its next two
+    // chunks in flight (register sets 0 / 1 by chunk parity) and the list indices of the one after.
+    struct RowSet {
+        u32x4_t q[LOADS], d[LOADS];
+        float l, dl;
+        bool live;
+    };
+    RowSet rs[2];
+    int qn[LOADS], ql = 0;
+    bool ql_live = false;
+    auto fetch_idx = [&](int c) {                // list entries of chunk c (entries past the list repeat its last one)
+        const int c0 = c * QC;
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) qn[i] = list[max(min(c0 + (lane + 64 * i) / (D / 8), cnt - 1), 0)];
+        ql = list[max(min(c0 + l32, cnt - 1), 0)];
+        ql_live = c0 + l32 < cnt;
+    };
+    auto fetch_rows = [&](RowSet& r) {           // rows of the chunk whose indices were fetched last
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int pc = (lane + 64 * i) % (D / 8);
+            r.q[i] = *reinterpret_cast<const u32x4_t*>(qbase + (long long)qn[i] * qss + pc * 16);
+            r.d[i] = *reinterpret_cast<const u32x4_t*>(dobase + (long long)qn[i] * doss + pc * 16);
+        }
+        r.l = lse_h[ql];
+        r.dl = dl_h[ql];
+        r.live = ql_live;
+    };
+    auto stage = [&](const RowSet& r) {
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int piece = lane + 64 * i;
+            const int row = piece / (D / 8), pc = piece % (D / 8);
+            *reinterpret_cast<u32x4_t*>(&tQ[row * STR + pc * 8]) = r.q[i];
+            *reinterpret_cast<u32x4_t*>(&tdO[row * STR + pc * 8]) = r.d[i];
+        }
+        if (hf == 0) {                           // rows past the end of the list: LSE = +inf (weight 0), delta = 0
+            tL[ld_pos] = r.live ? r.l * LOG2E : INFINITY;
+            tDl[ld_pos] = r.live ? r.dl : 0.f;
+        }
+    };
+    // the wavefront's k-th chunk is chunk wave + 4 k
+    const int my_chunks = n_chunks > wave ? (n_chunks - wave + 3) / 4 : 0;
+    if (my_chunks > 0) {
+        fetch_idx(wave);
+        fetch_rows(rs[0]);
+        fetch_idx(wave + 4);
+        fetch_rows(rs[1]);
+        fetch_idx(wave + 8);
+    }
+    auto one_chunk = [&](int k, RowSet& r) {
+        stage(r);
+        fetch_rows(r);                           // chunk k + 2 (indices are already here)
+        fetch_idx(wave + 4 * (k + 3));
+        // S = Q . K^T and dP = dO . V^T
+        f32x16_t sacc = zero16, dpacc = zero16;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            const bf16x8_t qa = *reinterpret_cast<const bf16x8_t*>(tQ + row_lane + ks * 16);
+            const bf16x8_t da = *reinterpret_cast<const bf16x8_t*>(tdO + row_lane + ks * 16);
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[ks], sacc, 0, 0, 0);
+            dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[ks], dpacc, 0, 0, 0);
+        }
+        float ld[16], dl[16];
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+            const f32x4_t a4 = *reinterpret_cast<const f32x4_t*>(tL + hf * 16 + g4 * 4);
+            const f32x4_t d4 = *reinterpret_cast<const f32x4_t*>(tDl + hf * 16 + g4 * 4);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { ld[g4 * 4 + u] = a4[u]; dl[g4 * 4 + u] = d4[u]; }
+        }
+        float pw[16], dsw[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            pw[i] = exp2_raw(fmaf(sacc[i], scale_log2, -ld[i]));
+            dsw[i] = pw[i] * (dpacc[i] - dl[i]);
+        }
+        // dV^T += dO^T . P and dK^T += Q^T . dS
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            const bf16x8_t pb = pack8(&pw[8 * s2]);
+            const bf16x8_t db = pack8(&dsw[8 * s2]);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                const bf16x8_t dot = tr_operand<STR>(tdO + tr_lane, 0, s2, dt * 32);
+                const bf16x8_t qt = tr_operand<STR>(tQ + tr_lane, 0, s2, dt * 32);
+                dvacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot, pb, dvacc[dt], 0, 0, 0);
+                dkacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, db, dkacc[dt], 0, 0, 0);
+            }
+        }
+    };
+    for (int k = 0; k < my_chunks; k += 2) {
+        one_chunk(k, rs[0]);
+        if (k + 1 < my_chunks) one_chunk(k + 1, rs[1]);
+    }
+    // ---- add the four wavefronts' partial sums (the row tiles are free now) and write the tail's rows
+    static_assert(sizeof(sT) >= 3 * 64 * DT * 16 * sizeof(float), "reduction buffer fits the row tiles");
+    float* red = reinterpret_cast<float*>(&sT[0][0][0]);       // [3][DT * 16][64]
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        f32x16_t* acc = pass == 0 ? dvacc : dkacc;
+        __syncthreads();
+        if (wave > 0) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) red[((wave - 1) * DT * 16 + dt * 16 + i) * 64 + lane] = acc[dt][i];
+        }
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int w = 0; w < 3; ++w)
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[dt][i] += red[(w * DT * 16 + dt * 16 + i) * 64 + lane];
+            if (key_live) {
+                const TensorView& dst = pass == 0 ? dV : dK;
+                const float fsc = pass == 0 ? 1.f : scale;
+                const int kout = rows ? rows[krow] : krow;
+                char* pd = dst.ptr + ((long long)b * dst.stride_b + (long long)kout * dst.stride_s + (long long)h * dst.stride_h) * 2;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        u32x2_t wv;
+                        wv.x = pack_bf16x2(acc[dt][4 * g + 0] * fsc, acc[dt][4 * g + 1] * fsc);
+                        wv.y = pack_bf16x2(acc[dt][4 * g + 2] * fsc, acc[dt][4 * g + 3] * fsc);
+                        *reinterpret_cast<u32x2_t*>(pd + (dt * 32 + g * 8 + hf * 4) * 2) = wv;
+                    }
+            }
+        }
+    }
+}
+
 // dQ[q] = scale * sum over the query's pairs of dQpart[pair] (bfloat16 partials when PBF16).
 template <bool BF16, bool PBF16, int D>
 __global__ __launch_bounds__(256) void dq_merge_kernel(const float* __restrict__ dQpart, const int* __restrict__ row_ptr,
@@ -897,7 +1102,7 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     // ---- dK, dV
     {
         const int KPW = simple ? 64 : 128;      // keys per workgroup
-        key_run_order_kernel<<<dim3(BH), dim3(256), 0, st>>>(blk_off, blk_ptr, ws.kb_start, ws.kb_order, n_blocks, KPW);
+        key_run_order_kernel<<<dim3(BH), dim3(256), 0, st>>>(blk_off, blk_ptr, ws.kb_start, ws.kb_order, n_blocks, KPW, simple ? 0 : 32);
         VMOBA_CHECK_LAUNCH();
         // a multiple of 8 so that (workgroup id % 8) is the same for every head; + 8 for the per-XCD rounding
         dim3 grid((unsigned)((S / KPW + n_blocks + 7) / 8 * 8 + 8), (unsigned)BH);
@@ -915,6 +1120,14 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
 #undef DKV_ARGS
         VMOBA_PROFILE_END(2, st);
         VMOBA_CHECK_LAUNCH();
+        if (!simple) {      // the blocks' last (block length % 128) <= 32 keys, which the key-run table left out
+            dim3 tgrid((unsigned)n_blocks, (unsigned)BH);
+#define TAIL_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.kb_order, dKv, dVv, rows, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
+            if (D == 128) attn_bwd_dkv_tail_kernel<128><<<tgrid, dim3(256), 0, st>>>(TAIL_ARGS);
+            else attn_bwd_dkv_tail_kernel<64><<<tgrid, dim3(256), 0, st>>>(TAIL_ARGS);
+#undef TAIL_ARGS
+            VMOBA_CHECK_LAUNCH();
+        }
     }
     return VMOBA_OK;
 }

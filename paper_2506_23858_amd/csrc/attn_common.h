@@ -94,3 +94,31 @@ __global__ __launch_bounds__(256) void tile_desc_kernel(const int* __restrict__ 
                                                         int nb, int TM, int tiles_per_head);
 
 inline __device__ float exp2_raw(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Flat tile list over all heads for the persistent tile kernels (defined next to tile_start_kernel).
+__global__ void head_base_kernel(const int* __restrict__ tile_start, int* __restrict__ head_base, int BH, int nb);
+__global__ __launch_bounds__(256) void flat_tile_desc_kernel(const int* __restrict__ tile_start, const int* __restrict__ blk_ptr,
+                                                             const int* __restrict__ blk_off, const int* __restrict__ head_base,
+                                                             int4* __restrict__ flat_desc, int nb, int TM, int tiles_per_head);
+// Compute units of the current device (queried once).
+int vmoba_num_cus();
+
+// Exchange between the two halves of a wavefront (lane i <-> lane i ^ 32), reduced with max / sum.
+__device__ __forceinline__ float swap_halves_max(float x) {
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
+    const u2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+}
+__device__ __forceinline__ float swap_halves_sum(float x) {
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
+    const u2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r.x) + __uint_as_float(r.y);
+}
+// 64 lanes x 16 bytes from base + byte_off (per lane) to LDS: lane i writes lds_addr + 16 * i (lds_addr is
+// wave-uniform).  Counts in vmcnt like any vector load; the compiler does not know about it.
+__device__ __forceinline__ void dma16(const char* base, uint32_t byte_off, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr)
+                 : "memory", "m0");
+}
+#define VMOBA_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+

@@ -51,6 +51,41 @@ __global__ __launch_bounds__(256) void tile_desc_kernel(const int* __restrict__ 
     tile_desc[(long long)bh * tiles_per_head + tile] = d;
 }
 
+// Flat tile list over all heads for the persistent tile kernels.  head_base[bh] = number of tiles of the heads
+// before bh (head_base[BH] = total); one thread.
+__global__ void head_base_kernel(const int* __restrict__ tile_start, int* __restrict__ head_base, int BH, int nb) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    int run = 0;
+    for (int bh = 0; bh < BH; ++bh) {
+        head_base[bh] = run;
+        run += tile_start[(long long)bh * (nb + 1) + nb];
+    }
+    head_base[BH] = run;
+}
+// flat_desc[head_base[bh] + tile] = {first list entry, count | bh << 10, first key, block length}; one thread per
+// (head, tile id below tiles_per_head).
+__global__ __launch_bounds__(256) void flat_tile_desc_kernel(const int* __restrict__ tile_start, const int* __restrict__ blk_ptr,
+                                                             const int* __restrict__ blk_off, const int* __restrict__ head_base,
+                                                             int4* __restrict__ flat_desc, int nb, int TM, int tiles_per_head) {
+    const int bh = blockIdx.y;
+    const int tile = blockIdx.x * 256 + threadIdx.x;
+    const int* ts = tile_start + (long long)bh * (nb + 1);
+    if (tile >= tiles_per_head || tile >= ts[nb]) return;
+    int lo = 0, hi = nb;           // largest j with ts[j] <= tile
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (ts[mid] <= tile) lo = mid; else hi = mid;
+    }
+    const int* bp = blk_ptr + (long long)bh * (nb + 1);
+    const int t0 = (tile - ts[lo]) * TM;
+    int4 d;
+    d.x = bp[lo] + t0;
+    d.y = min(TM, bp[lo + 1] - bp[lo] - t0) | (bh << 10);
+    d.z = blk_off[lo];
+    d.w = blk_off[lo + 1] - blk_off[lo];
+    flat_desc[head_base[bh] + tile] = d;
+}
+
 namespace {
 
 constexpr float LOG2E = 1.4426950408889634f;
@@ -174,24 +209,6 @@ __global__ __launch_bounds__(64) void attn_fwd_tile_simple_kernel(
 // and K(0..3), V(0..1) during the final step, into slots nobody reads any more (the rings are
 // indexed by running group counters, so the next tile's first V slots differ from the slot of the
 // group the final step reads).
-__device__ __forceinline__ float swap_halves_max(float x) {
-    typedef unsigned u2 __attribute__((ext_vector_type(2)));
-    const u2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
-}
-__device__ __forceinline__ float swap_halves_sum(float x) {
-    typedef unsigned u2 __attribute__((ext_vector_type(2)));
-    const u2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float(r.x) + __uint_as_float(r.y);
-}
-// 64 lanes x 16 bytes from base + byte_off (per lane) to LDS: lane i writes lds_addr + 16 * i (lds_addr is
-// wave-uniform).  Counts in vmcnt like any vector load; the compiler does not know about it.
-__device__ __forceinline__ void dma16(const char* base, uint32_t byte_off, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr)
-                 : "memory", "m0");
-}
-#define VMOBA_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
-
 template <int D, int NW>
 __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
     TensorView Q, TensorView K, TensorView V, const int* __restrict__ q_idx, const int4* __restrict__ flat_desc,
@@ -494,41 +511,6 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
         kb += Ge;
         vb += Ge;
     }
-}
-
-// Flat tile list over all heads for the persistent tile kernels.  head_base[bh] = number of tiles of the heads
-// before bh (head_base[BH] = total); one thread.
-__global__ void head_base_kernel(const int* __restrict__ tile_start, int* __restrict__ head_base, int BH, int nb) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    int run = 0;
-    for (int bh = 0; bh < BH; ++bh) {
-        head_base[bh] = run;
-        run += tile_start[(long long)bh * (nb + 1) + nb];
-    }
-    head_base[BH] = run;
-}
-// flat_desc[head_base[bh] + tile] = {first list entry, count | bh << 10, first key, block length}; one thread per
-// (head, tile id below tiles_per_head).
-__global__ __launch_bounds__(256) void flat_tile_desc_kernel(const int* __restrict__ tile_start, const int* __restrict__ blk_ptr,
-                                                             const int* __restrict__ blk_off, const int* __restrict__ head_base,
-                                                             int4* __restrict__ flat_desc, int nb, int TM, int tiles_per_head) {
-    const int bh = blockIdx.y;
-    const int tile = blockIdx.x * 256 + threadIdx.x;
-    const int* ts = tile_start + (long long)bh * (nb + 1);
-    if (tile >= tiles_per_head || tile >= ts[nb]) return;
-    int lo = 0, hi = nb;           // largest j with ts[j] <= tile
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (ts[mid] <= tile) lo = mid; else hi = mid;
-    }
-    const int* bp = blk_ptr + (long long)bh * (nb + 1);
-    const int t0 = (tile - ts[lo]) * TM;
-    int4 d;
-    d.x = bp[lo] + t0;
-    d.y = min(TM, bp[lo + 1] - bp[lo] - t0) | (bh << 10);
-    d.z = blk_off[lo];
-    d.w = blk_off[lo + 1] - blk_off[lo];
-    flat_desc[head_base[bh] + tile] = d;
 }
 
 // ---------------------------------------------------------------------------------------------

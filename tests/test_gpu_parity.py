@@ -270,6 +270,15 @@ def test_bf16_small(D):
     compare_layer(Q, K, V, dO, grid, block, 0, 0.4, torch.bfloat16, f"bf16-small-D{D}")
 
 
+@pytest.mark.parametrize("block", [(1, 4, 8), (1, 3, 8)])
+def test_bf16_blocks_no_longer_than_one_key_group(block):
+    """Key blocks of 32 (and 24, ragged: 16) tokens: the forward and dQ kernels see blocks of a single
+    32-key group, and dK/dV of every key comes from the kernel for short block tails alone."""
+    grid = (4, 8, 16)
+    Q, K, V, dO = (synth.to_bf16_grid(synth.blurred_noise(340 + i, grid, 2, 128, 1.5)) for i in range(4))
+    compare_layer(Q, K, V, dO, grid, block, 0, 0.4, torch.bfloat16, f"bf16-one-group-{block}")
+
+
 def test_bf16_mid_lite():
     """The mid configuration's grid and 3D blocks (9x30x52, blocks 3x10x13 of 390 tokens) with 2 of
     its 12 heads, so the float64 oracle finishes in seconds."""
