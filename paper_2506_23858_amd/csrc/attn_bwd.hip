@@ -403,12 +403,16 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
 //   matrix:  S or dP of half-chunk t + 1,  dV or dK of half-chunk t - 1      vector: P or dS of t
 //   memory (even hc): rows of chunk hc/2 + 2 from registers into the ring, loads of chunk hc/2 + 3.
 // The ring buffer written during steps 2c, 2c + 1 was last read in step 2c - 1 and is first read in 2c + 3.
+// LDS bytes of the pair body: a ring of four 64-row tiles of Q and of dO, their LSE / delta, the packed-P hand-over
 template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_pair_kernel(
-    TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
-    const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
-    const int* __restrict__ kb_start, const int* __restrict__ kb_order, TensorView dK, TensorView dV, const int* __restrict__ rows, int Hh, int S, int nb, long long cap,
-    float scale_log2, float scale) {
+constexpr int dkv_pair_lds_bytes() { return 2 * 4 * 64 * (D + 8) * 2 + 2 * 4 * 64 * 4 + 2 * 2 * 4 * 64 * 16; }
+
+template <int D>
+__device__ __forceinline__ void dkv_pair_body(
+    char* smem, int run_id, const TensorView& Q, const TensorView& K, const TensorView& V, const TensorView& dO, const float* __restrict__ LSE,
+    const float* __restrict__ delta, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
+    const int* __restrict__ kb_start, const int* __restrict__ kb_order, const TensorView& dK, const TensorView& dV, const int* __restrict__ rows,
+    int Hh, int S, int nb, long long cap, float scale_log2, float scale) {
     constexpr int NT = 256;
     constexpr int QC = 64;
     constexpr int STR = D + 8;
@@ -418,18 +422,19 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_pair_kernel(
     constexpr int NST = KSTEPS;
     static_assert(NST == 2 * DT && NST == 2 * LOADS, "one row piece, one k-step and one (s, dt) step per step");
     constexpr int VP = 8 / NST;               // value pairs per key group and step
-    __shared__ __align__(16) __bf16 sQ[NBUF][QC * STR];
-    __shared__ __align__(16) __bf16 sdO[NBUF][QC * STR];
-    __shared__ __align__(16) float sL[NBUF][QC];
-    __shared__ __align__(16) float sDl[NBUF][QC];
-    __shared__ __align__(16) u32x4_t sX[2][2][4][64];     // [pair][step parity][kg * 2 + s][lane]: packed P
+    __bf16(*sQ)[QC * STR] = reinterpret_cast<__bf16(*)[QC * STR]>(smem);
+    __bf16(*sdO)[QC * STR] = reinterpret_cast<__bf16(*)[QC * STR]>(smem + NBUF * QC * STR * 2);
+    float(*sL)[QC] = reinterpret_cast<float(*)[QC]>(smem + 2 * NBUF * QC * STR * 2);
+    float(*sDl)[QC] = reinterpret_cast<float(*)[QC]>(smem + 2 * NBUF * QC * STR * 2 + NBUF * QC * 4);
+    // [pair][step parity][kg * 2 + s][lane]: packed P
+    u32x4_t(*sX)[2][4][64] = reinterpret_cast<u32x4_t(*)[2][4][64]>(smem + 2 * NBUF * QC * STR * 2 + 2 * NBUF * QC * 4);
+    static_assert(dkv_pair_lds_bytes<D>() == 2 * NBUF * QC * STR * 2 + 2 * NBUF * QC * 4 + 2 * 2 * 4 * 64 * 16, "LDS carve");
 
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
     const int* ks = kb_start + (long long)bh * (nb + 1);
-    if ((int)blockIdx.x >= ks[nb]) return;
     int lo = 0, hi = nb;
-    while (hi - lo > 1) { int mid = (lo + hi) >> 1; if (ks[mid] <= (int)blockIdx.x) lo = mid; else hi = mid; }
-    const int j = kb_order[(long long)bh * nb + lo], run = (int)blockIdx.x - ks[lo];
+    while (hi - lo > 1) { int mid = (lo + hi) >> 1; if (ks[mid] <= run_id) lo = mid; else hi = mid; }
+    const int j = kb_order[(long long)bh * nb + lo], run = run_id - ks[lo];
     const int k0 = blk_off[j], L = blk_off[j + 1] - k0;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int pair = wave >> 1, role = wave & 1;
@@ -729,20 +734,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_pair_kernel(
 // products for its chunks (same operand orientation as above, key = MFMA column) from its own LDS tiles,
 // without workgroup barriers; the four partial dK^T / dV^T are added through LDS at the end.
 template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_tail_kernel(
-    TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
-    const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
-    const int* __restrict__ kb_order, TensorView dK, TensorView dV, const int* __restrict__ rows, int Hh, int S, int nb, long long cap,
-    float scale_log2, float scale) {
+__device__ __forceinline__ void dkv_tail_body(
+    char* smem, int rank, const TensorView& Q, const TensorView& K, const TensorView& V, const TensorView& dO, const float* __restrict__ LSE,
+    const float* __restrict__ delta, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
+    const int* __restrict__ kb_order, const TensorView& dK, const TensorView& dV, const int* __restrict__ rows, int Hh, int S, int nb,
+    long long cap, float scale_log2, float scale) {
     constexpr int QC = 32;                       // queries per chunk
     constexpr int STR = D + 8;
     constexpr int KSTEPS = D / 16, DT = D / 32;
     constexpr int LOADS = QC * (D / 8) / 64;     // 16-byte pieces per lane per chunk and tensor
-    __shared__ __align__(16) __bf16 sT[2][4][QC * STR];      // Q tiles, then dO tiles, one of each per wavefront
-    __shared__ __align__(16) float sL[4][QC];
-    __shared__ __align__(16) float sDl[4][QC];
+    // Q tiles, then dO tiles, one of each per wavefront; then LSE and delta
+    __bf16(*sT)[4][QC * STR] = reinterpret_cast<__bf16(*)[4][QC * STR]>(smem);
+    float(*sL)[QC] = reinterpret_cast<float(*)[QC]>(smem + 2 * 4 * QC * STR * 2);
+    float(*sDl)[QC] = reinterpret_cast<float(*)[QC]>(smem + 2 * 4 * QC * STR * 2 + 4 * QC * 4);
+    static_assert(2 * 4 * QC * STR * 2 + 2 * 4 * QC * 4 <= dkv_pair_lds_bytes<D>(), "the tail body fits the pair body's LDS");
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
-    const int j = kb_order[(long long)bh * nb + blockIdx.x];      // longest query list first
+    const int j = kb_order[(long long)bh * nb + rank];            // longest query list first
     const int k0 = blk_off[j], L = blk_off[j + 1] - k0;
     const int tail = L % 128;
     if (tail == 0 || tail > 32) return;
@@ -883,7 +890,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_tail_kernel(
         if (k + 1 < my_chunks) one_chunk(k + 1, rs[1]);
     }
     // ---- add the four wavefronts' partial sums (the row tiles are free now) and write the tail's rows
-    static_assert(sizeof(sT) >= 3 * 64 * DT * 16 * sizeof(float), "reduction buffer fits the row tiles");
+    static_assert(2 * 4 * QC * STR * 2 >= 3 * 64 * DT * 16 * sizeof(float), "reduction buffer fits the row tiles");
     float* red = reinterpret_cast<float*>(&sT[0][0][0]);       // [3][DT * 16][64]
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
@@ -920,6 +927,24 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_tail_kernel(
             }
         }
     }
+}
+
+// The dK/dV launch: workgroups [0, runs of the head) run the pair body on one 128-key run each (longest query list
+// first); the next n_blocks workgroups run the tail body on one block each.  The tail workgroups are short and
+// dispatched last, so they fill the end of the launch, where the long runs finish unevenly.
+template <int D>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
+    TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
+    const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
+    const int* __restrict__ kb_start, const int* __restrict__ kb_order, TensorView dK, TensorView dV, const int* __restrict__ rows, int Hh, int S, int nb, long long cap,
+    float scale_log2, float scale) {
+    __shared__ __align__(16) char smem[dkv_pair_lds_bytes<D>()];
+    const int runs = kb_start[(long long)blockIdx.y * (nb + 1) + nb];
+    const int id = (int)blockIdx.x;
+    if (id < runs)
+        dkv_pair_body<D>(smem, id, Q, K, V, dO, LSE, delta, blk_off, blk_ptr, q_idx, kb_start, kb_order, dK, dV, rows, Hh, S, nb, cap, scale_log2, scale);
+    else if (id - runs < nb)
+        dkv_tail_body<D>(smem, id - runs, Q, K, V, dO, LSE, delta, blk_off, blk_ptr, q_idx, kb_order, dK, dV, rows, Hh, S, nb, cap, scale_log2, scale);
 }
 
 // dQ[q] = scale * sum over the query's pairs of dQpart[pair] (bfloat16 partials when PBF16).
@@ -1105,7 +1130,7 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         key_run_order_kernel<<<dim3(BH), dim3(256), 0, st>>>(blk_off, blk_ptr, ws.kb_start, ws.kb_order, n_blocks, KPW, simple ? 0 : 32);
         VMOBA_CHECK_LAUNCH();
         // a multiple of 8 so that (workgroup id % 8) is the same for every head; + 8 for the per-XCD rounding
-        dim3 grid((unsigned)((S / KPW + n_blocks + 7) / 8 * 8 + 8), (unsigned)BH);
+        dim3 grid((unsigned)((S / KPW + n_blocks + 7) / 8 * 8 + 8 + (simple ? 0 : n_blocks)), (unsigned)BH);
         VMOBA_PROFILE_BEGIN(2, st);
 #define DKV_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.kb_start, ws.kb_order, dKv, dVv, rows, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
         if (simple) {
@@ -1114,20 +1139,12 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
             else if (D == 128) attn_bwd_dkv_simple_kernel<false, 128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
             else attn_bwd_dkv_simple_kernel<false, 64><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
         } else {
-            if (D == 128) attn_bwd_dkv_pair_kernel<128><<<grid, dim3(256), 0, st>>>(DKV_ARGS);
-            else attn_bwd_dkv_pair_kernel<64><<<grid, dim3(256), 0, st>>>(DKV_ARGS);
+            if (D == 128) attn_bwd_dkv_kernel<128><<<grid, dim3(256), 0, st>>>(DKV_ARGS);
+            else attn_bwd_dkv_kernel<64><<<grid, dim3(256), 0, st>>>(DKV_ARGS);
         }
 #undef DKV_ARGS
         VMOBA_PROFILE_END(2, st);
         VMOBA_CHECK_LAUNCH();
-        if (!simple) {      // the blocks' last (block length % 128) <= 32 keys, which the key-run table left out
-            dim3 tgrid((unsigned)n_blocks, (unsigned)BH);
-#define TAIL_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.kb_order, dKv, dVv, rows, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
-            if (D == 128) attn_bwd_dkv_tail_kernel<128><<<tgrid, dim3(256), 0, st>>>(TAIL_ARGS);
-            else attn_bwd_dkv_tail_kernel<64><<<tgrid, dim3(256), 0, st>>>(TAIL_ARGS);
-#undef TAIL_ARGS
-            VMOBA_CHECK_LAUNCH();
-        }
     }
     return VMOBA_OK;
 }
