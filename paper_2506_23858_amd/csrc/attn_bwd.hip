@@ -347,11 +347,16 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
                     sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc, 0, 0, 0);
                     dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[ks], dpacc, 0, 0, 0);
                 }
+                if (valid < KC) {                 // last chunk (uniform branch): keys past the block get weight 0
+                    const int vh = valid - mt * 32 - hf;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        if (acc_row(i, 0) >= vh) sacc[i] = -INFINITY;
+                }
                 float ds[16];
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    float p = exp2_raw(fmaf(sacc[i], scale_log2, -lse2));
-                    if (valid < KC && mt * 32 + acc_row(i, hf) >= valid) p = 0.f;
+                    const float p = exp2_raw(fmaf(sacc[i], scale_log2, -lse2));
                     ds[i] = p * (dpacc[i] - dl);
                 }
 #pragma unroll
