@@ -259,7 +259,8 @@ template <int D>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
-    const int4* __restrict__ tile_desc, int tiles_per_head, float* __restrict__ dQpart, int Hh, int S, int nb, long long cap, float scale_log2) {
+    const int4* __restrict__ flat_desc, const int* __restrict__ head_base, int BH, float* __restrict__ dQpart, int Hh, int S, int nb,
+    long long cap, float scale_log2) {
     constexpr int TM = 128, KC = 64;
     constexpr int STR = D + 8;
     constexpr int KSTEPS = D / 16, DT = D / 32;
@@ -267,9 +268,21 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
     __shared__ __align__(16) __bf16 sK[KC * STR];
     __shared__ __align__(16) __bf16 sV[KC * STR];
 
-    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
+    // One workgroup per tile of the flat list (all heads).  Workgroup ids go round the 8 XCDs, so XCD x = id % 8 takes the
+    // x-th eighth of the list: a key block's tiles then share one L2 instead of eight (gridDim.x is a multiple of 8).
+    const int total = head_base[BH];
+    const int per_xcd = (total + 7) >> 3;
+    const int slot = (int)(blockIdx.x >> 3);
+    const int f = (int)(blockIdx.x & 7) * per_xcd + slot;
+    if (slot >= per_xcd || f >= total) return;
     TileCoord tc;
-    if (!find_tile(tile_desc, tiles_per_head, bh, blockIdx.x, tc)) return;
+    const int4 fd = flat_desc[f];               // {first list entry, count | head << 10, first key, block length}
+    tc.list0 = fd.x;
+    tc.t0 = 0;
+    tc.count = fd.y & 1023;
+    tc.k0 = fd.z;
+    tc.L = fd.w;
+    const int bh = fd.y >> 10, b = bh / Hh, h = bh % Hh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hf = lane >> 5;
     const long long seg = (long long)bh * cap;
@@ -1016,7 +1029,8 @@ struct BwdWs {
     float* dQpart;     // [BH * cap][D]
     float* delta;      // [BH][S]
     int* tile_start;   // [BH][257]
-    int4* tile_desc;   // [BH][tiles_per_head]
+    int4* tile_desc;   // [BH][tiles_per_head], or the flat list of all heads' tiles
+    int* head_base;    // [BH + 1]
     int* kb_start;     // [BH][257]
     int* kb_order;     // [BH][256]
     char* dO_copy;     // [BH, S, D] block-order copy of dO (used with a row map)
@@ -1031,6 +1045,7 @@ BwdWs carve_bwd(void* base, int BH, int64_t S, int D, int64_t cap, int es) {
     w.delta = (float*)(p + off);     off += align_up((size_t)BH * S * 4, 256);
     w.tile_start = (int*)(p + off);  off += align_up((size_t)BH * (VMOBA_MAX_BLOCKS + 1) * 4, 256);
     w.tile_desc = (int4*)(p + off);  off += align_up((size_t)BH * vmoba_max_tiles(cap, 64) * 16, 256);
+    w.head_base = (int*)(p + off);   off += align_up((size_t)(BH + 1) * 4, 256);
     w.kb_start = (int*)(p + off);    off += align_up((size_t)BH * (VMOBA_MAX_BLOCKS + 1) * 4, 256);
     w.kb_order = (int*)(p + off);    off += align_up((size_t)BH * VMOBA_MAX_BLOCKS * 4, 256);
     w.dO_copy = p + off;             off += align_up((size_t)BH * S * D * es, 256);
@@ -1097,23 +1112,34 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     tile_start_kernel<<<dim3((BH + 63) / 64), dim3(64), 0, st>>>(blk_ptr, ws.tile_start, BH, n_blocks, TM);
     VMOBA_CHECK_LAUNCH();
     const int64_t max_tiles = std::min<int64_t>(vmoba_max_tiles(nnz_capacity, TM), (nnz_capacity / TM + n_blocks + 7) / 8 * 8);
-    tile_desc_kernel<<<dim3((unsigned)ceil_div64(max_tiles, 256), (unsigned)BH), dim3(256), 0, st>>>(
-        ws.tile_start, blk_ptr, blk_off, ws.tile_desc, n_blocks, TM, (int)max_tiles);
+    if (simple) {
+        tile_desc_kernel<<<dim3((unsigned)ceil_div64(max_tiles, 256), (unsigned)BH), dim3(256), 0, st>>>(
+            ws.tile_start, blk_ptr, blk_off, ws.tile_desc, n_blocks, TM, (int)max_tiles);
+    } else {
+        head_base_kernel<<<dim3(1), dim3(64), 0, st>>>(ws.tile_start, ws.head_base, BH, n_blocks);
+        VMOBA_CHECK_LAUNCH();
+        flat_tile_desc_kernel<<<dim3((unsigned)ceil_div64(max_tiles, 256), (unsigned)BH), dim3(256), 0, st>>>(
+            ws.tile_start, blk_ptr, blk_off, ws.head_base, ws.tile_desc, n_blocks, TM, (int)max_tiles);
+    }
     VMOBA_CHECK_LAUNCH();
     {
-        dim3 grid((unsigned)max_tiles, (unsigned)BH);
         VMOBA_PROFILE_BEGIN(1, st);
-#define DQ_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.tile_desc, (int)max_tiles, ws.dQpart, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2
         if (simple) {
+            dim3 grid((unsigned)max_tiles, (unsigned)BH);
+#define DQ_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.tile_desc, (int)max_tiles, ws.dQpart, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2
             if (bf16 && D == 128) attn_bwd_dq_simple_kernel<true, 128><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
             else if (bf16) attn_bwd_dq_simple_kernel<true, 64><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
             else if (D == 128) attn_bwd_dq_simple_kernel<false, 128><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
             else attn_bwd_dq_simple_kernel<false, 64><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
+#undef DQ_ARGS
         } else {
+            // one workgroup per entry of the flat tile list; the bound on the list length is a multiple of 8
+            const dim3 grid((unsigned)std::min<int64_t>((int64_t)BH * max_tiles, ((nnz_capacity / TM + n_blocks) * (int64_t)BH + 15) / 8 * 8));
+#define DQ_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.tile_desc, ws.head_base, BH, ws.dQpart, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2
             if (D == 128) attn_bwd_dq_mfma_kernel<128><<<grid, dim3(256), 0, st>>>(DQ_ARGS);
             else attn_bwd_dq_mfma_kernel<64><<<grid, dim3(256), 0, st>>>(DQ_ARGS);
-        }
 #undef DQ_ARGS
+        }
         VMOBA_PROFILE_END(1, st);
         VMOBA_CHECK_LAUNCH();
         const bool pbf16 = !simple;           // the MFMA tile kernel writes bfloat16 partials
