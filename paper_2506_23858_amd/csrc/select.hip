@@ -114,8 +114,14 @@ __global__ __launch_bounds__(256) void block_mean_kernel(TensorView K, const int
 // A workgroup owns a tile of QT = 64 queries of one head.  The head's block means sit in LDS
 // as float32; thread (q = tid % 64, g = tid / 64) keeps its query row in registers and
 // computes the dot products with blocks g, g+4, g+8, ...
+// floor(p * 2^fix_shift) for a finite p >= 0 below 2^(63 - fix_shift), by integer shifts of the float's mantissa
+// (exact, like the product in double precision it replaces, and a fraction of its instructions)
 __device__ __forceinline__ unsigned long long to_fixed(float p, int fix_shift) {
-    return (unsigned long long)((double)p * (double)(1ull << fix_shift));
+    const uint32_t b = __float_as_uint(p);
+    const int e = (int)(b >> 23);
+    const uint32_t m = e ? ((b & 0x7fffffu) | 0x800000u) : (b & 0x7fffffu);
+    const int sh = (e ? e - 150 : -149) + fix_shift;
+    return sh >= 0 ? ((unsigned long long)m << sh) : (sh > -32 ? (unsigned long long)(m >> -sh) : 0ull);
 }
 
 template <bool BF16, int D>
@@ -309,6 +315,7 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(TensorView Q, const flo
         if (row_stat && q < S && hf == 0) row_stat[(long long)bh * S + q] = make_float2(m, den);
         if (q < S) {
             float* dst = P + ((long long)bh * S + q) * nb;
+            const float inv_den = 1.f / den;
 #pragma unroll
             for (int mt = 0; mt < MAX_MT; ++mt) {
                 if (mt < n_mt) {
@@ -317,7 +324,7 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(TensorView Q, const flo
                         const int j0 = mt * 32 + 8 * g + 4 * hf;
                         float pv[4];
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) pv[r] = acc[mt][4 * g + r] / den;
+                        for (int r = 0; r < 4; ++r) pv[r] = acc[mt][4 * g + r] * inv_den;
                         if (vec_ok && j0 + 3 < nb) {
                             f32x4_t o = {pv[0], pv[1], pv[2], pv[3]};
                             *reinterpret_cast<f32x4_t*>(dst + j0) = o;
