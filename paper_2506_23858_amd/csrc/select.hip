@@ -228,20 +228,26 @@ __global__ __launch_bounds__(256) void score_kernel(TensorView Q, const float* _
 // by ~4e-3.  S^T[block, q] = sum over the three terms of Bx[block, :] . Q[q, :], with the query on
 // the MFMA column (= lane % 32), so the soft-max over blocks is a reduction over a lane's own
 // registers plus one exchange with lane ^ 32.  4 wavefronts x 32 queries per tile.
-template <int D>
+// With more than 128 blocks the three bfloat16 copies no longer fit the LDS; FLY keeps the means there as float32 (row
+// stride D + 4) and splits every operand after its fetch: the same three terms from the same operations, so P is the
+// same, at the price of vector work per matrix instruction.
+template <int D, bool FLY>
 __global__ __launch_bounds__(256) void score_mfma_kernel(TensorView Q, const float* __restrict__ Bmean,
                                                          float* __restrict__ P, unsigned int* __restrict__ hist_cnt,
                                                          unsigned long long* __restrict__ hist_sum,
                                                          int Hh, int S, int nb, float score_scale, int fix_shift,
                                                          float2* __restrict__ row_stat) {
     constexpr int STR = D + 8;                 // LDS row stride in bf16 elements
+    constexpr int FSTR = D + 4;                // LDS row stride in float elements (FLY)
     constexpr int KSTEPS = D / 16;
-    constexpr int MAX_MT = 4;                  // up to 128 blocks
+    constexpr int MAX_MT = FLY ? 8 : 4;        // up to 256 / 128 blocks
     extern __shared__ __align__(16) unsigned char smem[];
     const int nb_pad = (nb + 31) & ~31;
     const int n_mt = nb_pad / 32;
     __bf16* sB = reinterpret_cast<__bf16*>(smem);                                  // [3][nb_pad][STR]
-    unsigned long long* sSum = reinterpret_cast<unsigned long long*>(sB + (size_t)3 * nb_pad * STR);   // [1024]
+    float* sBf = reinterpret_cast<float*>(smem);                                   // FLY: [nb_pad][FSTR]
+    unsigned long long* sSum = FLY ? reinterpret_cast<unsigned long long*>(sBf + (size_t)nb_pad * FSTR)
+                                   : reinterpret_cast<unsigned long long*>(sB + (size_t)3 * nb_pad * STR);   // [1024]
     unsigned int* sCnt = reinterpret_cast<unsigned int*>(sSum + HIST_BINS);        // [1024]
 
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
@@ -251,6 +257,10 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(TensorView Q, const flo
     for (int i = tid; i < nb_pad * D; i += 256) {
         const int j = i / D, d = i % D;
         const float x = j < nb ? Bmean[((long long)bh * nb + j) * D + d] : 0.f;
+        if constexpr (FLY) {
+            sBf[j * FSTR + d] = x;
+            continue;
+        }
         const __bf16 xh = (__bf16)x;
         const float r1 = x - (float)xh;
         const __bf16 xm = (__bf16)r1;
@@ -281,13 +291,34 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(TensorView Q, const flo
             acc[mt] = zero16;
             if (mt < n_mt) {
 #pragma unroll
-                for (int ks = 0; ks < KSTEPS; ++ks)
+                for (int ks = 0; ks < KSTEPS; ++ks) {
+                    if constexpr (FLY) {
+                        const float* src = &sBf[(mt * 32 + l32) * FSTR + ks * 16 + hf * 8];
+                        const f32x4_t x0 = *reinterpret_cast<const f32x4_t*>(src), x1 = *reinterpret_cast<const f32x4_t*>(src + 4);
+                        bf16x8_t bh8, bm8, bl8;
 #pragma unroll
-                    for (int x = 0; x < 3; ++x) {
-                        const bf16x8_t bf = *reinterpret_cast<const bf16x8_t*>(
-                            &sB[((size_t)x * nb_pad + mt * 32 + l32) * STR + ks * 16 + hf * 8]);
-                        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, qf[ks], acc[mt], 0, 0, 0);
+                        for (int i = 0; i < 8; ++i) {
+                            const float x = i < 4 ? x0[i] : x1[i - 4];
+                            const __bf16 xh = (__bf16)x;
+                            const float r1 = x - (float)xh;
+                            const __bf16 xm = (__bf16)r1;
+                            const float r2 = r1 - (float)xm;
+                            bh8[i] = xh;
+                            bm8[i] = xm;
+                            bl8[i] = (__bf16)r2;
+                        }
+                        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh8, qf[ks], acc[mt], 0, 0, 0);
+                        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bm8, qf[ks], acc[mt], 0, 0, 0);
+                        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bl8, qf[ks], acc[mt], 0, 0, 0);
+                    } else {
+#pragma unroll
+                        for (int x = 0; x < 3; ++x) {
+                            const bf16x8_t bf = *reinterpret_cast<const bf16x8_t*>(
+                                &sB[((size_t)x * nb_pad + mt * 32 + l32) * STR + ks * 16 + hf * 8]);
+                            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, qf[ks], acc[mt], 0, 0, 0);
+                        }
                     }
+                }
             }
         }
         // accumulator value v of tile mt <-> block 32*mt + 8*(v>>2) + 4*hf + (v&3)
@@ -984,21 +1015,27 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
         kfn<<<sgrid, dim3(256), lds, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks,  \
                                            score_scale, fix_shift, row_stat);                             \
     } while (0)
-    // bfloat16 queries and at most 128 blocks: scores on the matrix cores
+    // bfloat16 queries: scores on the matrix cores; block means in LDS as three bfloat16 terms up to 128 blocks, as
+    // float32 (split after the fetch) beyond
     const int nb_pad = (n_blocks + 31) & ~31;
-    const size_t lds_mfma = (size_t)3 * nb_pad * (D + 8) * 2 + HIST_BINS * 12;
-    const bool score_mfma = bf16 && n_blocks <= 128 && lds_mfma <= 160 * 1024 && getenv("VMOBA_SCORE_FMA") == nullptr;
+    const bool fly = n_blocks > 128;
+    const size_t lds_mfma = (fly ? (size_t)nb_pad * (D + 4) * 4 : (size_t)3 * nb_pad * (D + 8) * 2) + HIST_BINS * 12;
+    const bool score_mfma = bf16 && n_blocks <= 256 && lds_mfma <= 160 * 1024 && getenv("VMOBA_SCORE_FMA") == nullptr;
     if (score_mfma) {
         dim3 mgrid((unsigned)ceil_div64(ceil_div64(S, 128), 4), (unsigned)BH);
-        if (D == 128) {
-            auto kfn = score_mfma_kernel<128>;
-            if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_mfma) != hipSuccess) return VMOBA_ERR_HIP;
-            kfn<<<mgrid, dim3(256), lds_mfma, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks, score_scale, fix_shift, row_stat);
-        } else {
-            auto kfn = score_mfma_kernel<64>;
-            if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_mfma) != hipSuccess) return VMOBA_ERR_HIP;
-            kfn<<<mgrid, dim3(256), lds_mfma, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks, score_scale, fix_shift, row_stat);
-        }
+#define LAUNCH_SCORE_MFMA(DD, FL)                                                                         \
+    do {                                                                                                  \
+        auto kfn = score_mfma_kernel<DD, FL>;                                                             \
+        if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_mfma) != hipSuccess) \
+            return VMOBA_ERR_HIP;                                                                         \
+        kfn<<<mgrid, dim3(256), lds_mfma, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks, score_scale, \
+                                                fix_shift, row_stat);                                     \
+    } while (0)
+        if (D == 128 && fly) LAUNCH_SCORE_MFMA(128, true);
+        else if (D == 128) LAUNCH_SCORE_MFMA(128, false);
+        else if (fly) LAUNCH_SCORE_MFMA(64, true);
+        else LAUNCH_SCORE_MFMA(64, false);
+#undef LAUNCH_SCORE_MFMA
     } else if (bf16 && D == 128) LAUNCH_SCORE(true, 128);
     else if (bf16 && D == 64) LAUNCH_SCORE(true, 64);
     else if (D == 128) LAUNCH_SCORE(false, 128);
