@@ -427,7 +427,7 @@ constexpr int dkv_pair_lds_bytes() { return 2 * 4 * 64 * (D + 8) * 2 + 2 * 4 * 6
 
 template <int D>
 __device__ __forceinline__ void dkv_pair_body(
-    char* smem, int run_id, const TensorView& Q, const TensorView& K, const TensorView& V, const TensorView& dO, const float* __restrict__ LSE,
+    char* smem, int bh, int run_id, const TensorView& Q, const TensorView& K, const TensorView& V, const TensorView& dO, const float* __restrict__ LSE,
     const float* __restrict__ delta, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
     const int* __restrict__ kb_start, const int* __restrict__ kb_order, const TensorView& dK, const TensorView& dV, const int* __restrict__ rows,
     int Hh, int S, int nb, long long cap, float scale_log2, float scale) {
@@ -448,7 +448,7 @@ __device__ __forceinline__ void dkv_pair_body(
     u32x4_t(*sX)[2][4][64] = reinterpret_cast<u32x4_t(*)[2][4][64]>(smem + 2 * NBUF * QC * STR * 2 + 2 * NBUF * QC * 4);
     static_assert(dkv_pair_lds_bytes<D>() == 2 * NBUF * QC * STR * 2 + 2 * NBUF * QC * 4 + 2 * 2 * 4 * 64 * 16, "LDS carve");
 
-    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
+    const int b = bh / Hh, h = bh % Hh;
     const int* ks = kb_start + (long long)bh * (nb + 1);
     int lo = 0, hi = nb;
     while (hi - lo > 1) { int mid = (lo + hi) >> 1; if (ks[mid] <= run_id) lo = mid; else hi = mid; }
@@ -753,7 +753,7 @@ __device__ __forceinline__ void dkv_pair_body(
 // without workgroup barriers; the four partial dK^T / dV^T are added through LDS at the end.
 template <int D>
 __device__ __forceinline__ void dkv_tail_body(
-    char* smem, int rank, const TensorView& Q, const TensorView& K, const TensorView& V, const TensorView& dO, const float* __restrict__ LSE,
+    char* smem, int bh, int rank, const TensorView& Q, const TensorView& K, const TensorView& V, const TensorView& dO, const float* __restrict__ LSE,
     const float* __restrict__ delta, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
     const int* __restrict__ kb_order, const TensorView& dK, const TensorView& dV, const int* __restrict__ rows, int Hh, int S, int nb,
     long long cap, float scale_log2, float scale) {
@@ -766,7 +766,7 @@ __device__ __forceinline__ void dkv_tail_body(
     float(*sL)[QC] = reinterpret_cast<float(*)[QC]>(smem + 2 * 4 * QC * STR * 2);
     float(*sDl)[QC] = reinterpret_cast<float(*)[QC]>(smem + 2 * 4 * QC * STR * 2 + 4 * QC * 4);
     static_assert(2 * 4 * QC * STR * 2 + 2 * 4 * QC * 4 <= dkv_pair_lds_bytes<D>(), "the tail body fits the pair body's LDS");
-    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
+    const int b = bh / Hh, h = bh % Hh;
     const int j = kb_order[(long long)bh * nb + rank];            // longest query list first
     const int k0 = blk_off[j], L = blk_off[j + 1] - k0;
     const int tail = L % 128;
@@ -947,9 +947,10 @@ __device__ __forceinline__ void dkv_tail_body(
     }
 }
 
-// The dK/dV launch: workgroups [0, runs of the head) run the pair body on one 128-key run each (longest query list
-// first); the next n_blocks workgroups run the tail body on one block each.  The tail workgroups are short and
-// dispatched last, so they fill the end of the launch, where the long runs finish unevenly.
+// The dK/dV launch, grid (heads, slots): slots [0, runs of the head) run the pair body on one 128-key run each
+// (longest query list first); the next n_blocks slots run the tail body on one block each.  With the head on grid x
+// the hardware hands out slot 0 of every head, then slot 1 of every head, ...: the order is longest-first over the
+// whole launch rather than per head, and the short tail workgroups fill its end, where the long runs finish unevenly.
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
@@ -957,12 +958,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
     const int* __restrict__ kb_start, const int* __restrict__ kb_order, TensorView dK, TensorView dV, const int* __restrict__ rows, int Hh, int S, int nb, long long cap,
     float scale_log2, float scale) {
     __shared__ __align__(16) char smem[dkv_pair_lds_bytes<D>()];
-    const int runs = kb_start[(long long)blockIdx.y * (nb + 1) + nb];
-    const int id = (int)blockIdx.x;
+    // grid (heads, slots): workgroups are dispatched x-fastest, so slot s of every head starts before slot s + 1 of any --
+    // with each head's runs sorted by length this is a longest-first order over the whole launch, not per head
+    const int bh = (int)blockIdx.x;
+    const int runs = kb_start[(long long)bh * (nb + 1) + nb];
+    const int id = (int)blockIdx.y;
     if (id < runs)
-        dkv_pair_body<D>(smem, id, Q, K, V, dO, LSE, delta, blk_off, blk_ptr, q_idx, kb_start, kb_order, dK, dV, rows, Hh, S, nb, cap, scale_log2, scale);
+        dkv_pair_body<D>(smem, bh, id, Q, K, V, dO, LSE, delta, blk_off, blk_ptr, q_idx, kb_start, kb_order, dK, dV, rows, Hh, S, nb, cap, scale_log2, scale);
     else if (id - runs < nb)
-        dkv_tail_body<D>(smem, id - runs, Q, K, V, dO, LSE, delta, blk_off, blk_ptr, q_idx, kb_order, dK, dV, rows, Hh, S, nb, cap, scale_log2, scale);
+        dkv_tail_body<D>(smem, bh, id - runs, Q, K, V, dO, LSE, delta, blk_off, blk_ptr, q_idx, kb_order, dK, dV, rows, Hh, S, nb, cap, scale_log2, scale);
 }
 
 // dQ[q] = scale * sum over the query's pairs of dQpart[pair] (bfloat16 partials when PBF16).
@@ -1170,8 +1174,9 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
             else if (D == 128) attn_bwd_dkv_simple_kernel<false, 128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
             else attn_bwd_dkv_simple_kernel<false, 64><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
         } else {
-            if (D == 128) attn_bwd_dkv_kernel<128><<<grid, dim3(256), 0, st>>>(DKV_ARGS);
-            else attn_bwd_dkv_kernel<64><<<grid, dim3(256), 0, st>>>(DKV_ARGS);
+            const dim3 hgrid(grid.y, grid.x);       // heads on x (see the kernel)
+            if (D == 128) attn_bwd_dkv_kernel<128><<<hgrid, dim3(256), 0, st>>>(DKV_ARGS);
+            else attn_bwd_dkv_kernel<64><<<hgrid, dim3(256), 0, st>>>(DKV_ARGS);
         }
 #undef DKV_ARGS
         VMOBA_PROFILE_END(2, st);
