@@ -398,6 +398,12 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
     }
 }
 
+// Load through a wave-uniform base and a 32-bit byte offset per lane (the address needs no 64-bit vector arithmetic).
+template <typename T>
+__device__ __forceinline__ T load_at(const void* base, uint32_t byte_off) {
+    return *reinterpret_cast<const T*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+
 // ---------------------------------------------------------------------------------------------
 // bf16 MFMA dK/dV kernel.  A workgroup owns 128 consecutive keys of one block (key = MFMA column
 // = lane % 32) and walks the block's query list in chunks of 64 gathered queries (two half-chunks
@@ -421,6 +427,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
 //   matrix:  S or dP of half-chunk t + 1,  dV or dK of half-chunk t - 1      vector: P or dS of t
 //   memory (even hc): rows of chunk hc/2 + 2 from registers into the ring, loads of chunk hc/2 + 3.
 // The ring buffer written during steps 2c, 2c + 1 was last read in step 2c - 1 and is first read in 2c + 3.
+// A wavefront issues in order and a matrix instruction occupies the matrix pipe for 32 cycles, so the step is cut
+// into units of one matrix instruction followed by an equal share of the vector, LDS and memory instructions,
+// with scheduling fences between them (two matrix instructions back to back would stall the second one while
+// the vector unit idles).  S / dP of even and odd half-chunks live in two register sets that swap roles, so
+// no accumulator is ever copied.
 // LDS bytes of the pair body: a ring of four 64-row tiles of Q and of dO, their LSE / delta, the packed-P hand-over
 template <int D>
 constexpr int dkv_pair_lds_bytes() { return 2 * 4 * 64 * (D + 8) * 2 + 2 * 4 * 64 * 4 + 2 * 2 * 4 * 64 * 16; }
@@ -490,7 +501,8 @@ __device__ __forceinline__ void dkv_pair_body(
     if (cnt > 0) {
         const char* qbase = Q.ptr + ((long long)b * Q.stride_b + (long long)h * Q.stride_h) * 2;
         const char* dobase = dO.ptr + ((long long)b * dO.stride_b + (long long)h * dO.stride_h) * 2;
-        const long long qss = Q.stride_s * 2, doss = dO.stride_s * 2;
+        // row strides in bytes: below 2^24 and rows below 2^24, so a row's offset is one 24-bit multiply (host-checked)
+        const uint32_t qss = (uint32_t)(Q.stride_s * 2), doss = (uint32_t)(dO.stride_s * 2);
         const int* list = q_idx + seg + list0;
         const float* lse_h = LSE + (long long)bh * S;
         const float* dl_h = delta + (long long)bh * S;
@@ -499,33 +511,37 @@ __device__ __forceinline__ void dkv_pair_body(
 
         u32x4_t qreg[LOADS], doreg[LOADS];
         float lreg = 0.f, dreg = 0.f;
-        int qn[LOADS], ql = 0;
+        uint32_t qn[LOADS], ql = 0;
         bool ql_live = false, rows_live = false;
-        auto prefetch_idx = [&](int c) {       // chunks past the list: indices clamp, rows count as dead
+        auto prefetch_idx_piece = [&](int c, int i) {       // chunks past the list: indices clamp, rows count as dead
             const int c0 = c * QC;
-#pragma unroll
-            for (int i = 0; i < LOADS; ++i) {
+            if (i < LOADS) {
                 const int r = (tid + NT * i) / (D / 8);
-                qn[i] = list[min(c0 + r, cnt - 1)];
+                qn[i] = load_at<uint32_t>(list, (uint32_t)min(c0 + r, cnt - 1) << 2);
+            } else {
+                ql = load_at<uint32_t>(list, (uint32_t)min(c0 + lane, cnt - 1) << 2);
+                ql_live = c0 + lane < cnt;
             }
-            ql = list[min(c0 + lane, cnt - 1)];
-            ql_live = c0 + lane < cnt;
+        };
+        auto prefetch_idx = [&](int c) {
+#pragma unroll
+            for (int i = 0; i <= LOADS; ++i) prefetch_idx_piece(c, i);
         };
         auto load_piece = [&](int i) {
             if (i < LOADS) {
-                const int pc = (tid + NT * i) % (D / 8);
-                qreg[i] = *reinterpret_cast<const u32x4_t*>(qbase + (long long)qn[i] * qss + pc * 16);
+                const uint32_t pc = (tid + NT * i) % (D / 8);
+                qreg[i] = load_at<u32x4_t>(qbase, __umul24(qn[i], qss) + pc * 16);
             } else {
                 const int k = i - LOADS;
-                const int pc = (tid + NT * k) % (D / 8);
-                doreg[k] = *reinterpret_cast<const u32x4_t*>(dobase + (long long)qn[k] * doss + pc * 16);
+                const uint32_t pc = (tid + NT * k) % (D / 8);
+                doreg[k] = load_at<u32x4_t>(dobase, __umul24(qn[k], doss) + pc * 16);
             }
         };
         // LSE and delta of the chunk's 64 rows: every wavefront fetches and stores all 64 (same values,
         // same places), which keeps these accesses free of branches inside the pipelined loop
         auto load_ld_regs = [&]() {
-            lreg = lse_h[ql];
-            dreg = dl_h[ql];
+            lreg = load_at<float>(lse_h, ql << 2);
+            dreg = load_at<float>(dl_h, ql << 2);
             rows_live = ql_live;
         };
         auto stage_piece = [&](int buf, int i) {
@@ -577,9 +593,13 @@ __device__ __forceinline__ void dkv_pair_body(
         auto read_tr = [&](int half, int step) {
             return tr_operand<STR>(tr_tile + half_off(half) + tr_lane, 0, step / DT, (step % DT) * 32);
         };
+        auto read_tr_half = [&](int half, int step, int part) {     // the two 8-byte transpose reads of read_tr, one at a time
+            const __bf16* pp = tr_tile + half_off(half) + tr_lane + (16 * (step / DT) + 2 * part) * STR + (step % DT) * 32;
+            return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_t*)(pp));
+        };
 
         if (pair_live) {
-            f32x16_t x_cur[2] = {zero16, zero16};          // S or dP of local half-chunk t
+            f32x16_t xa[2] = {zero16, zero16}, xb[2] = {zero16, zero16};    // S or dP of the even / odd local half-chunks
             bf16x8_t w_prev[2][2];                          // packed P or dS of local half-chunk t - 1, [kg][s]
             {
                 const f32x4_t z4 = {0.f, 0.f, 0.f, 0.f};
@@ -594,14 +614,15 @@ __device__ __forceinline__ void dkv_pair_body(
                 const bf16x8_t a = read_rows(0, ks);
 #pragma unroll
                 for (int kg = 0; kg < 2; ++kg)
-                    x_cur[kg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, frag[kg][ks], ks == 0 ? zero16 : x_cur[kg], 0, 0, 0);
+                    xa[kg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, frag[kg][ks], ks == 0 ? zero16 : xa[kg], 0, 0, 0);
             }
             bf16x8_t rcur = read_rows(1, 0);
             bf16x8_t tcur = read_tr(0, 0);                  // local step 0 multiplies it by zeros
             u32x4_t* xbuf = &sX[pair][0][0][lane];          // + parity * 256 + slot * 64
 
             // one local step; ROLE and EVEN (parity of the workgroup step hc = t + ROLE) are compile-time
-            auto local_step = [&](int t, auto role_tag, auto even_tag) {
+            // (x_cur holds S or dP of half-chunk t, x_nxt receives that of t + 1: the two sets swap roles every step)
+            auto local_step = [&](int t, auto role_tag, auto even_tag, f32x16_t(&x_cur)[2], f32x16_t(&x_nxt)[2]) {
                 constexpr int ROLE = decltype(role_tag)::value;
                 constexpr bool EVEN = decltype(even_tag)::value;
                 const int hc = t + ROLE;
@@ -621,25 +642,30 @@ __device__ __forceinline__ void dkv_pair_body(
 #pragma unroll
                     for (int sl = 0; sl < 4; ++sl) pin[sl] = xbuf[(t & 1) * 256 + sl * 64];
                 }
-                f32x16_t x_nxt[2] = {zero16, zero16};
                 float w[2][16];
                 const int th = t > 0 ? t - 1 : 0;
 #pragma unroll
                 for (int st = 0; st < NST; ++st) {
-                    bf16x8_t rn, tn;
-                    if (st + 1 < NST) { rn = read_rows(t + 1, st + 1); tn = read_tr(th, st + 1); }
-                    else { rn = read_rows(t + 2, 0); tn = read_tr(t, 0); }
+                    // four units per k-step, each one matrix instruction plus a quarter of everything else, fenced so
+                    // that the matrix instructions stay evenly spaced in the (in-order) instruction stream
+                    bf16x8_t rn;
+                    bf16x4_t tlo, thi;
+                    const bool last_st = st + 1 == NST;
 #pragma unroll
-                    for (int kg = 0; kg < 2; ++kg)
-                        x_nxt[kg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rcur, frag[kg][st], st == 0 ? zero16 : x_nxt[kg], 0, 0, 0);
+                    for (int q = 0; q < 4; ++q) {
+                        const int kg = q >> 1;
+                        if (q == 0) rn = last_st ? read_rows(t + 2, 0) : read_rows(t + 1, st + 1);
+                        if (q == 1) tlo = last_st ? read_tr_half(t, 0, 0) : read_tr_half(th, st + 1, 0);
+                        if (q == 2) thi = last_st ? read_tr_half(t, 0, 1) : read_tr_half(th, st + 1, 1);
+                        if ((q & 1) == 0)
+                            x_nxt[kg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rcur, frag[kg][st], st == 0 ? zero16 : x_nxt[kg], 0, 0, 0);
+                        else
+                            acc[kg][st % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tcur, w_prev[kg][st / DT], acc[kg][st % DT], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);          // the matrix instruction leads its unit
+                        // the unit's VP values of P or dS: second half of this k-step's values when q is odd, key group kg
 #pragma unroll
-                    for (int kg = 0; kg < 2; ++kg)
-                        acc[kg][st % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tcur, w_prev[kg][st / DT], acc[kg][st % DT], 0, 0, 0);
-#pragma unroll
-                    for (int kg = 0; kg < 2; ++kg)
-#pragma unroll
-                        for (int u = 0; u < 2 * VP; ++u) {
-                            const int i = 2 * VP * st + u;
+                        for (int u = 0; u < VP; ++u) {
+                            const int i = 2 * VP * st + VP * (q & 1) + u;
                             if constexpr (ROLE == 0) {
                                 w[kg][i] = exp2_raw(fmaf(x_cur[kg][i], scale_log2, -ld[i]));
                             } else {
@@ -648,33 +674,33 @@ __device__ __forceinline__ void dkv_pair_body(
                                 const float pval = (i & 1) ? bf16hi_to_f32(word) : bf16lo_to_f32(word);
                                 w[kg][i] = pval * (x_cur[kg][i] - ld[i]);
                             }
+                            asm volatile("" : "+v"(w[kg][i]));
                         }
-                    // packed operands are replaced as soon as their last reader of this step has issued
-                    if (st == NST / 2 - 1 || st == NST - 1) {
-                        const int sidx = st == NST - 1 ? 1 : 0;
+                        // packed operands are replaced as soon as their last reader of this step has issued
+                        if (q == 3 && (st == NST / 2 - 1 || last_st)) {
+                            const int sidx = last_st ? 1 : 0;
 #pragma unroll
-                        for (int kg = 0; kg < 2; ++kg) {
-                            w_prev[kg][sidx] = pack8(&w[kg][8 * sidx]);
-                            if constexpr (ROLE == 0) {
-                                u32x4_t o;
-                                __builtin_memcpy(&o, &w_prev[kg][sidx], 16);
-                                xbuf[(t & 1) * 256 + (kg * 2 + sidx) * 64] = o;
+                            for (int k2 = 0; k2 < 2; ++k2) {
+                                w_prev[k2][sidx] = pack8(&w[k2][8 * sidx]);
+                                if constexpr (ROLE == 0) {
+                                    u32x4_t o;
+                                    __builtin_memcpy(&o, &w_prev[k2][sidx], 16);
+                                    xbuf[(t & 1) * 256 + (k2 * 2 + sidx) * 64] = o;
+                                }
                             }
                         }
-                    }
-                    if constexpr (EVEN) {
-                        stage_piece(wbuf, st);
-                        load_piece(st);
-                        if (st == 0) { stage_ld(wbuf); load_ld_regs(); }
-                    } else {
-                        if (st == 0) prefetch_idx((hc >> 1) + 4);
+                        if constexpr (EVEN) {
+                            if (q == 2) stage_piece(wbuf, st);
+                            if (q == 3) load_piece(st);
+                            if (st == 0 && q == 1) { stage_ld(wbuf); load_ld_regs(); }
+                        } else {
+                            if (4 * st + q <= LOADS) prefetch_idx_piece((hc >> 1) + 4, 4 * st + q);     // one index load per unit
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                     rcur = rn;
-                    tcur = tn;
-                    __builtin_amdgcn_sched_barrier(0);
+                    tcur = __builtin_shufflevector(tlo, thi, 0, 1, 2, 3, 4, 5, 6, 7);
                 }
-                x_cur[0] = x_nxt[0];
-                x_cur[1] = x_nxt[1];
             };
             // a step in which this wavefront has no local step (hc = 0 for wavefront 1, hc = H + 1 for
             // wavefront 0) still moves its share of the rows
@@ -690,24 +716,24 @@ __device__ __forceinline__ void dkv_pair_body(
             if (role == 0) {
                 for (int c = 0; c < n_chunks; ++c) {
                     if (c > 0) __syncthreads();
-                    local_step(2 * c, std::integral_constant<int, 0>{}, std::true_type{});
+                    local_step(2 * c, std::integral_constant<int, 0>{}, std::true_type{}, xa, xb);
                     __syncthreads();
-                    local_step(2 * c + 1, std::integral_constant<int, 0>{}, std::false_type{});
+                    local_step(2 * c + 1, std::integral_constant<int, 0>{}, std::false_type{}, xb, xa);
                 }
                 __syncthreads();
-                local_step(H, std::integral_constant<int, 0>{}, std::true_type{});       // drain: dV of the last half-chunk
+                local_step(H, std::integral_constant<int, 0>{}, std::true_type{}, xa, xb);       // drain: dV of the last half-chunk
                 __syncthreads();
                 idle_step(H + 1, std::false_type{});
             } else {
                 idle_step(0, std::true_type{});
                 for (int c = 0; c < n_chunks; ++c) {
                     __syncthreads();
-                    local_step(2 * c, std::integral_constant<int, 1>{}, std::false_type{});
+                    local_step(2 * c, std::integral_constant<int, 1>{}, std::false_type{}, xa, xb);
                     __syncthreads();
-                    local_step(2 * c + 1, std::integral_constant<int, 1>{}, std::true_type{});
+                    local_step(2 * c + 1, std::integral_constant<int, 1>{}, std::true_type{}, xb, xa);
                 }
                 __syncthreads();
-                local_step(H, std::integral_constant<int, 1>{}, std::false_type{});      // drain: dK of the last half-chunk
+                local_step(H, std::integral_constant<int, 1>{}, std::false_type{}, xa, xb);      // drain: dK of the last half-chunk
             }
         } else {
             // a pair whose keys lie past the end of the block only helps to move rows
@@ -1094,6 +1120,13 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     TensorView dOv = make_view(dO);
     const float scale_log2 = softmax_scale * LOG2E;
     const bool simple = !bf16 || getenv("VMOBA_FORCE_SIMPLE") != nullptr;
+    // the dK/dV kernel forms the byte offset of a gathered Q' or dO row with one 24-bit multiply and 32-bit adds
+    if (!simple) {
+        const int64_t do_stride = rows ? D : dO->stride_s;          // dO is read from its block-order copy when `rows` is given
+        if (S >= (1 << 24) || Qp->stride_s <= 0 || do_stride <= 0 || Qp->stride_s * 2 >= (1 << 24) || do_stride * 2 >= (1 << 24) ||
+            (uint64_t)S * (uint64_t)Qp->stride_s * 2 >= ((uint64_t)1 << 32) || (uint64_t)S * (uint64_t)do_stride * 2 >= ((uint64_t)1 << 32))
+            return VMOBA_ERR_UNSUPPORTED;
+    }
 
     {   // delta
         const int epp = bf16 ? 8 : 4;
