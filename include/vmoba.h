@@ -199,7 +199,7 @@ int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int3
  *        (not Q', K', V', LSE) are addressed through it -- block-order row r is row rows[r] of each:
  *        pass the partition's perm and tensors in the caller's token order to skip the partition
  *        of dO and the inverse partition of the three gradients.
- *  Limit (bfloat16): S < 2^24, and for Q' and dO a positive stride_s with stride_s * 2 < 2^24 and
+ *  Limit (bfloat16): S < 2^24, and for Q', K', V' and dO a positive stride_s with stride_s * 2 < 2^24 and
  *  S * stride_s * 2 < 2^32 (one (batch, head) slice spans less than 4 GiB); otherwise
  *  VMOBA_ERR_UNSUPPORTED.
  */

@@ -248,6 +248,12 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_simple_kernel(
     }
 }
 
+// Load through a wave-uniform base and a 32-bit byte offset per lane (the address needs no 64-bit vector arithmetic).
+template <typename T>
+__device__ __forceinline__ T load_at(const void* base, uint32_t byte_off) {
+    return *reinterpret_cast<const T*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+
 // ---------------------------------------------------------------------------------------------
 // bf16 MFMA dQ tile kernel.  Same decomposition and operand orientation as the forward tile
 // kernel (query = MFMA column = lane % 32); 4 wavefronts x 32 gathered queries, key chunks of 64:
@@ -311,7 +317,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
 
     const char* kbase = K.ptr + ((long long)b * K.stride_b + (long long)h * K.stride_h) * 2;
     const char* vbase = V.ptr + ((long long)b * V.stride_b + (long long)h * V.stride_h) * 2;
-    const long long kss = K.stride_s * 2, vss = V.stride_s * 2;
+    // row strides in bytes: below 2^24 and rows below 2^24, so a row's offset is one 24-bit multiply (host-checked)
+    const uint32_t kss = (uint32_t)(K.stride_s * 2), vss = (uint32_t)(V.stride_s * 2);
     const int n_chunks = (tc.L + KC - 1) / KC;
 
     u32x4_t kreg[LOADS], vreg[LOADS];
@@ -321,9 +328,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
         for (int i = 0; i < LOADS; ++i) {
             const int piece = tid + 256 * i;
             const int r = piece / (D / 8), pc = piece % (D / 8);
-            const long long row = tc.k0 + min(c0 + r, tc.L - 1);
-            kreg[i] = *reinterpret_cast<const u32x4_t*>(kbase + row * kss + pc * 16);
-            vreg[i] = *reinterpret_cast<const u32x4_t*>(vbase + row * vss + pc * 16);
+            const uint32_t row = (uint32_t)(tc.k0 + min(c0 + r, tc.L - 1));
+            kreg[i] = load_at<u32x4_t>(kbase, __umul24(row, kss) + pc * 16);
+            vreg[i] = load_at<u32x4_t>(vbase, __umul24(row, vss) + pc * 16);
         }
     };
     auto stage = [&]() {
@@ -366,20 +373,31 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
                     for (int i = 0; i < 16; ++i)
                         if (acc_row(i, 0) >= vh) sacc[i] = -INFINITY;
                 }
+                // dS of the first 16 keys, then the third product over those keys with dS of the other 16 keys computed
+                // between its matrix instructions (fenced, so that they overlap), then the third product over the rest
                 float ds[16];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
+                auto ds_value = [&](int i) {
                     const float p = exp2_raw(fmaf(sacc[i], scale_log2, -lse2));
                     ds[i] = p * (dpacc[i] - dl);
+                    asm volatile("" : "+v"(ds[i]));
+                };
+#pragma unroll
+                for (int i = 0; i < 8; ++i) ds_value(i);
+                const bf16x8_t dsf0 = pack8(&ds[0]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    const bf16x8_t ktf = tr_operand<STR>(sKt_lane, mt * 32, 0, dt * 32);
+                    dqacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf0, dqacc[dt], 0, 0, 0);
+#pragma unroll
+                    for (int u = 0; u < 8 / DT; ++u) ds_value(8 + dt * (8 / DT) + u);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
+                const bf16x8_t dsf1 = pack8(&ds[8]);
 #pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    const bf16x8_t dsf = pack8(&ds[8 * s]);
-#pragma unroll
-                    for (int dt = 0; dt < DT; ++dt) {
-                        const bf16x8_t ktf = tr_operand<STR>(sKt_lane, mt * 32, s, dt * 32);
-                        dqacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf, dqacc[dt], 0, 0, 0);
-                    }
+                for (int dt = 0; dt < DT; ++dt) {
+                    const bf16x8_t ktf = tr_operand<STR>(sKt_lane, mt * 32, 1, dt * 32);
+                    dqacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf1, dqacc[dt], 0, 0, 0);
                 }
             }
         }
@@ -396,12 +414,6 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
                 *reinterpret_cast<u32x2_t*>(dst + dt * 32 + g * 8 + hf * 4) = v;
             }
     }
-}
-
-// Load through a wave-uniform base and a 32-bit byte offset per lane (the address needs no 64-bit vector arithmetic).
-template <typename T>
-__device__ __forceinline__ T load_at(const void* base, uint32_t byte_off) {
-    return *reinterpret_cast<const T*>(reinterpret_cast<const char*>(base) + byte_off);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1120,12 +1132,13 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     TensorView dOv = make_view(dO);
     const float scale_log2 = softmax_scale * LOG2E;
     const bool simple = !bf16 || getenv("VMOBA_FORCE_SIMPLE") != nullptr;
-    // the dK/dV kernel forms the byte offset of a gathered Q' or dO row with one 24-bit multiply and 32-bit adds
+    // the tile kernels form the byte offset of a row of Q', K', V' or dO with one 24-bit multiply and 32-bit adds
     if (!simple) {
         const int64_t do_stride = rows ? D : dO->stride_s;          // dO is read from its block-order copy when `rows` is given
-        if (S >= (1 << 24) || Qp->stride_s <= 0 || do_stride <= 0 || Qp->stride_s * 2 >= (1 << 24) || do_stride * 2 >= (1 << 24) ||
-            (uint64_t)S * (uint64_t)Qp->stride_s * 2 >= ((uint64_t)1 << 32) || (uint64_t)S * (uint64_t)do_stride * 2 >= ((uint64_t)1 << 32))
-            return VMOBA_ERR_UNSUPPORTED;
+        const int64_t strides[4] = {Qp->stride_s, Kp->stride_s, Vp->stride_s, do_stride};
+        if (S >= (1 << 24)) return VMOBA_ERR_UNSUPPORTED;
+        for (int64_t ss : strides)
+            if (ss <= 0 || ss * 2 >= (1 << 24) || (uint64_t)S * (uint64_t)ss * 2 >= ((uint64_t)1 << 32)) return VMOBA_ERR_UNSUPPORTED;
     }
 
     {   // delta
