@@ -346,6 +346,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
     const __bf16* sV_lane = sV + rho(l32) * STR + hf * 8;
     const __bf16* sKt_lane = sK + tr_lane_offset<STR>(lane);
 
+    // LDS operands are fetched two matrix-instruction pairs ahead of their use (rings of three), across the phases of a
+    // 32-key group and into the next group; fences keep the order, so no matrix instruction waits a full LDS round trip
+    auto rd_k = [&](int mt, int ks) { return *reinterpret_cast<const bf16x8_t*>(sK_lane + mt * 32 * STR + ks * 16); };
+    auto rd_v = [&](int mt, int ks) { return *reinterpret_cast<const bf16x8_t*>(sV_lane + mt * 32 * STR + ks * 16); };
+    constexpr int NU = 2 * DT;                  // matrix instructions of the third product per 32-key group
     prefetch(0);
     for (int c = 0; c < n_chunks; ++c) {
         __syncthreads();
@@ -354,6 +359,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
         if (c + 1 < n_chunks) prefetch(c + 1);
         const int valid = tc.L - c * KC;
         const int n_mt = valid > 32 ? 2 : 1;
+        bf16x8_t kf[3], vf[3], ktf[3];
+        kf[0] = rd_k(0, 0); vf[0] = rd_v(0, 0);
+        kf[1] = rd_k(0, 1); vf[1] = rd_v(0, 1);
+        kf[2] = kf[0]; vf[2] = vf[0]; ktf[0] = ktf[1] = ktf[2] = kf[0];
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
             if (mt < n_mt) {
@@ -362,10 +371,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
                 for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dpacc[i] = 0.f; }
 #pragma unroll
                 for (int ks = 0; ks < KSTEPS; ++ks) {
-                    const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sK_lane + mt * 32 * STR + ks * 16);
-                    const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(sV_lane + mt * 32 * STR + ks * 16);
-                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc, 0, 0, 0);
-                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[ks], dpacc, 0, 0, 0);
+                    if (ks + 2 < KSTEPS) { kf[(ks + 2) % 3] = rd_k(mt, ks + 2); vf[(ks + 2) % 3] = rd_v(mt, ks + 2); }
+                    else ktf[ks + 2 - KSTEPS] = tr_operand<STR>(sKt_lane, mt * 32, 0, (ks + 2 - KSTEPS) * 32);
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks % 3], qf[ks], sacc, 0, 0, 0);
+                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks % 3], dof[ks], dpacc, 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
                 if (valid < KC) {                 // last chunk (uniform branch): keys past the block get weight 0
                     const int vh = valid - mt * 32 - hf;
@@ -383,21 +393,19 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
                 };
 #pragma unroll
                 for (int i = 0; i < 8; ++i) ds_value(i);
-                const bf16x8_t dsf0 = pack8(&ds[0]);
+                bf16x8_t dsf = pack8(&ds[0]);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    const bf16x8_t ktf = tr_operand<STR>(sKt_lane, mt * 32, 0, dt * 32);
-                    dqacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf0, dqacc[dt], 0, 0, 0);
+                for (int u = 0; u < NU; ++u) {
+                    if (u + 2 < NU) ktf[(u + 2) % 3] = tr_operand<STR>(sKt_lane, mt * 32, (u + 2) / DT, ((u + 2) % DT) * 32);
+                    else if (mt == 0) { kf[u + 2 - NU] = rd_k(1, u + 2 - NU); vf[u + 2 - NU] = rd_v(1, u + 2 - NU); }   // next group's first operands
+                    if (u == DT) dsf = pack8(&ds[8]);
+                    dqacc[u % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf[u % 3], dsf, dqacc[u % DT], 0, 0, 0);
+                    if (u < DT) {
 #pragma unroll
-                    for (int u = 0; u < 8 / DT; ++u) ds_value(8 + dt * (8 / DT) + u);
+                        for (int v = 0; v < 8 / DT; ++v) ds_value(8 + u * (8 / DT) + v);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
-                }
-                const bf16x8_t dsf1 = pack8(&ds[8]);
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    const bf16x8_t ktf = tr_operand<STR>(sKt_lane, mt * 32, 1, dt * 32);
-                    dqacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf1, dqacc[dt], 0, 0, 0);
                 }
             }
         }
