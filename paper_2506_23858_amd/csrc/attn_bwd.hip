@@ -346,11 +346,22 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
     const __bf16* sV_lane = sV + rho(l32) * STR + hf * 8;
     const __bf16* sKt_lane = sK + tr_lane_offset<STR>(lane);
 
-    // LDS operands are fetched two matrix-instruction pairs ahead of their use (rings of three), across the phases of a
-    // 32-key group and into the next group; fences keep the order, so no matrix instruction waits a full LDS round trip
-    auto rd_k = [&](int mt, int ks) { return *reinterpret_cast<const bf16x8_t*>(sK_lane + mt * 32 * STR + ks * 16); };
-    auto rd_v = [&](int mt, int ks) { return *reinterpret_cast<const bf16x8_t*>(sV_lane + mt * 32 * STR + ks * 16); };
+    // A 32-key group is a sequence of 2 * KSTEPS + NU matrix instructions: S^T over the k-steps, dP^T over the k-steps
+    // (with P = exp(S - LSE) computed between them), then the third product, first over the keys whose dS is ready
+    // (with the rest of dS computed between them).  Their LDS operands pass through one ring of AHEAD + 1 registers,
+    // fetched AHEAD instructions before use, across the phases and into the next group; fences keep that order, so no
+    // matrix instruction waits a full LDS round trip.
     constexpr int NU = 2 * DT;                  // matrix instructions of the third product per 32-key group
+    constexpr int NSEQ = 2 * KSTEPS + NU;
+    constexpr int AHEAD = 3, RING = AHEAD + 1;
+    static_assert(NSEQ % RING == 0, "the second group continues the ring where the first one left it");
+    auto fetch = [&](int mt, int n) -> bf16x8_t {     // operand of instruction n of group mt (n past the end: next group)
+        if (n >= NSEQ) { mt += 1; n -= NSEQ; }
+        if (n < KSTEPS) return *reinterpret_cast<const bf16x8_t*>(sK_lane + mt * 32 * STR + n * 16);
+        if (n < 2 * KSTEPS) return *reinterpret_cast<const bf16x8_t*>(sV_lane + mt * 32 * STR + (n - KSTEPS) * 16);
+        const int u = n - 2 * KSTEPS;
+        return tr_operand<STR>(sKt_lane, mt * 32, u / DT, (u % DT) * 32);
+    };
     prefetch(0);
     for (int c = 0; c < n_chunks; ++c) {
         __syncthreads();
@@ -359,51 +370,55 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
         if (c + 1 < n_chunks) prefetch(c + 1);
         const int valid = tc.L - c * KC;
         const int n_mt = valid > 32 ? 2 : 1;
-        bf16x8_t kf[3], vf[3], ktf[3];
-        kf[0] = rd_k(0, 0); vf[0] = rd_v(0, 0);
-        kf[1] = rd_k(0, 1); vf[1] = rd_v(0, 1);
-        kf[2] = kf[0]; vf[2] = vf[0]; ktf[0] = ktf[1] = ktf[2] = kf[0];
+        bf16x8_t op[RING];
+#pragma unroll
+        for (int n = 0; n < RING; ++n) op[n] = fetch(0, n < AHEAD ? n : 0);
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
             if (mt < n_mt) {
                 f32x16_t sacc, dpacc;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dpacc[i] = 0.f; }
-#pragma unroll
-                for (int ks = 0; ks < KSTEPS; ++ks) {
-                    if (ks + 2 < KSTEPS) { kf[(ks + 2) % 3] = rd_k(mt, ks + 2); vf[(ks + 2) % 3] = rd_v(mt, ks + 2); }
-                    else ktf[ks + 2 - KSTEPS] = tr_operand<STR>(sKt_lane, mt * 32, 0, (ks + 2 - KSTEPS) * 32);
-                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks % 3], qf[ks], sacc, 0, 0, 0);
-                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks % 3], dof[ks], dpacc, 0, 0, 0);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                if (valid < KC) {                 // last chunk (uniform branch): keys past the block get weight 0
-                    const int vh = valid - mt * 32 - hf;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        if (acc_row(i, 0) >= vh) sacc[i] = -INFINITY;
-                }
-                // dS of the first 16 keys, then the third product over those keys with dS of the other 16 keys computed
-                // between its matrix instructions (fenced, so that they overlap), then the third product over the rest
                 float ds[16];
+                bf16x8_t dsf;
+                auto p_value = [&](int i) {           // S^T value -> P^T value, in place
+                    sacc[i] = exp2_raw(fmaf(sacc[i], scale_log2, -lse2));
+                };
                 auto ds_value = [&](int i) {
-                    const float p = exp2_raw(fmaf(sacc[i], scale_log2, -lse2));
-                    ds[i] = p * (dpacc[i] - dl);
+                    ds[i] = sacc[i] * (dpacc[i] - dl);
                     asm volatile("" : "+v"(ds[i]));
                 };
 #pragma unroll
-                for (int i = 0; i < 8; ++i) ds_value(i);
-                bf16x8_t dsf = pack8(&ds[0]);
-                __builtin_amdgcn_sched_barrier(0);
+                for (int n = 0; n < NSEQ; ++n) {
+                    // the operand AHEAD instructions on (the group after the second one waits for the next chunk)
+                    if (n + AHEAD < NSEQ || mt == 0) op[(n + AHEAD) % RING] = fetch(mt, n + AHEAD);
+                    if (n < KSTEPS) {
+                        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[n % RING], qf[n], sacc, 0, 0, 0);
+                    } else if (n < 2 * KSTEPS) {
+                        const int ks = n - KSTEPS;
+                        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[n % RING], dof[ks], dpacc, 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (ks == 0 && valid < KC) {      // last chunk (uniform branch): keys past the block get weight 0
+                            const int vh = valid - mt * 32 - hf;
 #pragma unroll
-                for (int u = 0; u < NU; ++u) {
-                    if (u + 2 < NU) ktf[(u + 2) % 3] = tr_operand<STR>(sKt_lane, mt * 32, (u + 2) / DT, ((u + 2) % DT) * 32);
-                    else if (mt == 0) { kf[u + 2 - NU] = rd_k(1, u + 2 - NU); vf[u + 2 - NU] = rd_v(1, u + 2 - NU); }   // next group's first operands
-                    if (u == DT) dsf = pack8(&ds[8]);
-                    dqacc[u % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf[u % 3], dsf, dqacc[u % DT], 0, 0, 0);
-                    if (u < DT) {
+                            for (int i = 0; i < 16; ++i)
+                                if (acc_row(i, 0) >= vh) sacc[i] = -INFINITY;
+                        }
 #pragma unroll
-                        for (int v = 0; v < 8 / DT; ++v) ds_value(8 + u * (8 / DT) + v);
+                        for (int v = 0; v < 16 / KSTEPS; ++v) p_value(ks * (16 / KSTEPS) + v);
+                    } else {
+                        const int u = n - 2 * KSTEPS;
+                        if (u == 0) {
+#pragma unroll
+                            for (int i = 0; i < 8; ++i) ds_value(i);
+                            dsf = pack8(&ds[0]);
+                        }
+                        if (u == DT) dsf = pack8(&ds[8]);
+                        dqacc[u % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[n % RING], dsf, dqacc[u % DT], 0, 0, 0);
+                        if (u < DT) {
+#pragma unroll
+                            for (int v = 0; v < 8 / DT; ++v) ds_value(8 + u * (8 / DT) + v);
+                        }
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
