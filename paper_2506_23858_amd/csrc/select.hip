@@ -227,12 +227,14 @@ __global__ __launch_bounds__(256) void score_kernel(TensorView Q, const float* _
 // in float32 and only the accumulation rounds -- a bfloat16 copy of the means alone would move P
 // by ~4e-3.  S^T[block, q] = sum over the three terms of Bx[block, :] . Q[q, :], with the query on
 // the MFMA column (= lane % 32), so the soft-max over blocks is a reduction over a lane's own
-// registers plus one exchange with lane ^ 32.  4 wavefronts x 32 queries per tile.
+// registers plus one exchange with lane ^ 32.  SCORE_NW wavefronts x 32 queries per tile.
 // With more than 128 blocks the three bfloat16 copies no longer fit the LDS; FLY keeps the means there as float32 (row
 // stride D + 4) and splits every operand after its fetch: the same three terms from the same operations, so P is the
 // same, at the price of vector work per matrix instruction.
+// wavefronts per workgroup of the matrix-core score kernel (two per SIMD share one copy of the block means in LDS)
+constexpr int SCORE_NW = 8, SCORE_NT = 64 * SCORE_NW, SCORE_QT = 32 * SCORE_NW;
 template <int D, bool FLY>
-__global__ __launch_bounds__(256) void score_mfma_kernel(TensorView Q, const float* __restrict__ Bmean,
+__global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, const float* __restrict__ Bmean,
                                                          float* __restrict__ P, unsigned int* __restrict__ hist_cnt,
                                                          unsigned long long* __restrict__ hist_sum,
                                                          int Hh, int S, int nb, float score_scale, int fix_shift,
@@ -254,44 +256,74 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(TensorView Q, const flo
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hf = lane >> 5;
 
-    for (int i = tid; i < nb_pad * D; i += 256) {
-        const int j = i / D, d = i % D;
-        const float x = j < nb ? Bmean[((long long)bh * nb + j) * D + d] : 0.f;
-        if constexpr (FLY) {
-            sBf[j * FSTR + d] = x;
-            continue;
+    // block means -> LDS, 16 bytes per lane and four loads in flight per lane (the head's means are one contiguous array)
+    {
+        const f32x4_t* src4 = reinterpret_cast<const f32x4_t*>(Bmean + (long long)bh * nb * D);
+        const int n4 = nb * D / 4, n4_pad = nb_pad * D / 4;
+        for (int i0 = tid; i0 < n4_pad; i0 += 4 * SCORE_NT) {
+            f32x4_t x4[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + u * SCORE_NT;
+                const f32x4_t z = {0.f, 0.f, 0.f, 0.f};
+                x4[u] = i < n4 ? src4[i] : z;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + u * SCORE_NT;
+                if (i >= n4_pad) continue;
+                const int j = (i * 4) / D, d = (i * 4) % D;
+                if constexpr (FLY) {
+                    *reinterpret_cast<f32x4_t*>(&sBf[j * FSTR + d]) = x4[u];
+                } else {
+                    bf16x4_t h4, m4, l4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float x = x4[u][e];
+                        const __bf16 xh = (__bf16)x;
+                        const float r1 = x - (float)xh;
+                        const __bf16 xm = (__bf16)r1;
+                        const float r2 = r1 - (float)xm;
+                        h4[e] = xh;
+                        m4[e] = xm;
+                        l4[e] = (__bf16)r2;
+                    }
+                    *reinterpret_cast<bf16x4_t*>(&sB[(0 * nb_pad + j) * STR + d]) = h4;
+                    *reinterpret_cast<bf16x4_t*>(&sB[(1 * nb_pad + j) * STR + d]) = m4;
+                    *reinterpret_cast<bf16x4_t*>(&sB[(2 * nb_pad + j) * STR + d]) = l4;
+                }
+            }
         }
-        const __bf16 xh = (__bf16)x;
-        const float r1 = x - (float)xh;
-        const __bf16 xm = (__bf16)r1;
-        const float r2 = r1 - (float)xm;
-        const __bf16 xl = (__bf16)r2;
-        sB[(0 * nb_pad + j) * STR + d] = xh;
-        sB[(1 * nb_pad + j) * STR + d] = xm;
-        sB[(2 * nb_pad + j) * STR + d] = xl;
     }
-    for (int i = tid; i < HIST_BINS; i += 256) { sCnt[i] = 0u; sSum[i] = 0ull; }
+    for (int i = tid; i < HIST_BINS; i += SCORE_NT) { sCnt[i] = 0u; sSum[i] = 0ull; }
     __syncthreads();
 
     const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    const int n_tiles = (S + 127) / 128;
+    const int n_tiles = (S + SCORE_QT - 1) / SCORE_QT;
     const bool vec_ok = (nb & 3) == 0;         // rows of P start 16-byte aligned
-    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const int q = tile * 128 + wave * 32 + l32;
-        const int qc = min(q, S - 1);          // rows past the end recompute the last query; never stored
-        bf16x8_t qf[KSTEPS];
-        {
-            const char* src = Q.ptr + ((long long)b * Q.stride_b + (long long)qc * Q.stride_s + (long long)h * Q.stride_h) * 2;
+    auto load_q = [&](int tile, bf16x8_t(&dst)[KSTEPS]) {
+        const int qc = min(tile * SCORE_QT + wave * 32 + l32, S - 1);     // rows past the end recompute the last query; never stored
+        const char* src = Q.ptr + ((long long)b * Q.stride_b + (long long)qc * Q.stride_s + (long long)h * Q.stride_h) * 2;
 #pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8_t*>(src + (ks * 16 + hf * 8) * 2);
-        }
+        for (int ks = 0; ks < KSTEPS; ++ks) dst[ks] = *reinterpret_cast<const bf16x8_t*>(src + (ks * 16 + hf * 8) * 2);
+    };
+    bf16x8_t qf[KSTEPS], qn[KSTEPS];
+    if ((int)blockIdx.x < n_tiles) load_q(blockIdx.x, qn);
+    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int q = tile * SCORE_QT + wave * 32 + l32;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) qf[ks] = qn[ks];
+        load_q(min(tile + (int)gridDim.x, n_tiles - 1), qn);          // the next tile's rows arrive during this tile's work
         f32x16_t acc[MAX_MT];
 #pragma unroll
-        for (int mt = 0; mt < MAX_MT; ++mt) {
-            acc[mt] = zero16;
-            if (mt < n_mt) {
+        for (int mt = 0; mt < MAX_MT; ++mt) acc[mt] = zero16;
+        // k-step outermost: consecutive matrix instructions go to different accumulators (each accumulator still sums
+        // its terms in the order k-step, then high / middle / low part)
 #pragma unroll
-                for (int ks = 0; ks < KSTEPS; ++ks) {
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+#pragma unroll
+            for (int mt = 0; mt < MAX_MT; ++mt) {
+                if (mt < n_mt) {
                     if constexpr (FLY) {
                         const float* src = &sBf[(mt * 32 + l32) * FSTR + ks * 16 + hf * 8];
                         const f32x4_t x0 = *reinterpret_cast<const f32x4_t*>(src), x1 = *reinterpret_cast<const f32x4_t*>(src + 4);
@@ -310,15 +342,19 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(TensorView Q, const flo
                         acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh8, qf[ks], acc[mt], 0, 0, 0);
                         acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bm8, qf[ks], acc[mt], 0, 0, 0);
                         acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bl8, qf[ks], acc[mt], 0, 0, 0);
-                    } else {
+                    }
+                }
+            }
+            if constexpr (!FLY) {
 #pragma unroll
-                        for (int x = 0; x < 3; ++x) {
+                for (int x = 0; x < 3; ++x)
+#pragma unroll
+                    for (int mt = 0; mt < MAX_MT; ++mt)
+                        if (mt < n_mt) {
                             const bf16x8_t bf = *reinterpret_cast<const bf16x8_t*>(
                                 &sB[((size_t)x * nb_pad + mt * 32 + l32) * STR + ks * 16 + hf * 8]);
                             acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, qf[ks], acc[mt], 0, 0, 0);
                         }
-                    }
-                }
             }
         }
         // accumulator value v of tile mt <-> block 32*mt + 8*(v>>2) + 4*hf + (v&3)
@@ -377,7 +413,7 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(TensorView Q, const flo
         }
     }
     __syncthreads();
-    for (int i = tid; i < HIST_BINS; i += 256) {
+    for (int i = tid; i < HIST_BINS; i += SCORE_NT) {
         const unsigned int c = sCnt[i];
         if (c) {
             atomicAdd(&hist_cnt[(long long)bh * HIST_BINS + i], c);
@@ -1022,13 +1058,13 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
     const size_t lds_mfma = (fly ? (size_t)nb_pad * (D + 4) * 4 : (size_t)3 * nb_pad * (D + 8) * 2) + HIST_BINS * 12;
     const bool score_mfma = bf16 && n_blocks <= 256 && lds_mfma <= 160 * 1024 && getenv("VMOBA_SCORE_FMA") == nullptr;
     if (score_mfma) {
-        dim3 mgrid((unsigned)ceil_div64(ceil_div64(S, 128), 4), (unsigned)BH);
+        dim3 mgrid((unsigned)ceil_div64(ceil_div64(S, SCORE_QT), 2), (unsigned)BH);
 #define LAUNCH_SCORE_MFMA(DD, FL)                                                                         \
     do {                                                                                                  \
         auto kfn = score_mfma_kernel<DD, FL>;                                                             \
         if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_mfma) != hipSuccess) \
             return VMOBA_ERR_HIP;                                                                         \
-        kfn<<<mgrid, dim3(256), lds_mfma, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks, score_scale, \
+        kfn<<<mgrid, dim3(SCORE_NT), lds_mfma, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks, score_scale, \
                                                 fix_shift, row_stat);                                     \
     } while (0)
         if (D == 128 && fly) LAUNCH_SCORE_MFMA(128, true);
