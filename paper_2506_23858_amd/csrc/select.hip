@@ -644,6 +644,10 @@ __global__ __launch_bounds__(SCAN_THREADS) void row_scan_kernel(const int* __res
                                                                 int S) {
     __shared__ int sW[SCAN_THREADS / 64];
     __shared__ int sCarry;
+    // a batch of SCAN_THREADS * SCAN_ITEMS values passes through LDS so that global memory is read and written in whole
+    // rows of consecutive lanes while every thread scans SCAN_ITEMS consecutive values; item i sits at i + i / SCAN_ITEMS
+    // (a thread's items then start SCAN_ITEMS + 1 words apart: no bank conflicts)
+    __shared__ int sBuf[SCAN_THREADS * (SCAN_ITEMS + 1)];
     const int bh = blockIdx.x, t = threadIdx.x;
     if (needs_ties) {
         const HeadState st = state[bh];
@@ -654,12 +658,17 @@ __global__ __launch_bounds__(SCAN_THREADS) void row_scan_kernel(const int* __res
     if (t == 0) sCarry = 0;
     __syncthreads();
     for (int base = 0; base < S; base += SCAN_THREADS * SCAN_ITEMS) {
-        int v[SCAN_ITEMS];
-        int sum = 0;
-        const int i0 = base + t * SCAN_ITEMS;
 #pragma unroll
         for (int e = 0; e < SCAN_ITEMS; ++e) {
-            v[e] = (i0 + e < S) ? src[i0 + e] : 0;
+            const int li = e * SCAN_THREADS + t;
+            sBuf[li + li / SCAN_ITEMS] = (base + li < S) ? src[base + li] : 0;
+        }
+        __syncthreads();
+        int v[SCAN_ITEMS];
+        int sum = 0;
+#pragma unroll
+        for (int e = 0; e < SCAN_ITEMS; ++e) {
+            v[e] = sBuf[t * (SCAN_ITEMS + 1) + e];
             sum += v[e];
         }
         // inclusive scan of `sum` across the workgroup: wave scan, then scan of wave totals
@@ -676,11 +685,16 @@ __global__ __launch_bounds__(SCAN_THREADS) void row_scan_kernel(const int* __res
         int run = sCarry + wave_base + incl - sum;
 #pragma unroll
         for (int e = 0; e < SCAN_ITEMS; ++e) {
-            if (i0 + e < S) dst[i0 + e] = run;
+            sBuf[t * (SCAN_ITEMS + 1) + e] = run;
             run += v[e];
         }
         __syncthreads();
         if (t == SCAN_THREADS - 1) sCarry = run;
+#pragma unroll
+        for (int e = 0; e < SCAN_ITEMS; ++e) {
+            const int li = e * SCAN_THREADS + t;
+            if (base + li < S) dst[base + li] = sBuf[li + li / SCAN_ITEMS];
+        }
         __syncthreads();
     }
     if (t == 0) dst[S] = sCarry;
@@ -715,24 +729,66 @@ __global__ __launch_bounds__(256) void mask_kernel(const float* __restrict__ P, 
     const int q0 = active ? w * 64 : 0;
     const int words = (nb + 31) / 32;
     const int rows = active ? min(64, S - q0) : 0;
-#pragma unroll 4
-    for (int r = 0; r < 64; ++r) {
-        const bool live = r < rows;
-        const unsigned int* row = reinterpret_cast<const unsigned int*>(P + ((long long)bh * S + q0 + (live ? r : 0)) * nb);
-        for (int j0 = 0; j0 < nb; j0 += 64) {
-            const int j = j0 + lane;
-            const unsigned int u = (live && j < nb) ? row[j] : 0u;
-            const bool in = live && j < nb;
-            const unsigned long long gt = __ballot(in && (st.all || u > st.prefix));
-            const unsigned long long ti = __ballot(in && !st.all && u == st.prefix);
-            if (lane == 0) {
-                sGt[wv][r][j0 / 32] = (unsigned)gt;
-                sTie[wv][r][j0 / 32] = (unsigned)ti;
-                if (j0 + 32 < nb) {
-                    sGt[wv][r][j0 / 32 + 1] = (unsigned)(gt >> 32);
-                    sTie[wv][r][j0 / 32 + 1] = (unsigned)(ti >> 32);
-                }
+    // The wavefront's 64 rows of P are one contiguous run of rows * nb values: it is read flat, 16 bytes per lane and
+    // eight loads in flight, and every lane ORs the bits of its four values into the rows' mask words in LDS (a group
+    // of four can straddle two words or two rows).
+    for (int wd = 0; wd < words; ++wd) { sGt[wv][lane][wd] = 0u; sTie[wv][lane][wd] = 0u; }
+    __syncthreads();
+    {
+        const int n_el = rows * nb;
+        const unsigned int* tile = reinterpret_cast<const unsigned int*>(P + ((long long)bh * S + q0) * nb);
+        const bool aligned = (reinterpret_cast<uintptr_t>(tile) & 15) == 0;      // wave-uniform
+        const int n4 = (aligned && nb >= 4) ? n_el / 4 : 0;                      // whole groups of four (a group spans at most two rows)
+        const float inv_nb = 1.f / (float)nb;
+        auto put = [&](unsigned int (*arr)[VMOBA_MAX_MASK_WORDS + 1], int row, int col, unsigned int bits, int count) {
+            // `count` (1..4) bits for columns col, col + 1, ... of `row`, continuing in the next row past column nb - 1
+            const int here = min(count, nb - col);
+            const unsigned int b0 = bits & ((1u << here) - 1u);
+            if (b0) {
+                const unsigned long long v = (unsigned long long)b0 << (col & 31);
+                atomicOr(&arr[row][col >> 5], (unsigned int)v);
+                if (v >> 32) atomicOr(&arr[row][(col >> 5) + 1], (unsigned int)(v >> 32));
             }
+            const unsigned int b1 = bits >> here;
+            if (b1) atomicOr(&arr[row + 1][0], b1);
+        };
+        for (int k0 = 0; k0 < n4; k0 += 64 * 8) {
+            u32x4_t x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i4 = k0 + u * 64 + lane;
+                const u32x4_t z = {0u, 0u, 0u, 0u};
+                x[u] = i4 < n4 ? reinterpret_cast<const u32x4_t*>(tile)[i4] : z;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i4 = k0 + u * 64 + lane;
+                if (i4 >= n4) continue;
+                const int e = 4 * i4;
+                int row = (int)((float)e * inv_nb);
+                if (row * nb > e) --row;
+                if ((row + 1) * nb <= e) ++row;
+                const int col = e - row * nb;
+                unsigned int gt = 0u, ti = 0u;
+#pragma unroll
+                for (int cidx = 0; cidx < 4; ++cidx) {
+                    const unsigned int v = x[u][cidx];
+                    if (st.all || v > st.prefix) gt |= 1u << cidx;
+                    else if (v == st.prefix) ti |= 1u << cidx;
+                }
+                put(sGt[wv], row, col, gt, 4);
+                if (ti) put(sTie[wv], row, col, ti, 4);
+            }
+        }
+        // what the groups of four did not cover (everything when the run does not start 16-byte aligned)
+        for (int e = 4 * n4 + lane; e < n_el; e += 64) {
+            int row = (int)((float)e * inv_nb);
+            if (row * nb > e) --row;
+            if ((row + 1) * nb <= e) ++row;
+            const int col = e - row * nb;
+            const unsigned int v = tile[e];
+            if (st.all || v > st.prefix) put(sGt[wv], row, col, 1u, 1);
+            else if (v == st.prefix) put(sTie[wv], row, col, 1u, 1);
         }
     }
     __syncthreads();
