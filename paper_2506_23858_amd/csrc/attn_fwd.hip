@@ -377,7 +377,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
         opV[0] = opK[0];
         opV[1] = opK[1];
         const Tile nxt = decode(nd);
-        int nq = 0;
+        const int nq = query_of(nxt);              // needed a tile later: the load has the whole tile to land
 
         // one pipeline step; the flags are compile-time: QK / PV = the step has a first / second product, SM = it has a
         // soft-max (MASK: with the keys past the block's end masked), NEXTPV = the next step has a second product,
@@ -449,11 +449,12 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
                         request(cur.vbase, v_off, v_last, v_adv, sV0, vb + g + 2);
                     }
                 }
-                if constexpr (LAST_SM) { if (u == 1) nq = query_of(nxt); }
-                if constexpr (FINAL) {
-                    if (u == 1) {          // the next tile: query rows first (the wait for nq must not cover the requests below)
+                if constexpr (LAST_SM) {
+                    // the next tile's query rows (Q^T is free: the first product is complete) and its first key groups (all K
+                    // slots are free, the two V slots after the current tile's last two as well): two steps ahead of their use
+                    if (u == 1) {
                         load_q(nxt, nq);
-                        request_first_groups(nxt, kb + g, vb + g);
+                        request_first_groups(nxt, kb + g + 1, vb + g + 1);
                     }
                 }
                 opK[u2 & 3] = nk;
