@@ -115,6 +115,9 @@ def test_tiny_config_fp32(kind, tau):
     ((5, 7, 9), (2, 3, 4), 0, 64),          # ragged in all three axes, blocks of 1..24 tokens
     ((3, 5, 7), (0, 0, 0), 25, 128),        # 1D chunks with a short tail, D = 128
     ((6, 10, 12), (6, 5, 4), 0, 64),        # the paper's 2D case: a spatial tile through all frames
+    ((4, 4, 5), (4, 4, 1), 0, 64),          # 5 blocks: every 16-byte group of a row of P straddles two rows
+    ((2, 4, 33), (2, 4, 1), 0, 64),         # 33 blocks: two mask words per row, groups straddle words and rows
+    ((1, 9, 13), (0, 0, 0), 9, 64),         # 13 blocks, S * N_b odd: rows of P not 16-byte aligned
 ])
 def test_ragged_grids_fp32(grid, block, chunk, D):
     S = grid[0] * grid[1] * grid[2]
