@@ -228,6 +228,10 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
     static_assert(UNITS % 4 == 0 && UNITS == 2 * DT && IPW >= 1 && IPW * NW * 1024 == SLOT && (D == 64 || D == 128), "unit bookkeeping");
     __shared__ __align__(1024) char sK[NR * SLOT];
     __shared__ __align__(1024) char sV[NR * SLOT];
+    // a wavefront's 32 partial rows on their way out: written as the accumulators hold them (8 bytes per lane and
+    // channel group), read back as whole rows, so that the global stores are 1 KB runs instead of 16-byte pieces
+    constexpr int OPITCH = D * 2 + 16;
+    __shared__ __align__(16) char sOut[NW * 32 * OPITCH];
 
     // Workgroup ids go round the 8 XCDs (each with its own L2), so XCD x = id % 8 takes the x-th eighth of the tile
     // list and its workgroups stride through it: a key block's tiles then share one L2 instead of eight.
@@ -491,10 +495,9 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
 
         // ---- partial output: O^T value i of tile dt <-> channel 32*dt + 8*(i>>2) + 4*hf + (i&3)
         const float l_tot = swap_halves_sum(l_run);
-        if (ent < cur.count) {
-            const long long pair = cur.seg + cur.list0 + ent;
+        {
             const float inv = 1.f / l_tot;
-            uint16_t* dst = reinterpret_cast<uint16_t*>(Opart) + pair * D;      // bf16 partials
+            char* mine = sOut + wave * 32 * OPITCH;                               // this wavefront's rows only: no barrier
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -502,9 +505,19 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
                     u32x2_t v;
                     v.x = pack_bf16x2(oacc[dt][4 * gq + 0] * inv, oacc[dt][4 * gq + 1] * inv);
                     v.y = pack_bf16x2(oacc[dt][4 * gq + 2] * inv, oacc[dt][4 * gq + 3] * inv);
-                    *reinterpret_cast<u32x2_t*>(dst + dt * 32 + gq * 8 + hf * 4) = v;
+                    *reinterpret_cast<u32x2_t*>(mine + l32 * OPITCH + (dt * 32 + gq * 8 + hf * 4) * 2) = v;
                 }
-            if (hf == 0) lse_part[pair] = (m_run + log2f(l_tot)) * LN2;
+            // the tile's partials are consecutive rows of Opart (bfloat16): row = first pair of the tile + entry
+            char* dst = reinterpret_cast<char*>(Opart) + (cur.seg + cur.list0) * (long long)(D * 2);
+            constexpr int LPR = D * 2 / 16;                                       // lanes per row
+#pragma unroll
+            for (int k = 0; k < 32 * LPR / 64; ++k) {
+                const int row = k * (64 / LPR) + lane / LPR, piece = lane % LPR;
+                const u32x4_t x = *reinterpret_cast<const u32x4_t*>(mine + row * OPITCH + piece * 16);
+                const int e = wave * 32 + row;
+                if (e < cur.count) *reinterpret_cast<u32x4_t*>(dst + (long long)e * (D * 2) + piece * 16) = x;
+            }
+            if (ent < cur.count && hf == 0) lse_part[cur.seg + cur.list0 + ent] = (m_run + log2f(l_tot)) * LN2;
         }
         if (!has_next) break;
         f = fn;
