@@ -273,6 +273,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
     constexpr int LOADS = KC * D * 2 / 16 / 256;
     __shared__ __align__(16) __bf16 sK[KC * STR];
     __shared__ __align__(16) __bf16 sV[KC * STR];
+    // a wavefront's 32 partial rows on their way out: written as the accumulators hold them, read back as whole rows
+    constexpr int OPITCH = D * 2 + 16;
+    __shared__ __align__(16) char sOut[4 * 32 * OPITCH];
 
     // One workgroup per tile of the flat list (all heads).  Workgroup ids go round the 8 XCDs, so XCD x = id % 8 takes the
     // x-th eighth of the list: a key block's tiles then share one L2 instead of eight (gridDim.x is a multiple of 8).
@@ -425,8 +428,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
             }
         }
     }
-    if (ent < tc.count) {
-        uint16_t* dst = reinterpret_cast<uint16_t*>(dQpart) + (seg + tc.list0 + tc.t0 + ent) * D;   // bf16 partials
+    {
+        // the tile's partials are consecutive rows of dQpart (bfloat16): stores of 1 KB runs instead of 16-byte pieces
+        char* mine = sOut + wave * 32 * OPITCH;                               // this wavefront's rows only: no barrier
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -434,8 +438,17 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
                 u32x2_t v;
                 v.x = pack_bf16x2(dqacc[dt][4 * g + 0], dqacc[dt][4 * g + 1]);
                 v.y = pack_bf16x2(dqacc[dt][4 * g + 2], dqacc[dt][4 * g + 3]);
-                *reinterpret_cast<u32x2_t*>(dst + dt * 32 + g * 8 + hf * 4) = v;
+                *reinterpret_cast<u32x2_t*>(mine + l32 * OPITCH + (dt * 32 + g * 8 + hf * 4) * 2) = v;
             }
+        char* dst = reinterpret_cast<char*>(dQpart) + (seg + tc.list0 + tc.t0) * (long long)(D * 2);
+        constexpr int LPR = D * 2 / 16;                                       // lanes per row
+#pragma unroll
+        for (int k = 0; k < 32 * LPR / 64; ++k) {
+            const int row = k * (64 / LPR) + lane / LPR, piece = lane % LPR;
+            const u32x4_t x = *reinterpret_cast<const u32x4_t*>(mine + row * OPITCH + piece * 16);
+            const int e2 = wave * 32 + row;
+            if (e2 < tc.count) *reinterpret_cast<u32x4_t*>(dst + (long long)e2 * (D * 2) + piece * 16) = x;
+        }
     }
 }
 
