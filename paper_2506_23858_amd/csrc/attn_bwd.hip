@@ -271,11 +271,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
     constexpr int STR = D + 8;
     constexpr int KSTEPS = D / 16, DT = D / 32;
     constexpr int LOADS = KC * D * 2 / 16 / 256;
-    __shared__ __align__(16) __bf16 sK[KC * STR];
-    __shared__ __align__(16) __bf16 sV[KC * STR];
+    __shared__ __align__(1024) char sKV[2 * KC * STR * 2];                     // the K tile, then the V tile
+    __bf16* const sK = reinterpret_cast<__bf16*>(sKV);
+    __bf16* const sV = reinterpret_cast<__bf16*>(sKV + KC * STR * 2);
     // a wavefront's 32 partial rows on their way out: written as the accumulators hold them, read back as whole rows
     constexpr int OPITCH = D * 2 + 16;
-    __shared__ __align__(16) char sOut[4 * 32 * OPITCH];
+    __shared__ __align__(1024) char sOut[4 * 32 * OPITCH];
+    static_assert(4 * 32 * D * 2 <= 2 * KC * STR * 2, "the gathered Q rows of the four wavefronts fit the K/V tiles");
 
     // One workgroup per tile of the flat list (all heads).  Workgroup ids go round the 8 XCDs, so XCD x = id % 8 takes the
     // x-th eighth of the list: a key block's tiles then share one L2 instead of eight (gridDim.x is a multiple of 8).
@@ -299,14 +301,25 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
     const int ent = wave * 32 + l32;
     const int e = min(ent, tc.count - 1);
     const int q = q_idx[seg + tc.list0 + tc.t0 + e];
-    bf16x8_t qf[KSTEPS], dof[KSTEPS];
+    // The wavefront's 32 gathered rows of Q' and of dO go straight to LDS, a whole row per 16 (8) lanes -- one request
+    // covers 4 (8) rows instead of a 32-byte piece of 32 rows -- into the K/V tiles (Q') and the output staging (dO),
+    // both idle at this point; piece p of row r sits at slot p ^ (r % pieces), which keeps the fragment reads below
+    // free of bank conflicts.  Each wavefront reads back only what it wrote.
+    constexpr int RB = D * 2, PPR = RB / 16, RPI = 64 / PPR;     // row bytes, 16-byte pieces per row, rows per request
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t gq0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)sKV + (uint32_t)wave_u * 32 * RB;
+    const uint32_t gd0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)sOut + (uint32_t)wave_u * 32 * OPITCH;
     {
-        const char* sq = Q.ptr + ((long long)b * Q.stride_b + (long long)q * Q.stride_s + (long long)h * Q.stride_h) * 2;
-        const char* sd = dO.ptr + ((long long)b * dO.stride_b + (long long)q * dO.stride_s + (long long)h * dO.stride_h) * 2;
+        const char* qb = Q.ptr + ((long long)b * Q.stride_b + (long long)h * Q.stride_h) * 2;
+        const char* db = dO.ptr + ((long long)b * dO.stride_b + (long long)h * dO.stride_h) * 2;
+        const uint32_t qss = (uint32_t)(Q.stride_s * 2), doss = (uint32_t)(dO.stride_s * 2);     // host-checked: 24-bit
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-            qf[ks] = *reinterpret_cast<const bf16x8_t*>(sq + (ks * 16 + hf * 8) * 2);
-            dof[ks] = *reinterpret_cast<const bf16x8_t*>(sd + (ks * 16 + hf * 8) * 2);
+        for (int k = 0; k < 32 / RPI; ++k) {
+            const int r = k * RPI + lane / PPR;
+            const uint32_t qr = (uint32_t)__shfl(q, r, 64);
+            const uint32_t pc = (uint32_t)(((lane % PPR) ^ (r & (PPR - 1))) * 16);
+            dma16(qb, __umul24(qr, qss) + pc, gq0 + k * 1024);
+            dma16(db, __umul24(qr, doss) + pc, gd0 + k * 1024);
         }
     }
     const float lse2 = LSE[(long long)bh * S + q] * LOG2E;
@@ -366,6 +379,19 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
         return tr_operand<STR>(sKt_lane, mt * 32, u / DT, (u % DT) * 32);
     };
     prefetch(0);
+    bf16x8_t qf[KSTEPS], dof[KSTEPS];
+    VMOBA_WAIT_VMCNT(0);                       // the gathered rows have landed (and the first key chunk with them)
+    asm volatile("" ::: "memory");
+    {
+        const char* gq = sKV + wave_u * 32 * RB + l32 * RB;
+        const char* gd = sOut + wave_u * 32 * OPITCH + l32 * RB;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            const int slot = (2 * ks + hf) ^ (l32 & (PPR - 1));
+            qf[ks] = *reinterpret_cast<const bf16x8_t*>(gq + slot * 16);
+            dof[ks] = *reinterpret_cast<const bf16x8_t*>(gd + slot * 16);
+        }
+    }
     for (int c = 0; c < n_chunks; ++c) {
         __syncthreads();
         stage();
