@@ -584,7 +584,7 @@ __device__ __forceinline__ void dkv_pair_body(
         const int H = 2 * n_chunks;
 
         u32x4_t qreg[LOADS], doreg[LOADS];
-        float lreg = 0.f, dreg = 0.f;
+        float lreg = 0.f;
         uint32_t qn[LOADS], ql = 0;
         bool ql_live = false, rows_live = false;
         auto prefetch_idx_piece = [&](int c, int i) {       // chunks past the list: indices clamp, rows count as dead
@@ -611,11 +611,13 @@ __device__ __forceinline__ void dkv_pair_body(
                 doreg[k] = load_at<u32x4_t>(dobase, __umul24(qn[k], doss) + pc * 16);
             }
         };
-        // LSE and delta of the chunk's 64 rows: every wavefront fetches and stores all 64 (same values,
-        // same places), which keeps these accesses free of branches inside the pipelined loop
+        // LSE and delta of the chunk's 64 rows: even wavefronts fetch and store the 64 LSE values, odd ones the 64
+        // delta values (same values, same places within each kind) -- free of branches inside the pipelined loop,
+        // and half the scattered 4-byte loads of fetching both everywhere
+        const float* ld_src = (wave & 1) ? dl_h : lse_h;
+        const float ld_mul = (wave & 1) ? 1.f : LOG2E, ld_dead = (wave & 1) ? 0.f : INFINITY;
         auto load_ld_regs = [&]() {
-            lreg = load_at<float>(lse_h, ql << 2);
-            dreg = load_at<float>(dl_h, ql << 2);
+            lreg = load_at<float>(ld_src, ql << 2);
             rows_live = ql_live;
         };
         auto stage_piece = [&](int buf, int i) {
@@ -627,9 +629,9 @@ __device__ __forceinline__ void dkv_pair_body(
         };
         // accumulator order: the 16 values a lane half needs per 32-query group are contiguous
         const int ld_pos = (lane & 32) + ((lane & 1) << 4) + (((lane & 31) >> 4) << 3) + (((lane >> 1) & 1) << 2) + ((lane >> 2) & 3);
+        float* const ld_dst = (wave & 1) ? &sDl[0][0] : &sL[0][0];
         auto stage_ld = [&](int buf) {         // rows past the end of the list: LSE = +inf (weight 0), delta = 0
-            sL[buf][ld_pos] = rows_live ? lreg * LOG2E : INFINITY;
-            sDl[buf][ld_pos] = rows_live ? dreg : 0.f;
+            ld_dst[buf * QC + ld_pos] = rows_live ? lreg * ld_mul : ld_dead;
         };
         auto load_all = [&]() {
 #pragma unroll
