@@ -586,6 +586,7 @@ __device__ __forceinline__ void dkv_pair_body(
         u32x4_t qreg[LOADS], doreg[LOADS];
         float lreg = 0.f;
         uint32_t qn[LOADS], ql = 0;
+        const int ld_row = (wave >> 1) * 32 + (lane & 31);      // the chunk row whose LSE or delta this lane moves
         bool ql_live = false, rows_live = false;
         auto prefetch_idx_piece = [&](int c, int i) {       // chunks past the list: indices clamp, rows count as dead
             const int c0 = c * QC;
@@ -593,8 +594,8 @@ __device__ __forceinline__ void dkv_pair_body(
                 const int r = (tid + NT * i) / (D / 8);
                 qn[i] = load_at<uint32_t>(list, (uint32_t)min(c0 + r, cnt - 1) << 2);
             } else {
-                ql = load_at<uint32_t>(list, (uint32_t)min(c0 + lane, cnt - 1) << 2);
-                ql_live = c0 + lane < cnt;
+                ql = load_at<uint32_t>(list, (uint32_t)min(c0 + ld_row, cnt - 1) << 2);
+                ql_live = c0 + ld_row < cnt;
             }
         };
         auto prefetch_idx = [&](int c) {
@@ -611,9 +612,9 @@ __device__ __forceinline__ void dkv_pair_body(
                 doreg[k] = load_at<u32x4_t>(dobase, __umul24(qn[k], doss) + pc * 16);
             }
         };
-        // LSE and delta of the chunk's 64 rows: even wavefronts fetch and store the 64 LSE values, odd ones the 64
-        // delta values (same values, same places within each kind) -- free of branches inside the pipelined loop,
-        // and half the scattered 4-byte loads of fetching both everywhere
+        // LSE and delta of the chunk's 64 rows: even wavefronts fetch and store LSE values, odd ones delta values, the
+        // first pair those of rows 0..31 and the second pair those of rows 32..63 (both halves of a wavefront the same
+        // 32) -- free of branches inside the pipelined loop, and a request touches 32 scattered words, not 2 x 64
         const float* ld_src = (wave & 1) ? dl_h : lse_h;
         const float ld_mul = (wave & 1) ? 1.f : LOG2E, ld_dead = (wave & 1) ? 0.f : INFINITY;
         auto load_ld_regs = [&]() {
@@ -628,7 +629,7 @@ __device__ __forceinline__ void dkv_pair_body(
             else *reinterpret_cast<u32x4_t*>(&sdO[buf][r * STR + pc * 8]) = doreg[k];
         };
         // accumulator order: the 16 values a lane half needs per 32-query group are contiguous
-        const int ld_pos = (lane & 32) + ((lane & 1) << 4) + (((lane & 31) >> 4) << 3) + (((lane >> 1) & 1) << 2) + ((lane >> 2) & 3);
+        const int ld_pos = (ld_row & 32) + ((ld_row & 1) << 4) + (((ld_row & 31) >> 4) << 3) + (((ld_row >> 1) & 1) << 2) + ((ld_row >> 2) & 3);
         float* const ld_dst = (wave & 1) ? &sDl[0][0] : &sL[0][0];
         auto stage_ld = [&](int buf) {         // rows past the end of the list: LSE = +inf (weight 0), delta = 0
             ld_dst[buf * QC + ld_pos] = rows_live ? lreg * ld_mul : ld_dead;
