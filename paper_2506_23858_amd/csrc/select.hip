@@ -985,6 +985,12 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(const unsigned int* __r
                                                          int* __restrict__ pair_pos, int S, int nb, int n_waves,
                                                          long long cap) {
     __shared__ int sBase[4][VMOBA_MAX_BLOCKS];
+    // The query-major entries of a wavefront's 64 rows form one contiguous run of col_idx / pair_pos.  Up to FILL_STAGE
+    // entries they are collected in LDS and written out as whole runs; a lane writing its own row's entries straight to
+    // global memory touches a different cache line in every lane of every store.
+    constexpr int FILL_STAGE = 2048;
+    __shared__ unsigned short sCol[4][FILL_STAGE];
+    __shared__ int sPos[4][FILL_STAGE];
     const int bh = blockIdx.y;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int w = blockIdx.x * 4 + wv;
@@ -1003,6 +1009,14 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(const unsigned int* __r
     long long r = live ? row_ptr[(long long)bh * (S + 1) + q] : 0;
     const long long seg = (long long)bh * cap;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    // the wavefront's run of the query-major lists: [run0, run1)
+    long long run0 = 0, run1 = 0;
+    if (active) {
+        run0 = row_ptr[(long long)bh * (S + 1) + (long long)w * 64];
+        run1 = row_ptr[(long long)bh * (S + 1) + min((long long)w * 64 + 64, (long long)S)];
+    }
+    const bool staged = run1 - run0 <= FILL_STAGE && run1 <= cap;       // wave-uniform
+    int lr = (int)(r - run0);                                            // position inside the run
     for (int j = 0; j < nb; ++j) {
         unsigned int word = 0;
 #pragma unroll
@@ -1012,8 +1026,24 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(const unsigned int* __r
         if (bit) {
             const long long pos = (long long)sBase[wv][j] + __popcll(bal & lt_mask);
             if (pos < cap) q_idx[seg + pos] = q;
-            if (r < cap) { col_idx[seg + r] = j; pair_pos[seg + r] = (int)pos; }
-            ++r;
+            if (staged) {
+                if (lr < FILL_STAGE) {         // always true: row_ptr is the scan of the rows' bit counts
+                    sCol[wv][lr] = (unsigned short)j;
+                    sPos[wv][lr] = (int)pos;
+                }
+                ++lr;
+            } else {
+                if (r < cap) { col_idx[seg + r] = j; pair_pos[seg + r] = (int)pos; }
+                ++r;
+            }
+        }
+    }
+    if (staged) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        const int n = (int)(run1 - run0);
+        for (int i = lane; i < n; i += 64) {
+            col_idx[seg + run0 + i] = sCol[wv][i];
+            pair_pos[seg + run0 + i] = sPos[wv][i];
         }
     }
 }
