@@ -204,11 +204,16 @@ __global__ __launch_bounds__(64) void attn_fwd_tile_simple_kernel(
 //
 // Persistence.  A workgroup strides through its XCD's share of the flat tile list (all heads, see
 // flat_tile_desc_kernel) and overlaps the start of its next tile with the end of the current one:
-// the next descriptor is fetched early in the tile, the next tile's query index during the last
-// soft-max step, and its query rows (into the Q^T registers, the first product is done by then)
-// and K(0..3), V(0..1) during the final step, into slots nobody reads any more (the rings are
-// indexed by running group counters, so the next tile's first V slots differ from the slot of the
-// group the final step reads).
+// the next descriptor and the next tile's query index are fetched at the start of the tile, and its
+// query rows (into the Q^T registers, the first product is done by then) and K(0..3), V(0..1)
+// during the last soft-max step, into slots nobody reads any more (the rings are indexed by
+// running group counters, so the next tile's first V slots differ from the slots of the two groups
+// the last two steps read).
+//
+// Output.  A wavefront writes its 32 partial rows to LDS as the accumulators hold them (8 bytes
+// per lane and channel group) and reads them back as whole rows: the tile's partials are
+// consecutive rows of Opart, so each store request is a 1 KB run instead of 16-byte pieces of 32
+// rows (the address unit needs about as long for one such request as for eight full-row ones).
 template <int D, int NW>
 __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
     TensorView Q, TensorView K, TensorView V, const int* __restrict__ q_idx, const int4* __restrict__ flat_desc,
@@ -391,7 +396,6 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
             constexpr bool QK = decltype(qk_t)::value, PV = decltype(pv_t)::value, SM = decltype(sm_t)::value;
             constexpr bool MASK = decltype(mask_t)::value, NEXTPV = decltype(nextpv_t)::value, STAGE = decltype(stage_t)::value;
             constexpr bool LAST_SM = SM && !QK;       // the first product is complete: Q^T may be replaced
-            constexpr bool FINAL = !SM;               // the tile's final step
             if constexpr (STAGE) { VMOBA_WAIT_VMCNT(NDMA); __syncthreads(); }
             if constexpr (LAST_SM) { VMOBA_WAIT_VMCNT(0); __syncthreads(); }
             uint32_t w[8];                            // P of this step as packed bf16 pairs (accumulator values 2j, 2j + 1)
