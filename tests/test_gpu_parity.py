@@ -282,6 +282,18 @@ def test_bf16_blocks_no_longer_than_one_key_group(block):
     compare_layer(Q, K, V, dO, grid, block, 0, 0.4, torch.bfloat16, f"bf16-one-group-{block}")
 
 
+@pytest.mark.parametrize("tau", [0.5, 0.9])
+def test_bf16_many_blocks_per_row(tau):
+    """64 blocks of 16 tokens; at tau = 0.9 the query-major entries of 64 consecutive rows exceed what the list
+    kernel collects in LDS (it then writes them directly), at 0.5 they fit."""
+    grid, block = (4, 16, 16), (1, 4, 4)
+    S = grid[0] * grid[1] * grid[2]
+    Q, K, V, dO = (synth.to_bf16_grid(synth.iid_normal(310 + i, (1, S, 2, 128))) for i in range(4))
+    g, o = compare_layer(Q, K, V, dO, grid, block, 0, tau, torch.bfloat16, f"many-blocks tau={tau}")
+    per_64_rows = g["row_ptr"][0, :, 64::64] - g["row_ptr"][0, :, :-64:64]
+    assert (per_64_rows.max() > 2048) == (tau > 0.8), per_64_rows.max()
+
+
 def test_bf16_mid_lite():
     """The mid configuration's grid and 3D blocks (9x30x52, blocks 3x10x13 of 390 tokens) with 2 of
     its 12 heads, so the float64 oracle finishes in seconds."""
