@@ -2,9 +2,10 @@
 """Benchmark of the VMoBA hot path on one MI355X.
 
 A step = one attention layer, forward and backward, through the whole path:
-partition(Q,K,V) -> select -> attn_fwd -> inverse partition(O) -> partition(dO) -> attn_bwd ->
-inverse partition(dQ,dK,dV).  Steps cycle through the 1D / 2D / 3D partitions (layer l uses kind
-l mod 3), so a multiple of 3 steps covers the cycle evenly.  Inputs are synthetic (blurred noise
+partition(Q,K,V) -> select -> attn_fwd -> attn_bwd, with O, dO, dQ, dK, dV in the caller's token
+order (the attention calls address them through the partition's row map, so the step has no
+separate inverse-partition or partition(dO) call).  Steps cycle through the 1D / 2D / 3D
+partitions (layer l uses kind l mod 3), so a multiple of 3 steps covers the cycle evenly.  Inputs are synthetic (blurred noise
 on the 480p latent grid 21x30x52, 12 heads x 128, bf16) and resident in HBM before timing.
 
 Prints ONE JSON line.  `value` is effective TFLOP/s of the whole step: 14 * D * (sum over

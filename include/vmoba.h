@@ -17,8 +17,9 @@
  *    nothing on this path waits for the device.  Sizes that depend on the data (k, nnz)
  *    stay on the device.
  *  - Return value: VMOBA_OK or a negative vmoba_status.  Arguments are validated on the
- *    host before anything is launched; a failing call launches nothing.  No C++ exception
- *    crosses this boundary.
+ *    host before anything is launched: a call that fails validation launches nothing.
+ *    (VMOBA_ERR_HIP reports a failed launch or runtime call; kernels enqueued before it stay
+ *    enqueued.)  No C++ exception crosses this boundary.
  *  - "Block order" is the token order produced by the partition (Eq. 1 of the paper):
  *    the tokens of key block 0 first, then block 1, ...  All index arrays (mask, CSR lists)
  *    are in block-order positions.
@@ -154,11 +155,14 @@ int vmoba_partition(const vmoba_grid* g, int inverse, int B, int Hh, int D, int 
  *    col_idx  [B*Hh * nnz_capacity] int32 blocks (ascending) kept by query q
  *    pair_pos [B*Hh * nnz_capacity] int32 for each (q, block) in query-major order, its offset
  *                                         in the block-major list
- *  In mode 0, k <= ceil(tau*S*n_blocks) always holds, so nnz_capacity = min(S*n_blocks,
- *  ceil(tau*S*n_blocks)) suffices; the top-k modes keep exactly min(topk, n_blocks)*S pairs; the local
- *  threshold mode can keep up to S*n_blocks.  If a head would still exceed it, nothing is written out of
- *  bounds, its lists are left incomplete and *dev_status is set to VMOBA_ERR_CAPACITY
- *  (dev_status is a device int32 the caller zeroes and reads after its own synchronisation).
+ *  In mode 0, k <= ceil(tau*S*n_blocks) holds in exact arithmetic (the k - 1 best of a pool of N values that sum to
+ *  S carry at least (k - 1)/N of it), so nnz_capacity = min(S*n_blocks, ceil(tau*S*n_blocks)) plus a few entries for
+ *  the rounding of P suffices; the top-k modes keep exactly min(topk, n_blocks)*S pairs; the local threshold mode
+ *  can keep up to S*n_blocks.  If a head would still exceed it, nothing is written out of bounds, *dev_status is set
+ *  to VMOBA_ERR_CAPACITY (dev_status is a device int32 the caller zeroes and reads after its own synchronisation),
+ *  and that head's blk_ptr is all zero: vmoba_attn_fwd / vmoba_attn_bwd called with these lists treat the head as
+ *  having selected nothing (O = 0, LSE = -inf, zero gradients) and read none of its incomplete list entries.
+ *  mask, k_out, theta_out and row_ptr are complete either way.
  */
 int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
                  const vmoba_tensor* Qp, const vmoba_tensor* Kp, float tau, float score_scale,

@@ -7,6 +7,7 @@ from __future__ import annotations
 import ctypes as C
 import math
 import os
+import struct
 
 import torch
 
@@ -136,9 +137,13 @@ def vmoba_workspace_bytes(op, B, Hh, S, D, n_blocks, nnz_capacity, dtype) -> int
 
 
 def nnz_capacity_for(S: int, n_blocks: int, tau: float) -> int:
-    """Per-head list capacity: the selection never keeps more than ceil(tau * S * N_b) pairs."""
+    """Per-head list capacity (buffer sizing only): in exact arithmetic the selection keeps at most
+    ceil(tau * S * N_b) pairs.  tau is taken as the float32 the library receives, and a margin covers
+    the float32 rounding of P (rows sum to 1 within ~1e-6, so the pool can fall short of S by that
+    fraction and the cut move by as much)."""
     n = S * n_blocks
-    return max(1, min(n, math.ceil(float(tau) * n) + 1))
+    tau32 = struct.unpack("f", struct.pack("f", float(tau)))[0]
+    return max(1, min(n, math.ceil(tau32 * n * (1.0 + 2.0 ** -18)) + 16))
 
 
 def vmoba_profile_events(slot: int, start_event=None, stop_event=None):

@@ -1,4 +1,4 @@
-"""Builds libvmoba.so (HIP, gfx950) and the C parts of the oracle, in-tree."""
+"""Builds libvmoba.so (HIP, gfx950) in-tree, next to this file."""
 from __future__ import annotations
 
 import glob

@@ -90,19 +90,17 @@ __global__ __launch_bounds__(256) void key_run_order_kernel(const int* __restric
     }
 }
 
-__device__ __forceinline__ float load_elem(const char* p, int d, bool bf16) {
-    return bf16 ? bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(p)[d]) : reinterpret_cast<const float*>(p)[d];
-}
+__device__ __forceinline__ float load_elem(const char* p, int d) { return reinterpret_cast<const float*>(p)[d]; }
 
 // ---------------------------------------------------------------------------------------------
-// Plain FMA dQ tile kernel: one wavefront per 64 gathered queries of one key block, lane = query.
-template <bool BF16, int D>
+// Plain FMA dQ tile kernel (float32 tensors): one wavefront per 64 gathered queries of one key block, lane = query.
+template <int D>
 __global__ __launch_bounds__(64) void attn_bwd_dq_simple_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
     const int4* __restrict__ tile_desc, int tiles_per_head, float* __restrict__ dQpart, int Hh, int S, int nb, long long cap, float scale_log2) {
-    constexpr int TM = 64, KC = 32;
-    constexpr int ES = BF16 ? 2 : 4;
+    constexpr int KC = 32;
+    constexpr int ES = 4;
     __shared__ float sK[KC][D];
     __shared__ float sV[KC][D];
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
@@ -118,8 +116,8 @@ __global__ __launch_bounds__(64) void attn_bwd_dq_simple_kernel(
         const char* sd = dO.ptr + ((long long)b * dO.stride_b + (long long)q * dO.stride_s + (long long)h * dO.stride_h) * ES;
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            qr[d] = load_elem(sq, d, BF16);
-            dor[d] = load_elem(sd, d, BF16);
+            qr[d] = load_elem(sq, d);
+            dor[d] = load_elem(sd, d);
             dq[d] = 0.f;
         }
     }
@@ -133,8 +131,8 @@ __global__ __launch_bounds__(64) void attn_bwd_dq_simple_kernel(
         for (int i = lane; i < kc * D; i += 64) {
             const int r = i / D, d = i % D;
             const long long row = tc.k0 + c0 + r;
-            sK[r][d] = load_elem(kbase + row * K.stride_s * ES, d, BF16);
-            sV[r][d] = load_elem(vbase + row * V.stride_s * ES, d, BF16);
+            sK[r][d] = load_elem(kbase + row * K.stride_s * ES, d);
+            sV[r][d] = load_elem(vbase + row * V.stride_s * ES, d);
         }
         __syncthreads();
         for (int r = 0; r < kc; ++r) {
@@ -157,16 +155,16 @@ __global__ __launch_bounds__(64) void attn_bwd_dq_simple_kernel(
     }
 }
 
-// Plain FMA dK/dV kernel: one wavefront per run of 64 keys of one block, lane = key; walks the
-// block's whole query list through LDS.
-template <bool BF16, int D>
+// Plain FMA dK/dV kernel (float32 tensors): one wavefront per run of 64 keys of one block, lane = key;
+// walks the block's whole query list through LDS.
+template <int D>
 __global__ __launch_bounds__(64) void attn_bwd_dkv_simple_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
     const int* __restrict__ kb_start, const int* __restrict__ kb_order, TensorView dK, TensorView dV, const int* __restrict__ rows, int Hh, int S, int nb, long long cap,
     float scale_log2, float scale) {
     constexpr int KPW = 64, QC = 16;
-    constexpr int ES = BF16 ? 2 : 4;
+    constexpr int ES = 4;
     __shared__ float sQ[QC][D];
     __shared__ float sdO[QC][D];
     __shared__ float sL[QC], sDl[QC];
@@ -190,8 +188,8 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_simple_kernel(
         const char* sv = V.ptr + ((long long)b * V.stride_b + (long long)krow * V.stride_s + (long long)h * V.stride_h) * ES;
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            kr[d] = load_elem(sk, d, BF16);
-            vr[d] = load_elem(sv, d, BF16);
+            kr[d] = load_elem(sk, d);
+            vr[d] = load_elem(sv, d);
             dk[d] = 0.f;
             dv[d] = 0.f;
         }
@@ -204,8 +202,8 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_simple_kernel(
         for (int i = lane; i < qc * D; i += 64) {
             const int r = i / D, d = i % D;
             const long long q = q_idx[seg + list0 + c0 + r];
-            sQ[r][d] = load_elem(qbase + q * Q.stride_s * ES, d, BF16);
-            sdO[r][d] = load_elem(dobase + q * dO.stride_s * ES, d, BF16);
+            sQ[r][d] = load_elem(qbase + q * Q.stride_s * ES, d);
+            sdO[r][d] = load_elem(dobase + q * dO.stride_s * ES, d);
         }
         if (lane < qc) {
             const long long q = q_idx[seg + list0 + c0 + lane];
@@ -234,16 +232,9 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_simple_kernel(
         char* pk = dK.ptr + ((long long)b * dK.stride_b + (long long)kout * dK.stride_s + (long long)h * dK.stride_h) * ES;
         char* pv = dV.ptr + ((long long)b * dV.stride_b + (long long)kout * dV.stride_s + (long long)h * dV.stride_h) * ES;
 #pragma unroll
-        for (int d = 0; d < D; d += 2) {
-            if (BF16) {
-                reinterpret_cast<uint32_t*>(pk)[d / 2] = pack_bf16x2(dk[d] * scale, dk[d + 1] * scale);
-                reinterpret_cast<uint32_t*>(pv)[d / 2] = pack_bf16x2(dv[d], dv[d + 1]);
-            } else {
-                reinterpret_cast<float*>(pk)[d] = dk[d] * scale;
-                reinterpret_cast<float*>(pk)[d + 1] = dk[d + 1] * scale;
-                reinterpret_cast<float*>(pv)[d] = dv[d];
-                reinterpret_cast<float*>(pv)[d + 1] = dv[d + 1];
-            }
+        for (int d = 0; d < D; ++d) {
+            reinterpret_cast<float*>(pk)[d] = dk[d] * scale;
+            reinterpret_cast<float*>(pv)[d] = dv[d];
         }
     }
 }
@@ -1072,19 +1063,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
         dkv_tail_body<D>(smem, bh, id - runs, Q, K, V, dO, LSE, delta, blk_off, blk_ptr, q_idx, kb_order, dK, dV, rows, Hh, S, nb, cap, scale_log2, scale);
 }
 
-// dQ[q] = scale * sum over the query's pairs of dQpart[pair] (bfloat16 partials when PBF16).
-template <bool BF16, bool PBF16, int D>
+// dQ[q] = scale * sum over the query's pairs of dQpart[pair]; the partials have the tensors' type.  A head whose
+// selection did not fit the lists (row_ptr[S] > cap, see vmoba_select) counts as having selected nothing.
+template <bool BF16, int D>
 __global__ __launch_bounds__(256) void dq_merge_kernel(const float* __restrict__ dQpart, const int* __restrict__ row_ptr,
                                                        const int* __restrict__ pair_pos, TensorView dQ, const int* __restrict__ rows, int Hh, int S,
                                                        long long cap, float scale) {
-    constexpr int CH = PBF16 ? 8 : 4;
+    constexpr int CH = BF16 ? 8 : 4;
     constexpr int LPQ = D / CH;
     constexpr int QPW = 256 / LPQ;
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
     const int q = blockIdx.x * QPW + threadIdx.x / LPQ;
     const int part = threadIdx.x % LPQ;
     if (q >= S) return;
-    const int r0 = row_ptr[(long long)bh * (S + 1) + q], r1 = row_ptr[(long long)bh * (S + 1) + q + 1];
+    const bool fits = row_ptr[(long long)bh * (S + 1) + S] <= cap;
+    const int r0 = row_ptr[(long long)bh * (S + 1) + q];
+    const int r1 = fits ? row_ptr[(long long)bh * (S + 1) + q + 1] : r0;
     const long long seg = (long long)bh * cap;
     float acc[CH];
 #pragma unroll
@@ -1096,12 +1090,12 @@ __global__ __launch_bounds__(256) void dq_merge_kernel(const float* __restrict__
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const float keep = (r + u < r1) ? 1.f : 0.f;
-            if constexpr (PBF16) {
+            if constexpr (BF16) {
                 const u32x4_t v = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const uint16_t*>(dQpart) + pair[u] * D + part * 8);
                 acc[0] += keep * bf16lo_to_f32(v.x); acc[1] += keep * bf16hi_to_f32(v.x);
                 acc[2] += keep * bf16lo_to_f32(v.y); acc[3] += keep * bf16hi_to_f32(v.y);
-                acc[4 % CH] += keep * bf16lo_to_f32(v.z); acc[5 % CH] += keep * bf16hi_to_f32(v.z);
-                acc[6 % CH] += keep * bf16lo_to_f32(v.w); acc[7 % CH] += keep * bf16hi_to_f32(v.w);
+                acc[4] += keep * bf16lo_to_f32(v.z); acc[5] += keep * bf16hi_to_f32(v.z);
+                acc[6] += keep * bf16lo_to_f32(v.w); acc[7] += keep * bf16hi_to_f32(v.w);
             } else {
                 const f32x4_t v = *reinterpret_cast<const f32x4_t*>(dQpart + pair[u] * D + part * 4);
                 acc[0] += keep * v.x; acc[1] += keep * v.y; acc[2] += keep * v.z; acc[3] += keep * v.w;
@@ -1113,16 +1107,9 @@ __global__ __launch_bounds__(256) void dq_merge_kernel(const float* __restrict__
     const int qo = rows ? rows[q] : q;
     char* dst = dQ.ptr + ((long long)b * dQ.stride_b + (long long)qo * dQ.stride_s + (long long)h * dQ.stride_h) * (BF16 ? 2 : 4);
     if constexpr (BF16) {
-        uint32_t w[CH / 2];
-#pragma unroll
-        for (int c = 0; c < CH / 2; ++c) w[c] = pack_bf16x2(acc[2 * c], acc[2 * c + 1]);
-        if constexpr (CH == 8) {
-            u32x4_t o = {w[0], w[1], w[2], w[3]};
-            *reinterpret_cast<u32x4_t*>(dst + part * 16) = o;
-        } else {
-            u32x2_t o = {w[0], w[1]};
-            *reinterpret_cast<u32x2_t*>(dst + part * 8) = o;
-        }
+        const u32x4_t o = {pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]), pack_bf16x2(acc[4], acc[5]),
+                           pack_bf16x2(acc[6], acc[7])};
+        *reinterpret_cast<u32x4_t*>(dst + part * 16) = o;
     } else {
 #pragma unroll
         for (int c = 0; c < CH; c += 4) {
@@ -1196,7 +1183,7 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     const TensorView dQv = make_view(dQ), dKv = make_view(dK), dVv = make_view(dV);
     TensorView dOv = make_view(dO);
     const float scale_log2 = softmax_scale * LOG2E;
-    const bool simple = !bf16 || getenv("VMOBA_FORCE_SIMPLE") != nullptr;
+    const bool simple = !bf16;              // float32 tensors take the plain FMA kernels
     // the tile kernels form the byte offset of a row of Q', K', V' or dO with one 24-bit multiply and 32-bit adds
     if (!simple) {
         const int64_t do_stride = rows ? D : dO->stride_s;          // dO is read from its block-order copy when `rows` is given
@@ -1242,10 +1229,8 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         if (simple) {
             dim3 grid((unsigned)max_tiles, (unsigned)BH);
 #define DQ_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.tile_desc, (int)max_tiles, ws.dQpart, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2
-            if (bf16 && D == 128) attn_bwd_dq_simple_kernel<true, 128><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
-            else if (bf16) attn_bwd_dq_simple_kernel<true, 64><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
-            else if (D == 128) attn_bwd_dq_simple_kernel<false, 128><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
-            else attn_bwd_dq_simple_kernel<false, 64><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
+            if (D == 128) attn_bwd_dq_simple_kernel<128><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
+            else attn_bwd_dq_simple_kernel<64><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
 #undef DQ_ARGS
         } else {
             // one workgroup per entry of the flat tile list; the bound on the list length is a multiple of 8
@@ -1257,16 +1242,13 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         }
         VMOBA_PROFILE_END(1, st);
         VMOBA_CHECK_LAUNCH();
-        const bool pbf16 = !simple;           // the MFMA tile kernel writes bfloat16 partials
-        const int qpw = 256 / (D / (pbf16 ? 8 : 4));
+        const int qpw = 256 / (D / (bf16 ? 8 : 4));     // partials: bfloat16 from the MFMA tile kernel, float32 otherwise
         dim3 mgrid((unsigned)ceil_div64(S, qpw), (unsigned)BH);
 #define MG_ARGS ws.dQpart, row_ptr, pair_pos, dQv, rows, Hh, (int)S, (long long)nnz_capacity, softmax_scale
-        if (pbf16 && D == 128) dq_merge_kernel<true, true, 128><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
-        else if (pbf16) dq_merge_kernel<true, true, 64><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
-        else if (bf16 && D == 128) dq_merge_kernel<true, false, 128><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
-        else if (bf16) dq_merge_kernel<true, false, 64><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
-        else if (D == 128) dq_merge_kernel<false, false, 128><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
-        else dq_merge_kernel<false, false, 64><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
+        if (bf16 && D == 128) dq_merge_kernel<true, 128><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
+        else if (bf16) dq_merge_kernel<true, 64><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
+        else if (D == 128) dq_merge_kernel<false, 128><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
+        else dq_merge_kernel<false, 64><<<mgrid, dim3(256), 0, st>>>(MG_ARGS);
 #undef MG_ARGS
         VMOBA_CHECK_LAUNCH();
     }
@@ -1280,10 +1262,8 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         VMOBA_PROFILE_BEGIN(2, st);
 #define DKV_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.kb_start, ws.kb_order, dKv, dVv, rows, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
         if (simple) {
-            if (bf16 && D == 128) attn_bwd_dkv_simple_kernel<true, 128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
-            else if (bf16) attn_bwd_dkv_simple_kernel<true, 64><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
-            else if (D == 128) attn_bwd_dkv_simple_kernel<false, 128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
-            else attn_bwd_dkv_simple_kernel<false, 64><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
+            if (D == 128) attn_bwd_dkv_simple_kernel<128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
+            else attn_bwd_dkv_simple_kernel<64><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
         } else {
             const dim3 hgrid(grid.y, grid.x);       // heads on x (see the kernel)
             if (D == 128) attn_bwd_dkv_kernel<128><<<hgrid, dim3(256), 0, st>>>(DKV_ARGS);

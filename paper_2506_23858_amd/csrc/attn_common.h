@@ -10,7 +10,9 @@
 // MFMA operand plumbing (v_mfma_f32_32x32x16_bf16; lane = 32*hf + l32):
 //   A operand: lane holds row l32, 8 consecutive k at 8*hf;   B operand: column l32, same k.
 //   C/D:       lane holds column l32, rows 8*i + 4*hf + r as value 4*i + r (i, r = 0..3).
-// LDS tiles are row-major [row][D] with a row stride of D + 8 bf16 (16 bytes of padding).
+// LDS tiles are row-major [row][D].  The backward kernels pad every row by 8 bf16 (row stride D + 8, 16 bytes); the
+// forward kernel's K/V rings are unpadded and swizzled instead (16-byte piece p of row r sits at piece p ^ f(r), see
+// attn_fwd.hip), because its rows arrive by direct global-to-LDS loads that fill 1024 consecutive bytes.
 //   * An operand that contracts over the channels of a row is a 16-byte row read.
 //   * An operand that contracts over the ROWS (the transposed tile) is two ds_read_b64_tr_b16:
 //     in each group of 16 lanes, lane 4*e + a supplies the address of 4 consecutive channels of
@@ -20,7 +22,7 @@
 //     accumulator values a lane holds per 16-row step belong to rows {16*s + 4*e + 2*t + hf},
 //     e = 0..3, t = 0..1: they pack straight into the next MFMA's B operand (no shuffle), the
 //     matching transposed A operand is exactly what the two transpose reads (t = 0, 1) deliver,
-//     and both kinds of LDS access are bank-conflict free with the one padded layout.
+//     and both kinds of LDS access are bank-conflict free with either layout.
 #pragma once
 #include "common.h"
 

@@ -92,16 +92,15 @@ constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
 // ---------------------------------------------------------------------------------------------
-// Plain FMA tile kernel (float32 or bfloat16 inputs, float32 arithmetic).  One wavefront per
-// tile of 64 gathered queries, lane = query.  Keys and values of the block pass through LDS in
-// chunks of KC rows.
-template <bool BF16, int D>
+// Plain FMA tile kernel for float32 inputs.  One wavefront per tile of 64 gathered queries,
+// lane = query.  Keys and values of the block pass through LDS in chunks of KC rows.
+template <int D>
 __global__ __launch_bounds__(64) void attn_fwd_tile_simple_kernel(
     TensorView Q, TensorView K, TensorView V, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr,
     const int* __restrict__ q_idx, const int4* __restrict__ tile_desc, int tiles_per_head, float* __restrict__ Opart,
     float* __restrict__ lse_part, int Hh, int nb, long long cap, float scale_log2) {
-    constexpr int TM = 64, KC = 32;
-    constexpr int ES = BF16 ? 2 : 4;
+    constexpr int KC = 32;
+    constexpr int ES = 4;
     __shared__ float sK[KC][D];
     __shared__ float sV[KC][D];
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
@@ -116,8 +115,7 @@ __global__ __launch_bounds__(64) void attn_fwd_tile_simple_kernel(
         const char* src = Q.ptr + ((long long)b * Q.stride_b + (long long)q * Q.stride_s + (long long)h * Q.stride_h) * ES;
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            qr[d] = BF16 ? bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(src)[d])
-                         : reinterpret_cast<const float*>(src)[d];
+            qr[d] = reinterpret_cast<const float*>(src)[d];
             o[d] = 0.f;
         }
     }
@@ -132,8 +130,8 @@ __global__ __launch_bounds__(64) void attn_fwd_tile_simple_kernel(
             const long long row = tc.k0 + c0 + r;
             const char* ks = kbase + row * K.stride_s * ES;
             const char* vs = vbase + row * V.stride_s * ES;
-            sK[r][d] = BF16 ? bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(ks)[d]) : reinterpret_cast<const float*>(ks)[d];
-            sV[r][d] = BF16 ? bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(vs)[d]) : reinterpret_cast<const float*>(vs)[d];
+            sK[r][d] = reinterpret_cast<const float*>(ks)[d];
+            sV[r][d] = reinterpret_cast<const float*>(vs)[d];
         }
         __syncthreads();
         for (int r = 0; r < kc; ++r) {
@@ -534,20 +532,23 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
 // ---------------------------------------------------------------------------------------------
 // Merge: O[q] = sum_pairs exp(lse_pair - LSE[q]) * Opart[pair], LSE[q] = logsumexp(lse_pair).
 // A group of lanes per query, each owning CH consecutive channels (one 16-byte load per partial).
-// Partials are bfloat16 when the MFMA tile kernels wrote them (PBF16), float32 otherwise.
-template <bool BF16, bool PBF16, int D>
+// Partials have the tensors' type: bfloat16 from the MFMA tile kernel, float32 from the FMA one.
+// A head whose selection did not fit the lists (row_ptr[S] > cap, see vmoba_select) counts as having selected nothing.
+template <bool BF16, int D>
 __global__ __launch_bounds__(256) void attn_fwd_merge_kernel(const float* __restrict__ Opart, const float* __restrict__ lse_part,
                                                              const int* __restrict__ row_ptr, const int* __restrict__ pair_pos,
                                                              TensorView O, float* __restrict__ LSE,
                                                              const int* __restrict__ out_rows, int Hh, int S, long long cap) {
-    constexpr int CH = PBF16 ? 8 : 4;
+    constexpr int CH = BF16 ? 8 : 4;
     constexpr int LPQ = D / CH;              // lanes per query
     constexpr int QPW = 256 / LPQ;           // queries per workgroup
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
     const int q = blockIdx.x * QPW + threadIdx.x / LPQ;
     const int part = threadIdx.x % LPQ;
     if (q >= S) return;
-    const int r0 = row_ptr[(long long)bh * (S + 1) + q], r1 = row_ptr[(long long)bh * (S + 1) + q + 1];
+    const bool fits = row_ptr[(long long)bh * (S + 1) + S] <= cap;
+    const int r0 = row_ptr[(long long)bh * (S + 1) + q];
+    const int r1 = fits ? row_ptr[(long long)bh * (S + 1) + q + 1] : r0;
     const long long seg = (long long)bh * cap;
     // one pass with a running maximum; four partials in flight per step (index -> lse and row loads)
     float mx = -INFINITY;
@@ -565,11 +566,10 @@ __global__ __launch_bounds__(256) void attn_fwd_merge_kernel(const float* __rest
         float v[4][CH];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            if constexpr (PBF16) {
+            if constexpr (BF16) {
                 const u32x4_t x = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const uint16_t*>(Opart) + pair[u] * D + part * 8);
                 v[u][0] = bf16lo_to_f32(x.x); v[u][1] = bf16hi_to_f32(x.x); v[u][2] = bf16lo_to_f32(x.y); v[u][3] = bf16hi_to_f32(x.y);
-                v[u][4 % CH] = bf16lo_to_f32(x.z); v[u][5 % CH] = bf16hi_to_f32(x.z);
-                v[u][6 % CH] = bf16lo_to_f32(x.w); v[u][7 % CH] = bf16hi_to_f32(x.w);
+                v[u][4] = bf16lo_to_f32(x.z); v[u][5] = bf16hi_to_f32(x.z); v[u][6] = bf16lo_to_f32(x.w); v[u][7] = bf16hi_to_f32(x.w);
             } else {
                 const f32x4_t x = *reinterpret_cast<const f32x4_t*>(Opart + pair[u] * D + part * 4);
                 v[u][0] = x.x; v[u][1] = x.y; v[u][2] = x.z; v[u][3] = x.w;
@@ -599,16 +599,9 @@ __global__ __launch_bounds__(256) void attn_fwd_merge_kernel(const float* __rest
     const int qo = out_rows ? out_rows[q] : q;       // row of O that block-order row q is written to
     char* dst = O.ptr + ((long long)b * O.stride_b + (long long)qo * O.stride_s + (long long)h * O.stride_h) * (BF16 ? 2 : 4);
     if constexpr (BF16) {
-        uint32_t w[CH / 2];
-#pragma unroll
-        for (int c = 0; c < CH / 2; ++c) w[c] = pack_bf16x2(acc[2 * c], acc[2 * c + 1]);
-        if constexpr (CH == 8) {
-            u32x4_t o = {w[0], w[1], w[2], w[3]};
-            *reinterpret_cast<u32x4_t*>(dst + part * 16) = o;
-        } else {
-            u32x2_t o = {w[0], w[1]};
-            *reinterpret_cast<u32x2_t*>(dst + part * 8) = o;
-        }
+        const u32x4_t o = {pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]), pack_bf16x2(acc[4], acc[5]),
+                           pack_bf16x2(acc[6], acc[7])};
+        *reinterpret_cast<u32x4_t*>(dst + part * 16) = o;
     } else {
 #pragma unroll
         for (int c = 0; c < CH; c += 4) {
@@ -691,7 +684,7 @@ extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     const bool bf16 = dt == VMOBA_BF16;
     const TensorView Qv = make_view(Qp), Kv = make_view(Kp), Vv = make_view(Vp), Ov = make_view(O);
     const float scale_log2 = softmax_scale * LOG2E;
-    const bool simple = !bf16 || getenv("VMOBA_FORCE_SIMPLE") != nullptr;
+    const bool simple = !bf16;              // float32 tensors take the plain FMA kernels
     // the MFMA kernel addresses the rows of one (batch, head) slice of K and V with 32-bit byte offsets
     if (!simple && (Kp->stride_s <= 0 || Vp->stride_s <= 0 ||
                     (uint64_t)(S + 256) * (uint64_t)Kp->stride_s * 2 >= ((uint64_t)1 << 32) ||
@@ -718,10 +711,8 @@ extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     if (simple) {
         dim3 grid((unsigned)max_tiles, (unsigned)BH);
 #define TILE_ARGS Qv, Kv, Vv, blk_off, blk_ptr, q_idx, ws.tile_desc, (int)max_tiles, ws.Opart, ws.lse_part, Hh, n_blocks, (long long)nnz_capacity, scale_log2
-        if (bf16 && D == 128) attn_fwd_tile_simple_kernel<true, 128><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
-        else if (bf16) attn_fwd_tile_simple_kernel<true, 64><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
-        else if (D == 128) attn_fwd_tile_simple_kernel<false, 128><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
-        else attn_fwd_tile_simple_kernel<false, 64><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
+        if (D == 128) attn_fwd_tile_simple_kernel<128><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
+        else attn_fwd_tile_simple_kernel<64><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
 #undef TILE_ARGS
     } else {
         const dim3 pgrid((unsigned)std::min<int64_t>((wide ? 1 : 2) * (int64_t)vmoba_num_cus(), (int64_t)BH * max_tiles));
@@ -732,16 +723,13 @@ extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     }
     VMOBA_PROFILE_END(0, st);
     VMOBA_CHECK_LAUNCH();
-    const bool pbf16 = !simple;               // the MFMA tile kernels write bfloat16 partials
-    const int qpw = 256 / (D / (pbf16 ? 8 : 4));
+    const int qpw = 256 / (D / (bf16 ? 8 : 4));     // partials: bfloat16 from the MFMA tile kernel, float32 otherwise
     dim3 mgrid((unsigned)ceil_div64(S, qpw), (unsigned)BH);
 #define MERGE_ARGS ws.Opart, ws.lse_part, row_ptr, pair_pos, Ov, LSE, out_rows, Hh, (int)S, (long long)nnz_capacity
-    if (pbf16 && D == 128) attn_fwd_merge_kernel<true, true, 128><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
-    else if (pbf16) attn_fwd_merge_kernel<true, true, 64><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
-    else if (bf16 && D == 128) attn_fwd_merge_kernel<true, false, 128><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
-    else if (bf16) attn_fwd_merge_kernel<true, false, 64><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
-    else if (D == 128) attn_fwd_merge_kernel<false, false, 128><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
-    else attn_fwd_merge_kernel<false, false, 64><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
+    if (bf16 && D == 128) attn_fwd_merge_kernel<true, 128><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
+    else if (bf16) attn_fwd_merge_kernel<true, 64><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
+    else if (D == 128) attn_fwd_merge_kernel<false, 128><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
+    else attn_fwd_merge_kernel<false, 64><<<mgrid, dim3(256), 0, st>>>(MERGE_ARGS);
 #undef MERGE_ARGS
     VMOBA_CHECK_LAUNCH();
     return VMOBA_OK;

@@ -109,11 +109,6 @@ __global__ __launch_bounds__(256) void block_mean_kernel(TensorView K, const int
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// Scores (Eq. 3), row soft-max, P write-out and the first radix level, fused.
-// A workgroup owns a tile of QT = 64 queries of one head.  The head's block means sit in LDS
-// as float32; thread (q = tid % 64, g = tid / 64) keeps its query row in registers and
-// computes the dot products with blocks g, g+4, g+8, ...
 // floor(p * 2^fix_shift) for a finite p >= 0 below 2^(63 - fix_shift), by integer shifts of the float's mantissa
 // (exact, like the product in double precision it replaces, and a fraction of its instructions)
 __device__ __forceinline__ unsigned long long to_fixed(float p, int fix_shift) {
@@ -124,7 +119,12 @@ __device__ __forceinline__ unsigned long long to_fixed(float p, int fix_shift) {
     return sh >= 0 ? ((unsigned long long)m << sh) : (sh > -32 ? (unsigned long long)(m >> -sh) : 0ull);
 }
 
-template <bool BF16, int D>
+// ---------------------------------------------------------------------------------------------
+// Scores (Eq. 3), row soft-max, P write-out and the first radix level, fused, for float32 queries
+// (bfloat16 queries take score_mfma_kernel below).  A workgroup owns a tile of QT = 64 queries of
+// one head.  The head's block means sit in LDS as float32; thread (q = tid % 64, g = tid / 64)
+// keeps its query row in registers and computes the dot products with blocks g, g+4, g+8, ...
+template <int D>
 __global__ __launch_bounds__(256) void score_kernel(TensorView Q, const float* __restrict__ Bmean,
                                                     float* __restrict__ P, unsigned int* __restrict__ hist_cnt,
                                                     unsigned long long* __restrict__ hist_sum,
@@ -152,26 +152,14 @@ __global__ __launch_bounds__(256) void score_kernel(TensorView Q, const float* _
         const int q0 = tile * QT;
         const int ql = lane;
         const int q = min(q0 + ql, S - 1);          // tail rows recompute the last query; never stored
-        // query row -> registers (float32)
+        // query row -> registers
         float qr[D];
         {
-            const char* src = Q.ptr + ((long long)b * Q.stride_b + (long long)q * Q.stride_s +
-                                       (long long)h * Q.stride_h) * (BF16 ? 2 : 4);
-            if (BF16) {
+            const char* src = Q.ptr + ((long long)b * Q.stride_b + (long long)q * Q.stride_s + (long long)h * Q.stride_h) * 4;
 #pragma unroll
-                for (int i = 0; i < D / 8; ++i) {
-                    u32x4_t v = reinterpret_cast<const u32x4_t*>(src)[i];
-                    qr[8 * i + 0] = bf16lo_to_f32(v.x); qr[8 * i + 1] = bf16hi_to_f32(v.x);
-                    qr[8 * i + 2] = bf16lo_to_f32(v.y); qr[8 * i + 3] = bf16hi_to_f32(v.y);
-                    qr[8 * i + 4] = bf16lo_to_f32(v.z); qr[8 * i + 5] = bf16hi_to_f32(v.z);
-                    qr[8 * i + 6] = bf16lo_to_f32(v.w); qr[8 * i + 7] = bf16hi_to_f32(v.w);
-                }
-            } else {
-#pragma unroll
-                for (int i = 0; i < D / 4; ++i) {
-                    f32x4_t v = reinterpret_cast<const f32x4_t*>(src)[i];
-                    qr[4 * i + 0] = v.x; qr[4 * i + 1] = v.y; qr[4 * i + 2] = v.z; qr[4 * i + 3] = v.w;
-                }
+            for (int i = 0; i < D / 4; ++i) {
+                f32x4_t v = reinterpret_cast<const f32x4_t*>(src)[i];
+                qr[4 * i + 0] = v.x; qr[4 * i + 1] = v.y; qr[4 * i + 2] = v.z; qr[4 * i + 3] = v.w;
             }
         }
         for (int j = wave; j < nb; j += 4) {
@@ -964,17 +952,23 @@ __global__ __launch_bounds__(256) void wave_scan_kernel(int* __restrict__ wcnt, 
 }
 
 // blk_ptr = exclusive scan of blk_cnt over blocks; capacity check.  One wavefront-sized loop per head.
+// A head that kept more than `cap` pairs gets an all-zero blk_ptr -- to the attention calls it selected nothing, so no
+// list entry of it is ever read (the merge kernels recognise the same head by row_ptr[S] > cap) -- and the status word
+// is set.
 __global__ __launch_bounds__(64) void blk_ptr_kernel(const int* __restrict__ blk_cnt, int* __restrict__ blk_ptr,
                                                      int nb, long long cap, int* __restrict__ dev_status) {
     const int bh = blockIdx.x;
     if (threadIdx.x != 0) return;
+    long long total = 0;
+    for (int j = 0; j < nb; ++j) total += blk_cnt[(long long)bh * nb + j];
+    const bool fits = total <= cap;
     long long run = 0;
     for (int j = 0; j < nb; ++j) {
-        blk_ptr[(long long)bh * (nb + 1) + j] = (int)min(run, cap);
+        blk_ptr[(long long)bh * (nb + 1) + j] = fits ? (int)run : 0;
         run += blk_cnt[(long long)bh * nb + j];
     }
-    blk_ptr[(long long)bh * (nb + 1) + nb] = (int)min(run, cap);
-    if (run > cap) atomicExch(dev_status, (int)VMOBA_ERR_CAPACITY);
+    blk_ptr[(long long)bh * (nb + 1) + nb] = fits ? (int)run : 0;
+    if (!fits) atomicExch(dev_status, (int)VMOBA_ERR_CAPACITY);
 }
 
 // Fill q_idx (block-major), col_idx and pair_pos (query-major).  One wavefront per 64 queries,
@@ -1088,14 +1082,19 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
     if (Qp->dtype != Kp->dtype) return VMOBA_ERR_UNSUPPORTED;
     if (n_blocks > VMOBA_MAX_BLOCKS || S > ((int64_t)1 << 30) || S * n_blocks > (int64_t)INT32_MAX)
         return VMOBA_ERR_UNSUPPORTED;
-    const size_t lds = score_lds_bytes(n_blocks, D);
+    const bool bf16 = Qp->dtype == VMOBA_BF16;
+    // LDS of the score kernel this call launches: bfloat16 queries go to the matrix-core kernel (block means as three
+    // bfloat16 terms up to 128 blocks, as float32 beyond), float32 queries to the plain FMA kernel
+    const int nb_pad = (n_blocks + 31) & ~31;
+    const bool fly = n_blocks > 128;
+    const size_t lds_mfma = (fly ? (size_t)nb_pad * (D + 4) * 4 : (size_t)3 * nb_pad * (D + 8) * 2) + HIST_BINS * 12;
+    const size_t lds = bf16 ? lds_mfma : score_lds_bytes(n_blocks, D);
     if (lds > 160 * 1024) return VMOBA_ERR_UNSUPPORTED;
     const int BH = B * Hh;
     SelectWs ws = carve(workspace, BH, S, n_blocks);
     if (workspace_bytes < ws.total) return VMOBA_ERR_WORKSPACE;
     if (((uintptr_t)workspace) & 255) return VMOBA_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
-    const bool bf16 = Qp->dtype == VMOBA_BF16;
     const int n_waves = (int)ceil_div64(S, 64);
     const long long pool = (long long)S * n_blocks;
     // the pool sums to S (row soft-max) or to 1 (pool soft-max); the fixed-point scale leaves headroom for either
@@ -1129,28 +1128,22 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
     const int n_tiles = (int)ceil_div64(S, QT);
     const int tiles_per_wg = 4;
     dim3 sgrid((unsigned)ceil_div64(n_tiles, tiles_per_wg), (unsigned)BH);
-#define LAUNCH_SCORE(BF, DD)                                                                              \
+#define LAUNCH_SCORE(DD)                                                                                  \
     do {                                                                                                  \
-        auto kfn = score_kernel<BF, DD>;                                                                  \
+        auto kfn = score_kernel<DD>;                                                                      \
         if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
             return VMOBA_ERR_HIP;                                                                         \
         kfn<<<sgrid, dim3(256), lds, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks,  \
                                            score_scale, fix_shift, row_stat);                             \
     } while (0)
-    // bfloat16 queries: scores on the matrix cores; block means in LDS as three bfloat16 terms up to 128 blocks, as
-    // float32 (split after the fetch) beyond
-    const int nb_pad = (n_blocks + 31) & ~31;
-    const bool fly = n_blocks > 128;
-    const size_t lds_mfma = (fly ? (size_t)nb_pad * (D + 4) * 4 : (size_t)3 * nb_pad * (D + 8) * 2) + HIST_BINS * 12;
-    const bool score_mfma = bf16 && n_blocks <= 256 && lds_mfma <= 160 * 1024 && getenv("VMOBA_SCORE_FMA") == nullptr;
-    if (score_mfma) {
+    if (bf16) {
         dim3 mgrid((unsigned)ceil_div64(ceil_div64(S, SCORE_QT), 2), (unsigned)BH);
 #define LAUNCH_SCORE_MFMA(DD, FL)                                                                         \
     do {                                                                                                  \
         auto kfn = score_mfma_kernel<DD, FL>;                                                             \
-        if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_mfma) != hipSuccess) \
+        if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
             return VMOBA_ERR_HIP;                                                                         \
-        kfn<<<mgrid, dim3(SCORE_NT), lds_mfma, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks, score_scale, \
+        kfn<<<mgrid, dim3(SCORE_NT), lds, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks, score_scale, \
                                                 fix_shift, row_stat);                                     \
     } while (0)
         if (D == 128 && fly) LAUNCH_SCORE_MFMA(128, true);
@@ -1158,10 +1151,8 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
         else if (fly) LAUNCH_SCORE_MFMA(64, true);
         else LAUNCH_SCORE_MFMA(64, false);
 #undef LAUNCH_SCORE_MFMA
-    } else if (bf16 && D == 128) LAUNCH_SCORE(true, 128);
-    else if (bf16 && D == 64) LAUNCH_SCORE(true, 64);
-    else if (D == 128) LAUNCH_SCORE(false, 128);
-    else LAUNCH_SCORE(false, 64);
+    } else if (D == 128) LAUNCH_SCORE(128);
+    else LAUNCH_SCORE(64);
 #undef LAUNCH_SCORE
     VMOBA_CHECK_LAUNCH();
     if (pool_softmax) {

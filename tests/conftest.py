@@ -23,3 +23,12 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+def pytest_sessionfinish(session, exitstatus):
+    """The GPU parity tests record every measured error; leave the table behind."""
+    mod = sys.modules.get("tests.gpu_util")
+    if mod is not None:
+        path = mod.write_records()
+        if path:
+            print(f"\n[parity] {len(mod.RECORDS)} measured errors written to {path}")
