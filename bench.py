@@ -31,7 +31,7 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak (published)
 HBM_PEAK_GBS = 8000.0              # MI355X HBM3E peak (published)
 # HBM bytes per launch of the MFMA kernels at the 480p workload (mean over the 1d/2d/3d partitions, tau = 0.25),
 # from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/layer_480p_tau025_hbm_traffic_pmc.md
-# (FETCH_SIZE scaled by 2.000, WRITE_SIZE by 1.000: the factors a plain copy kernel of known size gives).
+# (FETCH_SIZE scaled by 1.992, WRITE_SIZE by 1.000: the factors kernels of known traffic give in the same runs).
 MEASURED_TRAFFIC_BYTES_480P = {"attn_fwd_tile": 1.963e9, "attn_bwd_dq_tile": 2.921e9, "attn_bwd_dkv": 5.142e9}
 METRIC = "VMoBA attn fwd+bwd ms/layer + effective TFLOP/s (%MFMA peak), 480p shape"
 
@@ -181,6 +181,7 @@ def main():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense comparators")
     ap.add_argument("--kinds", default="1d,2d,3d")
     ap.add_argument("--no-extras", action="store_true", help="skip the copy-rate probe and the tau = 0.5 run (profiling runs)")
+    ap.add_argument("--input-sets", type=int, default=3, help="copies of the inputs the steps rotate over")
     ap.add_argument("--sweep", action="store_true", help="sequence-length sweep instead of the benchmark line")
     ap.add_argument("--sweep-frames", default="9,15,21,36,48,72")
     args = ap.parse_args()
@@ -209,6 +210,11 @@ def main():
     t_gen = time.perf_counter() - t_gen
     Q, K, V, dO = (torch.from_numpy(x).to(dev).to(dtype).contiguous() for x in (Qn, Kn, Vn, dOn))
     S = Q.shape[1]
+    # Rotating input sets: the same values at N_SETS different addresses, one set per step in turn, so that no step
+    # finds its inputs in the 256 MB last-level cache from the step before (4 tensors of ~100 MB per set at 480p;
+    # identical values keep the selection, and with it the counted work, the same for every step).
+    N_SETS = max(1, args.input_sets)
+    sets = [(Q, K, V, dO)] + [tuple(t.clone() for t in (Q, K, V, dO)) for _ in range(N_SETS - 1)]
     kinds = [k for k in args.kinds.split(",") if k in cfg["partitions"]]
     plans = {}
     for kind in kinds:
@@ -217,8 +223,9 @@ def main():
 
     def step(i):
         p = plans[kinds[i % len(kinds)]]
-        p.forward(Q, K, V)
-        p.backward(dO)
+        q, k, v, g = sets[i % N_SETS]
+        p.forward(q, k, v)
+        p.backward(g)
 
     for i in range(args.warmup):
         step(i)
@@ -229,18 +236,22 @@ def main():
     # ---- timed region: exactly `steps` steps, kernel events on the launch stream
     SLOTS = {0: "attn_fwd_tile", 1: "attn_bwd_dq_tile", 2: "attn_bwd_dkv"}
     ev = {s: [(hip.event(), hip.event()) for _ in range(args.steps)] for s in SLOTS}
+    step_ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # step boundaries, same stream
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    step_ev[0].record()
     for i in range(args.steps):
         for s in SLOTS:
             vb.vmoba_profile_events(s, *ev[s][i])
         step(i)
+        step_ev[i + 1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     for s in SLOTS:
         vb.vmoba_profile_events(s, None, None)
     total_s = t1 - t0
     ms_per_step = total_s * 1e3 / args.steps
+    step_ms = [step_ev[i].elapsed_time(step_ev[i + 1]) for i in range(args.steps)]
 
     # ---- work accounting (selected blocks only)
     keysum, pairs = {}, {}
@@ -260,27 +271,61 @@ def main():
     traffic = None
     if args.config == "480p" and abs(args.tau - 0.25) < 1e-9 and len(kinds) == 3:
         traffic = MEASURED_TRAFFIC_BYTES_480P.get(SLOTS[dom])
+    def by_kind(vals):      # median and minimum of a per-step series, per partition kind (the kinds differ in work)
+        return {k: {"median_ms": float(np.median([v for v, sk in zip(vals, step_kinds) if sk == k])),
+                    "min_ms": float(min(v for v, sk in zip(vals, step_kinds) if sk == k))} for k in kinds if k in step_kinds}
+
     roofline = {"bound": "mfma", "kernel": SLOTS[dom], "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": traffic,
                 "avg_launch_ms": dom_ms / args.steps,
                 "all_kernels": {SLOTS[s]: {"avg_launch_ms": sum(ktime[s]) / args.steps,
-                                           "tflops": sum(kflops[s] * D * keysum[k] for k in step_kinds) / (sum(ktime[s]) * 1e-3) / 1e12}
+                                           "tflops": sum(kflops[s] * D * keysum[k] for k in step_kinds) / (sum(ktime[s]) * 1e-3) / 1e12,
+                                           "per_kind": by_kind(ktime[s])}
                                 for s in SLOTS}}
+    # ---- what the matrix cores of this GPU sustain with nothing but matrix instructions in flight (measured here,
+    # at the clock the chip holds under that load), next to the published peak the fractions above are taken against
+    try:
+        sink = torch.zeros(1, dtype=torch.float32, device=dev)
+        wgs = 2 * torch.cuda.get_device_properties(0).multi_processor_count        # two wavefronts per SIMD
+        best = 0.0
+        for _ in range(4):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            flop = vb.vmoba_probe_mfma(20000, wgs, sink)
+            b.record()
+            torch.cuda.synchronize()
+            best = max(best, flop / (a.elapsed_time(b) * 1e-3) / 1e12)
+        roofline["measured_mfma_ceiling_tflops"] = best
+        roofline["measured_mfma_ceiling_note"] = ("independent v_mfma_f32_32x32x16_bf16 only, two wavefronts per SIMD, best of 4 launches "
+                                                  "(vmoba_probe_mfma); `peak` is the published figure, this is the measured one")
+        roofline["frac_of_measured_ceiling"] = achieved / best
+    except Exception as e:
+        roofline["measured_mfma_ceiling_error"] = repr(e)[:120]
 
     # ---- per-call breakdown (outside the timed region), per kind
-    def timed_calls(p):
-        # the attention calls read dO and write O, dQ, dK, dV in the caller's token order (row map = perm)
-        names = ["partition", "select", "attn_fwd", "attn_bwd"]
-        fns = [lambda: p.partition(Q, K, V), p.select, p.attn_fwd, lambda: p.attn_bwd(dO)]
-        evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(fns) + 1)]
-        evs[0].record()
-        for f, e in zip(fns, evs[1:]):
-            f()
-            e.record()
-        torch.cuda.synchronize()
-        return {n: evs[i].elapsed_time(evs[i + 1]) for i, n in enumerate(names)}
+    BREAKDOWN_REPS = 7
 
-    breakdown = {kind: timed_calls(p) for kind, p in plans.items()}
+    def timed_calls(p):
+        # the attention calls read dO and write O, dQ, dK, dV in the caller's token order (row map = perm);
+        # BREAKDOWN_REPS passes over the rotating input sets, median and minimum per call
+        names = ["partition", "select", "attn_fwd", "attn_bwd"]
+        series = {n: [] for n in names}
+        for rep in range(BREAKDOWN_REPS):
+            q, k, v, g = sets[rep % N_SETS]
+            fns = [lambda: p.partition(q, k, v), p.select, p.attn_fwd, lambda: p.attn_bwd(g)]
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(fns) + 1)]
+            evs[0].record()
+            for f, e in zip(fns, evs[1:]):
+                f()
+                e.record()
+            torch.cuda.synchronize()
+            for i, n in enumerate(names):
+                series[n].append(evs[i].elapsed_time(evs[i + 1]))
+        return ({n: float(np.median(v)) for n, v in series.items()}, {n: float(min(v)) for n, v in series.items()})
+
+    timed = {kind: timed_calls(p) for kind, p in plans.items()}
+    breakdown = {kind: t[0] for kind, t in timed.items()}
+    breakdown_min = {kind: t[1] for kind, t in timed.items()}
     # memory-bound steps: algorithmic bytes / time of the call
     es = 2 if dtype == torch.bfloat16 else 4
     row_bytes = S * Hh * D * es
@@ -290,7 +335,9 @@ def main():
         sel_bytes = 2 * row_bytes + Hh * S * nbk * 4 + Hh * S * ((nbk + 31) // 32) * 4 + 3 * 4 * pairs[kind]
         mem_steps[kind] = {
             "partition_qkv_GBps": 3 * 2 * row_bytes / (bd["partition"] * 1e-3) / 1e9,
+            "partition_qkv_GBps_best": 3 * 2 * row_bytes / (breakdown_min[kind]["partition"] * 1e-3) / 1e9,
             "select_GBps": sel_bytes / (bd["select"] * 1e-3) / 1e9,
+            "select_GBps_best": sel_bytes / (breakdown_min[kind]["select"] * 1e-3) / 1e9,
             "select_algorithmic_bytes": sel_bytes}
     empty_rows = {kind: float((p.row_ptr[:, 1:] == p.row_ptr[:, :-1]).float().mean().item()) for kind, p in plans.items()}
     per_kind = {kind: {"ms_per_layer": sum(b.values()),
@@ -308,10 +355,14 @@ def main():
                                   f"layer cycle {'/'.join(kinds)}, fwd+bwd per layer", "tokens": S,
                       "input_generation_s": round(t_gen, 1)},
            "frac_of_bf16_mfma_peak": value / BF16_MFMA_PEAK_TFLOPS,
-           "roofline": roofline, "per_kind": per_kind, "breakdown_ms": breakdown,
+           "ms_per_step_median": float(np.median(step_ms)), "ms_per_step_min": float(min(step_ms)),
+           "ms_per_step_by_kind": by_kind(step_ms), "input_sets_rotated": N_SETS,
+           "roofline": roofline, "per_kind": per_kind, "breakdown_ms": breakdown, "breakdown_min_ms": breakdown_min,
+           "breakdown_note": f"per call: median and minimum of {BREAKDOWN_REPS} passes over the rotating input sets",
            "memory_bound_steps": dict(mem_steps, hbm_peak_GBps=HBM_PEAK_GBS,
                                       note="algorithmic bytes (permute: read+write of every row; select: K and Q read once, "
-                                           "P, mask and the three lists written once) over the call's time")}
+                                           "P, mask and the three lists written once) over the call's median time; "
+                                           "*_best over its minimum; inputs rotate over the sets")}
 
     # ---- measured copy ceiling (plain device-to-device copy of 1 GiB, read + write counted)
     try:

@@ -225,6 +225,15 @@ int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int3
  */
 int vmoba_profile_events(int slot, void* start_event, void* stop_event);
 
+/*
+ * vmoba_probe_mfma -- measurement aid, not part of the method.  Launches `workgroups` workgroups of four
+ * wavefronts that each issue iters x 4 independent v_mfma_f32_32x32x16_bf16 and nothing else; *flop_out (host)
+ * receives the FLOP count of the launch.  Timed by the caller, it gives the bfloat16 matrix rate the GPU
+ * sustains under matrix load (its clock drops below the nominal one there), next to the published peak.
+ * sink: device float the kernel never writes in practice (it keeps the loop from being optimised away).
+ */
+int vmoba_probe_mfma(int64_t iters, int workgroups, float* sink, double* flop_out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,8 @@ VMOBA_F32, VMOBA_BF16 = 0, 1
 OP_SELECT, OP_ATTN_FWD, OP_ATTN_BWD = 1, 2, 3
 
 EXPORTS = ["vmoba_layer_kind", "vmoba_partition_dims", "vmoba_workspace_bytes", "vmoba_status_string",
-           "vmoba_partition", "vmoba_select", "vmoba_attn_fwd", "vmoba_attn_bwd", "vmoba_profile_events"]
+           "vmoba_partition", "vmoba_select", "vmoba_attn_fwd", "vmoba_attn_bwd",
+           "vmoba_profile_events", "vmoba_probe_mfma"]
 
 
 class vmoba_grid(C.Structure):
@@ -81,6 +82,8 @@ def lib():
     L.vmoba_attn_bwd.restype = C.c_int
     L.vmoba_profile_events.argtypes = [C.c_int, P, P]
     L.vmoba_profile_events.restype = C.c_int
+    L.vmoba_probe_mfma.argtypes = [C.c_int64, C.c_int, P, C.POINTER(C.c_double), P]
+    L.vmoba_probe_mfma.restype = C.c_int
     _lib = L
     return L
 
@@ -151,6 +154,13 @@ def vmoba_profile_events(slot: int, start_event=None, stop_event=None):
     _check("vmoba_profile_events", lib().vmoba_profile_events(
         int(slot), C.c_void_p(start_event) if start_event else None,
         C.c_void_p(stop_event) if stop_event else None))
+
+
+def vmoba_probe_mfma(iters: int, workgroups: int, sink, stream=None) -> float:
+    """Launches the matrix-rate probe; returns the FLOP count of the launch (time it with events)."""
+    flop = C.c_double(0.0)
+    _check("vmoba_probe_mfma", lib().vmoba_probe_mfma(int(iters), int(workgroups), _ptr(sink), C.byref(flop), _stream(stream)))
+    return flop.value
 
 
 # ------------------------------------------------------------------------------- entry points

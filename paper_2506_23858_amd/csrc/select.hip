@@ -11,6 +11,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 
 namespace {
 
@@ -1046,6 +1047,21 @@ size_t score_lds_bytes(int nb, int D) {
     return (size_t)nb * D * 4 + (size_t)QT * (nb | 1) * 4 + HIST_BINS * 4 + HIST_BINS * 8;
 }
 
+// The score kernels use more dynamic LDS than the default limit: raise a kernel's limit to the whole 160 KB of a
+// compute unit, once per kernel (slot) and device.
+int allow_full_lds(const void* kernel, int slot) {
+    static std::mutex mu;
+    static bool done[6][64] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return VMOBA_ERR_HIP;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!done[slot][dev]) {
+        if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return VMOBA_ERR_HIP;
+        done[slot][dev] = true;
+    }
+    return VMOBA_OK;
+}
+
 int fix_shift_for(int64_t S) {
     int bits = 0;
     while (((int64_t)1 << bits) < S) ++bits;
@@ -1058,30 +1074,49 @@ size_t vmoba_select_workspace_bytes(int B, int Hh, int64_t S, int nb) {
     return carve(nullptr, B * Hh, S, nb).total;
 }
 
-extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
-                            const vmoba_tensor* Qp, const vmoba_tensor* Kp, float tau, float score_scale,
-                            int mode, int32_t topk, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
-                            int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
-                            int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
-                            void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+
+// Host-side validation shared by the two entry points; everything that can be rejected without touching the device.
+int select_args_ok(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off, const vmoba_tensor* Qp,
+                   const vmoba_tensor* Kp, float tau, float score_scale, int mode, int32_t topk, const float* Bmean,
+                   const float* P, const uint32_t* mask, const int32_t* blk_ptr, const int32_t* q_idx,
+                   const int32_t* row_ptr, const int32_t* col_idx, const int32_t* pair_pos, int64_t nnz_capacity,
+                   const int64_t* k_out, const float* theta_out, const int32_t* dev_status) {
     if (B <= 0 || Hh <= 0 || S <= 0 || n_blocks <= 0 || nnz_capacity <= 0) return VMOBA_ERR_INVALID_ARG;
     if (!blk_off || !Bmean || !P || !mask || !blk_ptr || !q_idx || !row_ptr || !col_idx || !pair_pos ||
-        !k_out || !theta_out || !dev_status || !workspace)
+        !k_out || !theta_out || !dev_status)
         return VMOBA_ERR_INVALID_ARG;
     if (!tensor_ok(Qp) || !tensor_ok(Kp)) return VMOBA_ERR_INVALID_ARG;
     if (!std::isfinite(score_scale)) return VMOBA_ERR_INVALID_ARG;
-    const bool own_block = (mode & VMOBA_SELECT_OWN_BLOCK) != 0;
     mode &= ~VMOBA_SELECT_OWN_BLOCK;
     if (mode < VMOBA_GLOBAL_THRESHOLD || mode > VMOBA_POOL_SOFTMAX_THRESHOLD) return VMOBA_ERR_UNSUPPORTED;
-    const int* own_off = own_block ? blk_off : nullptr;
-    const bool pool_softmax = mode == VMOBA_POOL_SOFTMAX_THRESHOLD;
-    const bool uses_tau = mode == VMOBA_GLOBAL_THRESHOLD || mode == VMOBA_LOCAL_THRESHOLD || pool_softmax;
+    const bool uses_tau = mode == VMOBA_GLOBAL_THRESHOLD || mode == VMOBA_LOCAL_THRESHOLD || mode == VMOBA_POOL_SOFTMAX_THRESHOLD;
     if (uses_tau && (!(tau > 0.f) || !(tau <= 1.f))) return VMOBA_ERR_INVALID_ARG;
     if (!uses_tau && topk < 1) return VMOBA_ERR_INVALID_ARG;
     if (D != 64 && D != 128) return VMOBA_ERR_UNSUPPORTED;
     if (Qp->dtype != Kp->dtype) return VMOBA_ERR_UNSUPPORTED;
     if (n_blocks > VMOBA_MAX_BLOCKS || S > ((int64_t)1 << 30) || S * n_blocks > (int64_t)INT32_MAX)
         return VMOBA_ERR_UNSUPPORTED;
+    return VMOBA_OK;
+}
+
+// The selection itself; `workspace` is the caller's buffer (vmoba_select) or the library's static one.
+int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
+                const vmoba_tensor* Qp, const vmoba_tensor* Kp, float tau, float score_scale,
+                int mode, int32_t topk, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
+                int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
+                int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
+                void* workspace, size_t workspace_bytes, void* stream) {
+    {
+        const int rc = select_args_ok(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode, topk, Bmean, P, mask,
+                                      blk_ptr, q_idx, row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status);
+        if (rc != VMOBA_OK) return rc;
+    }
+    if (!workspace) return VMOBA_ERR_INVALID_ARG;
+    const bool own_block = (mode & VMOBA_SELECT_OWN_BLOCK) != 0;
+    mode &= ~VMOBA_SELECT_OWN_BLOCK;
+    const int* own_off = own_block ? blk_off : nullptr;
+    const bool pool_softmax = mode == VMOBA_POOL_SOFTMAX_THRESHOLD;
     const bool bf16 = Qp->dtype == VMOBA_BF16;
     // LDS of the score kernel this call launches: bfloat16 queries go to the matrix-core kernel (block means as three
     // bfloat16 terms up to 128 blocks, as float32 beyond), float32 queries to the plain FMA kernel
@@ -1131,8 +1166,7 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
 #define LAUNCH_SCORE(DD)                                                                                  \
     do {                                                                                                  \
         auto kfn = score_kernel<DD>;                                                                      \
-        if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
-            return VMOBA_ERR_HIP;                                                                         \
+        if (allow_full_lds((const void*)kfn, DD == 128 ? 0 : 1) != VMOBA_OK) return VMOBA_ERR_HIP;        \
         kfn<<<sgrid, dim3(256), lds, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks,  \
                                            score_scale, fix_shift, row_stat);                             \
     } while (0)
@@ -1141,8 +1175,7 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
 #define LAUNCH_SCORE_MFMA(DD, FL)                                                                         \
     do {                                                                                                  \
         auto kfn = score_mfma_kernel<DD, FL>;                                                             \
-        if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
-            return VMOBA_ERR_HIP;                                                                         \
+        if (allow_full_lds((const void*)kfn, 2 + (DD == 128 ? 0 : 2) + (FL ? 1 : 0)) != VMOBA_OK) return VMOBA_ERR_HIP; \
         kfn<<<mgrid, dim3(SCORE_NT), lds, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks, score_scale, \
                                                 fix_shift, row_stat);                                     \
     } while (0)
@@ -1223,4 +1256,17 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
                                                               (long long)nnz_capacity);
     VMOBA_CHECK_LAUNCH();
     return VMOBA_OK;
+}
+
+}  // namespace
+
+extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
+                            const vmoba_tensor* Qp, const vmoba_tensor* Kp, float tau, float score_scale,
+                            int mode, int32_t topk, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
+                            int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
+                            int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    return select_impl(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode, topk, Bmean, P, mask, blk_ptr, q_idx,
+                       row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status, workspace, workspace_bytes,
+                       stream);
 }

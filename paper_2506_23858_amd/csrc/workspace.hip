@@ -24,3 +24,35 @@ extern "C" int vmoba_profile_events(int slot, void* start_event, void* stop_even
     g_profile[slot].stop = (hipEvent_t)stop_event;
     return VMOBA_OK;
 }
+
+// vmoba_probe_mfma: measurement aid.  Every wavefront issues `iters` rounds of four independent
+// v_mfma_f32_32x32x16_bf16 (nothing else in the loop), so the launch's duration gives the matrix rate this GPU
+// sustains at its clock under matrix load: what a kernel made of matrix instructions alone could reach.
+__global__ __launch_bounds__(256) void mfma_probe_kernel(long long iters, float* __restrict__ sink) {
+    const float seed = (float)(threadIdx.x & 7) * 0.125f;
+    f32x4_t lo = {seed, 0.5f, 0.25f, 1.f};
+    const bf16x4_t b4 = __builtin_convertvector(lo, bf16x4_t);
+    const bf16x8_t a = __builtin_shufflevector(b4, b4, 0, 1, 2, 3, 4, 5, 6, 7), b = a;
+    f32x16_t c0, c1, c2, c3;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { c0[i] = 0.f; c1[i] = 0.f; c2[i] = 0.f; c3[i] = 0.f; }
+    for (long long it = 0; it < iters; ++it) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+    }
+    float r = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) r += c0[i] + c1[i] + c2[i] + c3[i];
+    if (r == -1.f) sink[0] = r;          // never true (the sums are >= 0): keeps the loop alive
+}
+
+extern "C" int vmoba_probe_mfma(int64_t iters, int workgroups, float* sink, double* flop_out, void* stream) {
+    if (iters <= 0 || iters > ((int64_t)1 << 24) || workgroups <= 0 || workgroups > (1 << 16) || !sink || !flop_out)
+        return VMOBA_ERR_INVALID_ARG;
+    mfma_probe_kernel<<<dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)stream>>>((long long)iters, sink);
+    VMOBA_CHECK_LAUNCH();
+    *flop_out = (double)workgroups * 4.0 * (double)iters * 4.0 * 32.0 * 32.0 * 16.0 * 2.0;
+    return VMOBA_OK;
+}
