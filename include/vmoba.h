@@ -172,6 +172,26 @@ int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_
                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * vmoba_select_static -- vmoba_select for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels
+ * and bit-identical results; the scratch memory vmoba_select takes as `workspace` is a static device array inside
+ * the library instead (VMOBA_SELECT_STATIC_MAX_BYTES, held on every GPU the library runs on until the process
+ * ends).  The call allocates and frees nothing.  Its first call on a device looks up the array's device address
+ * (hipGetSymbolAddress): make that call outside any capture.
+ * Limit: geometries with vmoba_workspace_bytes(VMOBA_OP_SELECT, ...) > VMOBA_SELECT_STATIC_MAX_BYTES return
+ * VMOBA_ERR_WORKSPACE before anything is launched (32 MiB covers 12 heads at 480p and at 720p).
+ * Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (two streams, two threads) race --
+ * serialise them.  The array keeps the previous call's contents; the call clears what it needs zeroed itself.
+ */
+#define VMOBA_SELECT_STATIC_MAX_BYTES ((size_t)32 << 20)
+int vmoba_select_static(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
+                        const vmoba_tensor* Qp, const vmoba_tensor* Kp, float tau, float score_scale,
+                        int mode, int32_t topk, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
+                        int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
+                        int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
+                        void* stream);
+
+/*
  * vmoba_attn_fwd -- Step 3 of Sec. 3.1: every query attends to the keys/values of its selected
  * blocks only.  O(q) = sum_n softmax_n(softmax_scale * <Q'(q), K'(n)>) V'(n) over the keys n of
  * the selected blocks; LSE [B, Hh, S] float32 is the natural-log-sum-exp of the scaled scores.

@@ -21,7 +21,7 @@ VMOBA_F32, VMOBA_BF16 = 0, 1
 OP_SELECT, OP_ATTN_FWD, OP_ATTN_BWD = 1, 2, 3
 
 EXPORTS = ["vmoba_layer_kind", "vmoba_partition_dims", "vmoba_workspace_bytes", "vmoba_status_string",
-           "vmoba_partition", "vmoba_select", "vmoba_attn_fwd", "vmoba_attn_bwd",
+           "vmoba_partition", "vmoba_select", "vmoba_select_static", "vmoba_attn_fwd", "vmoba_attn_bwd",
            "vmoba_profile_events", "vmoba_probe_mfma"]
 
 
@@ -69,6 +69,8 @@ def lib():
                                C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor), C.c_float, C.c_float, C.c_int,
                                C.c_int32, P, P, P, P, P, P, P, P, C.c_int64, P, P, P, P, C.c_size_t, P]
     L.vmoba_select.restype = C.c_int
+    L.vmoba_select_static.argtypes = L.vmoba_select.argtypes[:-3] + [P]      # no workspace pointer / size
+    L.vmoba_select_static.restype = C.c_int
     L.vmoba_attn_fwd.argtypes = [C.c_int, C.c_int, C.c_int64, C.c_int, C.c_int32, P,
                                  C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor),
                                  P, P, P, P, C.c_int64, C.c_float, C.POINTER(vmoba_tensor), P, P, P, C.c_size_t, P]
@@ -189,6 +191,22 @@ def vmoba_select(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode,
                             int(nnz_capacity), _ptr(k_out), _ptr(theta_out), _ptr(dev_status),
                             _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     _check("vmoba_select", rc)
+
+
+SELECT_STATIC_MAX_BYTES = 32 << 20
+
+
+def vmoba_select_static(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode, topk, Bmean, P, mask,
+                        blk_ptr, q_idx, row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status,
+                        stream=None):
+    """vmoba_select on the library's static scratch array (no workspace argument, nothing allocated)."""
+    q, k = tensor_desc(Qp), tensor_desc(Kp)
+    rc = lib().vmoba_select_static(B, Hh, S, D, n_blocks, _ptr(blk_off), C.byref(q), C.byref(k),
+                                   float(tau), float(score_scale), int(mode), int(topk), _ptr(Bmean), _ptr(P),
+                                   _ptr(mask), _ptr(blk_ptr), _ptr(q_idx), _ptr(row_ptr), _ptr(col_idx),
+                                   _ptr(pair_pos), int(nnz_capacity), _ptr(k_out), _ptr(theta_out),
+                                   _ptr(dev_status), _stream(stream))
+    _check("vmoba_select_static", rc)
 
 
 def vmoba_attn_fwd(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, Vp, blk_ptr, q_idx, row_ptr, pair_pos,

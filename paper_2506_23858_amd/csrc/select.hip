@@ -1270,3 +1270,52 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
                        row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status, workspace, workspace_bytes,
                        stream);
 }
+
+// ---------------------------------------------------------------------------------------------
+// vmoba_select_static: vmoba_select for callers that cannot allocate.  Its scratch memory (histograms, head state,
+// tie ranks, row and block counts) is a file-scope device array instead of a caller-provided workspace.  In host code
+// the array's name is only a handle for the runtime: the device address is looked up once per device with
+// hipGetSymbolAddress and that pointer is what the kernels get, exactly as they get the caller's workspace above.
+static __device__ __align__(256) unsigned char scratch[VMOBA_SELECT_STATIC_MAX_BYTES];
+
+namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};          // device address of `scratch` on each device, null until first use
+
+int static_scratch_of_current_device(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return VMOBA_ERR_HIP;
+    if (dev < 0 || dev >= MAX_DEVICES) return VMOBA_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return VMOBA_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return VMOBA_OK;
+}
+
+}  // namespace
+
+extern "C" int vmoba_select_static(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
+                                   const vmoba_tensor* Qp, const vmoba_tensor* Kp, float tau, float score_scale,
+                                   int mode, int32_t topk, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
+                                   int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
+                                   int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
+                                   void* stream) {
+    // everything that can be rejected on the host first, the size limit included
+    const int rc = select_args_ok(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode, topk, Bmean, P, mask,
+                                  blk_ptr, q_idx, row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status);
+    if (rc != VMOBA_OK) return rc;
+    if ((int64_t)B * Hh > (1 << 20)) return VMOBA_ERR_WORKSPACE;
+    if (carve(nullptr, B * Hh, S, n_blocks).total > VMOBA_SELECT_STATIC_MAX_BYTES) return VMOBA_ERR_WORKSPACE;
+    void* ws = nullptr;
+    const int rs = static_scratch_of_current_device(&ws);
+    if (rs != VMOBA_OK) return rs;
+    return select_impl(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode, topk, Bmean, P, mask, blk_ptr, q_idx,
+                       row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status, ws,
+                       VMOBA_SELECT_STATIC_MAX_BYTES, stream);
+}
