@@ -1120,7 +1120,7 @@ __global__ __launch_bounds__(256) void dq_merge_kernel(const float* __restrict__
 }
 
 struct BwdWs {
-    float* dQpart;     // [BH * cap][D]
+    float* dQpart;     // [BH * cap][D], in the tensors' type
     float* delta;      // [BH][S]
     int* tile_start;   // [BH][257]
     int4* tile_desc;   // [BH][tiles_per_head], or the flat list of all heads' tiles
@@ -1135,7 +1135,7 @@ BwdWs carve_bwd(void* base, int BH, int64_t S, int D, int64_t cap, int es) {
     BwdWs w;
     char* p = (char*)base;
     size_t off = 0;
-    w.dQpart = (float*)(p + off);    off += align_up((size_t)BH * cap * D * 4, 256);
+    w.dQpart = (float*)(p + off);    off += align_up((size_t)BH * cap * D * es, 256);
     w.delta = (float*)(p + off);     off += align_up((size_t)BH * S * 4, 256);
     w.tile_start = (int*)(p + off);  off += align_up((size_t)BH * (VMOBA_MAX_BLOCKS + 1) * 4, 256);
     w.tile_desc = (int4*)(p + off);  off += align_up((size_t)BH * vmoba_max_tiles(cap, 64) * 16, 256);

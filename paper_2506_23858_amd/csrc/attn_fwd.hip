@@ -613,7 +613,7 @@ __global__ __launch_bounds__(256) void attn_fwd_merge_kernel(const float* __rest
 }
 
 struct FwdWs {
-    float* Opart;      // [BH * cap][D]
+    float* Opart;      // [BH * cap][D], in the tensors' type
     float* lse_part;   // [BH * cap]
     int* tile_start;   // [BH][nb + 1]
     int4* tile_desc;   // [BH][tiles_per_head], or the flat list of all heads' tiles
@@ -626,16 +626,15 @@ struct FwdWs {
 int64_t vmoba_max_tiles(int64_t cap, int TM) { return (cap / TM + VMOBA_MAX_BLOCKS + 7) / 8 * 8; }
 namespace {
 
-FwdWs carve_fwd(void* base, int BH, int D, int64_t cap, int nb) {
+FwdWs carve_fwd(void* base, int BH, int D, int64_t cap, int es) {       // es: bytes per element of the partial rows
     FwdWs w;
     char* p = (char*)base;
     size_t off = 0;
-    w.Opart = (float*)(p + off);     off += align_up((size_t)BH * cap * D * 4, 256);
+    w.Opart = (float*)(p + off);     off += align_up((size_t)BH * cap * D * es, 256);
     w.lse_part = (float*)(p + off);  off += align_up((size_t)BH * cap * 4, 256);
     w.tile_start = (int*)(p + off);  off += align_up((size_t)BH * (VMOBA_MAX_BLOCKS + 1) * 4, 256);
     w.tile_desc = (int4*)(p + off);  off += align_up((size_t)BH * vmoba_max_tiles(cap, 64) * 16, 256);
     w.head_base = (int*)(p + off);   off += align_up((size_t)(BH + 1) * 4, 256);
-    (void)nb;
     w.total = off;
     return w;
 }
@@ -643,8 +642,8 @@ FwdWs carve_fwd(void* base, int BH, int D, int64_t cap, int nb) {
 }  // namespace
 
 size_t vmoba_attn_fwd_workspace_bytes(int B, int Hh, int64_t S, int D, int64_t cap, int dtype) {
-    (void)S; (void)dtype;
-    return carve_fwd(nullptr, B * Hh, D, cap, 0).total;
+    (void)S;
+    return carve_fwd(nullptr, B * Hh, D, cap, dtype == VMOBA_BF16 ? 2 : 4).total;
 }
 
 // Compute units of the current device (queried once).
@@ -677,7 +676,7 @@ extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     if (Kp->dtype != dt || Vp->dtype != dt || O->dtype != dt) return VMOBA_ERR_UNSUPPORTED;
     const int BH = B * Hh;
     if (nnz_capacity > INT32_MAX || (int64_t)BH * nnz_capacity * D > ((int64_t)1 << 40)) return VMOBA_ERR_UNSUPPORTED;
-    FwdWs ws = carve_fwd(workspace, BH, D, nnz_capacity, n_blocks);
+    FwdWs ws = carve_fwd(workspace, BH, D, nnz_capacity, dt == VMOBA_BF16 ? 2 : 4);
     if (workspace_bytes < ws.total) return VMOBA_ERR_WORKSPACE;
     if (((uintptr_t)workspace) & 255) return VMOBA_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;

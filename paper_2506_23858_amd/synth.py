@@ -27,8 +27,18 @@ CONFIGS = {
                  partitions={"1d": (0, 0, 0, 1560), "2d": (1, 15, 26, 0), "3d": (3, 15, 13, 0),
                              "1d_tf": (3, 30, 52, 0), "2d_tf": (21, 5, 13, 0), "3d_tf": (7, 5, 13, 0)}),
     "720p": dict(grid=(21, 45, 80), heads=12, D=128, dtype="bf16", sigma=2.0, seed=4000,
+                 # *_tf: the paper's block sizes at this resolution (same table): 7 | 40 | 36 blocks
                  partitions={"1d": (0, 0, 0, 2100), "2d": (1, 30, 40, 0), "2d_half": (1, 45, 40, 0),
-                             "3d": (3, 15, 40, 0)}),
+                             "3d": (3, 15, 40, 0),
+                             "1d_tf": (3, 45, 80, 0), "2d_tf": (21, 9, 10, 0), "3d_tf": (7, 15, 20, 0)}),
+    # the two latent grids the paper fine-tunes on (93 x 576 x 1024 and 141 x 480 x 832 video), with the block
+    # sizes its hyperparameter table gives for them: 8 | 48 | 72 blocks on the first; 3-frame, 5 x 13 and
+    # 12 x 10 x 13 blocks on the second, i.e. 12 | 24 | 36 blocks (the table prints 7 for the first of these,
+    # which 36 frames in blocks of 3 cannot give)
+    "train55k": dict(grid=(24, 36, 64), heads=12, D=128, dtype="bf16", sigma=2.0, seed=6000,
+                     partitions={"1d": (3, 36, 64, 0), "2d": (24, 6, 8, 0), "3d": (8, 12, 8, 0)}),
+    "train56k": dict(grid=(36, 30, 52), heads=12, D=128, dtype="bf16", sigma=2.0, seed=7000,
+                     partitions={"1d": (3, 30, 52, 0), "2d": (36, 5, 13, 0), "3d": (12, 10, 13, 0)}),
     "stress": dict(grid=(31, 45, 80), heads=40, D=128, dtype="bf16", sigma=(1.0, 4.0, 16.0),
                    seed=5000, partitions={"3d": (3, 15, 16, 0)}),
 }

@@ -194,6 +194,20 @@ def test_720p_forward_sampled(kind):
     check_layer_sampled("720p", kind, 0.25, bwd=False, sel_heads=[0, 7], groups=2, max_rows=12000)
 
 
+@pytest.mark.parametrize("name,kind,n_blocks", [
+    ("720p", "2d_tf", 40), ("720p", "3d_tf", 36),
+    ("train55k", "1d", 8), ("train55k", "2d", 48), ("train55k", "3d", 72),
+    ("train56k", "2d", 24), ("train56k", "3d", 36),
+])
+def test_paper_table_block_shapes(name, kind, n_blocks):
+    """The block shapes of the paper's hyperparameter table (App. A) on its 720p grid and on the two grids it
+    fine-tunes on (24x36x64 = 55 296 and 36x30x52 = 56 160 latent tokens), with its training setting -- global
+    threshold, tau = 0.25, forward and backward -- on 3 heads."""
+    c = synth.CONFIGS[name]
+    assert len(vo.partition_index(*c["grid"], *c["partitions"][kind])[2]) - 1 == n_blocks
+    check_layer_sampled(name, kind, 0.25, heads=3, sel_heads=[0, 2], groups=2, max_rows=12000, fused_io=True)
+
+
 @pytest.mark.parametrize("tau", [0.25, 0.75])
 def test_stress_shape_reduced_heads(tau):
     """Long-sequence stress shape (31x45x80 = 111 600 tokens, blocks 3x15x16: 165 blocks, the last temporal slab

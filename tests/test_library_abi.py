@@ -38,12 +38,29 @@ def test_layer_kind_cycle():
     ((21, 30, 52), (7, 5, 13), 0, 32760, 72), ((21, 30, 52), (0, 0, 0), 1560, 32760, 21),
     ((21, 45, 80), (1, 30, 40), 0, 75600, 84), ((31, 45, 80), (3, 15, 16), 0, 111600, 165),
     ((5, 7, 9), (2, 3, 4), 0, 315, 27),
+    # the block shapes of the paper's hyperparameter table on its 720p and fine-tuning grids
+    ((21, 45, 80), (21, 9, 10), 0, 75600, 40), ((21, 45, 80), (7, 15, 20), 0, 75600, 36),
+    ((24, 36, 64), (3, 36, 64), 0, 55296, 8), ((24, 36, 64), (24, 6, 8), 0, 55296, 48),
+    ((24, 36, 64), (8, 12, 8), 0, 55296, 72), ((36, 30, 52), (12, 10, 13), 0, 56160, 36),
 ])
 def test_partition_dims(grid, block, chunk, S, nb):
     g = vb.make_grid(*grid, *block, chunk)
     assert vb.vmoba_partition_dims(g) == (S, nb)
     from oracle import vmoba_oracle as vo
     assert vo.partition_dims(*grid, *block, chunk) == (S, nb)
+
+
+def test_named_partitions_have_the_papers_block_counts():
+    """synth.CONFIGS' entries for the paper's own block shapes (App. A, hyperparameter table)."""
+    from paper_2506_23858_amd import synth
+    want = {("480p", "1d_tf"): 7, ("480p", "2d_tf"): 24, ("480p", "3d_tf"): 72,
+            ("720p", "1d_tf"): 7, ("720p", "2d_tf"): 40, ("720p", "3d_tf"): 36,
+            ("train55k", "1d"): 8, ("train55k", "2d"): 48, ("train55k", "3d"): 72,
+            ("train56k", "1d"): 12, ("train56k", "2d"): 24, ("train56k", "3d"): 36}
+    for (name, kind), nb in want.items():
+        c = synth.CONFIGS[name]
+        bt, bh, bw, chunk = c["partitions"][kind]
+        assert vb.vmoba_partition_dims(vb.make_grid(*c["grid"], bt, bh, bw, chunk))[1] == nb, (name, kind)
 
 
 def test_bad_arguments_are_rejected_before_any_launch(L):
