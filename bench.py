@@ -170,6 +170,86 @@ def sweep(args):
                       "log_log_slope": fit}))
 
 
+def tau_sweep(args):
+    """Threshold sweep of one configuration (the long-sequence stress shape asks for tau = 0.1 .. 0.75): inputs are
+    generated once; per tau and partition kind a whole layer fwd+bwd is timed, with the selected-pair fraction,
+    the token sparsity and the effective TFLOP/s on the selected blocks."""
+    import torch
+    from paper_2506_23858_amd import binding as vb, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    Hh, D = cfg["heads"], cfg["D"]
+    dtype = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+    t_gen = time.perf_counter()
+    Q, K, V, dO = (torch.from_numpy(x).to("cuda").to(dtype).contiguous() for x in synth.make_qkv(args.config))
+    t_gen = time.perf_counter() - t_gen
+    print(f"[tau-sweep] {args.config}: inputs in {t_gen:.1f} s", file=sys.stderr, flush=True)
+    S = Q.shape[1]
+    kinds = [k for k in args.kinds.split(",") if k in cfg["partitions"]]
+    points = []
+    for tau in [float(x) for x in args.tau_sweep.split(",")]:
+        for kind in kinds:
+            bt, bh, bw, chunk = cfg["partitions"][kind]
+            p = vb.LayerPlan(1, Hh, D, cfg["grid"], (bt, bh, bw), chunk, tau, dtype, fused_io=True)
+            p.forward(Q, K, V); p.backward(dO)
+            torch.cuda.synchronize()
+            assert int(p.dev_status.item()) == 0
+            reps, times = 3, []
+            for _ in range(reps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                p.forward(Q, K, V); p.backward(dO)
+                b.record()
+                torch.cuda.synchronize()
+                times.append(a.elapsed_time(b))
+            keysum, pairs = selected_key_sum(p)
+            ms = float(np.median(times))
+            pt = {"tau": tau, "kind": kind, "n_blocks": p.nb, "ms_per_layer_median": ms, "ms_per_layer_min": float(min(times)),
+                  "selected_pair_fraction": pairs / (Hh * S * p.nb), "token_sparsity": keysum / (Hh * S * S),
+                  "empty_row_fraction": float((p.row_ptr[:, 1:] == p.row_ptr[:, :-1]).float().mean().item()),
+                  "effective_tflops": 14.0 * D * keysum / (ms * 1e-3) / 1e12,
+                  "frac_of_bf16_mfma_peak": 14.0 * D * keysum / (ms * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS}
+            points.append(pt)
+            print(f"[tau-sweep] {json.dumps(pt)}", file=sys.stderr, flush=True)
+            del p
+            torch.cuda.empty_cache()
+    print(json.dumps({"metric": "threshold sweep: VMoBA layer fwd+bwd, whole path", "config": args.config,
+                      "workload": f"grid {cfg['grid']}, {Hh} heads x {D}", "tokens": S, "dtype": "bf16", "data": "synthetic",
+                      "input_generation_s": round(t_gen, 1), "points": points}))
+
+
+def probe_atomics(args):
+    """Why dQ is not formed inside the dK/dV kernel with atomics: the atomic traffic of that design alone (no matrix
+    work), per partition of the 480p workload at the measured list densities, against the dQ path it would replace."""
+    import torch
+    from paper_2506_23858_amd import binding as vb
+
+    torch.cuda.set_device(0)
+    S, heads = 32760, 12
+    dq = torch.zeros(heads, S, 128, dtype=torch.float32, device="cuda")
+    rng = np.random.default_rng(7)
+    points = []
+    for name, nb, L, frac in (("3d", 56, 585, 0.144), ("2d", 84, 390, 0.167), ("1d", 21, 1560, 0.209)):
+        cnt = int(frac * S)
+        lists = torch.from_numpy(np.stack([np.sort(rng.choice(S, cnt, replace=False)) for _ in range(64)]).astype(np.int32)).cuda()
+        runs = nb * (-(-L // 128))
+        best = 1e9
+        for _ in range(4):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            vb.vmoba_probe_atomic_rows(dq, lists, cnt, S, runs, heads)
+            b.record()
+            torch.cuda.synchronize()
+            best = min(best, a.elapsed_time(b))
+        nbytes = runs * heads * cnt * 512.0
+        points.append({"partition": name, "runs": runs, "heads": heads, "list_rows": cnt, "atomic_GB": nbytes / 1e9,
+                       "ms": best, "TBps": nbytes / best / 1e9})
+    print(json.dumps({"metric": "float32 atomic row adds of a dQ-inside-dK/dV design, 480p tau=0.25 list densities",
+                      "points": points}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -184,6 +264,8 @@ def main():
     ap.add_argument("--input-sets", type=int, default=3, help="copies of the inputs the steps rotate over")
     ap.add_argument("--sweep", action="store_true", help="sequence-length sweep instead of the benchmark line")
     ap.add_argument("--sweep-frames", default="9,15,21,36,48,72")
+    ap.add_argument("--tau-sweep", default="", help="comma-separated thresholds: time a whole layer per tau and kind instead")
+    ap.add_argument("--probe-atomics", action="store_true", help="time the atomic traffic of a dQ-inside-dK/dV design instead")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; --gpus must be 1 (the path shards by head, see DESIGN.md)",
@@ -192,6 +274,10 @@ def main():
 
     if args.sweep:
         return sweep(args)
+    if args.probe_atomics:
+        return probe_atomics(args)
+    if args.tau_sweep:
+        return tau_sweep(args)
 
     import torch
     from paper_2506_23858_amd import binding as vb, synth

@@ -254,6 +254,16 @@ int vmoba_profile_events(int slot, void* start_event, void* stop_event);
  */
 int vmoba_probe_mfma(int64_t iters, int workgroups, float* sink, double* flop_out, void* stream);
 
+/*
+ * vmoba_probe_atomic_rows -- measurement aid, not part of the method.  Launches only the atomic traffic of a
+ * backward pass that would add dQ from inside the dK/dV kernel (the design this library does not use): `runs` x `heads`
+ * workgroups, each walking one of n_lists ascending query lists of cnt rows (lists: device int32 [n_lists][cnt], rows
+ * in [0, S)) and adding a row of 128 floats per entry into dq (device float32 [heads][S][128], which the caller
+ * zeroes) with hardware float atomics.  bench.py --probe-atomics times it against the dQ path it would replace.
+ */
+int vmoba_probe_atomic_rows(float* dq, const int32_t* lists, int n_lists, int cnt, int64_t S, int runs, int heads,
+                            void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,7 @@ OP_SELECT, OP_ATTN_FWD, OP_ATTN_BWD = 1, 2, 3
 
 EXPORTS = ["vmoba_layer_kind", "vmoba_partition_dims", "vmoba_workspace_bytes", "vmoba_status_string",
            "vmoba_partition", "vmoba_select", "vmoba_select_static", "vmoba_attn_fwd", "vmoba_attn_bwd",
-           "vmoba_profile_events", "vmoba_probe_mfma"]
+           "vmoba_profile_events", "vmoba_probe_mfma", "vmoba_probe_atomic_rows"]
 
 
 class vmoba_grid(C.Structure):
@@ -86,6 +86,8 @@ def lib():
     L.vmoba_profile_events.restype = C.c_int
     L.vmoba_probe_mfma.argtypes = [C.c_int64, C.c_int, P, C.POINTER(C.c_double), P]
     L.vmoba_probe_mfma.restype = C.c_int
+    L.vmoba_probe_atomic_rows.argtypes = [P, P, C.c_int, C.c_int, C.c_int64, C.c_int, C.c_int, P]
+    L.vmoba_probe_atomic_rows.restype = C.c_int
     _lib = L
     return L
 
@@ -163,6 +165,12 @@ def vmoba_probe_mfma(iters: int, workgroups: int, sink, stream=None) -> float:
     flop = C.c_double(0.0)
     _check("vmoba_probe_mfma", lib().vmoba_probe_mfma(int(iters), int(workgroups), _ptr(sink), C.byref(flop), _stream(stream)))
     return flop.value
+
+
+def vmoba_probe_atomic_rows(dq, lists, cnt, S, runs, heads, stream=None):
+    """dq: float32 [heads, S, 128] (zeroed); lists: int32 [n_lists, cnt] ascending rows."""
+    _check("vmoba_probe_atomic_rows", lib().vmoba_probe_atomic_rows(_ptr(dq), _ptr(lists), int(lists.shape[0]), int(cnt),
+                                                                     int(S), int(runs), int(heads), _stream(stream)))
 
 
 # ------------------------------------------------------------------------------- entry points

@@ -56,3 +56,34 @@ extern "C" int vmoba_probe_mfma(int64_t iters, int workgroups, float* sink, doub
     *flop_out = (double)workgroups * 4.0 * (double)iters * 4.0 * 32.0 * 32.0 * 16.0 * 2.0;
     return VMOBA_OK;
 }
+
+// vmoba_probe_atomic_rows: measurement aid.  The atomic traffic -- and nothing else -- of a backward pass that would form
+// dQ inside the dK/dV kernel: workgroup (run, head) walks a query list of `cnt` rows in 64-row steps and adds one
+// 128-float row per listed query into dq[head][row][:] with hardware float atomics (no return value).  `lists` holds
+// n_lists lists of cnt ascending rows; run r uses list r % n_lists.
+__global__ __launch_bounds__(256) void atomic_rows_probe_kernel(float* __restrict__ dq, const int* __restrict__ lists, int n_lists,
+                                                                int cnt, int S) {
+    const int head = blockIdx.y;
+    const int* lst = lists + (size_t)(blockIdx.x % n_lists) * cnt;
+    float* base = dq + (size_t)head * S * 128;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int c0 = 0; c0 < cnt; c0 += 64) {
+        for (int r = 0; r < 16; ++r) {
+            const int e = c0 + wave * 16 + r;
+            if (e >= cnt) break;
+            float* row = base + (size_t)lst[e] * 128;
+            unsafeAtomicAdd(row + lane, 1.0f);
+            unsafeAtomicAdd(row + 64 + lane, 1.0f);
+        }
+    }
+}
+
+extern "C" int vmoba_probe_atomic_rows(float* dq, const int32_t* lists, int n_lists, int cnt, int64_t S, int runs, int heads,
+                                       void* stream) {
+    if (!dq || !lists || n_lists <= 0 || cnt <= 0 || S <= 0 || S > (1 << 30) || runs <= 0 || runs > (1 << 20) || heads <= 0 ||
+        heads > 65535)
+        return VMOBA_ERR_INVALID_ARG;
+    atomic_rows_probe_kernel<<<dim3((unsigned)runs, (unsigned)heads), dim3(256), 0, (hipStream_t)stream>>>(dq, lists, n_lists, cnt, (int)S);
+    VMOBA_CHECK_LAUNCH();
+    return VMOBA_OK;
+}
