@@ -27,7 +27,8 @@
  *    ptr + (b*stride_b + s*stride_s + h*stride_h + d) elements; the D channels of one
  *    (token, head) are contiguous and 16-byte aligned.
  *  - Supported: head dimension D in {64, 128}; dtype float32 or bfloat16 (all tensors of a
- *    call share one dtype); 1 <= n_blocks <= 256; bidirectional attention (no causal mask).
+ *    call share one dtype); 1 <= n_blocks <= 512 (float32: as long as the score kernel's tile of block means
+ *    fits the LDS, n_blocks * (D + 64) * 4 + 12 KB <= 160 KB); bidirectional attention (no causal mask).
  */
 #ifndef VMOBA_H
 #define VMOBA_H
@@ -133,7 +134,11 @@ int vmoba_partition(const vmoba_grid* g, int inverse, int B, int Hh, int D, int 
  * cumulative-sum threshold (Eq. 4) and the TopkMask of Eq. 3, returned as a bit mask and as
  * two sparse lists.
  *
- *  Qp, Kp      block-order tensors (b, s, h, d) with the strides given
+ *  Qp, Kp      tensors (b, s, h, d) with the strides given.  Row k of Kp is key position k in BLOCK order (keys are
+ *              what Eq. 1 rearranges).  Row q of Qp is "query q" in every output -- the rows of P and mask, row_ptr,
+ *              the entries of q_idx, later LSE: pass the block-order Q' (query ids are then block-order positions),
+ *              or the caller's Q as it is (query ids are then token ids; the paper rearranges K only and the
+ *              selection treats every query on its own, so Q never has to move)
  *  tau         threshold in (0, 1]; tau >= 1 keeps every pair
  *  score_scale factor applied to <q, b> before the soft-max (1/sqrt(D) by convention)
  *  mode        a vmoba_select_mode, optionally | VMOBA_SELECT_OWN_BLOCK (then allow S more pairs in
@@ -145,7 +150,7 @@ int vmoba_partition(const vmoba_grid* g, int inverse, int B, int Hh, int D, int 
  *  mask   out  [B, Hh, S, ceil(n_blocks/32)] uint32, bit j of a row = query keeps block j
  *  Per (b, h) the pool of S*n_blocks values is cut after the k best, k = the shortest
  *  descending prefix whose sum reaches tau*S; equal values at the cut are taken in ascending
- *  (query, block) order.  k_out [B*Hh] int64 and theta_out [B*Hh] float (the k-th value; 0 when
+ *  (query id, block) order.  k_out [B*Hh] int64 and theta_out [B*Hh] float (the k-th value; 0 when
  *  every pair is kept).
  *  Sparse lists, every (b, h) owning a segment of nnz_capacity entries starting at
  *  (b*Hh + h)*nnz_capacity:
@@ -163,13 +168,15 @@ int vmoba_partition(const vmoba_grid* g, int inverse, int B, int Hh, int D, int 
  *  and that head's blk_ptr is all zero: vmoba_attn_fwd / vmoba_attn_bwd called with these lists treat the head as
  *  having selected nothing (O = 0, LSE = -inf, zero gradients) and read none of its incomplete list entries.
  *  mask, k_out, theta_out and row_ptr are complete either way.
+ *  query_pos   optional int32 [S]: block-order position of query q (the partition's inv_perm).  Only read with
+ *              VMOBA_SELECT_OWN_BLOCK, to find the block a query lies in; null = query q sits at position q.
  */
 int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
                  const vmoba_tensor* Qp, const vmoba_tensor* Kp, float tau, float score_scale,
                  int mode, int32_t topk, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
                  int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
                  int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
-                 void* workspace, size_t workspace_bytes, void* stream);
+                 const int32_t* query_pos, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * vmoba_select_static -- vmoba_select for callers that cannot allocate device memory or hand over a workspace:
@@ -189,15 +196,16 @@ int vmoba_select_static(int B, int Hh, int64_t S, int D, int32_t n_blocks, const
                         int mode, int32_t topk, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
                         int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
                         int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
-                        void* stream);
+                        const int32_t* query_pos, void* stream);
 
 /*
  * vmoba_attn_fwd -- Step 3 of Sec. 3.1: every query attends to the keys/values of its selected
  * blocks only.  O(q) = sum_n softmax_n(softmax_scale * <Q'(q), K'(n)>) V'(n) over the keys n of
  * the selected blocks; LSE [B, Hh, S] float32 is the natural-log-sum-exp of the scaled scores.
  * A query that selected nothing gets O = 0 and LSE = -inf.
- * Inputs: block-order Q', K', V', blk_off, and the lists written by vmoba_select with the same
- * nnz_capacity.  Accumulation and soft-max are float32; bfloat16 inputs are multiplied on the
+ * Inputs: Q as vmoba_select saw it (block-order Q', or the caller's Q with token ids as query ids), block-order
+ * K', V', blk_off, and the lists written by vmoba_select with the same nnz_capacity.  O and LSE are indexed
+ * by query id.  Accumulation and soft-max are float32; bfloat16 inputs are multiplied on the
  * matrix cores.
  *  out_rows  optional int32 [S].  Null: O is written in block order.  Otherwise block-order row q
  *            goes to row out_rows[q] of O: pass the partition's perm and a tensor in the caller's
@@ -219,10 +227,12 @@ int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int3
  * dS = A * (dP - delta), dQ = softmax_scale * dS K, dK = softmax_scale * dS^T Q.
  * O and LSE are the forward results; dQ, dK, dV are written (not accumulated into).  Rows that
  * selected nothing get dQ = 0 and contribute nothing.
- *  rows  optional int32 [S].  Null: all tensors are in block order.  Otherwise O, dO, dQ, dK and dV
- *        (not Q', K', V', LSE) are addressed through it -- block-order row r is row rows[r] of each:
- *        pass the partition's perm and tensors in the caller's token order to skip the partition
- *        of dO and the inverse partition of the three gradients.
+ *  rows  optional int32 [S].  Null: O, dO, dQ are indexed by query id and dK, dV by key position like Q and K', V'.
+ *        Otherwise O, dO, dQ, dK and dV (not Q, K', V', LSE) are addressed through it -- row r is row rows[r] of
+ *        each: with block-order Q', pass the partition's perm and tensors in the caller's token order to skip the
+ *        partition of dO and the inverse partition of the three gradients.
+ *  key_rows  optional int32 [S]: row map of dK and dV alone (key position k -> row key_rows[k]); overrides `rows`
+ *        for them.  With the caller's Q as it is (query ids = token ids): rows = null, key_rows = perm.
  *  Limit (bfloat16): S < 2^24, and for Q', K', V' and dO a positive stride_s with stride_s * 2 < 2^24 and
  *  S * stride_s * 2 < 2^32 (one (batch, head) slice spans less than 4 GiB); otherwise
  *  VMOBA_ERR_UNSUPPORTED.
@@ -233,7 +243,8 @@ int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int3
                    const int32_t* blk_ptr, const int32_t* q_idx, const int32_t* row_ptr,
                    const int32_t* pair_pos, int64_t nnz_capacity, float softmax_scale,
                    const vmoba_tensor* dQ, const vmoba_tensor* dK, const vmoba_tensor* dV,
-                   const int32_t* rows, void* workspace, size_t workspace_bytes, void* stream);
+                   const int32_t* rows, const int32_t* key_rows, void* workspace, size_t workspace_bytes,
+                   void* stream);
 
 /*
  * vmoba_profile_events -- measurement aid, not part of the method.  Asks the library to record

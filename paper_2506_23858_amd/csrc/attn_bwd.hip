@@ -61,12 +61,12 @@ __global__ __launch_bounds__(256) void delta_kernel(TensorView O, TensorView dO,
 // order: the short ones fill the tail of the launch): kb_order[r] = block at rank r,
 // kb_start[r] = number of runs of the blocks at ranks 0..r-1.  One workgroup per head.
 // A last run of at most tail_max keys is not counted: the tail kernel takes those keys.
-__global__ __launch_bounds__(256) void key_run_order_kernel(const int* __restrict__ blk_off, const int* __restrict__ blk_ptr,
-                                                            int* __restrict__ kb_start, int* __restrict__ kb_order, int nb, int KPW,
-                                                            int tail_max) {
+__global__ __launch_bounds__(VMOBA_MAX_BLOCKS) void key_run_order_kernel(const int* __restrict__ blk_off, const int* __restrict__ blk_ptr,
+                                                                         int* __restrict__ kb_start, int* __restrict__ kb_order, int nb,
+                                                                         int KPW, int tail_max) {
     __shared__ int sCnt[VMOBA_MAX_BLOCKS];
     __shared__ int sRuns[VMOBA_MAX_BLOCKS];
-    const int bh = blockIdx.x, j = threadIdx.x;
+    const int bh = blockIdx.x, j = threadIdx.x;          // one thread per block
     const int* bp = blk_ptr + (long long)bh * (nb + 1);
     const int cnt = j < nb ? bp[j + 1] - bp[j] : -1;
     if (j < nb) sCnt[j] = cnt;
@@ -1159,7 +1159,8 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
                               const int32_t* blk_ptr, const int32_t* q_idx, const int32_t* row_ptr,
                               const int32_t* pair_pos, int64_t nnz_capacity, float softmax_scale,
                               const vmoba_tensor* dQ, const vmoba_tensor* dK, const vmoba_tensor* dV,
-                              const int32_t* rows, void* workspace, size_t workspace_bytes, void* stream) {
+                              const int32_t* rows, const int32_t* key_rows, void* workspace, size_t workspace_bytes,
+                              void* stream) {
     if (B <= 0 || Hh <= 0 || S <= 0 || n_blocks <= 0 || nnz_capacity <= 0) return VMOBA_ERR_INVALID_ARG;
     if (!blk_off || !blk_ptr || !q_idx || !row_ptr || !pair_pos || !LSE || !workspace) return VMOBA_ERR_INVALID_ARG;
     if (!tensor_ok(Qp) || !tensor_ok(Kp) || !tensor_ok(Vp) || !tensor_ok(O) || !tensor_ok(dO) || !tensor_ok(dQ) ||
@@ -1255,12 +1256,13 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     // ---- dK, dV
     {
         const int KPW = simple ? 64 : 128;      // keys per workgroup
-        key_run_order_kernel<<<dim3(BH), dim3(256), 0, st>>>(blk_off, blk_ptr, ws.kb_start, ws.kb_order, n_blocks, KPW, simple ? 0 : 32);
+        key_run_order_kernel<<<dim3(BH), dim3(VMOBA_MAX_BLOCKS), 0, st>>>(blk_off, blk_ptr, ws.kb_start, ws.kb_order, n_blocks, KPW, simple ? 0 : 32);
         VMOBA_CHECK_LAUNCH();
         // a multiple of 8 so that (workgroup id % 8) is the same for every head; + 8 for the per-XCD rounding
         dim3 grid((unsigned)((S / KPW + n_blocks + 7) / 8 * 8 + 8 + (simple ? 0 : n_blocks)), (unsigned)BH);
         VMOBA_PROFILE_BEGIN(2, st);
-#define DKV_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.kb_start, ws.kb_order, dKv, dVv, rows, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
+        const int32_t* krows = key_rows ? key_rows : rows;      // row map of dK and dV
+#define DKV_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.kb_start, ws.kb_order, dKv, dVv, krows, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
         if (simple) {
             if (D == 128) attn_bwd_dkv_simple_kernel<128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
             else attn_bwd_dkv_simple_kernel<64><<<grid, dim3(64), 0, st>>>(DKV_ARGS);

@@ -5,7 +5,7 @@
 #include <stddef.h>
 #include "vmoba.h"
 
-#define VMOBA_MAX_BLOCKS 256
+#define VMOBA_MAX_BLOCKS 512
 #define VMOBA_MAX_MASK_WORDS (VMOBA_MAX_BLOCKS / 32)
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));

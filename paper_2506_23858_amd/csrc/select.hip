@@ -220,14 +220,17 @@ __global__ __launch_bounds__(256) void score_kernel(TensorView Q, const float* _
 // With more than 128 blocks the three bfloat16 copies no longer fit the LDS; FLY keeps the means there as float32 (row
 // stride D + 4) and splits every operand after its fetch: the same three terms from the same operations, so P is the
 // same, at the price of vector work per matrix instruction.
+// With more than 256 blocks neither the means nor a query's scores fit: the host then launches the kernel once per
+// chunk of up to 256 blocks with RAW set -- the launch covers blocks [jb0, jb0 + nb) of nb_total and writes the scaled
+// scores themselves into its columns of P -- and softmax_rows_kernel below turns the rows into P afterwards.
 // wavefronts per workgroup of the matrix-core score kernel (two per SIMD share one copy of the block means in LDS)
 constexpr int SCORE_NW = 8, SCORE_NT = 64 * SCORE_NW, SCORE_QT = 32 * SCORE_NW;
-template <int D, bool FLY>
+template <int D, bool FLY, bool RAW>
 __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, const float* __restrict__ Bmean,
                                                          float* __restrict__ P, unsigned int* __restrict__ hist_cnt,
                                                          unsigned long long* __restrict__ hist_sum,
-                                                         int Hh, int S, int nb, float score_scale, int fix_shift,
-                                                         float2* __restrict__ row_stat) {
+                                                         int Hh, int S, int nb, int nb_total, int jb0, float score_scale,
+                                                         int fix_shift, float2* __restrict__ row_stat) {
     constexpr int STR = D + 8;                 // LDS row stride in bf16 elements
     constexpr int FSTR = D + 4;                // LDS row stride in float elements (FLY)
     constexpr int KSTEPS = D / 16;
@@ -247,7 +250,7 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
 
     // block means -> LDS, 16 bytes per lane and four loads in flight per lane (the head's means are one contiguous array)
     {
-        const f32x4_t* src4 = reinterpret_cast<const f32x4_t*>(Bmean + (long long)bh * nb * D);
+        const f32x4_t* src4 = reinterpret_cast<const f32x4_t*>(Bmean + ((long long)bh * nb_total + jb0) * D);
         const int n4 = nb * D / 4, n4_pad = nb_pad * D / 4;
         for (int i0 = tid; i0 < n4_pad; i0 += 4 * SCORE_NT) {
             f32x4_t x4[4];
@@ -289,7 +292,7 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
 
     const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     const int n_tiles = (S + SCORE_QT - 1) / SCORE_QT;
-    const bool vec_ok = (nb & 3) == 0;         // rows of P start 16-byte aligned
+    const bool vec_ok = ((nb_total | jb0) & 3) == 0;         // this launch's part of a row of P starts 16-byte aligned
     auto load_q = [&](int tile, bf16x8_t(&dst)[KSTEPS]) {
         const int qc = min(tile * SCORE_QT + wave * 32 + l32, S - 1);     // rows past the end recompute the last query; never stored
         const char* src = Q.ptr + ((long long)b * Q.stride_b + (long long)qc * Q.stride_s + (long long)h * Q.stride_h) * 2;
@@ -347,6 +350,30 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
             }
         }
         // accumulator value v of tile mt <-> block 32*mt + 8*(v>>2) + 4*hf + (v&3)
+        if constexpr (RAW) {
+            if (q < S) {
+                float* dst = P + ((long long)bh * S + q) * nb_total + jb0;
+#pragma unroll
+                for (int mt = 0; mt < MAX_MT; ++mt) {
+                    if (mt < n_mt) {
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            const int j0 = mt * 32 + 8 * g + 4 * hf;
+                            if (vec_ok && j0 + 3 < nb) {
+                                const f32x4_t o = {acc[mt][4 * g] * score_scale, acc[mt][4 * g + 1] * score_scale,
+                                                   acc[mt][4 * g + 2] * score_scale, acc[mt][4 * g + 3] * score_scale};
+                                *reinterpret_cast<f32x4_t*>(dst + j0) = o;
+                            } else {
+#pragma unroll
+                                for (int r = 0; r < 4; ++r) if (j0 + r < nb) dst[j0 + r] = acc[mt][4 * g + r] * score_scale;
+                            }
+                        }
+                    }
+                }
+            }
+            continue;
+        }
+        // accumulator value v of tile mt <-> block 32*mt + 8*(v>>2) + 4*hf + (v&3)
         float m = -INFINITY;
 #pragma unroll
         for (int mt = 0; mt < MAX_MT; ++mt)
@@ -370,7 +397,7 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
         den += __shfl_xor(den, 32, 64);
         if (row_stat && q < S && hf == 0) row_stat[(long long)bh * S + q] = make_float2(m, den);
         if (q < S) {
-            float* dst = P + ((long long)bh * S + q) * nb;
+            float* dst = P + ((long long)bh * S + q) * nb_total + jb0;
             const float inv_den = 1.f / den;
 #pragma unroll
             for (int mt = 0; mt < MAX_MT; ++mt) {
@@ -403,6 +430,62 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
     }
     __syncthreads();
     for (int i = tid; i < HIST_BINS; i += SCORE_NT) {
+        const unsigned int c = sCnt[i];
+        if (c) {
+            atomicAdd(&hist_cnt[(long long)bh * HIST_BINS + i], c);
+            atomicAdd(&hist_sum[(long long)bh * HIST_BINS + i], sSum[i]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// More than 256 blocks: P holds the scaled scores (score_mfma_kernel with RAW); this kernel turns every row into its
+// soft-max in place and takes the first radix level.  One wavefront per row, a lane owns columns lane, lane + 64, ...
+__global__ __launch_bounds__(256) void softmax_rows_kernel(float* __restrict__ P, unsigned int* __restrict__ hist_cnt,
+                                                           unsigned long long* __restrict__ hist_sum, int S, int nb,
+                                                           int fix_shift, float2* __restrict__ row_stat) {
+    constexpr int MAXC = VMOBA_MAX_BLOCKS / 64;
+    __shared__ unsigned int sCnt[HIST_BINS];
+    __shared__ unsigned long long sSum[HIST_BINS];
+    const int bh = blockIdx.y;
+    for (int i = threadIdx.x; i < HIST_BINS; i += 256) { sCnt[i] = 0u; sSum[i] = 0ull; }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    for (int q = blockIdx.x * 4 + wv; q < S; q += gridDim.x * 4) {
+        float* row = P + ((long long)bh * S + q) * nb;
+        float v[MAXC];
+        float m = -INFINITY;
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) {
+            const int j = c * 64 + lane;
+            v[c] = j < nb ? row[j] : -INFINITY;
+            m = fmaxf(m, v[c]);
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+        float den = 0.f;
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) {
+            v[c] = expf(v[c] - m);            // exp(-inf) = 0 past the row's end
+            den += v[c];
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) den += __shfl_xor(den, off, 64);
+        if (row_stat && lane == 0) row_stat[(long long)bh * S + q] = make_float2(m, den);
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) {
+            const int j = c * 64 + lane;
+            if (j < nb) {
+                const float p = v[c] / den;
+                row[j] = p;
+                const unsigned int bin = min(__float_as_uint(p) >> 20, (unsigned)(HIST_BINS - 1));
+                atomicAdd(&sCnt[bin], 1u);
+                atomicAdd(&sSum[bin], to_fixed(p, fix_shift));
+            }
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < HIST_BINS; i += 256) {
         const unsigned int c = sCnt[i];
         if (c) {
             atomicAdd(&hist_cnt[(long long)bh * HIST_BINS + i], c);
@@ -569,15 +652,25 @@ __global__ __launch_bounds__(256) void refine_hist_kernel(const float* __restric
     const u32x4_t* src = reinterpret_cast<const u32x4_t*>(P + (long long)bh * pool_size);
     // 16-byte loads need every head's pool to start on a 16-byte boundary
     const long long n4 = (pool_size % 4 == 0) ? pool_size / 4 : 0;
-    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n4; i += (long long)gridDim.x * 256) {
-        u32x4_t v = src[i];
-        unsigned int u[4] = {v.x, v.y, v.z, v.w};
+    // four 16-byte loads in flight per thread: a workgroup takes runs of 4 * 256 vectors
+    for (long long i0 = (long long)blockIdx.x * 1024 + threadIdx.x; i0 < n4; i0 += (long long)gridDim.x * 1024) {
+        u32x4_t v[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if ((u[e] >> SHIFT_HI) == want) {
-                unsigned int bin = (u[e] >> SHIFT_LO) & (HIST_BINS - 1);
-                atomicAdd(&sCnt[bin], 1u);
-                atomicAdd(&sSum[bin], to_fixed(__uint_as_float(u[e]), fix_shift));
+        for (int k = 0; k < 4; ++k) {
+            const long long i = i0 + 256 * k;
+            const u32x4_t none = {~0u, ~0u, ~0u, ~0u};      // matches no prefix (a NaN pattern; P holds none)
+            v[k] = i < n4 ? src[i] : none;
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const unsigned int u[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if ((u[e] >> SHIFT_HI) == want) {
+                    unsigned int bin = (u[e] >> SHIFT_LO) & (HIST_BINS - 1);
+                    atomicAdd(&sCnt[bin], 1u);
+                    atomicAdd(&sSum[bin], to_fixed(__uint_as_float(u[e]), fix_shift));
+                }
             }
         }
     }
@@ -703,11 +796,13 @@ __device__ __forceinline__ int block_of_position(const int* __restrict__ blk_off
     return lo;
 }
 
-// own_blk_off: null, or blk_off when every query also keeps the block it lies in itself.
+// own_blk_off: null, or blk_off when every query also keeps the block it lies in itself; query_pos: null when query q
+// sits at block-order position q, else the position of every query (queries kept in the caller's token order).
 __global__ __launch_bounds__(256) void mask_kernel(const float* __restrict__ P, const HeadState* __restrict__ state,
                                                    const int* __restrict__ tie_base, unsigned int* __restrict__ mask,
                                                    int* __restrict__ rowcnt, int* __restrict__ wcnt,
-                                                   int S, int nb, int n_waves, const int* __restrict__ own_blk_off) {
+                                                   int S, int nb, int n_waves, const int* __restrict__ own_blk_off,
+                                                   const int* __restrict__ query_pos) {
     __shared__ unsigned int sGt[4][64][VMOBA_MAX_MASK_WORDS + 1];
     __shared__ unsigned int sTie[4][64][VMOBA_MAX_MASK_WORDS + 1];
     const int bh = blockIdx.y;
@@ -789,7 +884,7 @@ __global__ __launch_bounds__(256) void mask_kernel(const float* __restrict__ P, 
     if (live) {
         const bool all_ties = (st.take == st.n_tie);
         int rank = all_ties ? 0 : tie_base[(long long)bh * (S + 1) + q];
-        const int own = own_blk_off ? block_of_position(own_blk_off, nb, q) : -1;
+        const int own = own_blk_off ? block_of_position(own_blk_off, nb, query_pos ? query_pos[q] : q) : -1;
 #pragma unroll
         for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) {
             unsigned int g = 0;
@@ -817,13 +912,18 @@ __global__ __launch_bounds__(256) void mask_kernel(const float* __restrict__ P, 
 #pragma unroll
         for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) mw[wd] = 0;
     }
-    // per-block count over the 64 rows of this wavefront
-    for (int j = 0; j < nb; ++j) {
-        unsigned int word = 0;
+    // per-block count over the 64 rows of this wavefront (word by word, so that a word is one register)
 #pragma unroll
-        for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) if (wd == (j >> 5)) word = mw[wd];
-        const unsigned long long bal = __ballot((word >> (j & 31)) & 1u);
-        if (lane == 0 && active) wcnt[((long long)bh * nb + j) * n_waves + w] = __popcll(bal);
+    for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) {
+        if (wd * 32 < nb) {
+            const unsigned int word = mw[wd];
+            const int jn = min(32, nb - wd * 32);
+            for (int bit = 0; bit < jn; ++bit) {
+                const int j = wd * 32 + bit;
+                const unsigned long long bal = __ballot((word >> bit) & 1u);
+                if (lane == 0 && active) wcnt[((long long)bh * nb + j) * n_waves + w] = __popcll(bal);
+            }
+        }
     }
 }
 
@@ -837,7 +937,7 @@ template <bool LOCAL_TOPK>
 __global__ __launch_bounds__(256) void local_mask_kernel(const float* __restrict__ P, unsigned int* __restrict__ mask,
                                                          int* __restrict__ rowcnt, int* __restrict__ wcnt,
                                                          int S, int nb, int n_waves, int topk, float tau,
-                                                         const int* __restrict__ own_blk_off) {
+                                                         const int* __restrict__ own_blk_off, const int* __restrict__ query_pos) {
     constexpr int MAXC = VMOBA_MAX_BLOCKS / 64;
     __shared__ float sRow[4][VMOBA_MAX_BLOCKS];
     __shared__ unsigned int sKeep[4][64][VMOBA_MAX_MASK_WORDS + 1];
@@ -867,9 +967,11 @@ __global__ __launch_bounds__(256) void local_mask_kernel(const float* __restrict
             const float x = sRow[wv][jp];
 #pragma unroll
             for (int c = 0; c < MAXC; ++c) {
-                const int j = c * 64 + lane;
-                const bool first = (x > v[c]) || (x == v[c] && jp < j);
-                before[c] += first ? (LOCAL_TOPK ? 1.f : x) : 0.f;
+                if (c < ncol) {               // uniform: columns past the row's end are not ranked
+                    const int j = c * 64 + lane;
+                    const bool first = (x > v[c]) || (x == v[c] && jp < j);
+                    before[c] += first ? (LOCAL_TOPK ? 1.f : x) : 0.f;
+                }
             }
         }
 #pragma unroll
@@ -889,7 +991,7 @@ __global__ __launch_bounds__(256) void local_mask_kernel(const float* __restrict
     const int q = q0 + lane;
     const bool live = lane < rows;
     int cnt = 0;
-    const int own = (own_blk_off && live) ? block_of_position(own_blk_off, nb, q) : -1;
+    const int own = (own_blk_off && live) ? block_of_position(own_blk_off, nb, query_pos ? query_pos[q] : q) : -1;
 #pragma unroll
     for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) {
         unsigned int g = 0;
@@ -902,12 +1004,17 @@ __global__ __launch_bounds__(256) void local_mask_kernel(const float* __restrict
         mw[wd] = g;
     }
     if (live) rowcnt[(long long)bh * S + q] = cnt;
-    for (int j = 0; j < nb; ++j) {
-        unsigned int word = 0;
 #pragma unroll
-        for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) if (wd == (j >> 5)) word = mw[wd];
-        const unsigned long long bal = __ballot((word >> (j & 31)) & 1u);
-        if (lane == 0 && active) wcnt[((long long)bh * nb + j) * n_waves + w] = __popcll(bal);
+    for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) {
+        if (wd * 32 < nb) {
+            const unsigned int word = mw[wd];
+            const int jn = min(32, nb - wd * 32);
+            for (int bit = 0; bit < jn; ++bit) {
+                const int j = wd * 32 + bit;
+                const unsigned long long bal = __ballot((word >> bit) & 1u);
+                if (lane == 0 && active) wcnt[((long long)bh * nb + j) * n_waves + w] = __popcll(bal);
+            }
+        }
     }
 }
 
@@ -1012,24 +1119,28 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(const unsigned int* __r
     }
     const bool staged = run1 - run0 <= FILL_STAGE && run1 <= cap;       // wave-uniform
     int lr = (int)(r - run0);                                            // position inside the run
-    for (int j = 0; j < nb; ++j) {
-        unsigned int word = 0;
 #pragma unroll
-        for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) if (wd == (j >> 5)) word = mw[wd];
-        const bool bit = (word >> (j & 31)) & 1u;
-        const unsigned long long bal = __ballot(bit);
-        if (bit) {
-            const long long pos = (long long)sBase[wv][j] + __popcll(bal & lt_mask);
-            if (pos < cap) q_idx[seg + pos] = q;
-            if (staged) {
-                if (lr < FILL_STAGE) {         // always true: row_ptr is the scan of the rows' bit counts
-                    sCol[wv][lr] = (unsigned short)j;
-                    sPos[wv][lr] = (int)pos;
+    for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) {          // word by word, so that a word is one register
+        if (wd * 32 >= nb) continue;
+        const unsigned int word = mw[wd];
+        const int jn = min(32, nb - wd * 32);
+        for (int b = 0; b < jn; ++b) {
+            const int j = wd * 32 + b;
+            const bool bit = (word >> b) & 1u;
+            const unsigned long long bal = __ballot(bit);
+            if (bit) {
+                const long long pos = (long long)sBase[wv][j] + __popcll(bal & lt_mask);
+                if (pos < cap) q_idx[seg + pos] = q;
+                if (staged) {
+                    if (lr < FILL_STAGE) {         // always true: row_ptr is the scan of the rows' bit counts
+                        sCol[wv][lr] = (unsigned short)j;
+                        sPos[wv][lr] = (int)pos;
+                    }
+                    ++lr;
+                } else {
+                    if (r < cap) { col_idx[seg + r] = j; pair_pos[seg + r] = (int)pos; }
+                    ++r;
                 }
-                ++lr;
-            } else {
-                if (r < cap) { col_idx[seg + r] = j; pair_pos[seg + r] = (int)pos; }
-                ++r;
             }
         }
     }
@@ -1051,7 +1162,7 @@ size_t score_lds_bytes(int nb, int D) {
 // compute unit, once per kernel (slot) and device.
 int allow_full_lds(const void* kernel, int slot) {
     static std::mutex mu;
-    static bool done[6][64] = {};
+    static bool done[8][64] = {};
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return VMOBA_ERR_HIP;
     std::lock_guard<std::mutex> lock(mu);
@@ -1106,7 +1217,7 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
                 int mode, int32_t topk, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
                 int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
                 int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
-                void* workspace, size_t workspace_bytes, void* stream) {
+                const int32_t* query_pos, void* workspace, size_t workspace_bytes, void* stream) {
     {
         const int rc = select_args_ok(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode, topk, Bmean, P, mask,
                                       blk_ptr, q_idx, row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status);
@@ -1120,7 +1231,9 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
     const bool bf16 = Qp->dtype == VMOBA_BF16;
     // LDS of the score kernel this call launches: bfloat16 queries go to the matrix-core kernel (block means as three
     // bfloat16 terms up to 128 blocks, as float32 beyond), float32 queries to the plain FMA kernel
-    const int nb_pad = (n_blocks + 31) & ~31;
+    constexpr int SCORE_CHUNK = 256;                        // blocks per launch of the score kernel beyond 256 blocks
+    const bool chunked = bf16 && n_blocks > SCORE_CHUNK;
+    const int nb_pad = chunked ? SCORE_CHUNK : ((n_blocks + 31) & ~31);
     const bool fly = n_blocks > 128;
     const size_t lds_mfma = (fly ? (size_t)nb_pad * (D + 4) * 4 : (size_t)3 * nb_pad * (D + 8) * 2) + HIST_BINS * 12;
     const size_t lds = bf16 ? lds_mfma : score_lds_bytes(n_blocks, D);
@@ -1172,17 +1285,27 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
     } while (0)
     if (bf16) {
         dim3 mgrid((unsigned)ceil_div64(ceil_div64(S, SCORE_QT), 2), (unsigned)BH);
-#define LAUNCH_SCORE_MFMA(DD, FL)                                                                         \
+#define LAUNCH_SCORE_MFMA(DD, FL, RW, NBC, JB0)                                                           \
     do {                                                                                                  \
-        auto kfn = score_mfma_kernel<DD, FL>;                                                             \
-        if (allow_full_lds((const void*)kfn, 2 + (DD == 128 ? 0 : 2) + (FL ? 1 : 0)) != VMOBA_OK) return VMOBA_ERR_HIP; \
-        kfn<<<mgrid, dim3(SCORE_NT), lds, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks, score_scale, \
-                                                fix_shift, row_stat);                                     \
+        auto kfn = score_mfma_kernel<DD, FL, RW>;                                                         \
+        if (allow_full_lds((const void*)kfn, 2 + (DD == 128 ? 0 : 3) + (RW ? 2 : FL ? 1 : 0)) != VMOBA_OK) return VMOBA_ERR_HIP; \
+        kfn<<<mgrid, dim3(SCORE_NT), lds, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, NBC, n_blocks, JB0, \
+                                                score_scale, fix_shift, row_stat);                        \
     } while (0)
-        if (D == 128 && fly) LAUNCH_SCORE_MFMA(128, true);
-        else if (D == 128) LAUNCH_SCORE_MFMA(128, false);
-        else if (fly) LAUNCH_SCORE_MFMA(64, true);
-        else LAUNCH_SCORE_MFMA(64, false);
+        if (chunked) {
+            // more than 256 blocks: scaled scores chunk by chunk, then the soft-max of the rows and the first radix level
+            for (int jb0 = 0; jb0 < n_blocks; jb0 += SCORE_CHUNK) {
+                const int nbc = std::min(SCORE_CHUNK, n_blocks - jb0);
+                if (D == 128) LAUNCH_SCORE_MFMA(128, true, true, nbc, jb0);
+                else LAUNCH_SCORE_MFMA(64, true, true, nbc, jb0);
+                VMOBA_CHECK_LAUNCH();
+            }
+            softmax_rows_kernel<<<dim3((unsigned)std::min<int64_t>(ceil_div64(S, 4 * 8), 2048), (unsigned)BH), dim3(256), 0, st>>>(
+                P, ws.hist_cnt, ws.hist_sum, (int)S, n_blocks, fix_shift, row_stat);
+        } else if (D == 128 && fly) LAUNCH_SCORE_MFMA(128, true, false, n_blocks, 0);
+        else if (D == 128) LAUNCH_SCORE_MFMA(128, false, false, n_blocks, 0);
+        else if (fly) LAUNCH_SCORE_MFMA(64, true, false, n_blocks, 0);
+        else LAUNCH_SCORE_MFMA(64, false, false, n_blocks, 0);
 #undef LAUNCH_SCORE_MFMA
     } else if (D == 128) LAUNCH_SCORE(128);
     else LAUNCH_SCORE(64);
@@ -1203,15 +1326,15 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
     unsigned int* hc2 = ws.hist_cnt + (size_t)2 * BH * HIST_BINS;
     unsigned long long* hs1 = ws.hist_sum + (size_t)BH * HIST_BINS;
     unsigned long long* hs2 = ws.hist_sum + (size_t)2 * BH * HIST_BINS;
-    const unsigned refine_gx = (unsigned)std::max<int64_t>(1, std::min<int64_t>(ceil_div64(pool / 4, 256 * 8), 2048));
+    const unsigned refine_gx = (unsigned)std::max<int64_t>(1, std::min<int64_t>(ceil_div64(pool / 4, 1024 * 2), 2048));
 
     const unsigned wave_gx = (unsigned)ceil_div64(n_waves, 4);
     const bool local = mode == VMOBA_LOCAL_TOPK || mode == VMOBA_LOCAL_THRESHOLD;
     if (local) {
         if (mode == VMOBA_LOCAL_TOPK)
-            local_mask_kernel<true><<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, mask, ws.rowcnt, ws.wcnt, (int)S, n_blocks, n_waves, topk, tau, own_off);
+            local_mask_kernel<true><<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, mask, ws.rowcnt, ws.wcnt, (int)S, n_blocks, n_waves, topk, tau, own_off, query_pos);
         else
-            local_mask_kernel<false><<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, mask, ws.rowcnt, ws.wcnt, (int)S, n_blocks, n_waves, topk, tau, own_off);
+            local_mask_kernel<false><<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, mask, ws.rowcnt, ws.wcnt, (int)S, n_blocks, n_waves, topk, tau, own_off, query_pos);
         VMOBA_CHECK_LAUNCH();
     } else {
 #define SCAN_LEVEL(LV, HC, HS)                                                                                        \
@@ -1238,7 +1361,7 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
         row_scan_kernel<<<dim3(BH), dim3(SCAN_THREADS), 0, st>>>(ws.ties, ws.tie_base, ws.state, 1, (int)S);
         VMOBA_CHECK_LAUNCH();
         mask_kernel<<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, ws.state, ws.tie_base, mask, ws.rowcnt, ws.wcnt,
-                                                            (int)S, n_blocks, n_waves, own_off);
+                                                            (int)S, n_blocks, n_waves, own_off, query_pos);
         VMOBA_CHECK_LAUNCH();
     }
     row_scan_kernel<<<dim3(BH), dim3(SCAN_THREADS), 0, st>>>(ws.rowcnt, row_ptr, ws.state, 0, (int)S);
@@ -1265,10 +1388,10 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
                             int mode, int32_t topk, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
                             int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
                             int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
-                            void* workspace, size_t workspace_bytes, void* stream) {
+                            const int32_t* query_pos, void* workspace, size_t workspace_bytes, void* stream) {
     return select_impl(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode, topk, Bmean, P, mask, blk_ptr, q_idx,
-                       row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status, workspace, workspace_bytes,
-                       stream);
+                       row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status, query_pos, workspace,
+                       workspace_bytes, stream);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1305,7 +1428,7 @@ extern "C" int vmoba_select_static(int B, int Hh, int64_t S, int D, int32_t n_bl
                                    int mode, int32_t topk, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
                                    int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
                                    int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
-                                   void* stream) {
+                                   const int32_t* query_pos, void* stream) {
     // everything that can be rejected on the host first, the size limit included
     const int rc = select_args_ok(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode, topk, Bmean, P, mask,
                                   blk_ptr, q_idx, row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status);
@@ -1316,6 +1439,6 @@ extern "C" int vmoba_select_static(int B, int Hh, int64_t S, int D, int32_t n_bl
     const int rs = static_scratch_of_current_device(&ws);
     if (rs != VMOBA_OK) return rs;
     return select_impl(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode, topk, Bmean, P, mask, blk_ptr, q_idx,
-                       row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status, ws,
+                       row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status, query_pos, ws,
                        VMOBA_SELECT_STATIC_MAX_BYTES, stream);
 }

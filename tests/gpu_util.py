@@ -109,14 +109,19 @@ def unpack_mask(words: np.ndarray, nb: int) -> np.ndarray:
 
 
 def run_gpu(Q, K, V, dO, grid, block=(0, 0, 0), chunk=0, tau=0.25, dtype=torch.float32,
-            score_scale=None, softmax_scale=None, mode=0, topk=0, fused_io=False):
+            score_scale=None, softmax_scale=None, mode=0, topk=0, fused_io=False, q_in_place=False):
     """Whole layer on the GPU.  Q, K, V, dO: numpy [B, S, Hh, D] float32 (dO may be None).
     With fused_io the attention calls write O and the gradients in the caller's token order
-    themselves; their block-order views (Op, dQp, ...) are then gathered here on the host."""
+    themselves; their block-order views (Op, dQp, ...) are then gathered here on the host.
+    With q_in_place the library never moves Q and numbers the queries by token: P, mask, LSE are
+    brought to block order here (row p = token perm[p]) so that they compare with the oracle's;
+    the lists stay as written (query ids = token ids) next to `mask_q`, the mask in that order."""
     B, S, Hh, D = Q.shape
     plan = vb.LayerPlan(B, Hh, D, grid, block, chunk, tau, dtype, score_scale=score_scale,
-                        softmax_scale=softmax_scale, need_bwd=dO is not None, mode=mode, topk=topk, fused_io=fused_io)
+                        softmax_scale=softmax_scale, need_bwd=dO is not None, mode=mode, topk=topk, fused_io=fused_io,
+                        q_in_place=q_in_place)
     assert plan.S == S
+    fused_io = plan.fused_io
     q, k, v = (to_dev(x, dtype) for x in (Q, K, V))
     plan.forward(q, k, v)
     out = {}
@@ -125,13 +130,21 @@ def run_gpu(Q, K, V, dO, grid, block=(0, 0, 0), chunk=0, tau=0.25, dtype=torch.f
     torch.cuda.synchronize()
     assert int(plan.dev_status.item()) == 0
     nb = plan.nb
+    perm = plan.perm.cpu().numpy()
+    mask_q = unpack_mask(plan.mask.cpu().numpy(), nb)
+    P, LSE = plan.P.cpu().numpy(), plan.LSE.cpu().numpy()
+    if q_in_place:
+        Qp = np.ascontiguousarray(Q[:, perm].transpose(0, 2, 1, 3))      # the library holds no block-order copy of Q
+        P, LSE, mask = P[:, :, perm], LSE[:, :, perm], mask_q[:, :, perm]
+    else:
+        Qp, mask = np32(plan.Qp.permute(0, 2, 1, 3)), mask_q
     out.update(plan=plan, nb=nb, cap=plan.cap,
-               perm=plan.perm.cpu().numpy(), inv_perm=plan.inv_perm.cpu().numpy(),
+               perm=perm, inv_perm=plan.inv_perm.cpu().numpy(),
                blk_off=plan.blk_off.cpu().numpy(),
-               Qp=np32(plan.Qp.permute(0, 2, 1, 3)), Kp=np32(plan.Kp.permute(0, 2, 1, 3)),
+               Qp=Qp, Kp=np32(plan.Kp.permute(0, 2, 1, 3)),
                Vp=np32(plan.Vp.permute(0, 2, 1, 3)),
-               O=np32(plan.O), LSE=plan.LSE.cpu().numpy(), Bmean=plan.Bmean.cpu().numpy(),
-               P=plan.P.cpu().numpy(), mask=unpack_mask(plan.mask.cpu().numpy(), nb),
+               O=np32(plan.O), LSE=LSE, Bmean=plan.Bmean.cpu().numpy(),
+               P=P, mask=mask, mask_q=mask_q,
                k=plan.k_out.cpu().numpy().reshape(B, Hh), theta=plan.theta.cpu().numpy().reshape(B, Hh),
                blk_ptr=plan.blk_ptr.cpu().numpy().reshape(B, Hh, nb + 1),
                row_ptr=plan.row_ptr.cpu().numpy().reshape(B, Hh, S + 1),
@@ -150,8 +163,8 @@ def run_gpu(Q, K, V, dO, grid, block=(0, 0, 0), chunk=0, tau=0.25, dtype=torch.f
 
 
 def check_lists(g, b, h):
-    """The sparse lists of head (b, h) must describe exactly the GPU's own bit mask."""
-    mask = g["mask"][b, h]
+    """The sparse lists of head (b, h) must describe exactly the GPU's own bit mask (both numbered by query id)."""
+    mask = g.get("mask_q", g["mask"])[b, h]
     blk_ptr, q_idx, row_ptr, col_idx = vo.csr_from_mask(mask)
     nnz = int(mask.sum())
     assert nnz == int(g["k"][b, h]), (nnz, g["k"][b, h])

@@ -52,11 +52,11 @@ def oracle_with_gpu_mask(g, Q, K, V, dO, softmax_scale):
     return res
 
 
-def compare_layer(Q, K, V, dO, grid, block, chunk, tau, dtype, label="", mode=0, topk=0, fused_io=False):
+def compare_layer(Q, K, V, dO, grid, block, chunk, tau, dtype, label="", mode=0, topk=0, fused_io=False, q_in_place=False):
     B, S, Hh, D = Q.shape
     case = f"{label} S={S} Hh={Hh} D={D} grid={grid} block={block} chunk={chunk} tau={tau} mode={mode}"
     print(f"[parity] {case} {dtype}", flush=True)
-    g = gu.run_gpu(Q, K, V, dO, grid, block, chunk, tau, dtype, mode=mode, topk=topk, fused_io=fused_io)
+    g = gu.run_gpu(Q, K, V, dO, grid, block, chunk, tau, dtype, mode=mode, topk=topk, fused_io=fused_io, q_in_place=q_in_place)
     o = oracle_selection(Q, K, grid, block, chunk, tau, mode, topk)
     # --- partition: bit exact
     assert np.array_equal(g["perm"], o["perm"])
@@ -210,6 +210,26 @@ def test_fused_io_matches_oracle_and_unfused(dtype):
         assert np.array_equal(g[n], u[n]), n
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("mode,topk", [(0, 0), (vb.LOCAL_TOPK | vb.SELECT_OWN_BLOCK, 2)])
+def test_queries_in_place(dtype, mode, topk):
+    """Only K and V are rearranged (Eq. 1 as written); Q is read where the caller has it and queries are numbered by
+    token: against the oracle, and against the path that also permutes Q -- every query's O, LSE and dQ bit for bit
+    (a query's arithmetic does not depend on its neighbours in a tile), dK and dV to rounding (their sums over the
+    queries run in another order).  The own-block flag finds a query's block through its position."""
+    grid, block = (5, 7, 9), (2, 3, 4)
+    S = grid[0] * grid[1] * grid[2]
+    Q, K, V, dO = (synth.to_bf16_grid(synth.iid_normal(160 + i, (2, S, 3, 64))) for i in range(4))
+    g, o = compare_layer(Q, K, V, dO, grid, block, 0, 0.3, dtype, "q-in-place", mode=mode, topk=topk, q_in_place=True)
+    assert g["plan"].Qp is None
+    u = gu.run_gpu(Q, K, V, dO, grid, block, 0, 0.3, dtype, mode=mode, topk=topk, fused_io=True)
+    for n in ("P", "mask", "k", "O", "LSE", "dQ"):
+        assert np.array_equal(g[n], u[n]), n
+    tol = 1e-5 if dtype == torch.float32 else 2e-2
+    for n in ("dK", "dV"):
+        np.testing.assert_allclose(g[n], u[n], rtol=tol, atol=tol)
+
+
 def test_tau_one_is_dense_attention():
     c = synth.CONFIGS["tiny"]
     Q, K, V, dO = synth.make_qkv("tiny")
@@ -290,6 +310,25 @@ def test_bf16_many_blocks_per_row(tau):
     g, o = compare_layer(Q, K, V, dO, grid, block, 0, tau, torch.bfloat16, f"many-blocks tau={tau}")
     per_64_rows = g["row_ptr"][0, :, 64::64] - g["row_ptr"][0, :, :-64:64]
     assert (per_64_rows.max() > 2048) == (tau > 0.8), per_64_rows.max()
+
+
+@pytest.mark.parametrize("grid,block,mode,topk", [
+    ((5, 6, 20), (1, 1, 2), 0, 0),       # 300 blocks: a full chunk of 256 and one of 44
+    ((4, 16, 16), (1, 2, 1), 0, 0),      # 512 blocks, the most the library takes
+    ((5, 6, 20), (1, 1, 2), 1, 7),       # per-query top-k over 300 blocks
+    ((5, 6, 20), (1, 1, 2), 4, 0),       # pool soft-max over 300 blocks (row statistics from the chunked path)
+])
+def test_bf16_more_than_256_blocks(grid, block, mode, topk):
+    """Beyond 256 blocks the score kernel runs once per chunk of 256 blocks and a second kernel normalises the rows;
+    mask rows have up to 16 words."""
+    S = grid[0] * grid[1] * grid[2]
+    Q, K, V, dO = (synth.to_bf16_grid(synth.iid_normal(330 + i, (1, S, 2, 128))) for i in range(4))
+    g, o = compare_layer(Q, K, V, dO, grid, block, 0, 0.3, torch.bfloat16, f"many-blocks-{g_nb(grid, block)}", mode=mode, topk=topk)
+    assert g["nb"] == g_nb(grid, block) > 256
+
+
+def g_nb(grid, block):
+    return math.prod(-(-a // b) for a, b in zip(grid, block))
 
 
 def test_bf16_mid_all_heads():
