@@ -263,6 +263,8 @@ def main():
     ap.add_argument("--kinds", default="1d,2d,3d")
     ap.add_argument("--no-extras", action="store_true", help="skip the copy-rate probe and the tau = 0.5 run (profiling runs)")
     ap.add_argument("--input-sets", type=int, default=3, help="copies of the inputs the steps rotate over")
+    ap.add_argument("--kv-in-place", action="store_true",
+                    help="rearrange nothing: K and V are read where the caller has them through the partition's row map")
     ap.add_argument("--permute-q", action="store_true",
                     help="also rearrange Q into block order (default: only K and V move, as in the paper's Eq. 1)")
     ap.add_argument("--sweep", action="store_true", help="sequence-length sweep instead of the benchmark line")
@@ -309,7 +311,7 @@ def main():
     for kind in kinds:
         bt, bh, bw, chunk = cfg["partitions"][kind]
         plans[kind] = vb.LayerPlan(1, Hh, D, cfg["grid"], (bt, bh, bw), chunk, args.tau, dtype, fused_io=True,
-                                   q_in_place=not args.permute_q)
+                                   q_in_place=not args.permute_q, kv_in_place=args.kv_in_place)
 
     def step(i):
         p = plans[kinds[i % len(kinds)]]
@@ -420,7 +422,7 @@ def main():
     es = 2 if dtype == torch.bfloat16 else 4
     row_bytes = S * Hh * D * es
     mem_steps = {}
-    n_part = 3 if args.permute_q else 2          # tensors the partition call moves: (Q,) K, V
+    n_part = 0 if args.kv_in_place else 3 if args.permute_q else 2          # tensors the partition call moves: (Q,) K, V
     for kind, bd in breakdown.items():
         nbk = plans[kind].nb
         sel_bytes = 2 * row_bytes + Hh * S * nbk * 4 + Hh * S * ((nbk + 31) // 32) * 4 + 3 * 4 * pairs[kind]
@@ -477,7 +479,7 @@ def main():
     if abs(args.tau - 0.5) > 1e-9 and "3d" in cfg["partitions"] and not args.no_extras:
         try:
             bt, bh, bw, chunk = cfg["partitions"]["3d"]
-            p5 = vb.LayerPlan(1, Hh, D, cfg["grid"], (bt, bh, bw), chunk, 0.5, dtype, q_in_place=not args.permute_q)
+            p5 = vb.LayerPlan(1, Hh, D, cfg["grid"], (bt, bh, bw), chunk, 0.5, dtype, q_in_place=not args.permute_q, kv_in_place=args.kv_in_place)
             p5.forward(Q, K, V); p5.backward(dO)
             torch.cuda.synchronize()
             t = time.perf_counter()
@@ -519,7 +521,7 @@ def main():
             for p in plans.values():
                 p.ws_attn = None
             torch.cuda.empty_cache()
-            pd = vb.LayerPlan(1, Hh, D, cfg["grid"], (bt, bh, bw), chunk, 1.0, dtype, q_in_place=not args.permute_q)
+            pd = vb.LayerPlan(1, Hh, D, cfg["grid"], (bt, bh, bw), chunk, 1.0, dtype, q_in_place=not args.permute_q, kv_in_place=args.kv_in_place)
             pd.forward(Q, K, V); pd.backward(dO)
             torch.cuda.synchronize()
             t = time.perf_counter()

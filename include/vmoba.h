@@ -170,13 +170,17 @@ int vmoba_partition(const vmoba_grid* g, int inverse, int B, int Hh, int D, int 
  *  mask, k_out, theta_out and row_ptr are complete either way.
  *  query_pos   optional int32 [S]: block-order position of query q (the partition's inv_perm).  Only read with
  *              VMOBA_SELECT_OWN_BLOCK, to find the block a query lies in; null = query q sits at position q.
+ *  kv_rows     optional int32 [S]: keys in place.  Null: Kp is in block order.  Otherwise key position k is row
+ *              kv_rows[k] of Kp -- pass the partition's perm and the caller's K: nothing is rearranged in memory,
+ *              the blocks of Eq. 1 are addressed where they lie.
  */
 int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
                  const vmoba_tensor* Qp, const vmoba_tensor* Kp, float tau, float score_scale,
                  int mode, int32_t topk, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
                  int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
                  int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
-                 const int32_t* query_pos, void* workspace, size_t workspace_bytes, void* stream);
+                 const int32_t* query_pos, const int32_t* kv_rows, void* workspace, size_t workspace_bytes,
+                 void* stream);
 
 /*
  * vmoba_select_static -- vmoba_select for callers that cannot allocate device memory or hand over a workspace:
@@ -196,7 +200,7 @@ int vmoba_select_static(int B, int Hh, int64_t S, int D, int32_t n_blocks, const
                         int mode, int32_t topk, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
                         int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
                         int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
-                        const int32_t* query_pos, void* stream);
+                        const int32_t* query_pos, const int32_t* kv_rows, void* stream);
 
 /*
  * vmoba_attn_fwd -- Step 3 of Sec. 3.1: every query attends to the keys/values of its selected
@@ -210,15 +214,19 @@ int vmoba_select_static(int B, int Hh, int64_t S, int D, int32_t n_blocks, const
  *  out_rows  optional int32 [S].  Null: O is written in block order.  Otherwise block-order row q
  *            goes to row out_rows[q] of O: pass the partition's perm and a tensor in the caller's
  *            token order to skip the inverse partition of O.  LSE stays in block order either way.
+ *  kv_rows   optional int32 [S]: keys in place, as in vmoba_select -- key position k is row kv_rows[k] of Kp and Vp.
+ *            (bfloat16: the tile kernel keeps the row numbers of a key block in LDS, up to 3584 keys per block;
+ *            longer blocks are looked up in global memory, which is correct but slower.)
  *  Limit (bfloat16): one (batch, head) slice of K' and of V' must span less than 4 GiB, i.e.
- *  (S + 256) * stride_s * 2 < 2^32 with a positive stride_s; otherwise VMOBA_ERR_UNSUPPORTED.
+ *  (S + 256) * stride_s * 2 < 2^32 with a positive stride_s; with kv_rows also S < 2^24 and stride_s * 2 < 2^24;
+ *  otherwise VMOBA_ERR_UNSUPPORTED.
  */
 int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t* blk_off,
                    const vmoba_tensor* Qp, const vmoba_tensor* Kp, const vmoba_tensor* Vp,
                    const int32_t* blk_ptr, const int32_t* q_idx, const int32_t* row_ptr,
                    const int32_t* pair_pos, int64_t nnz_capacity, float softmax_scale,
-                   const vmoba_tensor* O, float* LSE, const int32_t* out_rows, void* workspace,
-                   size_t workspace_bytes, void* stream);
+                   const vmoba_tensor* O, float* LSE, const int32_t* out_rows, const int32_t* kv_rows,
+                   void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * vmoba_attn_bwd -- gradient of vmoba_attn_fwd with the selection held fixed (the paper trains
@@ -233,6 +241,7 @@ int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int3
  *        partition of dO and the inverse partition of the three gradients.
  *  key_rows  optional int32 [S]: row map of dK and dV alone (key position k -> row key_rows[k]); overrides `rows`
  *        for them.  With the caller's Q as it is (query ids = token ids): rows = null, key_rows = perm.
+ *  kv_rows   optional int32 [S]: keys in place, as in vmoba_select -- key position k is row kv_rows[k] of Kp and Vp.
  *  Limit (bfloat16): S < 2^24, and for Q', K', V' and dO a positive stride_s with stride_s * 2 < 2^24 and
  *  S * stride_s * 2 < 2^32 (one (batch, head) slice spans less than 4 GiB); otherwise
  *  VMOBA_ERR_UNSUPPORTED.
@@ -243,8 +252,8 @@ int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int3
                    const int32_t* blk_ptr, const int32_t* q_idx, const int32_t* row_ptr,
                    const int32_t* pair_pos, int64_t nnz_capacity, float softmax_scale,
                    const vmoba_tensor* dQ, const vmoba_tensor* dK, const vmoba_tensor* dV,
-                   const int32_t* rows, const int32_t* key_rows, void* workspace, size_t workspace_bytes,
-                   void* stream);
+                   const int32_t* rows, const int32_t* key_rows, const int32_t* kv_rows, void* workspace,
+                   size_t workspace_bytes, void* stream);
 
 /*
  * vmoba_profile_events -- measurement aid, not part of the method.  Asks the library to record

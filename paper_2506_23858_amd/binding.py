@@ -67,20 +67,20 @@ def lib():
     L.vmoba_partition.restype = C.c_int
     L.vmoba_select.argtypes = [C.c_int, C.c_int, C.c_int64, C.c_int, C.c_int32, P,
                                C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor), C.c_float, C.c_float, C.c_int,
-                               C.c_int32, P, P, P, P, P, P, P, P, C.c_int64, P, P, P, P, P, C.c_size_t, P]
+                               C.c_int32, P, P, P, P, P, P, P, P, C.c_int64, P, P, P, P, P, P, C.c_size_t, P]
     L.vmoba_select.restype = C.c_int
     L.vmoba_select_static.argtypes = L.vmoba_select.argtypes[:-3] + [P]      # no workspace pointer / size
     L.vmoba_select_static.restype = C.c_int
     L.vmoba_attn_fwd.argtypes = [C.c_int, C.c_int, C.c_int64, C.c_int, C.c_int32, P,
                                  C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor),
-                                 P, P, P, P, C.c_int64, C.c_float, C.POINTER(vmoba_tensor), P, P, P, C.c_size_t, P]
+                                 P, P, P, P, C.c_int64, C.c_float, C.POINTER(vmoba_tensor), P, P, P, P, C.c_size_t, P]
     L.vmoba_attn_fwd.restype = C.c_int
     L.vmoba_attn_bwd.argtypes = [C.c_int, C.c_int, C.c_int64, C.c_int, C.c_int32, P,
                                  C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor),
                                  C.POINTER(vmoba_tensor), P, C.POINTER(vmoba_tensor),
                                  P, P, P, P, C.c_int64, C.c_float,
                                  C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor), C.POINTER(vmoba_tensor),
-                                 P, P, P, C.c_size_t, P]
+                                 P, P, P, P, C.c_size_t, P]
     L.vmoba_attn_bwd.restype = C.c_int
     L.vmoba_profile_events.argtypes = [C.c_int, P, P]
     L.vmoba_profile_events.restype = C.c_int
@@ -191,13 +191,13 @@ SELECT_OWN_BLOCK = 0x100
 
 def vmoba_select(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode, topk, Bmean, P, mask,
                  blk_ptr, q_idx, row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status,
-                 workspace, stream=None, query_pos=None):
+                 workspace, stream=None, query_pos=None, kv_rows=None):
     q, k = tensor_desc(Qp), tensor_desc(Kp)
     rc = lib().vmoba_select(B, Hh, S, D, n_blocks, _ptr(blk_off), C.byref(q), C.byref(k),
                             float(tau), float(score_scale), int(mode), int(topk), _ptr(Bmean), _ptr(P), _ptr(mask),
                             _ptr(blk_ptr), _ptr(q_idx), _ptr(row_ptr), _ptr(col_idx), _ptr(pair_pos),
                             int(nnz_capacity), _ptr(k_out), _ptr(theta_out), _ptr(dev_status), _ptr(query_pos),
-                            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+                            _ptr(kv_rows), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     _check("vmoba_select", rc)
 
 
@@ -206,34 +206,36 @@ SELECT_STATIC_MAX_BYTES = 32 << 20
 
 def vmoba_select_static(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode, topk, Bmean, P, mask,
                         blk_ptr, q_idx, row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status,
-                        stream=None, query_pos=None):
+                        stream=None, query_pos=None, kv_rows=None):
     """vmoba_select on the library's static scratch array (no workspace argument, nothing allocated)."""
     q, k = tensor_desc(Qp), tensor_desc(Kp)
     rc = lib().vmoba_select_static(B, Hh, S, D, n_blocks, _ptr(blk_off), C.byref(q), C.byref(k),
                                    float(tau), float(score_scale), int(mode), int(topk), _ptr(Bmean), _ptr(P),
                                    _ptr(mask), _ptr(blk_ptr), _ptr(q_idx), _ptr(row_ptr), _ptr(col_idx),
                                    _ptr(pair_pos), int(nnz_capacity), _ptr(k_out), _ptr(theta_out),
-                                   _ptr(dev_status), _ptr(query_pos), _stream(stream))
+                                   _ptr(dev_status), _ptr(query_pos), _ptr(kv_rows), _stream(stream))
     _check("vmoba_select_static", rc)
 
 
 def vmoba_attn_fwd(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, Vp, blk_ptr, q_idx, row_ptr, pair_pos,
-                   nnz_capacity, softmax_scale, O, LSE, workspace, stream=None, out_rows=None):
+                   nnz_capacity, softmax_scale, O, LSE, workspace, stream=None, out_rows=None, kv_rows=None):
     q, k, v, o = tensor_desc(Qp), tensor_desc(Kp), tensor_desc(Vp), tensor_desc(O)
     rc = lib().vmoba_attn_fwd(B, Hh, S, D, n_blocks, _ptr(blk_off), C.byref(q), C.byref(k), C.byref(v),
                               _ptr(blk_ptr), _ptr(q_idx), _ptr(row_ptr), _ptr(pair_pos), int(nnz_capacity),
-                              float(softmax_scale), C.byref(o), _ptr(LSE), _ptr(out_rows), _ptr(workspace),
+                              float(softmax_scale), C.byref(o), _ptr(LSE), _ptr(out_rows), _ptr(kv_rows), _ptr(workspace),
                               workspace.numel() * workspace.element_size(), _stream(stream))
     _check("vmoba_attn_fwd", rc)
 
 
 def vmoba_attn_bwd(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, Vp, O, LSE, dO, blk_ptr, q_idx, row_ptr,
-                   pair_pos, nnz_capacity, softmax_scale, dQ, dK, dV, workspace, stream=None, rows=None, key_rows=None):
+                   pair_pos, nnz_capacity, softmax_scale, dQ, dK, dV, workspace, stream=None, rows=None, key_rows=None,
+                   kv_rows=None):
     d = [tensor_desc(t) for t in (Qp, Kp, Vp, O, dO, dQ, dK, dV)]
     rc = lib().vmoba_attn_bwd(B, Hh, S, D, n_blocks, _ptr(blk_off), C.byref(d[0]), C.byref(d[1]), C.byref(d[2]),
                               C.byref(d[3]), _ptr(LSE), C.byref(d[4]), _ptr(blk_ptr), _ptr(q_idx),
                               _ptr(row_ptr), _ptr(pair_pos), int(nnz_capacity), float(softmax_scale),
-                              C.byref(d[5]), C.byref(d[6]), C.byref(d[7]), _ptr(rows), _ptr(key_rows), _ptr(workspace),
+                              C.byref(d[5]), C.byref(d[6]), C.byref(d[7]), _ptr(rows), _ptr(key_rows), _ptr(kv_rows),
+                              _ptr(workspace),
                               workspace.numel() * workspace.element_size(), _stream(stream))
     _check("vmoba_attn_bwd", rc)
 
@@ -247,13 +249,16 @@ class LayerPlan:
     inverse partitions, and the block-order copies Op, dOp, dQp, dKp, dVp do not exist.
     With q_in_place (implies fused_io) only K and V are rearranged, as in the paper's Eq. 1: Q is read
     where the caller has it, a query's id is its token index everywhere (P, mask, lists, LSE), and O,
-    dO, dQ need no row map at all; dK and dV go back through key_rows = perm."""
+    dO, dQ need no row map at all; dK and dV go back through key_rows = perm.
+    With kv_in_place (implies q_in_place) nothing is rearranged in memory at all: the partition call only
+    builds the index arrays and every kernel finds key position k at row perm[k] of the caller's K and V."""
 
     def __init__(self, B, Hh, D, grid, block=(0, 0, 0), chunk=0, tau=0.25, dtype=torch.bfloat16,
                  device="cuda", score_scale=None, softmax_scale=None, need_bwd=True, mode=GLOBAL_THRESHOLD, topk=0,
-                 fused_io=False, q_in_place=False):
+                 fused_io=False, q_in_place=False, kv_in_place=False):
         T, H, W = grid
-        self.q_in_place = bool(q_in_place)
+        self.kv_in_place = bool(kv_in_place)
+        self.q_in_place = bool(q_in_place) or self.kv_in_place
         self.fused_io = bool(fused_io) or self.q_in_place
         fused_io = self.fused_io
         self.Qin = None
@@ -283,7 +288,7 @@ class LayerPlan:
         def blk_tensor(dt=dtype):   # block-order storage [B, Hh, S, D], handed out as a (b, s, h, d) view
             return torch.empty(B, Hh, S, D, dtype=dt, device=device).permute(0, 2, 1, 3)
 
-        self.Kp, self.Vp = (blk_tensor() for _ in range(2))
+        self.Kp, self.Vp = (None, None) if self.kv_in_place else (blk_tensor() for _ in range(2))
         self.Qp = None if self.q_in_place else blk_tensor()
         self.Op = None if fused_io else blk_tensor()
         self.LSE = torch.empty(B, Hh, S, **f32)
@@ -313,6 +318,10 @@ class LayerPlan:
 
     # -- the hot path, one method per C-ABI call -------------------------------------------
     def partition(self, Q, K, V):
+        if self.kv_in_place:         # index arrays only; the blocks of Eq. 1 are addressed where they lie
+            self.Qin, self.Kp, self.Vp = Q, K, V
+            vmoba_partition(self.g, 0, self.B, self.Hh, self.D, [], [], self.perm, self.inv_perm, self.blk_off)
+            return
         if self.q_in_place:          # Eq. 1 as written: only the keys (and their values) are rearranged
             self.Qin = Q
             vmoba_partition(self.g, 0, self.B, self.Hh, self.D, [K, V], [self.Kp, self.Vp],
@@ -328,13 +337,14 @@ class LayerPlan:
         vmoba_select(self.B, self.Hh, self.S, self.D, self.nb, self.blk_off, self._q(), self.Kp, self.tau,
                      self.score_scale, self.mode, self.topk, self.Bmean, self.P, self.mask, self.blk_ptr, self.q_idx,
                      self.row_ptr, self.col_idx, self.pair_pos, self.cap, self.k_out, self.theta,
-                     self.dev_status, self.ws_select, query_pos=self.inv_perm if self.q_in_place else None)
+                     self.dev_status, self.ws_select, query_pos=self.inv_perm if self.q_in_place else None,
+                     kv_rows=self.perm if self.kv_in_place else None)
 
     def attn_fwd(self):
         if self.q_in_place:
             vmoba_attn_fwd(self.B, self.Hh, self.S, self.D, self.nb, self.blk_off, self.Qin, self.Kp, self.Vp,
                            self.blk_ptr, self.q_idx, self.row_ptr, self.pair_pos, self.cap, self.softmax_scale,
-                           self.O, self.LSE, self.ws_attn)
+                           self.O, self.LSE, self.ws_attn, kv_rows=self.perm if self.kv_in_place else None)
             return
         vmoba_attn_fwd(self.B, self.Hh, self.S, self.D, self.nb, self.blk_off, self.Qp, self.Kp, self.Vp,
                        self.blk_ptr, self.q_idx, self.row_ptr, self.pair_pos, self.cap, self.softmax_scale,
@@ -352,7 +362,8 @@ class LayerPlan:
         if self.q_in_place:
             vmoba_attn_bwd(self.B, self.Hh, self.S, self.D, self.nb, self.blk_off, self.Qin, self.Kp, self.Vp,
                            self.O, self.LSE, dO, self.blk_ptr, self.q_idx, self.row_ptr, self.pair_pos,
-                           self.cap, self.softmax_scale, self.dQ, self.dK, self.dV, self.ws_attn, key_rows=self.perm)
+                           self.cap, self.softmax_scale, self.dQ, self.dK, self.dV, self.ws_attn, key_rows=self.perm,
+                           kv_rows=self.perm if self.kv_in_place else None)
             return
         if self.fused_io:
             vmoba_attn_bwd(self.B, self.Hh, self.S, self.D, self.nb, self.blk_off, self.Qp, self.Kp, self.Vp,

@@ -98,7 +98,8 @@ template <int D>
 __global__ __launch_bounds__(64) void attn_bwd_dq_simple_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
-    const int4* __restrict__ tile_desc, int tiles_per_head, float* __restrict__ dQpart, int Hh, int S, int nb, long long cap, float scale_log2) {
+    const int4* __restrict__ tile_desc, int tiles_per_head, float* __restrict__ dQpart, int Hh, int S, int nb, long long cap, float scale_log2,
+    const int* __restrict__ kv_rows) {
     constexpr int KC = 32;
     constexpr int ES = 4;
     __shared__ float sK[KC][D];
@@ -130,7 +131,8 @@ __global__ __launch_bounds__(64) void attn_bwd_dq_simple_kernel(
         __syncthreads();
         for (int i = lane; i < kc * D; i += 64) {
             const int r = i / D, d = i % D;
-            const long long row = tc.k0 + c0 + r;
+            const int pos = tc.k0 + c0 + r;
+            const long long row = kv_rows ? kv_rows[pos] : pos;       // key position -> row of K and V
             sK[r][d] = load_elem(kbase + row * K.stride_s * ES, d);
             sV[r][d] = load_elem(vbase + row * V.stride_s * ES, d);
         }
@@ -162,7 +164,7 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_simple_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
     const int* __restrict__ kb_start, const int* __restrict__ kb_order, TensorView dK, TensorView dV, const int* __restrict__ rows, int Hh, int S, int nb, long long cap,
-    float scale_log2, float scale) {
+    float scale_log2, float scale, const int* __restrict__ kv_rows) {
     constexpr int KPW = 64, QC = 16;
     constexpr int ES = 4;
     __shared__ float sQ[QC][D];
@@ -184,8 +186,9 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_simple_kernel(
     const int cnt = blk_ptr[(long long)bh * (nb + 1) + j + 1] - list0;
     float kr[D], vr[D], dk[D], dv[D];
     {
-        const char* sk = K.ptr + ((long long)b * K.stride_b + (long long)krow * K.stride_s + (long long)h * K.stride_h) * ES;
-        const char* sv = V.ptr + ((long long)b * V.stride_b + (long long)krow * V.stride_s + (long long)h * V.stride_h) * ES;
+        const long long kin = kv_rows ? kv_rows[krow] : krow;         // row of K and V that holds this key
+        const char* sk = K.ptr + ((long long)b * K.stride_b + kin * K.stride_s + (long long)h * K.stride_h) * ES;
+        const char* sv = V.ptr + ((long long)b * V.stride_b + kin * V.stride_s + (long long)h * V.stride_h) * ES;
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             kr[d] = load_elem(sk, d);
@@ -257,7 +260,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
     const int4* __restrict__ flat_desc, const int* __restrict__ head_base, int BH, float* __restrict__ dQpart, int Hh, int S, int nb,
-    long long cap, float scale_log2) {
+    long long cap, float scale_log2, const int* __restrict__ kv_rows) {
     constexpr int TM = 128, KC = 64;
     constexpr int STR = D + 8;
     constexpr int KSTEPS = D / 16, DT = D / 32;
@@ -329,16 +332,27 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
     const int n_chunks = (tc.L + KC - 1) / KC;
 
     u32x4_t kreg[LOADS], vreg[LOADS];
-    auto prefetch = [&](int c) {
+    // rows of K and V that hold the keys of the chunk to be fetched next: the key positions themselves, or, with keys in
+    // place, what kv_rows says -- looked up one chunk before the rows are fetched, so that two dependent loads never
+    // sit in one chunk's shadow
+    uint32_t krow_n[LOADS];
+    auto lookup_rows = [&](int c) {
         const int c0 = c * KC;
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
-            const int piece = tid + 256 * i;
-            const int r = piece / (D / 8), pc = piece % (D / 8);
-            const uint32_t row = (uint32_t)(tc.k0 + min(c0 + r, tc.L - 1));
-            kreg[i] = load_at<u32x4_t>(kbase, __umul24(row, kss) + pc * 16);
-            vreg[i] = load_at<u32x4_t>(vbase, __umul24(row, vss) + pc * 16);
+            const int r = (tid + 256 * i) / (D / 8);
+            const uint32_t pos = (uint32_t)(tc.k0 + min(c0 + r, tc.L - 1));
+            krow_n[i] = kv_rows ? (uint32_t)kv_rows[pos] : pos;
         }
+    };
+    auto prefetch = [&](int c) {
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int pc = (tid + 256 * i) % (D / 8);
+            kreg[i] = load_at<u32x4_t>(kbase, __umul24(krow_n[i], kss) + pc * 16);
+            vreg[i] = load_at<u32x4_t>(vbase, __umul24(krow_n[i], vss) + pc * 16);
+        }
+        lookup_rows(c + 1);
     };
     auto stage = [&]() {
 #pragma unroll
@@ -369,6 +383,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(
         const int u = n - 2 * KSTEPS;
         return tr_operand<STR>(sKt_lane, mt * 32, u / DT, (u % DT) * 32);
     };
+    lookup_rows(0);
     prefetch(0);
     bf16x8_t qf[KSTEPS], dof[KSTEPS];
     VMOBA_WAIT_VMCNT(0);                       // the gathered rows have landed (and the first key chunk with them)
@@ -506,7 +521,7 @@ __device__ __forceinline__ void dkv_pair_body(
     char* smem, int bh, int run_id, const TensorView& Q, const TensorView& K, const TensorView& V, const TensorView& dO, const float* __restrict__ LSE,
     const float* __restrict__ delta, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
     const int* __restrict__ kb_start, const int* __restrict__ kb_order, const TensorView& dK, const TensorView& dV, const int* __restrict__ rows,
-    int Hh, int S, int nb, long long cap, float scale_log2, float scale) {
+    const int* __restrict__ kv_rows, int Hh, int S, int nb, long long cap, float scale_log2, float scale) {
     constexpr int NT = 256;
     constexpr int QC = 64;
     constexpr int STR = D + 8;
@@ -550,7 +565,8 @@ __device__ __forceinline__ void dkv_pair_body(
             const int kk = kbase + kg * 32 + l32;
             key_live[kg] = kk < L;
             krow[kg] = k0 + min(kk, L - 1);
-            const char* sp = src.ptr + ((long long)b * src.stride_b + (long long)krow[kg] * src.stride_s + (long long)h * src.stride_h) * 2;
+            const long long kin = kv_rows ? kv_rows[krow[kg]] : krow[kg];     // row of K / V that holds this key
+            const char* sp = src.ptr + ((long long)b * src.stride_b + kin * src.stride_s + (long long)h * src.stride_h) * 2;
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ++ks) frag[kg][ks] = *reinterpret_cast<const bf16x8_t*>(sp + (ks * 16 + hf * 8) * 2);
         }
@@ -849,8 +865,8 @@ template <int D>
 __device__ __forceinline__ void dkv_tail_body(
     char* smem, int bh, int rank, const TensorView& Q, const TensorView& K, const TensorView& V, const TensorView& dO, const float* __restrict__ LSE,
     const float* __restrict__ delta, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
-    const int* __restrict__ kb_order, const TensorView& dK, const TensorView& dV, const int* __restrict__ rows, int Hh, int S, int nb,
-    long long cap, float scale_log2, float scale) {
+    const int* __restrict__ kb_order, const TensorView& dK, const TensorView& dV, const int* __restrict__ rows,
+    const int* __restrict__ kv_rows, int Hh, int S, int nb, long long cap, float scale_log2, float scale) {
     constexpr int QC = 32;                       // queries per chunk
     constexpr int STR = D + 8;
     constexpr int KSTEPS = D / 16, DT = D / 32;
@@ -879,8 +895,9 @@ __device__ __forceinline__ void dkv_tail_body(
     const int krow = k0 + min(L - tail + l32, L - 1);
     bf16x8_t kf[KSTEPS], vf[KSTEPS];
     {
-        const char* pk = K.ptr + ((long long)b * K.stride_b + (long long)krow * K.stride_s + (long long)h * K.stride_h) * 2;
-        const char* pv = V.ptr + ((long long)b * V.stride_b + (long long)krow * V.stride_s + (long long)h * V.stride_h) * 2;
+        const long long kin = kv_rows ? kv_rows[krow] : krow;         // row of K and V that holds this key
+        const char* pk = K.ptr + ((long long)b * K.stride_b + kin * K.stride_s + (long long)h * K.stride_h) * 2;
+        const char* pv = V.ptr + ((long long)b * V.stride_b + kin * V.stride_s + (long long)h * V.stride_h) * 2;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
             kf[ks] = *reinterpret_cast<const bf16x8_t*>(pk + (ks * 16 + hf * 8) * 2);
@@ -1050,7 +1067,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
     const int* __restrict__ kb_start, const int* __restrict__ kb_order, TensorView dK, TensorView dV, const int* __restrict__ rows, int Hh, int S, int nb, long long cap,
-    float scale_log2, float scale) {
+    float scale_log2, float scale, const int* __restrict__ kv_rows) {
     __shared__ __align__(16) char smem[dkv_pair_lds_bytes<D>()];
     // grid (heads, slots): workgroups are dispatched x-fastest, so slot s of every head starts before slot s + 1 of any --
     // with each head's runs sorted by length this is a longest-first order over the whole launch, not per head
@@ -1058,9 +1075,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
     const int runs = kb_start[(long long)bh * (nb + 1) + nb];
     const int id = (int)blockIdx.y;
     if (id < runs)
-        dkv_pair_body<D>(smem, bh, id, Q, K, V, dO, LSE, delta, blk_off, blk_ptr, q_idx, kb_start, kb_order, dK, dV, rows, Hh, S, nb, cap, scale_log2, scale);
+        dkv_pair_body<D>(smem, bh, id, Q, K, V, dO, LSE, delta, blk_off, blk_ptr, q_idx, kb_start, kb_order, dK, dV, rows, kv_rows, Hh, S, nb, cap, scale_log2, scale);
     else if (id - runs < nb)
-        dkv_tail_body<D>(smem, bh, id - runs, Q, K, V, dO, LSE, delta, blk_off, blk_ptr, q_idx, kb_order, dK, dV, rows, Hh, S, nb, cap, scale_log2, scale);
+        dkv_tail_body<D>(smem, bh, id - runs, Q, K, V, dO, LSE, delta, blk_off, blk_ptr, q_idx, kb_order, dK, dV, rows, kv_rows, Hh, S, nb, cap, scale_log2, scale);
 }
 
 // dQ[q] = scale * sum over the query's pairs of dQpart[pair]; the partials have the tensors' type.  A head whose
@@ -1159,8 +1176,8 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
                               const int32_t* blk_ptr, const int32_t* q_idx, const int32_t* row_ptr,
                               const int32_t* pair_pos, int64_t nnz_capacity, float softmax_scale,
                               const vmoba_tensor* dQ, const vmoba_tensor* dK, const vmoba_tensor* dV,
-                              const int32_t* rows, const int32_t* key_rows, void* workspace, size_t workspace_bytes,
-                              void* stream) {
+                              const int32_t* rows, const int32_t* key_rows, const int32_t* kv_rows, void* workspace,
+                              size_t workspace_bytes, void* stream) {
     if (B <= 0 || Hh <= 0 || S <= 0 || n_blocks <= 0 || nnz_capacity <= 0) return VMOBA_ERR_INVALID_ARG;
     if (!blk_off || !blk_ptr || !q_idx || !row_ptr || !pair_pos || !LSE || !workspace) return VMOBA_ERR_INVALID_ARG;
     if (!tensor_ok(Qp) || !tensor_ok(Kp) || !tensor_ok(Vp) || !tensor_ok(O) || !tensor_ok(dO) || !tensor_ok(dQ) ||
@@ -1229,14 +1246,14 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         VMOBA_PROFILE_BEGIN(1, st);
         if (simple) {
             dim3 grid((unsigned)max_tiles, (unsigned)BH);
-#define DQ_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.tile_desc, (int)max_tiles, ws.dQpart, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2
+#define DQ_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.tile_desc, (int)max_tiles, ws.dQpart, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, kv_rows
             if (D == 128) attn_bwd_dq_simple_kernel<128><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
             else attn_bwd_dq_simple_kernel<64><<<grid, dim3(64), 0, st>>>(DQ_ARGS);
 #undef DQ_ARGS
         } else {
             // one workgroup per entry of the flat tile list; the bound on the list length is a multiple of 8
             const dim3 grid((unsigned)std::min<int64_t>((int64_t)BH * max_tiles, ((nnz_capacity / TM + n_blocks) * (int64_t)BH + 15) / 8 * 8));
-#define DQ_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.tile_desc, ws.head_base, BH, ws.dQpart, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2
+#define DQ_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.tile_desc, ws.head_base, BH, ws.dQpart, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, kv_rows
             if (D == 128) attn_bwd_dq_mfma_kernel<128><<<grid, dim3(256), 0, st>>>(DQ_ARGS);
             else attn_bwd_dq_mfma_kernel<64><<<grid, dim3(256), 0, st>>>(DQ_ARGS);
 #undef DQ_ARGS
@@ -1262,7 +1279,7 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         dim3 grid((unsigned)((S / KPW + n_blocks + 7) / 8 * 8 + 8 + (simple ? 0 : n_blocks)), (unsigned)BH);
         VMOBA_PROFILE_BEGIN(2, st);
         const int32_t* krows = key_rows ? key_rows : rows;      // row map of dK and dV
-#define DKV_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.kb_start, ws.kb_order, dKv, dVv, krows, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale
+#define DKV_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.kb_start, ws.kb_order, dKv, dVv, krows, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale, kv_rows
         if (simple) {
             if (D == 128) attn_bwd_dkv_simple_kernel<128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
             else attn_bwd_dkv_simple_kernel<64><<<grid, dim3(64), 0, st>>>(DKV_ARGS);

@@ -122,5 +122,10 @@ __device__ __forceinline__ void dma16(const char* base, uint32_t byte_off, uint3
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr)
                  : "memory", "m0");
 }
+// The same with 4 bytes per lane: lane i writes lds_addr + 4 * i.
+__device__ __forceinline__ void dma4(const char* base, uint32_t byte_off, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr)
+                 : "memory", "m0");
+}
 #define VMOBA_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 

@@ -98,7 +98,7 @@ template <int D>
 __global__ __launch_bounds__(64) void attn_fwd_tile_simple_kernel(
     TensorView Q, TensorView K, TensorView V, const int* __restrict__ blk_off, const int* __restrict__ blk_ptr,
     const int* __restrict__ q_idx, const int4* __restrict__ tile_desc, int tiles_per_head, float* __restrict__ Opart,
-    float* __restrict__ lse_part, int Hh, int nb, long long cap, float scale_log2) {
+    float* __restrict__ lse_part, int Hh, int nb, long long cap, float scale_log2, const int* __restrict__ kv_rows) {
     constexpr int KC = 32;
     constexpr int ES = 4;
     __shared__ float sK[KC][D];
@@ -127,7 +127,8 @@ __global__ __launch_bounds__(64) void attn_fwd_tile_simple_kernel(
         __syncthreads();
         for (int i = lane; i < kc * D; i += 64) {
             const int r = i / D, d = i % D;
-            const long long row = tc.k0 + c0 + r;
+            const int pos = tc.k0 + c0 + r;
+            const long long row = kv_rows ? kv_rows[pos] : pos;       // key position -> row of K and V
             const char* ks = kbase + row * K.stride_s * ES;
             const char* vs = vbase + row * V.stride_s * ES;
             sK[r][d] = reinterpret_cast<const float*>(ks)[d];
@@ -212,11 +213,17 @@ __global__ __launch_bounds__(64) void attn_fwd_tile_simple_kernel(
 // per lane and channel group) and reads them back as whole rows: the tile's partials are
 // consecutive rows of Opart, so each store request is a 1 KB run instead of 16-byte pieces of 32
 // rows (the address unit needs about as long for one such request as for eight full-row ones).
-template <int D, int NW>
+//
+// Keys in place (KVR).  K and V may stay where the caller has them: key position p of the block order is then row
+// kv_rows[p] of both.  A tile's slice of that map, kv_rows[k0 .. k0 + L), is copied into LDS (global_load_lds_dword,
+// 64 entries per instruction) one tile ahead -- two tables that alternate, filled for the next tile at the start of
+// the current one -- and a row request reads its row number there instead of advancing an offset.  Blocks longer
+// than a table (TOKMAX keys) look their rows up in global memory, which is correct but waits for the lookup.
+template <int D, int NW, bool KVR>
 __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
     TensorView Q, TensorView K, TensorView V, const int* __restrict__ q_idx, const int4* __restrict__ flat_desc,
     const int* __restrict__ head_base, int BH, float* __restrict__ Opart, float* __restrict__ lse_part, int Hh,
-    long long cap, float scale_log2) {
+    long long cap, float scale_log2, const int* __restrict__ kv_rows) {
     constexpr int G = 32;                   // keys per group
     constexpr int RB = 2 * D;               // bytes per LDS row
     constexpr int PPR = D / 8;              // 16-byte pieces per row
@@ -235,6 +242,8 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
     // channel group), read back as whole rows, so that the global stores are 1 KB runs instead of 16-byte pieces
     constexpr int OPITCH = D * 2 + 16;
     __shared__ __align__(16) char sOut[NW * 32 * OPITCH];
+    constexpr int TOKMAX = 3584;            // entries per row-number table (two of them fill what is left of the 160 KB)
+    __shared__ __align__(256) int sTok[KVR ? 2 * TOKMAX : 4];
 
     // Workgroup ids go round the 8 XCDs (each with its own L2), so XCD x = id % 8 takes the x-th eighth of the tile
     // list and its workgroups stride through it: a key block's tiles then share one L2 instead of eight.
@@ -252,6 +261,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
     const int ent = wave * 32 + l32;
     const uint32_t sK0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)sK;
     const uint32_t sV0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)sV;
+    const uint32_t sTok0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int*)sTok;
 
     // ---- per-tile state.  Descriptor: {first list entry, count | head << 10, first key, block length}
     struct Tile {
@@ -309,13 +319,42 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
             off[i] += adv;
         }
     };
+    // KVR: the row-number table of tile t into table `tb`; the instructions are dealt round the wavefronts, entries
+    // past the block's end repeat its last key
+    auto dma_tokens = [&](const Tile& t, int tb) {
+        if (t.L > TOKMAX) return;
+        const int n_instr = (t.L + 63) >> 6;
+        for (int i = wave; i < n_instr; i += NW) {
+            const int e = min(i * 64 + lane, t.L - 1);
+            dma4(reinterpret_cast<const char*>(kv_rows), (uint32_t)(t.k0 + e) << 2, sTok0 + (uint32_t)(tb * TOKMAX + i * 64) * 4);
+        }
+    };
+    // KVR: request group `grp` of tile t (whose row numbers are in table `tb`) into ring slot `slot`
+    auto request_rows = [&](const Tile& t, const char* base, uint32_t stride, int grp, uint32_t ring0, int slot, int tb) {
+#pragma unroll
+        for (int i = 0; i < IPW; ++i) {
+            const int dr = (wave * IPW + i) * RPI + lane / PPR;
+            const uint32_t pc16 = (uint32_t)((lane % PPR) ^ ((dr >> SH) & (PPR - 1))) * 16;
+            const int idx = min(grp * G + dr, t.L - 1);
+            const uint32_t row = t.L <= TOKMAX ? (uint32_t)sTok[tb * TOKMAX + idx] : (uint32_t)kv_rows[t.k0 + idx];
+            dma16(base, __umul24(row, stride) + pc16, ring0 + (uint32_t)(slot & (NR - 1)) * SLOT + (uint32_t)(wave * IPW + i) * 1024);
+        }
+    };
     int kb = 0, vb = 0;                    // running group counters: group x of the current tile uses slot (kb + x) & 3 / (vb + x) & 3
-    auto request_first_groups = [&](const Tile& t, int kb_t, int vb_t) {     // K(0..3), V(0..1) of tile t
-        first_offsets(t);
+    int tp = 0;                            // KVR: table that holds the current tile's row numbers
+    auto request_first_groups = [&](const Tile& t, int kb_t, int vb_t, int tb) {     // K(0..3), V(0..1) of tile t
+        if constexpr (KVR) {
 #pragma unroll
-        for (int x = 0; x < 4; ++x) request(t.kbase, k_off, k_last, k_adv, sK0, kb_t + x);
+            for (int x = 0; x < 4; ++x) request_rows(t, t.kbase, kss, x, sK0, kb_t + x, tb);
 #pragma unroll
-        for (int x = 0; x < 2; ++x) request(t.vbase, v_off, v_last, v_adv, sV0, vb_t + x);
+            for (int x = 0; x < 2; ++x) request_rows(t, t.vbase, vss, x, sV0, vb_t + x, tb);
+        } else {
+            first_offsets(t);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) request(t.kbase, k_off, k_last, k_adv, sK0, kb_t + x);
+#pragma unroll
+            for (int x = 0; x < 2; ++x) request(t.vbase, v_off, v_last, v_adv, sV0, vb_t + x);
+        }
     };
 
     // read side: per-lane byte offsets inside a slot, completed by XOR with the k-step / channel-tile bits
@@ -346,7 +385,12 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
 
     Tile cur = decode(flat_desc[f]);
     load_q(cur, query_of(cur));
-    request_first_groups(cur, kb, vb);
+    if constexpr (KVR) {                   // the first tile's row numbers: nothing to overlap them with
+        dma_tokens(cur, 0);
+        VMOBA_WAIT_VMCNT(0);
+        __syncthreads();
+    }
+    request_first_groups(cur, kb, vb, 0);
 
     for (;;) {
         const int fn = f + f_step;
@@ -451,8 +495,16 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
                 }
                 if constexpr (STAGE) {
                     if (u == 1) {
-                        request(cur.kbase, k_off, k_last, k_adv, sK0, kb + g + 4);
-                        request(cur.vbase, v_off, v_last, v_adv, sV0, vb + g + 2);
+                        if constexpr (KVR) {
+                            // the next tile's row numbers go first: they are then older than this step's row requests and
+                            // have landed when the next step's wait lets only those stay in flight
+                            if (g == 0) dma_tokens(nxt, tp ^ 1);
+                            request_rows(cur, cur.kbase, kss, g + 4, sK0, kb + g + 4, tp);
+                            request_rows(cur, cur.vbase, vss, g + 2, sV0, vb + g + 2, tp);
+                        } else {
+                            request(cur.kbase, k_off, k_last, k_adv, sK0, kb + g + 4);
+                            request(cur.vbase, v_off, v_last, v_adv, sV0, vb + g + 2);
+                        }
                     }
                 }
                 if constexpr (LAST_SM) {
@@ -460,7 +512,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
                     // slots are free, the two V slots after the current tile's last two as well): two steps ahead of their use
                     if (u == 1) {
                         load_q(nxt, nq);
-                        request_first_groups(nxt, kb + g + 1, vb + g + 1);
+                        request_first_groups(nxt, kb + g + 1, vb + g + 1, tp ^ 1);
                     }
                 }
                 opK[u2 & 3] = nk;
@@ -526,6 +578,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_fwd_tile_mfma_kernel(
         cur = nxt;
         kb += Ge;
         vb += Ge;
+        tp ^= 1;
     }
 }
 
@@ -664,8 +717,8 @@ extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
                               const vmoba_tensor* Qp, const vmoba_tensor* Kp, const vmoba_tensor* Vp,
                               const int32_t* blk_ptr, const int32_t* q_idx, const int32_t* row_ptr,
                               const int32_t* pair_pos, int64_t nnz_capacity, float softmax_scale,
-                              const vmoba_tensor* O, float* LSE, const int32_t* out_rows, void* workspace,
-                              size_t workspace_bytes, void* stream) {
+                              const vmoba_tensor* O, float* LSE, const int32_t* out_rows, const int32_t* kv_rows,
+                              void* workspace, size_t workspace_bytes, void* stream) {
     if (B <= 0 || Hh <= 0 || S <= 0 || n_blocks <= 0 || nnz_capacity <= 0) return VMOBA_ERR_INVALID_ARG;
     if (!blk_off || !blk_ptr || !q_idx || !row_ptr || !pair_pos || !LSE || !workspace) return VMOBA_ERR_INVALID_ARG;
     if (!tensor_ok(Qp) || !tensor_ok(Kp) || !tensor_ok(Vp) || !tensor_ok(O)) return VMOBA_ERR_INVALID_ARG;
@@ -689,6 +742,9 @@ extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
                     (uint64_t)(S + 256) * (uint64_t)Kp->stride_s * 2 >= ((uint64_t)1 << 32) ||
                     (uint64_t)(S + 256) * (uint64_t)Vp->stride_s * 2 >= ((uint64_t)1 << 32)))
         return VMOBA_ERR_UNSUPPORTED;
+    // with keys in place a row's byte offset is one 24-bit multiply of its row number and the row stride
+    if (!simple && kv_rows && (S >= (1 << 24) || Kp->stride_s * 2 >= (1 << 24) || Vp->stride_s * 2 >= (1 << 24)))
+        return VMOBA_ERR_UNSUPPORTED;
     // bf16, D = 128: 256-query tiles, one persistent workgroup of 8 wavefronts per compute unit (a tile's K and V
     // rows are fetched once per 256 queries); D = 64: 128-query tiles, two workgroups of 4 wavefronts per compute unit
     const bool wide = !simple && D == 128;
@@ -709,15 +765,17 @@ extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     VMOBA_PROFILE_BEGIN(0, st);
     if (simple) {
         dim3 grid((unsigned)max_tiles, (unsigned)BH);
-#define TILE_ARGS Qv, Kv, Vv, blk_off, blk_ptr, q_idx, ws.tile_desc, (int)max_tiles, ws.Opart, ws.lse_part, Hh, n_blocks, (long long)nnz_capacity, scale_log2
+#define TILE_ARGS Qv, Kv, Vv, blk_off, blk_ptr, q_idx, ws.tile_desc, (int)max_tiles, ws.Opart, ws.lse_part, Hh, n_blocks, (long long)nnz_capacity, scale_log2, kv_rows
         if (D == 128) attn_fwd_tile_simple_kernel<128><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
         else attn_fwd_tile_simple_kernel<64><<<grid, dim3(64), 0, st>>>(TILE_ARGS);
 #undef TILE_ARGS
     } else {
         const dim3 pgrid((unsigned)std::min<int64_t>((wide ? 1 : 2) * (int64_t)vmoba_num_cus(), (int64_t)BH * max_tiles));
-#define MFMA_ARGS Qv, Kv, Vv, q_idx, ws.tile_desc, ws.head_base, BH, ws.Opart, ws.lse_part, Hh, (long long)nnz_capacity, scale_log2
-        if (wide) attn_fwd_tile_mfma_kernel<128, 8><<<pgrid, dim3(512), 0, st>>>(MFMA_ARGS);
-        else attn_fwd_tile_mfma_kernel<64, 4><<<pgrid, dim3(256), 0, st>>>(MFMA_ARGS);
+#define MFMA_ARGS Qv, Kv, Vv, q_idx, ws.tile_desc, ws.head_base, BH, ws.Opart, ws.lse_part, Hh, (long long)nnz_capacity, scale_log2, kv_rows
+        if (wide && kv_rows) attn_fwd_tile_mfma_kernel<128, 8, true><<<pgrid, dim3(512), 0, st>>>(MFMA_ARGS);
+        else if (wide) attn_fwd_tile_mfma_kernel<128, 8, false><<<pgrid, dim3(512), 0, st>>>(MFMA_ARGS);
+        else if (kv_rows) attn_fwd_tile_mfma_kernel<64, 4, true><<<pgrid, dim3(256), 0, st>>>(MFMA_ARGS);
+        else attn_fwd_tile_mfma_kernel<64, 4, false><<<pgrid, dim3(256), 0, st>>>(MFMA_ARGS);
 #undef MFMA_ARGS
     }
     VMOBA_PROFILE_END(0, st);

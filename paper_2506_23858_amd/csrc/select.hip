@@ -72,9 +72,11 @@ __global__ __launch_bounds__(256) void zero_words_kernel(unsigned int* p, size_t
 // Block means, Eq. 2.  One workgroup per (block, b*Hh + h).  Threads are laid out as
 // (row group, 16-byte piece of a row); every thread sums its piece over the rows of its group,
 // the groups are then added in a fixed order, so the result is reproducible.
+// kv_rows: null when K is in block order, else the row of K that holds key position r (keys in place).
 template <bool BF16, int D>
 __global__ __launch_bounds__(256) void block_mean_kernel(TensorView K, const int* __restrict__ blk_off,
-                                                         float* __restrict__ Bmean, int Hh, int nb) {
+                                                         float* __restrict__ Bmean, int Hh, int nb,
+                                                         const int* __restrict__ kv_rows) {
     constexpr int EPP = BF16 ? 8 : 4;          // elements per 16-byte piece
     constexpr int PIECES = D / EPP;            // pieces per row
     constexpr int GROUPS = 256 / PIECES;
@@ -87,7 +89,8 @@ __global__ __launch_bounds__(256) void block_mean_kernel(TensorView K, const int
     for (int e = 0; e < EPP; ++e) acc[e] = 0.f;
     const char* base = K.ptr + ((long long)b * K.stride_b + (long long)h * K.stride_h) * (BF16 ? 2 : 4);
     for (int r = r0 + grp; r < r1; r += GROUPS) {
-        const char* src = base + (long long)r * K.stride_s * (BF16 ? 2 : 4) + piece * 16;
+        const int row = kv_rows ? kv_rows[r] : r;
+        const char* src = base + (long long)row * K.stride_s * (BF16 ? 2 : 4) + piece * 16;
         u32x4_t v = *reinterpret_cast<const u32x4_t*>(src);
         if constexpr (BF16) {
             acc[0] += bf16lo_to_f32(v.x); acc[1] += bf16hi_to_f32(v.x);
@@ -1217,7 +1220,7 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
                 int mode, int32_t topk, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
                 int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
                 int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
-                const int32_t* query_pos, void* workspace, size_t workspace_bytes, void* stream) {
+                const int32_t* query_pos, const int32_t* kv_rows, void* workspace, size_t workspace_bytes, void* stream) {
     {
         const int rc = select_args_ok(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode, topk, Bmean, P, mask,
                                       blk_ptr, q_idx, row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status);
@@ -1264,7 +1267,7 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
     zero_words_kernel<<<dim3(64), dim3(256), 0, st>>>((unsigned int*)workspace, ws.zero_bytes / 4);
     VMOBA_CHECK_LAUNCH();
 
-#define LAUNCH_MEAN(BF, DD) block_mean_kernel<BF, DD><<<dim3(n_blocks, BH), dim3(256), 0, st>>>(Kv, blk_off, Bmean, Hh, n_blocks)
+#define LAUNCH_MEAN(BF, DD) block_mean_kernel<BF, DD><<<dim3(n_blocks, BH), dim3(256), 0, st>>>(Kv, blk_off, Bmean, Hh, n_blocks, kv_rows)
     if (bf16 && D == 128) LAUNCH_MEAN(true, 128);
     else if (bf16 && D == 64) LAUNCH_MEAN(true, 64);
     else if (D == 128) LAUNCH_MEAN(false, 128);
@@ -1388,9 +1391,9 @@ extern "C" int vmoba_select(int B, int Hh, int64_t S, int D, int32_t n_blocks, c
                             int mode, int32_t topk, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
                             int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
                             int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
-                            const int32_t* query_pos, void* workspace, size_t workspace_bytes, void* stream) {
+                            const int32_t* query_pos, const int32_t* kv_rows, void* workspace, size_t workspace_bytes, void* stream) {
     return select_impl(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode, topk, Bmean, P, mask, blk_ptr, q_idx,
-                       row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status, query_pos, workspace,
+                       row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status, query_pos, kv_rows, workspace,
                        workspace_bytes, stream);
 }
 
@@ -1428,7 +1431,7 @@ extern "C" int vmoba_select_static(int B, int Hh, int64_t S, int D, int32_t n_bl
                                    int mode, int32_t topk, float* Bmean, float* P, uint32_t* mask, int32_t* blk_ptr,
                                    int32_t* q_idx, int32_t* row_ptr, int32_t* col_idx, int32_t* pair_pos,
                                    int64_t nnz_capacity, int64_t* k_out, float* theta_out, int32_t* dev_status,
-                                   const int32_t* query_pos, void* stream) {
+                                   const int32_t* query_pos, const int32_t* kv_rows, void* stream) {
     // everything that can be rejected on the host first, the size limit included
     const int rc = select_args_ok(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode, topk, Bmean, P, mask,
                                   blk_ptr, q_idx, row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status);
@@ -1439,6 +1442,6 @@ extern "C" int vmoba_select_static(int B, int Hh, int64_t S, int D, int32_t n_bl
     const int rs = static_scratch_of_current_device(&ws);
     if (rs != VMOBA_OK) return rs;
     return select_impl(B, Hh, S, D, n_blocks, blk_off, Qp, Kp, tau, score_scale, mode, topk, Bmean, P, mask, blk_ptr, q_idx,
-                       row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status, query_pos, ws,
+                       row_ptr, col_idx, pair_pos, nnz_capacity, k_out, theta_out, dev_status, query_pos, kv_rows, ws,
                        VMOBA_SELECT_STATIC_MAX_BYTES, stream);
 }

@@ -109,17 +109,19 @@ def unpack_mask(words: np.ndarray, nb: int) -> np.ndarray:
 
 
 def run_gpu(Q, K, V, dO, grid, block=(0, 0, 0), chunk=0, tau=0.25, dtype=torch.float32,
-            score_scale=None, softmax_scale=None, mode=0, topk=0, fused_io=False, q_in_place=False):
+            score_scale=None, softmax_scale=None, mode=0, topk=0, fused_io=False, q_in_place=False, kv_in_place=False):
     """Whole layer on the GPU.  Q, K, V, dO: numpy [B, S, Hh, D] float32 (dO may be None).
     With fused_io the attention calls write O and the gradients in the caller's token order
     themselves; their block-order views (Op, dQp, ...) are then gathered here on the host.
     With q_in_place the library never moves Q and numbers the queries by token: P, mask, LSE are
     brought to block order here (row p = token perm[p]) so that they compare with the oracle's;
-    the lists stay as written (query ids = token ids) next to `mask_q`, the mask in that order."""
+    the lists stay as written (query ids = token ids) next to `mask_q`, the mask in that order.
+    With kv_in_place (implies q_in_place) the library moves nothing at all."""
     B, S, Hh, D = Q.shape
     plan = vb.LayerPlan(B, Hh, D, grid, block, chunk, tau, dtype, score_scale=score_scale,
                         softmax_scale=softmax_scale, need_bwd=dO is not None, mode=mode, topk=topk, fused_io=fused_io,
-                        q_in_place=q_in_place)
+                        q_in_place=q_in_place, kv_in_place=kv_in_place)
+    q_in_place = plan.q_in_place
     assert plan.S == S
     fused_io = plan.fused_io
     q, k, v = (to_dev(x, dtype) for x in (Q, K, V))
@@ -141,8 +143,9 @@ def run_gpu(Q, K, V, dO, grid, block=(0, 0, 0), chunk=0, tau=0.25, dtype=torch.f
     out.update(plan=plan, nb=nb, cap=plan.cap,
                perm=perm, inv_perm=plan.inv_perm.cpu().numpy(),
                blk_off=plan.blk_off.cpu().numpy(),
-               Qp=Qp, Kp=np32(plan.Kp.permute(0, 2, 1, 3)),
-               Vp=np32(plan.Vp.permute(0, 2, 1, 3)),
+               Qp=Qp,
+               Kp=np.ascontiguousarray(K[:, perm].transpose(0, 2, 1, 3)) if kv_in_place else np32(plan.Kp.permute(0, 2, 1, 3)),
+               Vp=np.ascontiguousarray(V[:, perm].transpose(0, 2, 1, 3)) if kv_in_place else np32(plan.Vp.permute(0, 2, 1, 3)),
                O=np32(plan.O), LSE=LSE, Bmean=plan.Bmean.cpu().numpy(),
                P=P, mask=mask, mask_q=mask_q,
                k=plan.k_out.cpu().numpy().reshape(B, Hh), theta=plan.theta.cpu().numpy().reshape(B, Hh),

@@ -52,11 +52,13 @@ def oracle_with_gpu_mask(g, Q, K, V, dO, softmax_scale):
     return res
 
 
-def compare_layer(Q, K, V, dO, grid, block, chunk, tau, dtype, label="", mode=0, topk=0, fused_io=False, q_in_place=False):
+def compare_layer(Q, K, V, dO, grid, block, chunk, tau, dtype, label="", mode=0, topk=0, fused_io=False, q_in_place=False,
+                  kv_in_place=False):
     B, S, Hh, D = Q.shape
     case = f"{label} S={S} Hh={Hh} D={D} grid={grid} block={block} chunk={chunk} tau={tau} mode={mode}"
     print(f"[parity] {case} {dtype}", flush=True)
-    g = gu.run_gpu(Q, K, V, dO, grid, block, chunk, tau, dtype, mode=mode, topk=topk, fused_io=fused_io, q_in_place=q_in_place)
+    g = gu.run_gpu(Q, K, V, dO, grid, block, chunk, tau, dtype, mode=mode, topk=topk, fused_io=fused_io, q_in_place=q_in_place,
+                   kv_in_place=kv_in_place)
     o = oracle_selection(Q, K, grid, block, chunk, tau, mode, topk)
     # --- partition: bit exact
     assert np.array_equal(g["perm"], o["perm"])
@@ -228,6 +230,29 @@ def test_queries_in_place(dtype, mode, topk):
     tol = 1e-5 if dtype == torch.float32 else 2e-2
     for n in ("dK", "dV"):
         np.testing.assert_allclose(g[n], u[n], rtol=tol, atol=tol)
+
+
+@pytest.mark.parametrize("dtype,D", [(torch.float32, 64), (torch.bfloat16, 64), (torch.bfloat16, 128)])
+def test_keys_in_place(dtype, D):
+    """Nothing is rearranged in memory: the partition call only builds the index arrays and every kernel finds key
+    position k at row perm[k] of the caller's K and V.  Against the oracle, and bit for bit against the path that
+    rearranges K and V (same rows, same order of work, other addresses)."""
+    grid, block = (6, 12, 13), (4, 5, 13)            # ragged; blocks of 130 .. 260 keys: several 32-key groups per tile
+    S = grid[0] * grid[1] * grid[2]
+    Q, K, V, dO = (synth.to_bf16_grid(synth.iid_normal(180 + i, (2, S, 3, D))) for i in range(4))
+    g, o = compare_layer(Q, K, V, dO, grid, block, 0, 0.4, dtype, "kv-in-place", kv_in_place=True)
+    u = gu.run_gpu(Q, K, V, dO, grid, block, 0, 0.4, dtype, q_in_place=True)
+    for n in ("Bmean", "P", "mask", "k", "O", "LSE", "dQ", "dK", "dV"):
+        assert np.array_equal(g[n], u[n]), n
+
+
+def test_keys_in_place_block_longer_than_the_row_table():
+    """A key block of 4000 keys: more than the forward tile kernel's in-LDS table of row numbers holds, so its rows are
+    looked up in global memory; next to it a block of 608 keys that uses the table."""
+    grid = (2, 48, 48)
+    S = grid[0] * grid[1] * grid[2]
+    Q, K, V, dO = (synth.to_bf16_grid(synth.iid_normal(190 + i, (1, S, 1, 128))) for i in range(4))
+    compare_layer(Q, K, V, dO, grid, (0, 0, 0), 4000, 0.7, torch.bfloat16, "kv-in-place-long-block", kv_in_place=True)
 
 
 def test_tau_one_is_dense_attention():

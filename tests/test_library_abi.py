@@ -75,12 +75,12 @@ def test_bad_arguments_are_rejected_before_any_launch(L):
     assert L.vmoba_partition(C.byref(g), 1, 1, 1, 48, 0, None, None, dummy, None, None, None) == vb.VMOBA_ERR_UNSUPPORTED
     t = vb.vmoba_tensor(256, vb.VMOBA_F32, 64 * 64, 64, 64)
     args = [1, 1, 64, 64, 8, dummy, C.byref(t), C.byref(t)]
-    tail = [dummy] * 8 + [100, dummy, dummy, dummy, None, dummy, 1 << 30, None]
+    tail = [dummy] * 8 + [100, dummy, dummy, dummy, None, None, dummy, 1 << 30, None]
     assert L.vmoba_select(*args, 0.0, 0.125, 0, 0, *tail) == vb.VMOBA_ERR_INVALID_ARG      # tau = 0
     assert L.vmoba_select(*args, 1.5, 0.125, 0, 0, *tail) == vb.VMOBA_ERR_INVALID_ARG      # tau > 1
     assert L.vmoba_select(*args, 0.25, 0.125, 7, 0, *tail) == vb.VMOBA_ERR_UNSUPPORTED     # unknown mode
     assert L.vmoba_select(*args, 0.25, 0.125, vb.LOCAL_TOPK, 0, *tail) == vb.VMOBA_ERR_INVALID_ARG   # top-k mode, k = 0
-    tail_small = [dummy] * 8 + [100, dummy, dummy, dummy, None, dummy, 16, None]
+    tail_small = [dummy] * 8 + [100, dummy, dummy, dummy, None, None, dummy, 16, None]
     assert L.vmoba_select(*args, 0.25, 0.125, 0, 0, *tail_small) == vb.VMOBA_ERR_WORKSPACE
     assert vb.status_string(vb.VMOBA_ERR_WORKSPACE) == "workspace too small"
 

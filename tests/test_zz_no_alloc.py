@@ -62,5 +62,5 @@ def test_static_scratch_rejects_geometries_beyond_its_size():
     need = vb.vmoba_workspace_bytes(vb.OP_SELECT, 1, 40, 111600, 128, 165, 1 << 20, vb.VMOBA_BF16)
     assert need > vb.SELECT_STATIC_MAX_BYTES
     rc = L.vmoba_select_static(1, 40, 111600, 128, 165, dummy, C.byref(t), C.byref(t), 0.25, 0.1, 0, 0,
-                               *([dummy] * 8), 1 << 20, dummy, dummy, dummy, None, None)
+                               *([dummy] * 8), 1 << 20, dummy, dummy, dummy, None, None, None)
     assert rc == vb.VMOBA_ERR_WORKSPACE
