@@ -361,7 +361,7 @@ def main():
     dom_ms = sum(ktime[dom])
     achieved = dom_flops / (dom_ms * 1e-3) / 1e12
     traffic = None
-    if args.config == "480p" and abs(args.tau - 0.25) < 1e-9 and len(kinds) == 3:
+    if args.config == "480p" and abs(args.tau - 0.25) < 1e-9 and kinds == ["1d", "2d", "3d"]:
         traffic = MEASURED_TRAFFIC_BYTES_480P.get(SLOTS[dom])
     def by_kind(vals):      # median and minimum of a per-step series, per partition kind (the kinds differ in work)
         return {k: {"median_ms": float(np.median([v for v, sk in zip(vals, step_kinds) if sk == k])),
