@@ -1100,12 +1100,13 @@ __global__ __launch_bounds__(256) void dq_merge_kernel(const float* __restrict__
     float acc[CH];
 #pragma unroll
     for (int c = 0; c < CH; ++c) acc[c] = 0.f;
-    for (int r = r0; r < r1; r += 4) {               // four partial rows in flight per step
-        long long pair[4];
+    constexpr int MB = 8;                            // partial rows in flight per lane
+    for (int r = r0; r < r1; r += MB) {
+        long long pair[MB];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) pair[u] = seg + pair_pos[seg + min(r + u, r1 - 1)];
+        for (int u = 0; u < MB; ++u) pair[u] = seg + pair_pos[seg + min(r + u, r1 - 1)];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < MB; ++u) {
             const float keep = (r + u < r1) ? 1.f : 0.f;
             if constexpr (BF16) {
                 const u32x4_t v = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const uint16_t*>(dQpart) + pair[u] * D + part * 8);
@@ -1229,17 +1230,15 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     }
     // ---- dQ
     const int TM = simple ? 64 : 128;
-    tile_start_kernel<<<dim3((BH + 63) / 64), dim3(64), 0, st>>>(blk_ptr, ws.tile_start, BH, n_blocks, TM);
+    tile_plan_kernel<<<dim3(1), dim3(1024), 0, st>>>(blk_ptr, ws.tile_start, ws.head_base, BH, n_blocks, TM);
     VMOBA_CHECK_LAUNCH();
     const int64_t max_tiles = std::min<int64_t>(vmoba_max_tiles(nnz_capacity, TM), (nnz_capacity / TM + n_blocks + 7) / 8 * 8);
     if (simple) {
         tile_desc_kernel<<<dim3((unsigned)ceil_div64(max_tiles, 256), (unsigned)BH), dim3(256), 0, st>>>(
             ws.tile_start, blk_ptr, blk_off, ws.tile_desc, n_blocks, TM, (int)max_tiles);
     } else {
-        head_base_kernel<<<dim3(1), dim3(64), 0, st>>>(ws.tile_start, ws.head_base, BH, n_blocks);
-        VMOBA_CHECK_LAUNCH();
         flat_tile_desc_kernel<<<dim3((unsigned)ceil_div64(max_tiles, 256), (unsigned)BH), dim3(256), 0, st>>>(
-            ws.tile_start, blk_ptr, blk_off, ws.head_base, ws.tile_desc, n_blocks, TM, (int)max_tiles);
+            ws.tile_start, blk_ptr, blk_off, ws.tile_desc, n_blocks, TM, (int)max_tiles);
     }
     VMOBA_CHECK_LAUNCH();
     {

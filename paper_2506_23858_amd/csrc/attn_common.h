@@ -3,8 +3,8 @@
 // Work decomposition (both directions).  The selection mask is kept block-major, the
 // orientation M_i in (N_b, s) of Eq. 3: for key block j, q_idx[blk_ptr[j] .. blk_ptr[j+1]) lists
 // the queries that keep it.  A "tile" is TM consecutive entries of one such list, i.e. TM gathered
-// queries that all attend to the same key block.  tile_start[bh][j] = number of tiles of blocks
-// 0..j-1, written on the device from blk_ptr, so the host never learns the data-dependent counts;
+// queries that all attend to the same key block.  tile_start[bh][j] = number of tiles before block
+// j of head bh, written on the device from blk_ptr, so the host never learns the data-dependent counts;
 // the grid is sized from nnz_capacity and surplus workgroups leave at once.
 //
 // MFMA operand plumbing (v_mfma_f32_32x32x16_bf16; lane = 32*hf + l32):
@@ -87,21 +87,21 @@ __device__ __forceinline__ bool find_tile(const int4* __restrict__ tile_desc, in
     return true;
 }
 
-// tile_start[bh][j] = number of tiles (of TM list entries) in blocks 0..j-1.  One thread per head.
-__global__ __launch_bounds__(64) void tile_start_kernel(const int* __restrict__ blk_ptr, int* __restrict__ tile_start,
-                                                        int BH, int nb, int TM);
-// Descriptor of every tile id below tiles_per_head (one thread per id; ids past the head's last tile get count 0).
+// Tile plan (defined in attn_fwd.hip): tile_start[bh][j] = tiles of all (head, block) pairs before (bh, j) in the call's
+// flat list, tile_start[bh][nb] = first tile of the next head, head_base[bh] = tile_start[bh][0], head_base[BH] = total.
+__global__ __launch_bounds__(1024) void tile_plan_kernel(const int* __restrict__ blk_ptr, int* __restrict__ tile_start,
+                                                         int* __restrict__ head_base, int BH, int nb, int TM);
+// Descriptor of every tile id below tiles_per_head of a head (one thread per id; ids past the head's last tile get count 0).
 __global__ __launch_bounds__(256) void tile_desc_kernel(const int* __restrict__ tile_start, const int* __restrict__ blk_ptr,
                                                         const int* __restrict__ blk_off, int4* __restrict__ tile_desc,
                                                         int nb, int TM, int tiles_per_head);
 
 inline __device__ float exp2_raw(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Flat tile list over all heads for the persistent tile kernels (defined next to tile_start_kernel).
-__global__ void head_base_kernel(const int* __restrict__ tile_start, int* __restrict__ head_base, int BH, int nb);
+// Flat tile list over all heads for the MFMA tile kernels.
 __global__ __launch_bounds__(256) void flat_tile_desc_kernel(const int* __restrict__ tile_start, const int* __restrict__ blk_ptr,
-                                                             const int* __restrict__ blk_off, const int* __restrict__ head_base,
-                                                             int4* __restrict__ flat_desc, int nb, int TM, int tiles_per_head);
+                                                             const int* __restrict__ blk_off, int4* __restrict__ flat_desc,
+                                                             int nb, int TM, int tiles_per_head);
 // Compute units of the current device (queried once).
 int vmoba_num_cus();
 

@@ -13,20 +13,55 @@
 #include <cmath>
 #include <type_traits>
 
-__global__ __launch_bounds__(64) void tile_start_kernel(const int* __restrict__ blk_ptr, int* __restrict__ tile_start,
-                                                        int BH, int nb, int TM) {
-    const int bh = blockIdx.x * 64 + threadIdx.x;
-    if (bh >= BH) return;
-    const int* bp = blk_ptr + (long long)bh * (nb + 1);
-    int* ts = tile_start + (long long)bh * (nb + 1);
-    int run = 0;
-    for (int j = 0; j < nb; ++j) {
-        ts[j] = run;
-        run += (bp[j + 1] - bp[j] + TM - 1) / TM;
+// Tile plan of a call: tile_start[bh][j] = number of tiles (of TM list entries) in all (head, block) pairs before
+// (bh, j), counted over the whole flat list of the call -- heads in order, blocks in order -- tile_start[bh][nb] = the
+// same for the first pair of the next head, and head_base[bh] = tile_start[bh][0], head_base[BH] = total.  One
+// workgroup; a scan over the BH * nb tile counts in batches of 1024.
+__global__ __launch_bounds__(1024) void tile_plan_kernel(const int* __restrict__ blk_ptr, int* __restrict__ tile_start,
+                                                         int* __restrict__ head_base, int BH, int nb, int TM) {
+    __shared__ int sW[16];
+    __shared__ int sCarry;
+    const int t = threadIdx.x, n = BH * nb;
+    if (t == 0) sCarry = 0;
+    __syncthreads();
+    for (int base = 0; base < n; base += 1024) {
+        const int i = base + t;
+        int v = 0, bh = 0, j = 0;
+        if (i < n) {
+            bh = i / nb;
+            j = i - bh * nb;
+            const int* bp = blk_ptr + (long long)bh * (nb + 1);
+            v = (bp[j + 1] - bp[j] + TM - 1) / TM;
+        }
+        int incl = v;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(incl, off, 64);
+            if ((t & 63) >= off) incl += o;
+        }
+        if ((t & 63) == 63) sW[t >> 6] = incl;
+        __syncthreads();
+        int wave_base = 0;
+        for (int w = 0; w < (t >> 6); ++w) wave_base += sW[w];
+        const int excl = sCarry + wave_base + incl - v;
+        if (i < n) {
+            tile_start[(long long)bh * (nb + 1) + j] = excl;
+            if (j == 0) {
+                head_base[bh] = excl;
+                if (bh > 0) tile_start[(long long)(bh - 1) * (nb + 1) + nb] = excl;
+            }
+        }
+        __syncthreads();
+        if (t == 1023) sCarry = excl + v;
+        __syncthreads();
     }
-    ts[nb] = run;
+    if (t == 0) {
+        tile_start[(long long)(BH - 1) * (nb + 1) + nb] = sCarry;
+        head_base[BH] = sCarry;
+    }
 }
 
+// Per-head tile descriptors of the float32 path (grid: tile id x head; ids past the head's last tile get count 0).
 __global__ __launch_bounds__(256) void tile_desc_kernel(const int* __restrict__ tile_start, const int* __restrict__ blk_ptr,
                                                         const int* __restrict__ blk_off, int4* __restrict__ tile_desc,
                                                         int nb, int TM, int tiles_per_head) {
@@ -34,15 +69,16 @@ __global__ __launch_bounds__(256) void tile_desc_kernel(const int* __restrict__ 
     const int tile = blockIdx.x * 256 + threadIdx.x;
     if (tile >= tiles_per_head) return;
     const int* ts = tile_start + (long long)bh * (nb + 1);
+    const int first = ts[0];
     int4 d = {0, 0, 0, 0};
-    if (tile < ts[nb]) {
-        int lo = 0, hi = nb;           // largest j with ts[j] <= tile
+    if (tile < ts[nb] - first) {
+        int lo = 0, hi = nb;           // largest j with ts[j] - first <= tile
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
-            if (ts[mid] <= tile) lo = mid; else hi = mid;
+            if (ts[mid] - first <= tile) lo = mid; else hi = mid;
         }
         const int* bp = blk_ptr + (long long)bh * (nb + 1);
-        const int t0 = (tile - ts[lo]) * TM;
+        const int t0 = (tile - (ts[lo] - first)) * TM;
         d.x = bp[lo] + t0;
         d.y = min(TM, bp[lo + 1] - bp[lo] - t0);
         d.z = blk_off[lo];
@@ -51,39 +87,29 @@ __global__ __launch_bounds__(256) void tile_desc_kernel(const int* __restrict__ 
     tile_desc[(long long)bh * tiles_per_head + tile] = d;
 }
 
-// Flat tile list over all heads for the persistent tile kernels.  head_base[bh] = number of tiles of the heads
-// before bh (head_base[BH] = total); one thread.
-__global__ void head_base_kernel(const int* __restrict__ tile_start, int* __restrict__ head_base, int BH, int nb) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    int run = 0;
-    for (int bh = 0; bh < BH; ++bh) {
-        head_base[bh] = run;
-        run += tile_start[(long long)bh * (nb + 1) + nb];
-    }
-    head_base[BH] = run;
-}
-// flat_desc[head_base[bh] + tile] = {first list entry, count | bh << 10, first key, block length}; one thread per
-// (head, tile id below tiles_per_head).
+// Flat tile list over all heads for the MFMA tile kernels: flat_desc[tile_start[bh][0] + tile] = {first list entry,
+// count | bh << 10, first key, block length}; one thread per (head, tile id below tiles_per_head).
 __global__ __launch_bounds__(256) void flat_tile_desc_kernel(const int* __restrict__ tile_start, const int* __restrict__ blk_ptr,
-                                                             const int* __restrict__ blk_off, const int* __restrict__ head_base,
-                                                             int4* __restrict__ flat_desc, int nb, int TM, int tiles_per_head) {
+                                                             const int* __restrict__ blk_off, int4* __restrict__ flat_desc,
+                                                             int nb, int TM, int tiles_per_head) {
     const int bh = blockIdx.y;
     const int tile = blockIdx.x * 256 + threadIdx.x;
     const int* ts = tile_start + (long long)bh * (nb + 1);
-    if (tile >= tiles_per_head || tile >= ts[nb]) return;
-    int lo = 0, hi = nb;           // largest j with ts[j] <= tile
+    const int first = ts[0];
+    if (tile >= tiles_per_head || tile >= ts[nb] - first) return;
+    int lo = 0, hi = nb;           // largest j with ts[j] - first <= tile
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
-        if (ts[mid] <= tile) lo = mid; else hi = mid;
+        if (ts[mid] - first <= tile) lo = mid; else hi = mid;
     }
     const int* bp = blk_ptr + (long long)bh * (nb + 1);
-    const int t0 = (tile - ts[lo]) * TM;
+    const int t0 = (tile - (ts[lo] - first)) * TM;
     int4 d;
     d.x = bp[lo] + t0;
     d.y = min(TM, bp[lo + 1] - bp[lo] - t0) | (bh << 10);
     d.z = blk_off[lo];
     d.w = blk_off[lo + 1] - blk_off[lo];
-    flat_desc[head_base[bh] + tile] = d;
+    flat_desc[first + tile] = d;
 }
 
 namespace {
@@ -593,6 +619,7 @@ __global__ __launch_bounds__(256) void attn_fwd_merge_kernel(const float* __rest
                                                              TensorView O, float* __restrict__ LSE,
                                                              const int* __restrict__ out_rows, int Hh, int S, long long cap) {
     constexpr int CH = BF16 ? 8 : 4;
+    constexpr int MB = 8;                    // partial rows in flight per lane
     constexpr int LPQ = D / CH;              // lanes per query
     constexpr int QPW = 256 / LPQ;           // queries per workgroup
     const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
@@ -603,22 +630,22 @@ __global__ __launch_bounds__(256) void attn_fwd_merge_kernel(const float* __rest
     const int r0 = row_ptr[(long long)bh * (S + 1) + q];
     const int r1 = fits ? row_ptr[(long long)bh * (S + 1) + q + 1] : r0;
     const long long seg = (long long)bh * cap;
-    // one pass with a running maximum; four partials in flight per step (index -> lse and row loads)
+    // one pass with a running maximum; MB partials in flight per step (index -> lse and row loads)
     float mx = -INFINITY;
     float acc[CH];
 #pragma unroll
     for (int c = 0; c < CH; ++c) acc[c] = 0.f;
     float wsum = 0.f;
-    for (int r = r0; r < r1; r += 4) {
-        long long pair[4];
-        float l[4];
+    for (int r = r0; r < r1; r += MB) {
+        long long pair[MB];
+        float l[MB];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) pair[u] = seg + pair_pos[seg + min(r + u, r1 - 1)];
+        for (int u = 0; u < MB; ++u) pair[u] = seg + pair_pos[seg + min(r + u, r1 - 1)];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) l[u] = (r + u < r1) ? lse_part[pair[u]] : -INFINITY;
-        float v[4][CH];
+        for (int u = 0; u < MB; ++u) l[u] = (r + u < r1) ? lse_part[pair[u]] : -INFINITY;
+        float v[MB][CH];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < MB; ++u) {
             if constexpr (BF16) {
                 const u32x4_t x = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const uint16_t*>(Opart) + pair[u] * D + part * 8);
                 v[u][0] = bf16lo_to_f32(x.x); v[u][1] = bf16hi_to_f32(x.x); v[u][2] = bf16lo_to_f32(x.y); v[u][3] = bf16hi_to_f32(x.y);
@@ -628,13 +655,15 @@ __global__ __launch_bounds__(256) void attn_fwd_merge_kernel(const float* __rest
                 v[u][0] = x.x; v[u][1] = x.y; v[u][2] = x.z; v[u][3] = x.w;
             }
         }
-        const float m_new = fmaxf(fmaxf(mx, fmaxf(l[0], l[1])), fmaxf(l[2], l[3]));
+        float m_new = mx;
+#pragma unroll
+        for (int u = 0; u < MB; ++u) m_new = fmaxf(m_new, l[u]);
         const float alpha = expf(mx - m_new);          // exp(-inf) = 0 on the first step (m_new is finite: l[0] is)
         wsum *= alpha;
 #pragma unroll
         for (int c = 0; c < CH; ++c) acc[c] *= alpha;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < MB; ++u) {
             const float w = expf(l[u] - m_new);        // 0 for the padding entries
             wsum += w;
 #pragma unroll
@@ -749,17 +778,15 @@ extern "C" int vmoba_attn_fwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
     // rows are fetched once per 256 queries); D = 64: 128-query tiles, two workgroups of 4 wavefronts per compute unit
     const bool wide = !simple && D == 128;
     const int TM = simple ? 64 : (wide ? 256 : 128);
-    tile_start_kernel<<<dim3((BH + 63) / 64), dim3(64), 0, st>>>(blk_ptr, ws.tile_start, BH, n_blocks, TM);
+    tile_plan_kernel<<<dim3(1), dim3(1024), 0, st>>>(blk_ptr, ws.tile_start, ws.head_base, BH, n_blocks, TM);
     VMOBA_CHECK_LAUNCH();
     const int64_t max_tiles = std::min<int64_t>(vmoba_max_tiles(nnz_capacity, TM), (nnz_capacity / TM + n_blocks + 7) / 8 * 8);
     if (simple) {
         tile_desc_kernel<<<dim3((unsigned)ceil_div64(max_tiles, 256), (unsigned)BH), dim3(256), 0, st>>>(
             ws.tile_start, blk_ptr, blk_off, ws.tile_desc, n_blocks, TM, (int)max_tiles);
     } else {
-        head_base_kernel<<<dim3(1), dim3(64), 0, st>>>(ws.tile_start, ws.head_base, BH, n_blocks);
-        VMOBA_CHECK_LAUNCH();
         flat_tile_desc_kernel<<<dim3((unsigned)ceil_div64(max_tiles, 256), (unsigned)BH), dim3(256), 0, st>>>(
-            ws.tile_start, blk_ptr, blk_off, ws.head_base, ws.tile_desc, n_blocks, TM, (int)max_tiles);
+            ws.tile_start, blk_ptr, blk_off, ws.tile_desc, n_blocks, TM, (int)max_tiles);
     }
     VMOBA_CHECK_LAUNCH();
     VMOBA_PROFILE_BEGIN(0, st);

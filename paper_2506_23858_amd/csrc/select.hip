@@ -196,16 +196,18 @@ __global__ __launch_bounds__(256) void score_kernel(TensorView Q, const float* _
             for (int j = lane; j < nb; j += 64) {
                 float p = sP[r * pstride + j];
                 dst[j] = p;
-                unsigned int bin = min(__float_as_uint(p) >> 20, (unsigned)(HIST_BINS - 1));
-                atomicAdd(&sCnt[bin], 1u);
-                atomicAdd(&sSum[bin], to_fixed(p, fix_shift));
+                if (hist_cnt) {               // null: the caller takes the first radix level elsewhere (pool soft-max)
+                    unsigned int bin = min(__float_as_uint(p) >> 20, (unsigned)(HIST_BINS - 1));
+                    atomicAdd(&sCnt[bin], 1u);
+                    atomicAdd(&sSum[bin], to_fixed(p, fix_shift));
+                }
             }
         }
         __syncthreads();
     }
     for (int i = tid; i < HIST_BINS; i += 256) {
         unsigned int c = sCnt[i];
-        if (c) {
+        if (c) {                               // stays 0 without a histogram
             atomicAdd(&hist_cnt[(long long)bh * HIST_BINS + i], c);
             atomicAdd(&hist_sum[(long long)bh * HIST_BINS + i], sSum[i]);
         }
@@ -420,7 +422,7 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
                         }
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            if (j0 + r < nb) {
+                            if (hist_cnt && j0 + r < nb) {
                                 const unsigned int bin = min(__float_as_uint(pv[r]) >> 20, (unsigned)(HIST_BINS - 1));
                                 atomicAdd(&sCnt[bin], 1u);
                                 atomicAdd(&sSum[bin], to_fixed(pv[r], fix_shift));
@@ -481,9 +483,11 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(float* __restrict__ P
             if (j < nb) {
                 const float p = v[c] / den;
                 row[j] = p;
-                const unsigned int bin = min(__float_as_uint(p) >> 20, (unsigned)(HIST_BINS - 1));
-                atomicAdd(&sCnt[bin], 1u);
-                atomicAdd(&sSum[bin], to_fixed(p, fix_shift));
+                if (hist_cnt) {
+                    const unsigned int bin = min(__float_as_uint(p) >> 20, (unsigned)(HIST_BINS - 1));
+                    atomicAdd(&sCnt[bin], 1u);
+                    atomicAdd(&sSum[bin], to_fixed(p, fix_shift));
+                }
             }
         }
     }
@@ -692,7 +696,7 @@ __global__ __launch_bounds__(256) void refine_hist_kernel(const float* __restric
     __syncthreads();
     for (int i = threadIdx.x; i < HIST_BINS; i += 256) {
         unsigned int c = sCnt[i];
-        if (c) {
+        if (c) {                               // stays 0 without a histogram
             atomicAdd(&hist_cnt[(long long)bh * HIST_BINS + i], c);
             atomicAdd(&hist_sum[(long long)bh * HIST_BINS + i], sSum[i]);
         }
@@ -1062,24 +1066,36 @@ __global__ __launch_bounds__(256) void wave_scan_kernel(int* __restrict__ wcnt, 
     if (t == 0) blk_cnt[(long long)bh * nb + j] = sCarry;
 }
 
-// blk_ptr = exclusive scan of blk_cnt over blocks; capacity check.  One wavefront-sized loop per head.
+// blk_ptr = exclusive scan of blk_cnt over blocks; capacity check.  One wavefront per head, a run of blocks per lane.
 // A head that kept more than `cap` pairs gets an all-zero blk_ptr -- to the attention calls it selected nothing, so no
 // list entry of it is ever read (the merge kernels recognise the same head by row_ptr[S] > cap) -- and the status word
 // is set.
 __global__ __launch_bounds__(64) void blk_ptr_kernel(const int* __restrict__ blk_cnt, int* __restrict__ blk_ptr,
                                                      int nb, long long cap, int* __restrict__ dev_status) {
-    const int bh = blockIdx.x;
-    if (threadIdx.x != 0) return;
-    long long total = 0;
-    for (int j = 0; j < nb; ++j) total += blk_cnt[(long long)bh * nb + j];
-    const bool fits = total <= cap;
-    long long run = 0;
-    for (int j = 0; j < nb; ++j) {
-        blk_ptr[(long long)bh * (nb + 1) + j] = fits ? (int)run : 0;
-        run += blk_cnt[(long long)bh * nb + j];
+    const int bh = blockIdx.x, lane = threadIdx.x;
+    const int per = (nb + 63) / 64;                  // consecutive blocks per lane
+    const int j0 = lane * per, j1 = min(nb, j0 + per);
+    const int* cnt = blk_cnt + (long long)bh * nb;
+    int* out = blk_ptr + (long long)bh * (nb + 1);
+    int mine = 0;
+    for (int j = j0; j < j1; ++j) mine += cnt[j];
+    int incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += o;
     }
-    blk_ptr[(long long)bh * (nb + 1) + nb] = fits ? (int)run : 0;
-    if (!fits) atomicExch(dev_status, (int)VMOBA_ERR_CAPACITY);
+    const long long total = __shfl(incl, 63, 64);
+    const bool fits = total <= cap;
+    int run = incl - mine;
+    for (int j = j0; j < j1; ++j) {
+        out[j] = fits ? run : 0;
+        run += cnt[j];
+    }
+    if (lane == 0) {
+        out[nb] = fits ? (int)total : 0;
+        if (!fits) atomicExch(dev_status, (int)VMOBA_ERR_CAPACITY);
+    }
 }
 
 // Fill q_idx (block-major), col_idx and pair_pos (query-major).  One wavefront per 64 queries,
@@ -1276,6 +1292,8 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
     VMOBA_CHECK_LAUNCH();
 
     float2* row_stat = pool_softmax ? ws.row_stat : nullptr;
+    // pool soft-max: the radix levels run over the pool-normalised values, which only exist after the row statistics
+    unsigned int* score_hist = pool_softmax ? nullptr : ws.hist_cnt;
     const int n_tiles = (int)ceil_div64(S, QT);
     const int tiles_per_wg = 4;
     dim3 sgrid((unsigned)ceil_div64(n_tiles, tiles_per_wg), (unsigned)BH);
@@ -1283,7 +1301,7 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
     do {                                                                                                  \
         auto kfn = score_kernel<DD>;                                                                      \
         if (allow_full_lds((const void*)kfn, DD == 128 ? 0 : 1) != VMOBA_OK) return VMOBA_ERR_HIP;        \
-        kfn<<<sgrid, dim3(256), lds, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, n_blocks,  \
+        kfn<<<sgrid, dim3(256), lds, st>>>(Qv, Bmean, P, score_hist, ws.hist_sum, Hh, (int)S, n_blocks,   \
                                            score_scale, fix_shift, row_stat);                             \
     } while (0)
     if (bf16) {
@@ -1292,7 +1310,7 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
     do {                                                                                                  \
         auto kfn = score_mfma_kernel<DD, FL, RW>;                                                         \
         if (allow_full_lds((const void*)kfn, 2 + (DD == 128 ? 0 : 3) + (RW ? 2 : FL ? 1 : 0)) != VMOBA_OK) return VMOBA_ERR_HIP; \
-        kfn<<<mgrid, dim3(SCORE_NT), lds, st>>>(Qv, Bmean, P, ws.hist_cnt, ws.hist_sum, Hh, (int)S, NBC, n_blocks, JB0, \
+        kfn<<<mgrid, dim3(SCORE_NT), lds, st>>>(Qv, Bmean, P, score_hist, ws.hist_sum, Hh, (int)S, NBC, n_blocks, JB0, \
                                                 score_scale, fix_shift, row_stat);                        \
     } while (0)
         if (chunked) {
@@ -1304,7 +1322,7 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
                 VMOBA_CHECK_LAUNCH();
             }
             softmax_rows_kernel<<<dim3((unsigned)std::min<int64_t>(ceil_div64(S, 4 * 8), 2048), (unsigned)BH), dim3(256), 0, st>>>(
-                P, ws.hist_cnt, ws.hist_sum, (int)S, n_blocks, fix_shift, row_stat);
+                P, score_hist, ws.hist_sum, (int)S, n_blocks, fix_shift, row_stat);
         } else if (D == 128 && fly) LAUNCH_SCORE_MFMA(128, true, false, n_blocks, 0);
         else if (D == 128) LAUNCH_SCORE_MFMA(128, false, false, n_blocks, 0);
         else if (fly) LAUNCH_SCORE_MFMA(64, true, false, n_blocks, 0);
@@ -1315,9 +1333,7 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
 #undef LAUNCH_SCORE
     VMOBA_CHECK_LAUNCH();
     if (pool_softmax) {
-        // the score kernel's first radix level was taken over the row soft-max: start it again over G
-        zero_words_kernel<<<dim3(64), dim3(256), 0, st>>>((unsigned int*)workspace, ws.zero_bytes / 4);
-        VMOBA_CHECK_LAUNCH();
+        // the score kernel took no histogram in this mode: the first radix level is taken over G here
         pool_stat_kernel<<<dim3(BH), dim3(1024), 0, st>>>(ws.row_stat, ws.pool_stat, (int)S);
         VMOBA_CHECK_LAUNCH();
         pool_rescale_kernel<<<dim3((unsigned)std::min<int64_t>(ceil_div64(S, 4 * 8), 1024), (unsigned)BH), dim3(256), 0, st>>>(
