@@ -255,6 +255,33 @@ def test_keys_in_place_block_longer_than_the_row_table():
     compare_layer(Q, K, V, dO, grid, (0, 0, 0), 4000, 0.7, torch.bfloat16, "kv-in-place-long-block", kv_in_place=True)
 
 
+@pytest.mark.parametrize("mode", ["permute", "q_in_place", "kv_in_place"])
+def test_strided_inputs_from_a_packed_qkv_tensor(mode):
+    """Q, K, V as views into one packed [B, S, 3, Hh, D] projection output (token stride 3 * Hh * D), dO and the outputs
+    as every other head of wider tensors: the kernels address everything through the strides, so the results are bit
+    for bit those of the contiguous tensors."""
+    grid, block, tau, D, Hh = (5, 7, 9), (2, 3, 4), 0.3, 128, 2
+    S = grid[0] * grid[1] * grid[2]
+    Q, K, V, dO = (synth.to_bf16_grid(synth.iid_normal(200 + i, (2, S, Hh, D))) for i in range(4))
+    kw = dict(fused_io=True, q_in_place=mode != "permute", kv_in_place=mode == "kv_in_place")
+    ref = gu.run_gpu(Q, K, V, dO, grid, block, 0, tau, torch.bfloat16, **kw)
+    plan = vb.LayerPlan(2, Hh, D, grid, block, 0, tau, torch.bfloat16, **kw)
+    packed = torch.stack([gu.to_dev(x, torch.bfloat16) for x in (Q, K, V)], dim=2)          # [B, S, 3, Hh, D]
+    q, k, v = (packed[:, :, i] for i in range(3))
+    assert q.stride(1) == 3 * Hh * D and not q.is_contiguous()
+    wide = torch.zeros(2, S, 2 * Hh, D, dtype=torch.bfloat16, device="cuda")
+    wide[:, :, ::2] = gu.to_dev(dO, torch.bfloat16)
+    g_in = wide[:, :, ::2]                                                                  # head stride 2 * D
+    for name in ("O", "dQ", "dK", "dV"):
+        setattr(plan, name, torch.zeros(2, S, 2 * Hh, D, dtype=torch.bfloat16, device="cuda")[:, :, 1::2])
+    plan.forward(q, k, v)
+    plan.backward(g_in)
+    torch.cuda.synchronize()
+    assert int(plan.dev_status.item()) == 0
+    for name in ("O", "dQ", "dK", "dV"):
+        assert np.array_equal(gu.np32(getattr(plan, name)), ref[name]), name
+
+
 def test_tau_one_is_dense_attention():
     c = synth.CONFIGS["tiny"]
     Q, K, V, dO = synth.make_qkv("tiny")
