@@ -8,6 +8,7 @@
 // the descending cumulative sum reaches tau * S.  Per-bin sums are kept as 64-bit integers
 // (value * 2^fix_shift, truncated) so the result does not depend on the order of atomics.
 #include "common.h"
+#include "attn_common.h"
 
 #include <algorithm>
 #include <cmath>
@@ -113,14 +114,46 @@ __global__ __launch_bounds__(256) void block_mean_kernel(TensorView K, const int
     }
 }
 
-// floor(p * 2^fix_shift) for a finite p >= 0 below 2^(63 - fix_shift), by integer shifts of the float's mantissa
-// (exact, like the product in double precision it replaces, and a fraction of its instructions)
+// p * 2^fix_shift as an integer for a finite p >= 0 below 2^(63 - fix_shift), by a shift of the float's mantissa.
+// Exact for every p whose last mantissa bit is worth at least 2^-fix_shift; smaller values (below 2^(-fix_shift + 23),
+// at most 2^-14 of the pool's mass all together) count as 0.  Exactness is what lets a bin's sum be formed either value
+// by value or as (count * leading bits + sum of trailing bits) << shift: both give the same integer.
 __device__ __forceinline__ unsigned long long to_fixed(float p, int fix_shift) {
     const uint32_t b = __float_as_uint(p);
     const int e = (int)(b >> 23);
-    const uint32_t m = e ? ((b & 0x7fffffu) | 0x800000u) : (b & 0x7fffffu);
-    const int sh = (e ? e - 150 : -149) + fix_shift;
-    return sh >= 0 ? ((unsigned long long)m << sh) : (sh > -32 ? (unsigned long long)(m >> -sh) : 0ull);
+    const int sh = e - 150 + fix_shift;
+    return (e && sh >= 0) ? ((unsigned long long)((b & 0x7fffffu) | 0x800000u) << sh) : 0ull;
+}
+
+// Level-0 histogram word in LDS: entries of one bin share sign, exponent and the three leading mantissa bits, so a bin
+// needs only how many there are (bits 40..63) and the sum of their 20 trailing mantissa bits (bits 0..39): one 64-bit
+// LDS atomic per entry.  Holds up to 2^20 entries per bin and workgroup.
+constexpr unsigned long long PK_ONE = 1ull << 40;
+// `copies` (a power of two) interleaved replicas of the 1024 words, word = bin * copies + (lane % copies): the entries of
+// a row crowd into a few neighbouring bins, and lanes that hit the same word are served one after the other.
+__device__ __forceinline__ void packed_hist_add(unsigned long long* sPk, int copy_shift, int copy, float p) {
+    const unsigned int u = __float_as_uint(p);
+    atomicAdd(&sPk[(min(u >> 20, (unsigned)(HIST_BINS - 1)) << copy_shift) + copy], PK_ONE | (unsigned long long)(u & 0xfffffu));
+}
+// A workgroup's packed words -> the head's level-0 histogram (count and fixed-point sum per bin).
+__device__ __forceinline__ void packed_hist_flush(const unsigned long long* sPk, int copy_shift,
+                                                  unsigned int* __restrict__ hist_cnt,
+                                                  unsigned long long* __restrict__ hist_sum, long long bh, int fix_shift,
+                                                  int tid, int n_threads) {
+    for (int i = tid; i < HIST_BINS; i += n_threads) {
+        unsigned long long cnt = 0, low = 0;
+        for (int c = 0; c < (1 << copy_shift); ++c) {
+            const unsigned long long w = sPk[(i << copy_shift) + c];
+            cnt += w >> 40;
+            low += w & (PK_ONE - 1);
+        }
+        if (cnt) {
+            const int e = i >> 3, sh = e - 150 + fix_shift;
+            const unsigned long long lead = 0x800000ull | ((unsigned long long)(i & 7) << 20);
+            atomicAdd(&hist_cnt[bh * HIST_BINS + i], (unsigned int)cnt);
+            if (e && sh >= 0) atomicAdd(&hist_sum[bh * HIST_BINS + i], (cnt * lead + low) << sh);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -230,31 +263,33 @@ __global__ __launch_bounds__(256) void score_kernel(TensorView Q, const float* _
 // scores themselves into its columns of P -- and softmax_rows_kernel below turns the rows into P afterwards.
 // wavefronts per workgroup of the matrix-core score kernel (two per SIMD share one copy of the block means in LDS)
 constexpr int SCORE_NW = 8, SCORE_NT = 64 * SCORE_NW, SCORE_QT = 32 * SCORE_NW;
-template <int D, bool FLY, bool RAW>
+// NMT > 0: the number of 32-block tiles is that constant (the launch for up to 128 blocks picks the instantiation), so the
+// loops over tiles carry no run-time tests and only the last tile knows padding blocks; NMT = 0: read from nb.
+template <int D, bool FLY, bool RAW, int NMT>
 __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, const float* __restrict__ Bmean,
                                                          float* __restrict__ P, unsigned int* __restrict__ hist_cnt,
                                                          unsigned long long* __restrict__ hist_sum,
-                                                         int Hh, int S, int nb, int nb_total, int jb0, float score_scale,
-                                                         int fix_shift, float2* __restrict__ row_stat) {
+                                                         int BH, int Hh, int S, int nb, int nb_total, int jb0, float score_scale,
+                                                         int fix_shift, int copy_shift, float2* __restrict__ row_stat) {
     constexpr int STR = D + 8;                 // LDS row stride in bf16 elements
     constexpr int FSTR = D + 4;                // LDS row stride in float elements (FLY)
     constexpr int KSTEPS = D / 16;
-    constexpr int MAX_MT = FLY ? 8 : 4;        // up to 256 / 128 blocks
+    constexpr int MAX_MT = NMT > 0 ? NMT : (FLY ? 8 : 4);        // up to 256 / 128 blocks
     extern __shared__ __align__(16) unsigned char smem[];
-    const int nb_pad = (nb + 31) & ~31;
-    const int n_mt = nb_pad / 32;
+    const int nb_pad = NMT > 0 ? NMT * 32 : ((nb + 31) & ~31);
+    const int n_mt = NMT > 0 ? NMT : nb_pad / 32;
     __bf16* sB = reinterpret_cast<__bf16*>(smem);                                  // [3][nb_pad][STR]
     float* sBf = reinterpret_cast<float*>(smem);                                   // FLY: [nb_pad][FSTR]
-    unsigned long long* sSum = FLY ? reinterpret_cast<unsigned long long*>(sBf + (size_t)nb_pad * FSTR)
-                                   : reinterpret_cast<unsigned long long*>(sB + (size_t)3 * nb_pad * STR);   // [1024]
-    unsigned int* sCnt = reinterpret_cast<unsigned int*>(sSum + HIST_BINS);        // [1024]
+    unsigned long long* sPk = FLY ? reinterpret_cast<unsigned long long*>(sBf + (size_t)nb_pad * FSTR)
+                                  : reinterpret_cast<unsigned long long*>(sB + (size_t)3 * nb_pad * STR);   // [1024 << copy_shift]
 
-    const int bh = blockIdx.y, b = bh / Hh, h = bh % Hh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hf = lane >> 5;
+    const int hist_copy = lane & ((1 << copy_shift) - 1);
 
-    // block means -> LDS, 16 bytes per lane and four loads in flight per lane (the head's means are one contiguous array)
-    {
+    // block means of head bh -> LDS, 16 bytes per lane and four loads in flight per lane (the head's means are one
+    // contiguous array); clears the histogram words
+    auto load_means = [&](int bh) {
         const f32x4_t* src4 = reinterpret_cast<const f32x4_t*>(Bmean + ((long long)bh * nb_total + jb0) * D);
         const int n4 = nb * D / 4, n4_pad = nb_pad * D / 4;
         for (int i0 = tid; i0 < n4_pad; i0 += 4 * SCORE_NT) {
@@ -291,26 +326,43 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
                 }
             }
         }
-    }
-    for (int i = tid; i < HIST_BINS; i += SCORE_NT) { sCnt[i] = 0u; sSum[i] = 0ull; }
-    __syncthreads();
+        for (int i = tid; i < (HIST_BINS << copy_shift); i += SCORE_NT) sPk[i] = 0ull;
+    };
 
     const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     const int n_tiles = (S + SCORE_QT - 1) / SCORE_QT;
     const bool vec_ok = ((nb_total | jb0) & 3) == 0;         // this launch's part of a row of P starts 16-byte aligned
-    auto load_q = [&](int tile, bf16x8_t(&dst)[KSTEPS]) {
+    // The launch's work is the flat list of (head, query tile) pairs; a workgroup takes one contiguous share of it, so
+    // all shares are equal to within one tile whatever the number of heads, and reloads the means when its share
+    // crosses into the next head.
+    const int n_flat = BH * n_tiles;
+    const int t0 = (int)((long long)blockIdx.x * n_flat / gridDim.x), t1 = (int)((long long)(blockIdx.x + 1) * n_flat / gridDim.x);
+    auto load_q = [&](int flat, bf16x8_t(&dst)[KSTEPS]) {
+        const int bh = flat / n_tiles, tile = flat - bh * n_tiles, b = bh / Hh, h = bh - b * Hh;
         const int qc = min(tile * SCORE_QT + wave * 32 + l32, S - 1);     // rows past the end recompute the last query; never stored
         const char* src = Q.ptr + ((long long)b * Q.stride_b + (long long)qc * Q.stride_s + (long long)h * Q.stride_h) * 2;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) dst[ks] = *reinterpret_cast<const bf16x8_t*>(src + (ks * 16 + hf * 8) * 2);
     };
     bf16x8_t qf[KSTEPS], qn[KSTEPS];
-    if ((int)blockIdx.x < n_tiles) load_q(blockIdx.x, qn);
-    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    if (t0 < t1) load_q(t0, qn);
+    int cur_bh = -1;
+    for (int flat = t0; flat < t1; ++flat) {
+        const int bh = flat / n_tiles, tile = flat - bh * n_tiles;
+        if (bh != cur_bh) {                                            // same decision in every wavefront
+            if (cur_bh >= 0) {
+                __syncthreads();
+                if (hist_cnt) packed_hist_flush(sPk, copy_shift, hist_cnt, hist_sum, cur_bh, fix_shift, tid, SCORE_NT);
+                __syncthreads();
+            }
+            load_means(bh);
+            __syncthreads();
+            cur_bh = bh;
+        }
         const int q = tile * SCORE_QT + wave * 32 + l32;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) qf[ks] = qn[ks];
-        load_q(min(tile + (int)gridDim.x, n_tiles - 1), qn);          // the next tile's rows arrive during this tile's work
+        load_q(min(flat + 1, t1 - 1), qn);                            // the next tile's rows arrive during this tile's work
         f32x16_t acc[MAX_MT];
 #pragma unroll
         for (int mt = 0; mt < MAX_MT; ++mt) acc[mt] = zero16;
@@ -354,23 +406,27 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
                         }
             }
         }
-        // accumulator value v of tile mt <-> block 32*mt + 8*(v>>2) + 4*hf + (v&3)
+        // accumulator value v of tile mt <-> block 32*mt + 8*(v>>2) + 4*hf + (v&3) = 32*mt + 4*hf + c(v).  A value is a
+        // real block (not padding up to the tile) when c(v) < lim, lim = nb - 32*mt - 4*hf; a whole group of four
+        // consecutive blocks when c(v) + 3 < lim.  With NMT fixed, every tile but the last is all real blocks.
+        auto tile_full = [&](int mt) { return NMT > 0 && mt < NMT - 1; };
         if constexpr (RAW) {
             if (q < S) {
                 float* dst = P + ((long long)bh * S + q) * nb_total + jb0;
 #pragma unroll
                 for (int mt = 0; mt < MAX_MT; ++mt) {
                     if (mt < n_mt) {
+                        const int lim = nb - 32 * mt - 4 * hf;
 #pragma unroll
                         for (int g = 0; g < 4; ++g) {
                             const int j0 = mt * 32 + 8 * g + 4 * hf;
-                            if (vec_ok && j0 + 3 < nb) {
+                            if (vec_ok && 8 * g + 3 < lim) {
                                 const f32x4_t o = {acc[mt][4 * g] * score_scale, acc[mt][4 * g + 1] * score_scale,
                                                    acc[mt][4 * g + 2] * score_scale, acc[mt][4 * g + 3] * score_scale};
                                 *reinterpret_cast<f32x4_t*>(dst + j0) = o;
                             } else {
 #pragma unroll
-                                for (int r = 0; r < 4; ++r) if (j0 + r < nb) dst[j0 + r] = acc[mt][4 * g + r] * score_scale;
+                                for (int r = 0; r < 4; ++r) if (8 * g + r < lim) dst[j0 + r] = acc[mt][4 * g + r] * score_scale;
                             }
                         }
                     }
@@ -378,27 +434,36 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
             }
             continue;
         }
-        // accumulator value v of tile mt <-> block 32*mt + 8*(v>>2) + 4*hf + (v&3)
         float m = -INFINITY;
 #pragma unroll
-        for (int mt = 0; mt < MAX_MT; ++mt)
+        for (int mt = 0; mt < MAX_MT; ++mt) {
+            if (mt < n_mt) {
+                const int lim = nb - 32 * mt - 4 * hf;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int j = mt * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-                const float sv = (mt < n_mt && j < nb) ? acc[mt][v] * score_scale : -INFINITY;
-                acc[mt][v] = sv;
-                m = fmaxf(m, sv);
+                for (int v = 0; v < 16; ++v) {
+                    float sv = acc[mt][v] * score_scale;
+                    if (!tile_full(mt)) sv = (8 * (v >> 2) + (v & 3) < lim) ? sv : -INFINITY;
+                    acc[mt][v] = sv;
+                    m = fmaxf(m, sv);
+                }
             }
+        }
         m = fmaxf(m, __shfl_xor(m, 32, 64));
+        // exp(x) for x <= 0 as 2^(x * log2 e): one rounding in the product (relative error of the result below
+        // 1e-7 * |x|, i.e. an absolute error below 1e-7 on every P that is not itself negligible) and the hardware's
+        // 2^x (1 ulp); exp(-inf) = 0 on padding blocks
         float den = 0.f;
 #pragma unroll
-        for (int mt = 0; mt < MAX_MT; ++mt)
+        for (int mt = 0; mt < MAX_MT; ++mt) {
+            if (mt < n_mt) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float e = (mt < n_mt) ? expf(acc[mt][v] - m) : 0.f;     // exp(-inf) = 0 on padding blocks
-                acc[mt][v] = e;
-                den += e;
+                for (int v = 0; v < 16; ++v) {
+                    const float e = __builtin_amdgcn_exp2f((acc[mt][v] - m) * 1.44269504088896340736f);
+                    acc[mt][v] = e;
+                    den += e;
+                }
             }
+        }
         den += __shfl_xor(den, 32, 64);
         if (row_stat && q < S && hf == 0) row_stat[(long long)bh * S + q] = make_float2(m, den);
         if (q < S) {
@@ -407,40 +472,37 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
 #pragma unroll
             for (int mt = 0; mt < MAX_MT; ++mt) {
                 if (mt < n_mt) {
+                    const int lim = nb - 32 * mt - 4 * hf;
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         const int j0 = mt * 32 + 8 * g + 4 * hf;
-                        float pv[4];
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) pv[r] = acc[mt][4 * g + r] * inv_den;
-                        if (vec_ok && j0 + 3 < nb) {
-                            f32x4_t o = {pv[0], pv[1], pv[2], pv[3]};
+                        for (int r = 0; r < 4; ++r) acc[mt][4 * g + r] *= inv_den;
+                        if (vec_ok && (tile_full(mt) || 8 * g + 3 < lim)) {
+                            const f32x4_t o = {acc[mt][4 * g], acc[mt][4 * g + 1], acc[mt][4 * g + 2], acc[mt][4 * g + 3]};
                             *reinterpret_cast<f32x4_t*>(dst + j0) = o;
                         } else {
 #pragma unroll
-                            for (int r = 0; r < 4; ++r) if (j0 + r < nb) dst[j0 + r] = pv[r];
+                            for (int r = 0; r < 4; ++r) if (8 * g + r < lim) dst[j0 + r] = acc[mt][4 * g + r];
                         }
+                    }
+                }
+            }
+            // first radix level.  Padding blocks hold P = 0 and land in bin 0 with the true zeros; that bin has no mass
+            // and is the last of the descending scan, so neither a cut by mass nor one by count ever looks at its count.
+            if (hist_cnt) {
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            if (hist_cnt && j0 + r < nb) {
-                                const unsigned int bin = min(__float_as_uint(pv[r]) >> 20, (unsigned)(HIST_BINS - 1));
-                                atomicAdd(&sCnt[bin], 1u);
-                                atomicAdd(&sSum[bin], to_fixed(pv[r], fix_shift));
-                            }
-                        }
+                for (int mt = 0; mt < MAX_MT; ++mt) {
+                    if (mt < n_mt) {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) packed_hist_add(sPk, copy_shift, hist_copy, acc[mt][v]);
                     }
                 }
             }
         }
     }
     __syncthreads();
-    for (int i = tid; i < HIST_BINS; i += SCORE_NT) {
-        const unsigned int c = sCnt[i];
-        if (c) {
-            atomicAdd(&hist_cnt[(long long)bh * HIST_BINS + i], c);
-            atomicAdd(&hist_sum[(long long)bh * HIST_BINS + i], sSum[i]);
-        }
-    }
+    if (hist_cnt && cur_bh >= 0) packed_hist_flush(sPk, copy_shift, hist_cnt, hist_sum, cur_bh, fix_shift, tid, SCORE_NT);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1181,7 +1243,7 @@ size_t score_lds_bytes(int nb, int D) {
 // compute unit, once per kernel (slot) and device.
 int allow_full_lds(const void* kernel, int slot) {
     static std::mutex mu;
-    static bool done[8][64] = {};
+    static bool done[24][64] = {};
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return VMOBA_ERR_HIP;
     std::lock_guard<std::mutex> lock(mu);
@@ -1254,7 +1316,11 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
     const bool chunked = bf16 && n_blocks > SCORE_CHUNK;
     const int nb_pad = chunked ? SCORE_CHUNK : ((n_blocks + 31) & ~31);
     const bool fly = n_blocks > 128;
-    const size_t lds_mfma = (fly ? (size_t)nb_pad * (D + 4) * 4 : (size_t)3 * nb_pad * (D + 8) * 2) + HIST_BINS * 12;
+    const size_t lds_means = fly ? (size_t)nb_pad * (D + 4) * 4 : (size_t)3 * nb_pad * (D + 8) * 2;
+    // the first radix level of the matrix-core kernel keeps up to 8 replicas of its 8 KB of histogram words, as many as fit
+    int copy_shift = 3;
+    while (copy_shift > 0 && lds_means + ((size_t)HIST_BINS * 8 << copy_shift) > 160 * 1024) --copy_shift;
+    const size_t lds_mfma = lds_means + ((size_t)HIST_BINS * 8 << copy_shift);
     const size_t lds = bf16 ? lds_mfma : score_lds_bytes(n_blocks, D);
     if (lds > 160 * 1024) return VMOBA_ERR_UNSUPPORTED;
     const int BH = B * Hh;
@@ -1305,28 +1371,40 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
                                            score_scale, fix_shift, row_stat);                             \
     } while (0)
     if (bf16) {
-        dim3 mgrid((unsigned)ceil_div64(ceil_div64(S, SCORE_QT), 2), (unsigned)BH);
-#define LAUNCH_SCORE_MFMA(DD, FL, RW, NBC, JB0)                                                           \
+        // one workgroup per compute unit (the LDS holds one), each with an equal share of all (head, query tile) pairs
+        dim3 mgrid((unsigned)std::min<int64_t>((int64_t)BH * ceil_div64(S, SCORE_QT), vmoba_num_cus()));
+#define LAUNCH_SCORE_MFMA(DD, FL, RW, NM, NBC, JB0)                                                       \
     do {                                                                                                  \
-        auto kfn = score_mfma_kernel<DD, FL, RW>;                                                         \
-        if (allow_full_lds((const void*)kfn, 2 + (DD == 128 ? 0 : 3) + (RW ? 2 : FL ? 1 : 0)) != VMOBA_OK) return VMOBA_ERR_HIP; \
-        kfn<<<mgrid, dim3(SCORE_NT), lds, st>>>(Qv, Bmean, P, score_hist, ws.hist_sum, Hh, (int)S, NBC, n_blocks, JB0, \
-                                                score_scale, fix_shift, row_stat);                        \
+        auto kfn = score_mfma_kernel<DD, FL, RW, NM>;                                                     \
+        if (allow_full_lds((const void*)kfn, 2 + (DD == 128 ? 0 : 8) + (RW ? 6 : FL ? 5 : NM - 1)) != VMOBA_OK) return VMOBA_ERR_HIP; \
+        kfn<<<mgrid, dim3(SCORE_NT), lds, st>>>(Qv, Bmean, P, score_hist, ws.hist_sum, BH, Hh, (int)S, NBC, n_blocks, JB0, \
+                                                score_scale, fix_shift, copy_shift, row_stat);            \
+    } while (0)
+        // up to 128 blocks: one instantiation per number of 32-block tiles
+#define LAUNCH_SCORE_TILES(DD)                                                                            \
+    do {                                                                                                  \
+        switch ((n_blocks + 31) / 32) {                                                                   \
+            case 1: LAUNCH_SCORE_MFMA(DD, false, false, 1, n_blocks, 0); break;                           \
+            case 2: LAUNCH_SCORE_MFMA(DD, false, false, 2, n_blocks, 0); break;                           \
+            case 3: LAUNCH_SCORE_MFMA(DD, false, false, 3, n_blocks, 0); break;                           \
+            default: LAUNCH_SCORE_MFMA(DD, false, false, 4, n_blocks, 0); break;                          \
+        }                                                                                                 \
     } while (0)
         if (chunked) {
             // more than 256 blocks: scaled scores chunk by chunk, then the soft-max of the rows and the first radix level
             for (int jb0 = 0; jb0 < n_blocks; jb0 += SCORE_CHUNK) {
                 const int nbc = std::min(SCORE_CHUNK, n_blocks - jb0);
-                if (D == 128) LAUNCH_SCORE_MFMA(128, true, true, nbc, jb0);
-                else LAUNCH_SCORE_MFMA(64, true, true, nbc, jb0);
+                if (D == 128) LAUNCH_SCORE_MFMA(128, true, true, 0, nbc, jb0);
+                else LAUNCH_SCORE_MFMA(64, true, true, 0, nbc, jb0);
                 VMOBA_CHECK_LAUNCH();
             }
             softmax_rows_kernel<<<dim3((unsigned)std::min<int64_t>(ceil_div64(S, 4 * 8), 2048), (unsigned)BH), dim3(256), 0, st>>>(
                 P, score_hist, ws.hist_sum, (int)S, n_blocks, fix_shift, row_stat);
-        } else if (D == 128 && fly) LAUNCH_SCORE_MFMA(128, true, false, n_blocks, 0);
-        else if (D == 128) LAUNCH_SCORE_MFMA(128, false, false, n_blocks, 0);
-        else if (fly) LAUNCH_SCORE_MFMA(64, true, false, n_blocks, 0);
-        else LAUNCH_SCORE_MFMA(64, false, false, n_blocks, 0);
+        } else if (D == 128 && fly) LAUNCH_SCORE_MFMA(128, true, false, 0, n_blocks, 0);
+        else if (D == 128) LAUNCH_SCORE_TILES(128);
+        else if (fly) LAUNCH_SCORE_MFMA(64, true, false, 0, n_blocks, 0);
+        else LAUNCH_SCORE_TILES(64);
+#undef LAUNCH_SCORE_TILES
 #undef LAUNCH_SCORE_MFMA
     } else if (D == 128) LAUNCH_SCORE(128);
     else LAUNCH_SCORE(64);
