@@ -346,10 +346,12 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
     };
     bf16x8_t qf[KSTEPS], qn[KSTEPS];
     if (t0 < t1) load_q(t0, qn);
-    int cur_bh = -1;
+    int cur_bh = -1, since_flush = 0;
+    const int flush_every = max(1, (1 << 20) / (SCORE_QT * nb_pad));   // tiles until a packed histogram word could overflow
     for (int flat = t0; flat < t1; ++flat) {
         const int bh = flat / n_tiles, tile = flat - bh * n_tiles;
-        if (bh != cur_bh) {                                            // same decision in every wavefront
+        if (bh != cur_bh || since_flush >= flush_every) {              // same decision in every wavefront
+            since_flush = 0;
             if (cur_bh >= 0) {
                 __syncthreads();
                 if (hist_cnt) packed_hist_flush(sPk, copy_shift, hist_cnt, hist_sum, cur_bh, fix_shift, tid, SCORE_NT);
@@ -359,6 +361,7 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
             __syncthreads();
             cur_bh = bh;
         }
+        ++since_flush;
         const int q = tile * SCORE_QT + wave * 32 + l32;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) qf[ks] = qn[ks];
@@ -702,65 +705,67 @@ __global__ __launch_bounds__(256) void pool_rescale_kernel(float* __restrict__ P
 }
 
 // Radix levels 1 and 2: histogram of the next 10 bits over the entries whose higher bits
-// equal the prefix found so far.
+// equal the prefix found so far.  The entries of one bin share every bit above the level's trailing bits (10 at level 1,
+// none at level 2), so a bin needs only their number and the sum of those trailing bits: one packed 64-bit LDS atomic
+// per candidate (count in bits 40..63), turned into count and fixed-point sum when the workgroup flushes.
+// Few, large workgroups (one per compute unit over all heads): every workgroup ends with up to two device-wide atomics per
+// bin, and those, not the pass over P, set the time when thousands of workgroups flush.
+constexpr int REFINE_NT = 1024;
 template <int LEVEL>
-__global__ __launch_bounds__(256) void refine_hist_kernel(const float* __restrict__ P, const HeadState* __restrict__ state,
+__global__ __launch_bounds__(REFINE_NT) void refine_hist_kernel(const float* __restrict__ P, const HeadState* __restrict__ state,
                                                           unsigned int* __restrict__ hist_cnt,
                                                           unsigned long long* __restrict__ hist_sum,
                                                           long long pool_size, int fix_shift) {
-    __shared__ unsigned int sCnt[HIST_BINS];
-    __shared__ unsigned long long sSum[HIST_BINS];
+    __shared__ unsigned long long sPk[HIST_BINS];
     const int bh = blockIdx.y;
     const HeadState st = state[bh];
     if (st.all) return;
-    for (int i = threadIdx.x; i < HIST_BINS; i += 256) { sCnt[i] = 0u; sSum[i] = 0ull; }
+    for (int i = threadIdx.x; i < HIST_BINS; i += REFINE_NT) sPk[i] = 0ull;
     __syncthreads();
     constexpr int SHIFT_HI = (LEVEL == 1) ? 20 : 10;
     constexpr int SHIFT_LO = (LEVEL == 1) ? 10 : 0;
+    constexpr unsigned int LOW_MASK = (1u << SHIFT_LO) - 1u;
     const unsigned int want = st.prefix >> SHIFT_HI;
+    auto take = [&](unsigned int u) {
+        if ((u >> SHIFT_HI) == want)
+            atomicAdd(&sPk[(u >> SHIFT_LO) & (HIST_BINS - 1)], PK_ONE | (unsigned long long)(u & LOW_MASK));
+    };
     const u32x4_t* src = reinterpret_cast<const u32x4_t*>(P + (long long)bh * pool_size);
     // 16-byte loads need every head's pool to start on a 16-byte boundary
     const long long n4 = (pool_size % 4 == 0) ? pool_size / 4 : 0;
-    // four 16-byte loads in flight per thread: a workgroup takes runs of 4 * 256 vectors
-    for (long long i0 = (long long)blockIdx.x * 1024 + threadIdx.x; i0 < n4; i0 += (long long)gridDim.x * 1024) {
+    // four 16-byte loads in flight per thread: a workgroup takes runs of 4 * REFINE_NT vectors
+    for (long long i0 = (long long)blockIdx.x * (4 * REFINE_NT) + threadIdx.x; i0 < n4; i0 += (long long)gridDim.x * (4 * REFINE_NT)) {
         u32x4_t v[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const long long i = i0 + 256 * k;
+            const long long i = i0 + REFINE_NT * k;
             const u32x4_t none = {~0u, ~0u, ~0u, ~0u};      // matches no prefix (a NaN pattern; P holds none)
             v[k] = i < n4 ? src[i] : none;
         }
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const unsigned int u[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if ((u[e] >> SHIFT_HI) == want) {
-                    unsigned int bin = (u[e] >> SHIFT_LO) & (HIST_BINS - 1);
-                    atomicAdd(&sCnt[bin], 1u);
-                    atomicAdd(&sSum[bin], to_fixed(__uint_as_float(u[e]), fix_shift));
-                }
-            }
+            take(v[k].x); take(v[k].y); take(v[k].z); take(v[k].w);
         }
     }
     {
         const unsigned int* s1 = reinterpret_cast<const unsigned int*>(P + (long long)bh * pool_size);
-        for (long long i = n4 * 4 + (long long)blockIdx.x * 256 + threadIdx.x; i < pool_size;
-             i += (long long)gridDim.x * 256) {
-            unsigned int u = s1[i];
-            if ((u >> SHIFT_HI) == want) {
-                unsigned int bin = (u >> SHIFT_LO) & (HIST_BINS - 1);
-                atomicAdd(&sCnt[bin], 1u);
-                atomicAdd(&sSum[bin], to_fixed(__uint_as_float(u), fix_shift));
-            }
-        }
+        for (long long i = n4 * 4 + (long long)blockIdx.x * REFINE_NT + threadIdx.x; i < pool_size;
+             i += (long long)gridDim.x * REFINE_NT)
+            take(s1[i]);
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < HIST_BINS; i += 256) {
-        unsigned int c = sCnt[i];
-        if (c) {                               // stays 0 without a histogram
-            atomicAdd(&hist_cnt[(long long)bh * HIST_BINS + i], c);
-            atomicAdd(&hist_sum[(long long)bh * HIST_BINS + i], sSum[i]);
+    for (int i = threadIdx.x; i < HIST_BINS; i += REFINE_NT) {
+        const unsigned long long w = sPk[i];
+        if (w) {
+            const unsigned long long cnt = w >> 40, low = w & (PK_ONE - 1);
+            // every entry of the bin is (lead | its trailing bits) as a float pattern; to_fixed is linear in the
+            // mantissa for a fixed exponent, and the exponent lies in the prefix
+            const unsigned int lead = (want << SHIFT_HI) | ((unsigned int)i << SHIFT_LO);
+            const int e = (int)(lead >> 23), sh = e - 150 + fix_shift;
+            atomicAdd(&hist_cnt[(long long)bh * HIST_BINS + i], (unsigned int)cnt);
+            if (e && sh >= 0)
+                atomicAdd(&hist_sum[(long long)bh * HIST_BINS + i],
+                          (cnt * (unsigned long long)((lead & 0x7fffffu) | 0x800000u) + low) << sh);
         }
     }
 }
@@ -1160,6 +1165,13 @@ __global__ __launch_bounds__(64) void blk_ptr_kernel(const int* __restrict__ blk
     }
 }
 
+// Workgroup i of n runs on XCD i % 8; this index makes the workgroups of one XCD neighbours in the work list, so runs
+// that different workgroups write into the same cache line meet in one L2.
+__device__ __forceinline__ int xcd_contiguous(int i, int n) {
+    const int per = n / 8;
+    return i < per * 8 ? (i % 8) * per + i / 8 : i;
+}
+
 // Fill q_idx (block-major), col_idx and pair_pos (query-major).  One wavefront per 64 queries,
 // lane = query; a ballot per block gives every query its rank inside the wavefront.
 __global__ __launch_bounds__(256) void fill_lists_kernel(const unsigned int* __restrict__ mask, const int* __restrict__ row_ptr,
@@ -1176,7 +1188,7 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(const unsigned int* __r
     __shared__ int sPos[4][FILL_STAGE];
     const int bh = blockIdx.y;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int w = blockIdx.x * 4 + wv;
+    const int w = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + wv;
     const bool active = w < n_waves;
     const int words = (nb + 31) / 32;
     if (active)
@@ -1423,7 +1435,8 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
     unsigned int* hc2 = ws.hist_cnt + (size_t)2 * BH * HIST_BINS;
     unsigned long long* hs1 = ws.hist_sum + (size_t)BH * HIST_BINS;
     unsigned long long* hs2 = ws.hist_sum + (size_t)2 * BH * HIST_BINS;
-    const unsigned refine_gx = (unsigned)std::max<int64_t>(1, std::min<int64_t>(ceil_div64(pool / 4, 1024 * 2), 2048));
+    // at most 2^20 entries per workgroup (the packed histogram words), else as many workgroups as compute units
+    const unsigned refine_gx = (unsigned)std::max<int64_t>(std::max<int64_t>(1, vmoba_num_cus() / BH), ceil_div64(pool, (int64_t)1 << 20));
 
     const unsigned wave_gx = (unsigned)ceil_div64(n_waves, 4);
     const bool local = mode == VMOBA_LOCAL_TOPK || mode == VMOBA_LOCAL_THRESHOLD;
@@ -1443,11 +1456,11 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
     } while (0)
         SCAN_LEVEL(0, ws.hist_cnt, ws.hist_sum);
         VMOBA_CHECK_LAUNCH();
-        refine_hist_kernel<1><<<dim3(refine_gx, BH), dim3(256), 0, st>>>(P, ws.state, hc1, hs1, pool, fix_shift);
+        refine_hist_kernel<1><<<dim3(refine_gx, BH), dim3(REFINE_NT), 0, st>>>(P, ws.state, hc1, hs1, pool, fix_shift);
         VMOBA_CHECK_LAUNCH();
         SCAN_LEVEL(1, hc1, hs1);
         VMOBA_CHECK_LAUNCH();
-        refine_hist_kernel<2><<<dim3(refine_gx, BH), dim3(256), 0, st>>>(P, ws.state, hc2, hs2, pool, fix_shift);
+        refine_hist_kernel<2><<<dim3(refine_gx, BH), dim3(REFINE_NT), 0, st>>>(P, ws.state, hc2, hs2, pool, fix_shift);
         VMOBA_CHECK_LAUNCH();
         SCAN_LEVEL(2, hc2, hs2);
         VMOBA_CHECK_LAUNCH();
