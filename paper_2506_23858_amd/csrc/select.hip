@@ -1179,10 +1179,11 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(const unsigned int* __r
                                                          int* __restrict__ q_idx, int* __restrict__ col_idx,
                                                          int* __restrict__ pair_pos, int S, int nb, int n_waves,
                                                          long long cap) {
-    __shared__ int sBase[4][VMOBA_MAX_BLOCKS];
-    // The query-major entries of a wavefront's 64 rows form one contiguous run of col_idx / pair_pos.  Up to FILL_STAGE
-    // entries they are collected in LDS and written out as whole runs; a lane writing its own row's entries straight to
-    // global memory touches a different cache line in every lane of every store.
+    // The query-major entries of a wavefront's 64 rows form one contiguous run of col_idx / pair_pos.  They are collected
+    // in LDS, a window of FILL_STAGE entries at a time, and written out as whole runs; a lane writing its own row's
+    // entries straight to global memory touches a different cache line in every lane of every store.  A run longer
+    // than the window walks the blocks once per window (the walk is a few hundred instructions; the window size sets
+    // how many wavefronts a compute unit holds).
     constexpr int FILL_STAGE = 2048;
     __shared__ unsigned short sCol[4][FILL_STAGE];
     __shared__ int sPos[4][FILL_STAGE];
@@ -1191,17 +1192,21 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(const unsigned int* __r
     const int w = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + wv;
     const bool active = w < n_waves;
     const int words = (nb + 31) / 32;
-    if (active)
-        for (int j = lane; j < nb; j += 64)
-            sBase[wv][j] = blk_ptr[(long long)bh * (nb + 1) + j] + wcnt[((long long)bh * nb + j) * n_waves + w];
-    __syncthreads();
+    // where this wavefront's entries of block j start in the block-major list: lane l keeps it for blocks l, l + 64, ...
+    // (the walk below reads it with a lane broadcast: no LDS round trip inside the loop)
+    int vbase[VMOBA_MAX_BLOCKS / 64];
+#pragma unroll
+    for (int i = 0; i < VMOBA_MAX_BLOCKS / 64; ++i) {
+        const int j = lane + 64 * i;
+        vbase[i] = (active && j < nb) ? blk_ptr[(long long)bh * (nb + 1) + j] + wcnt[((long long)bh * nb + j) * n_waves + w] : 0;
+    }
     const int q = w * 64 + lane;
     const bool live = active && q < S;
     unsigned int mw[VMOBA_MAX_MASK_WORDS];
 #pragma unroll
     for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd)
         mw[wd] = (live && wd < words) ? mask[((long long)bh * S + q) * words + wd] : 0u;
-    long long r = live ? row_ptr[(long long)bh * (S + 1) + q] : 0;
+    const long long r0 = live ? row_ptr[(long long)bh * (S + 1) + q] : 0;
     const long long seg = (long long)bh * cap;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
     // the wavefront's run of the query-major lists: [run0, run1)
@@ -1210,39 +1215,46 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(const unsigned int* __r
         run0 = row_ptr[(long long)bh * (S + 1) + (long long)w * 64];
         run1 = row_ptr[(long long)bh * (S + 1) + min((long long)w * 64 + 64, (long long)S)];
     }
-    const bool staged = run1 - run0 <= FILL_STAGE && run1 <= cap;       // wave-uniform
-    int lr = (int)(r - run0);                                            // position inside the run
+    const bool staged = run1 <= cap;                                     // wave-uniform; false only for a head that overflowed
+    const int n_run = (int)(run1 - run0);
+    // window 0 always runs (it also writes q_idx); an overflowed head writes its entries below cap one by one
+    for (int win0 = 0; win0 == 0 || (staged && win0 < n_run); win0 += FILL_STAGE) {
+        long long r = r0;
+        int lr = (int)(r0 - run0) - win0;                                // position inside the window
 #pragma unroll
-    for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) {          // word by word, so that a word is one register
-        if (wd * 32 >= nb) continue;
-        const unsigned int word = mw[wd];
-        const int jn = min(32, nb - wd * 32);
-        for (int b = 0; b < jn; ++b) {
-            const int j = wd * 32 + b;
-            const bool bit = (word >> b) & 1u;
-            const unsigned long long bal = __ballot(bit);
-            if (bit) {
-                const long long pos = (long long)sBase[wv][j] + __popcll(bal & lt_mask);
-                if (pos < cap) q_idx[seg + pos] = q;
-                if (staged) {
-                    if (lr < FILL_STAGE) {         // always true: row_ptr is the scan of the rows' bit counts
-                        sCol[wv][lr] = (unsigned short)j;
-                        sPos[wv][lr] = (int)pos;
+        for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) {          // word by word, so that a word is one register
+            if (wd * 32 >= nb) continue;
+            const unsigned int word = mw[wd];
+            const int jn = min(32, nb - wd * 32);
+            for (int b = 0; b < jn; ++b) {
+                const int j = wd * 32 + b;
+                const bool bit = (word >> b) & 1u;
+                const unsigned long long bal = __ballot(bit);
+                const int base_j = __builtin_amdgcn_readlane(vbase[wd >> 1], (wd & 1) * 32 + b);
+                if (bit) {
+                    const long long pos = (long long)base_j + __popcll(bal & lt_mask);
+                    if (win0 == 0 && pos < cap) q_idx[seg + pos] = q;
+                    if (staged) {
+                        if ((unsigned)lr < (unsigned)FILL_STAGE) {
+                            sCol[wv][lr] = (unsigned short)j;
+                            sPos[wv][lr] = (int)pos;
+                        }
+                        ++lr;
+                    } else {
+                        if (r < cap) { col_idx[seg + r] = j; pair_pos[seg + r] = (int)pos; }
+                        ++r;
                     }
-                    ++lr;
-                } else {
-                    if (r < cap) { col_idx[seg + r] = j; pair_pos[seg + r] = (int)pos; }
-                    ++r;
                 }
             }
         }
-    }
-    if (staged) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        const int n = (int)(run1 - run0);
-        for (int i = lane; i < n; i += 64) {
-            col_idx[seg + run0 + i] = sCol[wv][i];
-            pair_pos[seg + run0 + i] = sPos[wv][i];
+        if (staged) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            const int n = min(FILL_STAGE, n_run - win0);
+            for (int i = lane; i < n; i += 64) {
+                col_idx[seg + run0 + win0 + i] = sCol[wv][i];
+                pair_pos[seg + run0 + win0 + i] = sPos[wv][i];
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         }
     }
 }
