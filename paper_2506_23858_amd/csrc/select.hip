@@ -263,6 +263,21 @@ __global__ __launch_bounds__(256) void score_kernel(TensorView Q, const float* _
 // scores themselves into its columns of P -- and softmax_rows_kernel below turns the rows into P afterwards.
 // wavefronts per workgroup of the matrix-core score kernel (two per SIMD share one copy of the block means in LDS)
 constexpr int SCORE_NW = 8, SCORE_NT = 64 * SCORE_NW, SCORE_QT = 32 * SCORE_NW;
+// every value of a lane's rows (N_T tiles of 16) into the packed histogram
+template <int N_T>
+__device__ __forceinline__ void packed_hist_add_rows(unsigned long long* sPk, int copy_shift, int copy, const f32x16_t (&rows)[N_T], int n_mt) {
+#pragma unroll
+    for (int mt = 0; mt < N_T; ++mt) {
+        if (mt < n_mt) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) packed_hist_add(sPk, copy_shift, copy, rows[mt][v]);
+        }
+    }
+}
+template <bool FIRST, class T>
+__device__ __forceinline__ T& pick_ref(T& a, T& b) {
+    if constexpr (FIRST) return a; else return b;
+}
 // NMT > 0: the number of 32-block tiles is that constant (the launch for up to 128 blocks picks the instantiation), so the
 // loops over tiles carry no run-time tests and only the last tile knows padding blocks; NMT = 0: read from nb.
 template <int D, bool FLY, bool RAW, int NMT>
@@ -344,15 +359,47 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) dst[ks] = *reinterpret_cast<const bf16x8_t*>(src + (ks * 16 + hf * 8) * 2);
     };
+    // Order inside a tile: request the next tile's query rows, matrix phase, soft-max arithmetic, then -- only then --
+    // wait for the rows requested a whole tile ago, take them over and store this tile's P.  The stores then drain during
+    // the next tile's arithmetic.  The take-over is written as opaque register moves: as a plain assignment the compiler
+    // turns it into the loop-carried copy at the bottom of the loop, behind the stores, and its wait for the rows there
+    // becomes a wait for every store just issued.
     bf16x8_t qf[KSTEPS], qn[KSTEPS];
-    if (t0 < t1) load_q(t0, qn);
+    auto take_next_rows = [&]() {
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            const u32x4_t src = __builtin_bit_cast(u32x4_t, qn[ks]);
+            unsigned int d0, d1, d2, d3;
+            asm volatile("v_mov_b32 %0, %4\n\tv_mov_b32 %1, %5\n\tv_mov_b32 %2, %6\n\tv_mov_b32 %3, %7"
+                         : "=&v"(d0), "=&v"(d1), "=&v"(d2), "=&v"(d3)
+                         : "v"(src.x), "v"(src.y), "v"(src.z), "v"(src.w));
+            const u32x4_t dst = {d0, d1, d2, d3};
+            qf[ks] = __builtin_bit_cast(bf16x8_t, dst);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    if (t0 < t1) {                                       // the first tile's rows come the same way (the matrix phase then
+        load_q(t0, qn);                                  // never reads a register that a load is still to fill)
+        take_next_rows();
+    }
     int cur_bh = -1, since_flush = 0;
     const int flush_every = max(1, (1 << 20) / (SCORE_QT * nb_pad));   // tiles until a packed histogram word could overflow
+    // A tile's P values stay in `outp` until the NEXT tile's matrix phase is over and are entered into the histogram only
+    // then.  That keeps them in registers of their own: the matrix phase then writes accumulators that no store still
+    // in flight reads (the compiler makes a wavefront wait for such stores before it overwrites their data).
+    // (With NMT = 0 -- up to 8 tiles of accumulators -- there are no registers for a second set: the values stay in the
+    // accumulators and are counted right after their stores.)
+    constexpr bool DEFER = NMT > 0;
+    f32x16_t outp_own[MAX_MT] = {};                                  // never touched unless DEFER
+    bool pending = false;                                             // this lane's outp holds a query's row not yet counted
+    const bool count = !RAW && hist_cnt != nullptr;
     for (int flat = t0; flat < t1; ++flat) {
         const int bh = flat / n_tiles, tile = flat - bh * n_tiles;
         if (bh != cur_bh || since_flush >= flush_every) {              // same decision in every wavefront
             since_flush = 0;
             if (cur_bh >= 0) {
+                if (DEFER && count && pending) packed_hist_add_rows<MAX_MT>(sPk, copy_shift, hist_copy, outp_own, n_mt);
+                pending = false;
                 __syncthreads();
                 if (hist_cnt) packed_hist_flush(sPk, copy_shift, hist_cnt, hist_sum, cur_bh, fix_shift, tid, SCORE_NT);
                 __syncthreads();
@@ -363,9 +410,8 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
         }
         ++since_flush;
         const int q = tile * SCORE_QT + wave * 32 + l32;
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) qf[ks] = qn[ks];
         load_q(min(flat + 1, t1 - 1), qn);                            // the next tile's rows arrive during this tile's work
+        __builtin_amdgcn_sched_barrier(0);                            // requested here, not after the matrix phase
         f32x16_t acc[MAX_MT];
 #pragma unroll
         for (int mt = 0; mt < MAX_MT; ++mt) acc[mt] = zero16;
@@ -398,22 +444,37 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
                 }
             }
             if constexpr (!FLY) {
+                // a batch of fragments is requested before its first matrix instruction, so one LDS latency is paid per
+                // batch, not per instruction; the whole k-step is one batch where the registers allow it
+                constexpr int XB = (NMT > 0 && NMT <= 3) ? 3 : 1;
 #pragma unroll
-                for (int x = 0; x < 3; ++x)
+                for (int x0 = 0; x0 < 3; x0 += XB) {
+                    bf16x8_t bf[XB][MAX_MT];
 #pragma unroll
-                    for (int mt = 0; mt < MAX_MT; ++mt)
-                        if (mt < n_mt) {
-                            const bf16x8_t bf = *reinterpret_cast<const bf16x8_t*>(
-                                &sB[((size_t)x * nb_pad + mt * 32 + l32) * STR + ks * 16 + hf * 8]);
-                            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, qf[ks], acc[mt], 0, 0, 0);
-                        }
+                    for (int x = 0; x < XB; ++x)
+#pragma unroll
+                        for (int mt = 0; mt < MAX_MT; ++mt)
+                            if (mt < n_mt)
+                                bf[x][mt] = *reinterpret_cast<const bf16x8_t*>(
+                                    &sB[((size_t)(x0 + x) * nb_pad + mt * 32 + l32) * STR + ks * 16 + hf * 8]);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int x = 0; x < XB; ++x)
+#pragma unroll
+                        for (int mt = 0; mt < MAX_MT; ++mt)
+                            if (mt < n_mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[x][mt], qf[ks], acc[mt], 0, 0, 0);
+                }
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
+        if (DEFER && count && pending) packed_hist_add_rows<MAX_MT>(sPk, copy_shift, hist_copy, outp_own, n_mt);   // the previous tile's row
+        pending = false;
         // accumulator value v of tile mt <-> block 32*mt + 8*(v>>2) + 4*hf + (v&3) = 32*mt + 4*hf + c(v).  A value is a
         // real block (not padding up to the tile) when c(v) < lim, lim = nb - 32*mt - 4*hf; a whole group of four
         // consecutive blocks when c(v) + 3 < lim.  With NMT fixed, every tile but the last is all real blocks.
         auto tile_full = [&](int mt) { return NMT > 0 && mt < NMT - 1; };
         if constexpr (RAW) {
+            take_next_rows();
             if (q < S) {
                 float* dst = P + ((long long)bh * S + q) * nb_total + jb0;
 #pragma unroll
@@ -468,10 +529,19 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
             }
         }
         den += __shfl_xor(den, 32, 64);
+        take_next_rows();
+        auto& outp = pick_ref<DEFER>(outp_own, acc);
+        {
+            const float inv_den = 1.f / den;
+#pragma unroll
+            for (int mt = 0; mt < MAX_MT; ++mt)
+                if (mt < n_mt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) outp[mt][v] = acc[mt][v] * inv_den;
+        }
         if (row_stat && q < S && hf == 0) row_stat[(long long)bh * S + q] = make_float2(m, den);
         if (q < S) {
             float* dst = P + ((long long)bh * S + q) * nb_total + jb0;
-            const float inv_den = 1.f / den;
 #pragma unroll
             for (int mt = 0; mt < MAX_MT; ++mt) {
                 if (mt < n_mt) {
@@ -479,31 +549,23 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         const int j0 = mt * 32 + 8 * g + 4 * hf;
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) acc[mt][4 * g + r] *= inv_den;
                         if (vec_ok && (tile_full(mt) || 8 * g + 3 < lim)) {
-                            const f32x4_t o = {acc[mt][4 * g], acc[mt][4 * g + 1], acc[mt][4 * g + 2], acc[mt][4 * g + 3]};
+                            const f32x4_t o = {outp[mt][4 * g], outp[mt][4 * g + 1], outp[mt][4 * g + 2], outp[mt][4 * g + 3]};
                             *reinterpret_cast<f32x4_t*>(dst + j0) = o;
                         } else {
 #pragma unroll
-                            for (int r = 0; r < 4; ++r) if (8 * g + r < lim) dst[j0 + r] = acc[mt][4 * g + r];
+                            for (int r = 0; r < 4; ++r) if (8 * g + r < lim) dst[j0 + r] = outp[mt][4 * g + r];
                         }
                     }
                 }
             }
-            // first radix level.  Padding blocks hold P = 0 and land in bin 0 with the true zeros; that bin has no mass
-            // and is the last of the descending scan, so neither a cut by mass nor one by count ever looks at its count.
-            if (hist_cnt) {
-#pragma unroll
-                for (int mt = 0; mt < MAX_MT; ++mt) {
-                    if (mt < n_mt) {
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) packed_hist_add(sPk, copy_shift, hist_copy, acc[mt][v]);
-                    }
-                }
-            }
         }
+        // first radix level, deferred: padding blocks hold P = 0 and land in bin 0 with the true zeros; that bin has no mass
+        // and is the last of the descending scan, so neither a cut by mass nor one by count ever looks at its count.
+        if constexpr (DEFER) pending = q < S;
+        else if (count && q < S) packed_hist_add_rows<MAX_MT>(sPk, copy_shift, hist_copy, acc, n_mt);
     }
+    if (DEFER && count && pending) packed_hist_add_rows<MAX_MT>(sPk, copy_shift, hist_copy, outp_own, n_mt);
     __syncthreads();
     if (hist_cnt && cur_bh >= 0) packed_hist_flush(sPk, copy_shift, hist_cnt, hist_sum, cur_bh, fix_shift, tid, SCORE_NT);
 }
