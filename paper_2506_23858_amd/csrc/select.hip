@@ -36,9 +36,9 @@ struct SelectWs {               // workspace carve-up (device pointers)
     HeadState* state;               // [BH]
     int* ties;                      // [BH][S]   per-row count of entries equal to theta
     int* tie_base;                  // [BH][S+1] exclusive scan of ties
-    int* rowcnt;                    // [BH][S]
+    int* wtot;                      // [BH][n_waves]  pairs kept by each group of 64 queries, then its exclusive scan
     int* wcnt;                      // [BH][n_blocks][n_waves]
-    int* blk_cnt;                   // [BH][n_blocks]
+    int* row_tot;                   // [BH][n_blocks + 1]  totals of the rows of wcnt, then of wtot
     size_t zero_bytes;              // leading bytes (hist + state) cleared on every call
     float2* row_stat;   // [BH * S] {row maximum, row denominator} of the score soft-max (pool soft-max mode)
     float2* pool_stat;  // [BH] {pool maximum, 1 / pool denominator}
@@ -55,18 +55,14 @@ SelectWs carve(void* base, int BH, int64_t S, int nb) {
     w.zero_bytes = off;
     w.ties = (int*)(p + off);                     off += align_up((size_t)BH * S * 4, 256);
     w.tie_base = (int*)(p + off);                 off += align_up((size_t)BH * (S + 1) * 4, 256);
-    w.rowcnt = (int*)(p + off);                   off += align_up((size_t)BH * S * 4, 256);
     int64_t n_waves = ceil_div64(S, 64);
+    w.wtot = (int*)(p + off);                     off += align_up((size_t)BH * n_waves * 4, 256);
     w.wcnt = (int*)(p + off);                     off += align_up((size_t)BH * nb * n_waves * 4, 256);
-    w.blk_cnt = (int*)(p + off);                  off += align_up((size_t)BH * nb * 4, 256);
+    w.row_tot = (int*)(p + off);                  off += align_up((size_t)BH * (nb + 1) * 4, 256);
     w.row_stat = (float2*)(p + off);              off += align_up((size_t)BH * S * 8, 256);
     w.pool_stat = (float2*)(p + off);             off += align_up((size_t)BH * 8, 256);
     w.total = off;
     return w;
-}
-
-__global__ __launch_bounds__(256) void zero_words_kernel(unsigned int* p, size_t n_words) {
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_words; i += (size_t)gridDim.x * 256) p[i] = 0u;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -77,12 +73,19 @@ __global__ __launch_bounds__(256) void zero_words_kernel(unsigned int* p, size_t
 template <bool BF16, int D>
 __global__ __launch_bounds__(256) void block_mean_kernel(TensorView K, const int* __restrict__ blk_off,
                                                          float* __restrict__ Bmean, int Hh, int nb,
-                                                         const int* __restrict__ kv_rows) {
+                                                         const int* __restrict__ kv_rows,
+                                                         unsigned int* __restrict__ zero_words, unsigned int n_zero) {
     constexpr int EPP = BF16 ? 8 : 4;          // elements per 16-byte piece
     constexpr int PIECES = D / EPP;            // pieces per row
     constexpr int GROUPS = 256 / PIECES;
     const int j = blockIdx.x, bh = blockIdx.y;
     const int b = bh / Hh, h = bh % Hh;
+    {   // this workgroup's share of the words that must be zero when the next kernel of the call starts (histograms, state)
+        const unsigned int n_wg = gridDim.x * gridDim.y, wg = bh * gridDim.x + j;
+        const unsigned int per = (n_zero + n_wg - 1) / n_wg;
+        const unsigned int z0 = min(n_zero, wg * per), z1 = min(n_zero, z0 + per);
+        for (unsigned int i = z0 + threadIdx.x; i < z1; i += 256) zero_words[i] = 0u;
+    }
     const int piece = threadIdx.x % PIECES, grp = threadIdx.x / PIECES;
     const int r0 = blk_off[j], r1 = blk_off[j + 1];
     float acc[EPP];
@@ -936,7 +939,7 @@ __device__ __forceinline__ int block_of_position(const int* __restrict__ blk_off
 // sits at block-order position q, else the position of every query (queries kept in the caller's token order).
 __global__ __launch_bounds__(256) void mask_kernel(const float* __restrict__ P, const HeadState* __restrict__ state,
                                                    const int* __restrict__ tie_base, unsigned int* __restrict__ mask,
-                                                   int* __restrict__ rowcnt, int* __restrict__ wcnt,
+                                                   int* __restrict__ wtot, int* __restrict__ wcnt,
                                                    int S, int nb, int n_waves, const int* __restrict__ own_blk_off,
                                                    const int* __restrict__ query_pos) {
     __shared__ unsigned int sGt[4][64][VMOBA_MAX_MASK_WORDS + 1];
@@ -1016,7 +1019,6 @@ __global__ __launch_bounds__(256) void mask_kernel(const float* __restrict__ P, 
     unsigned int mw[VMOBA_MAX_MASK_WORDS];
     const int q = q0 + lane;
     const bool live = lane < rows;
-    int cnt = 0;
     if (live) {
         const bool all_ties = (st.take == st.n_tie);
         int rank = all_ties ? 0 : tie_base[(long long)bh * (S + 1) + q];
@@ -1039,16 +1041,16 @@ __global__ __launch_bounds__(256) void mask_kernel(const float* __restrict__ P, 
                     }
                 }
                 mask[((long long)bh * S + q) * words + wd] = g;
-                cnt += __popc(g);
             }
             mw[wd] = g;
         }
-        rowcnt[(long long)bh * S + q] = cnt;
     } else {
 #pragma unroll
         for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) mw[wd] = 0;
     }
-    // per-block count over the 64 rows of this wavefront (word by word, so that a word is one register)
+    // per-block count over the 64 rows of this wavefront (word by word, so that a word is one register) and their sum,
+    // the number of pairs these 64 queries keep
+    int kept = 0;
 #pragma unroll
     for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) {
         if (wd * 32 < nb) {
@@ -1056,11 +1058,13 @@ __global__ __launch_bounds__(256) void mask_kernel(const float* __restrict__ P, 
             const int jn = min(32, nb - wd * 32);
             for (int bit = 0; bit < jn; ++bit) {
                 const int j = wd * 32 + bit;
-                const unsigned long long bal = __ballot((word >> bit) & 1u);
-                if (lane == 0 && active) wcnt[((long long)bh * nb + j) * n_waves + w] = __popcll(bal);
+                const int c = __popcll(__ballot((word >> bit) & 1u));
+                kept += c;
+                if (lane == 0 && active) wcnt[((long long)bh * nb + j) * n_waves + w] = c;
             }
         }
     }
+    if (lane == 0 && active) wtot[(long long)bh * n_waves + w] = kept;
 }
 
 // Per-query ("local") selection, the block-choice variants of the paper's ablation and of its
@@ -1071,7 +1075,7 @@ __global__ __launch_bounds__(256) void mask_kernel(const float* __restrict__ P, 
 // Same outputs as mask_kernel.
 template <bool LOCAL_TOPK>
 __global__ __launch_bounds__(256) void local_mask_kernel(const float* __restrict__ P, unsigned int* __restrict__ mask,
-                                                         int* __restrict__ rowcnt, int* __restrict__ wcnt,
+                                                         int* __restrict__ wtot, int* __restrict__ wcnt,
                                                          int S, int nb, int n_waves, int topk, float tau,
                                                          const int* __restrict__ own_blk_off, const int* __restrict__ query_pos) {
     constexpr int MAXC = VMOBA_MAX_BLOCKS / 64;
@@ -1126,7 +1130,6 @@ __global__ __launch_bounds__(256) void local_mask_kernel(const float* __restrict
     unsigned int mw[VMOBA_MAX_MASK_WORDS];
     const int q = q0 + lane;
     const bool live = lane < rows;
-    int cnt = 0;
     const int own = (own_blk_off && live) ? block_of_position(own_blk_off, nb, query_pos ? query_pos[q] : q) : -1;
 #pragma unroll
     for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) {
@@ -1135,11 +1138,10 @@ __global__ __launch_bounds__(256) void local_mask_kernel(const float* __restrict
             g = sKeep[wv][lane][wd];
             if (wd == (own >> 5)) g |= 1u << (own & 31);
             mask[((long long)bh * S + q) * words + wd] = g;
-            cnt += __popc(g);
         }
         mw[wd] = g;
     }
-    if (live) rowcnt[(long long)bh * S + q] = cnt;
+    int kept = 0;
 #pragma unroll
     for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) {
         if (wd * 32 < nb) {
@@ -1147,30 +1149,27 @@ __global__ __launch_bounds__(256) void local_mask_kernel(const float* __restrict
             const int jn = min(32, nb - wd * 32);
             for (int bit = 0; bit < jn; ++bit) {
                 const int j = wd * 32 + bit;
-                const unsigned long long bal = __ballot((word >> bit) & 1u);
-                if (lane == 0 && active) wcnt[((long long)bh * nb + j) * n_waves + w] = __popcll(bal);
+                const int c = __popcll(__ballot((word >> bit) & 1u));
+                kept += c;
+                if (lane == 0 && active) wcnt[((long long)bh * nb + j) * n_waves + w] = c;
             }
         }
     }
+    if (lane == 0 && active) wtot[(long long)bh * n_waves + w] = kept;
 }
 
-// k_out / theta_out of the per-query modes: the number of kept pairs is the end of row_ptr.
-__global__ __launch_bounds__(64) void local_k_kernel(const int* __restrict__ row_ptr, long long* __restrict__ k_out,
-                                                     float* __restrict__ theta_out, int BH, int S, int zero_theta) {
-    const int bh = blockIdx.x * 64 + threadIdx.x;
-    if (bh >= BH) return;
-    k_out[bh] = row_ptr[(long long)bh * (S + 1) + S];
-    if (zero_theta) theta_out[bh] = 0.f;
-}
-
-// Exclusive scan of wcnt over the wavefront index for every (head, block) (in place) and the
-// per-block totals.  One workgroup of 256 threads per (block, head).
-__global__ __launch_bounds__(256) void wave_scan_kernel(int* __restrict__ wcnt, int* __restrict__ blk_cnt,
-                                                        int nb, int n_waves) {
+// Offsets of both list forms, in two small launches.
+// wave_scan_kernel, one workgroup per (row, head), rows 0..nb:
+//  * row j < nb: wcnt[j][w] (pairs of block j among the 64 queries of wavefront w) -> its exclusive scan over w, in place:
+//    where wavefront w's entries of block j start inside the block's list; the total is the block's count;
+//  * row nb: wtot[w] (pairs kept by the 64 queries of wavefront w) -> its exclusive scan, in place: where their rows
+//    start in the query-major lists; the total is row_ptr[S].
+__global__ __launch_bounds__(256) void wave_scan_kernel(int* __restrict__ wcnt, int* __restrict__ wtot,
+                                                        int* __restrict__ row_tot, int nb, int n_waves) {
     __shared__ int sW[4];
     __shared__ int sCarry;
     const int j = blockIdx.x, bh = blockIdx.y, t = threadIdx.x;
-    int* col = wcnt + ((long long)bh * nb + j) * n_waves;
+    int* col = j < nb ? wcnt + ((long long)bh * nb + j) * n_waves : wtot + (long long)bh * n_waves;
     if (t == 0) sCarry = 0;
     __syncthreads();
     for (int base = 0; base < n_waves; base += 256) {
@@ -1192,19 +1191,22 @@ __global__ __launch_bounds__(256) void wave_scan_kernel(int* __restrict__ wcnt, 
         if (t == 255) sCarry = excl + v;
         __syncthreads();
     }
-    if (t == 0) blk_cnt[(long long)bh * nb + j] = sCarry;
+    if (t == 0) row_tot[(long long)bh * (nb + 1) + j] = sCarry;
 }
 
-// blk_ptr = exclusive scan of blk_cnt over blocks; capacity check.  One wavefront per head, a run of blocks per lane.
-// A head that kept more than `cap` pairs gets an all-zero blk_ptr -- to the attention calls it selected nothing, so no
-// list entry of it is ever read (the merge kernels recognise the same head by row_ptr[S] > cap) -- and the status word
-// is set.
-__global__ __launch_bounds__(64) void blk_ptr_kernel(const int* __restrict__ blk_cnt, int* __restrict__ blk_ptr,
-                                                     int nb, long long cap, int* __restrict__ dev_status) {
+// blk_ptr = exclusive scan of the block counts, with the capacity check.  One wavefront per head, a run of blocks per
+// lane.  A head that kept more than `cap` pairs gets an all-zero blk_ptr -- to the attention calls it selected nothing,
+// so no list entry of it is ever read (the merge kernels recognise the same head by row_ptr[S] > cap) -- and the status
+// word is set.  Also row_ptr[S], the head's number of pairs; write_k != 0 (per-query modes, or every query keeps its
+// own block: the number of kept pairs is not the k of the cut) copies it to k_out, write_k == 2 also clears theta_out.
+__global__ __launch_bounds__(64) void blk_ptr_kernel(const int* __restrict__ row_tot, int* __restrict__ blk_ptr,
+                                                     int* __restrict__ row_ptr, long long* __restrict__ k_out,
+                                                     float* __restrict__ theta_out, int nb, int S, long long cap,
+                                                     int* __restrict__ dev_status, int write_k) {
     const int bh = blockIdx.x, lane = threadIdx.x;
     const int per = (nb + 63) / 64;                  // consecutive blocks per lane
-    const int j0 = lane * per, j1 = min(nb, j0 + per);
-    const int* cnt = blk_cnt + (long long)bh * nb;
+    const int j0 = min(nb, lane * per), j1 = min(nb, j0 + per);
+    const int* cnt = row_tot + (long long)bh * (nb + 1);
     int* out = blk_ptr + (long long)bh * (nb + 1);
     int mine = 0;
     for (int j = j0; j < j1; ++j) mine += cnt[j];
@@ -1224,6 +1226,9 @@ __global__ __launch_bounds__(64) void blk_ptr_kernel(const int* __restrict__ blk
     if (lane == 0) {
         out[nb] = fits ? (int)total : 0;
         if (!fits) atomicExch(dev_status, (int)VMOBA_ERR_CAPACITY);
+        row_ptr[(long long)bh * (S + 1) + S] = cnt[nb];
+        if (write_k) k_out[bh] = cnt[nb];
+        if (write_k == 2) theta_out[bh] = 0.f;
     }
 }
 
@@ -1236,7 +1241,8 @@ __device__ __forceinline__ int xcd_contiguous(int i, int n) {
 
 // Fill q_idx (block-major), col_idx and pair_pos (query-major).  One wavefront per 64 queries,
 // lane = query; a ballot per block gives every query its rank inside the wavefront.
-__global__ __launch_bounds__(256) void fill_lists_kernel(const unsigned int* __restrict__ mask, const int* __restrict__ row_ptr,
+__global__ __launch_bounds__(256) void fill_lists_kernel(const unsigned int* __restrict__ mask, int* __restrict__ row_ptr,
+                                                         const int* __restrict__ wbase,
                                                          const int* __restrict__ blk_ptr, const int* __restrict__ wcnt,
                                                          int* __restrict__ q_idx, int* __restrict__ col_idx,
                                                          int* __restrict__ pair_pos, int S, int nb, int n_waves,
@@ -1268,15 +1274,23 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(const unsigned int* __r
 #pragma unroll
     for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd)
         mw[wd] = (live && wd < words) ? mask[((long long)bh * S + q) * words + wd] : 0u;
-    const long long r0 = live ? row_ptr[(long long)bh * (S + 1) + q] : 0;
+    // row_ptr of the wavefront's rows: where the wavefront's run of the query-major lists starts (wbase, the scan of the
+    // wavefronts' totals) plus the pairs of the lanes before; written here, row_ptr[S] by the offsets kernel
+    int cnt = 0;
+#pragma unroll
+    for (int wd = 0; wd < VMOBA_MAX_MASK_WORDS; ++wd) cnt += __popc(mw[wd]);
+    int incl = cnt;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += o;
+    }
+    const long long run0 = active ? wbase[(long long)bh * n_waves + w] : 0;
+    const long long run1 = run0 + __shfl(incl, 63, 64);             // the wavefront's run: [run0, run1)
+    const long long r0 = run0 + incl - cnt;
+    if (live) row_ptr[(long long)bh * (S + 1) + q] = (int)r0;
     const long long seg = (long long)bh * cap;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
-    // the wavefront's run of the query-major lists: [run0, run1)
-    long long run0 = 0, run1 = 0;
-    if (active) {
-        run0 = row_ptr[(long long)bh * (S + 1) + (long long)w * 64];
-        run1 = row_ptr[(long long)bh * (S + 1) + min((long long)w * 64 + 64, (long long)S)];
-    }
     const bool staged = run1 <= cap;                                     // wave-uniform; false only for a head that overflowed
     const int n_run = (int)(run1 - run0);
     // window 0 always runs (it also writes q_idx); an overflowed head writes its entries below cap one by one
@@ -1412,6 +1426,7 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
     const int BH = B * Hh;
     SelectWs ws = carve(workspace, BH, S, n_blocks);
     if (workspace_bytes < ws.total) return VMOBA_ERR_WORKSPACE;
+    if (ws.zero_bytes / 4 > (size_t)UINT32_MAX) return VMOBA_ERR_UNSUPPORTED;       // more than 10^5 heads in one call
     if (((uintptr_t)workspace) & 255) return VMOBA_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
     const int n_waves = (int)ceil_div64(S, 64);
@@ -1432,10 +1447,8 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
     }
     const TensorView Qv = make_view(Qp), Kv = make_view(Kp);
 
-    zero_words_kernel<<<dim3(64), dim3(256), 0, st>>>((unsigned int*)workspace, ws.zero_bytes / 4);
-    VMOBA_CHECK_LAUNCH();
-
-#define LAUNCH_MEAN(BF, DD) block_mean_kernel<BF, DD><<<dim3(n_blocks, BH), dim3(256), 0, st>>>(Kv, blk_off, Bmean, Hh, n_blocks, kv_rows)
+    // the block-mean kernel also clears the leading words of the workspace (histograms, head state)
+#define LAUNCH_MEAN(BF, DD) block_mean_kernel<BF, DD><<<dim3(n_blocks, BH), dim3(256), 0, st>>>(Kv, blk_off, Bmean, Hh, n_blocks, kv_rows, (unsigned int*)workspace, (unsigned int)(ws.zero_bytes / 4))
     if (bf16 && D == 128) LAUNCH_MEAN(true, 128);
     else if (bf16 && D == 64) LAUNCH_MEAN(true, 64);
     else if (D == 128) LAUNCH_MEAN(false, 128);
@@ -1516,9 +1529,9 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
     const bool local = mode == VMOBA_LOCAL_TOPK || mode == VMOBA_LOCAL_THRESHOLD;
     if (local) {
         if (mode == VMOBA_LOCAL_TOPK)
-            local_mask_kernel<true><<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, mask, ws.rowcnt, ws.wcnt, (int)S, n_blocks, n_waves, topk, tau, own_off, query_pos);
+            local_mask_kernel<true><<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, mask, ws.wtot, ws.wcnt, (int)S, n_blocks, n_waves, topk, tau, own_off, query_pos);
         else
-            local_mask_kernel<false><<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, mask, ws.rowcnt, ws.wcnt, (int)S, n_blocks, n_waves, topk, tau, own_off, query_pos);
+            local_mask_kernel<false><<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, mask, ws.wtot, ws.wcnt, (int)S, n_blocks, n_waves, topk, tau, own_off, query_pos);
         VMOBA_CHECK_LAUNCH();
     } else {
 #define SCAN_LEVEL(LV, HC, HS)                                                                                        \
@@ -1544,21 +1557,16 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
         VMOBA_CHECK_LAUNCH();
         row_scan_kernel<<<dim3(BH), dim3(SCAN_THREADS), 0, st>>>(ws.ties, ws.tie_base, ws.state, 1, (int)S);
         VMOBA_CHECK_LAUNCH();
-        mask_kernel<<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, ws.state, ws.tie_base, mask, ws.rowcnt, ws.wcnt,
+        mask_kernel<<<dim3(wave_gx, BH), dim3(256), 0, st>>>(P, ws.state, ws.tie_base, mask, ws.wtot, ws.wcnt,
                                                             (int)S, n_blocks, n_waves, own_off, query_pos);
         VMOBA_CHECK_LAUNCH();
     }
-    row_scan_kernel<<<dim3(BH), dim3(SCAN_THREADS), 0, st>>>(ws.rowcnt, row_ptr, ws.state, 0, (int)S);
+    wave_scan_kernel<<<dim3(n_blocks + 1, BH), dim3(256), 0, st>>>(ws.wcnt, ws.wtot, ws.row_tot, n_blocks, n_waves);
     VMOBA_CHECK_LAUNCH();
-    if (local || own_off) {     // the number of kept pairs is not the k of the cut: take it from the lists
-        local_k_kernel<<<dim3((BH + 63) / 64), dim3(64), 0, st>>>(row_ptr, (long long*)k_out, theta_out, BH, (int)S, local ? 1 : 0);
-        VMOBA_CHECK_LAUNCH();
-    }
-    wave_scan_kernel<<<dim3(n_blocks, BH), dim3(256), 0, st>>>(ws.wcnt, ws.blk_cnt, n_blocks, n_waves);
+    blk_ptr_kernel<<<dim3(BH), dim3(64), 0, st>>>(ws.row_tot, blk_ptr, row_ptr, (long long*)k_out, theta_out, n_blocks, (int)S,
+                                                 (long long)nnz_capacity, dev_status, local ? 2 : (own_off ? 1 : 0));
     VMOBA_CHECK_LAUNCH();
-    blk_ptr_kernel<<<dim3(BH), dim3(64), 0, st>>>(ws.blk_cnt, blk_ptr, n_blocks, (long long)nnz_capacity, dev_status);
-    VMOBA_CHECK_LAUNCH();
-    fill_lists_kernel<<<dim3(wave_gx, BH), dim3(256), 0, st>>>(mask, row_ptr, blk_ptr, ws.wcnt, q_idx, col_idx,
+    fill_lists_kernel<<<dim3(wave_gx, BH), dim3(256), 0, st>>>(mask, row_ptr, ws.wtot, blk_ptr, ws.wcnt, q_idx, col_idx,
                                                               pair_pos, (int)S, n_blocks, n_waves,
                                                               (long long)nnz_capacity);
     VMOBA_CHECK_LAUNCH();
