@@ -244,3 +244,40 @@ def test_stress_shape_reduced_heads(tau):
     end of its threshold sweep.  165 blocks: the matrix-core score kernel keeps the block means in LDS as float32."""
     check_layer_sampled("stress", "3d", tau, heads=3, sel_heads=[0, 1, 2] if tau < 0.5 else [1], groups=2 if tau < 0.5 else 1,
                         max_rows=8000, q_in_place=tau >= 0.5)
+
+
+def test_selection_invariants_many_heads_long_workgroup_shares():
+    """Selection alone at a shape no CPU run can follow (64 heads x 20 480 tokens x 250 blocks: 328 M scores), checked
+    through what defines the result (Eq. 4, Eq. 3) with plain torch reductions in float64 on the library's own P.
+    The shape is chosen for the score kernel's bookkeeping: a workgroup's share of the (head, tile) list is 20 tiles
+    of 256 queries x 256 block columns, more than the 16 after which it must flush its packed histogram words, and
+    crosses head boundaries; the refinement passes run with more workgroups per head than compute units / heads."""
+    B, Hh, D, grid, chunk, tau = 1, 64, 128, (20, 32, 32), 82, 0.25
+    S = grid[0] * grid[1] * grid[2]
+    gen = torch.Generator(device="cuda").manual_seed(20250628)
+    Q = torch.randn(B, S, Hh, D, generator=gen, device="cuda").to(torch.bfloat16)
+    K = (2.0 * torch.randn(B, S, Hh, D, generator=gen, device="cuda")).to(torch.bfloat16)
+    plan = vb.LayerPlan(B, Hh, D, grid, (0, 0, 0), chunk, tau, torch.bfloat16, need_bwd=False, kv_in_place=True)
+    nb = plan.nb
+    assert nb == 250
+    plan.partition(Q, K, K)
+    plan.select()
+    torch.cuda.synchronize()
+    assert int(plan.dev_status.item()) == 0
+    shifts = torch.arange(32, device="cuda", dtype=torch.int32)
+    target = tau * S
+    for h in range(Hh):
+        P = plan.P[0, h]
+        theta = float(plan.theta[h].item())
+        k = int(plan.k_out[h].item())
+        assert float((P.double().sum(dim=1) - 1.0).abs().max().item()) < 1e-5, h
+        sel = ((plan.mask[0, h].unsqueeze(-1) >> shifts) & 1).bool().reshape(S, -1)
+        assert not bool(sel[:, nb:].any().item()), h                 # no bit beyond the last block
+        sel = sel[:, :nb]
+        assert int(sel.sum().item()) == k, h
+        assert int(plan.row_ptr[h, S].item()) == k and int(plan.blk_ptr[h, nb].item()) == k, h
+        assert bool(sel[P > theta].all().item()), h                   # everything above theta is kept ...
+        assert not bool(sel[P < theta].any().item()), h               # ... nothing below it
+        mass = float(P[sel].double().sum().item())
+        assert mass >= target - 1e-4, (h, mass, target)               # the kept pairs reach tau * S (Eq. 4) ...
+        assert mass - theta < target + 1e-4, (h, mass, theta)         # ... and would not without the smallest of them
