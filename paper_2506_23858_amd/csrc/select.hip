@@ -289,6 +289,10 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
                                                          unsigned long long* __restrict__ hist_sum,
                                                          int BH, int Hh, int S, int nb, int nb_total, int jb0, float score_scale,
                                                          int fix_shift, int copy_shift, float2* __restrict__ row_stat) {
+    // LDS rows of the bf16 terms are padded by 16 bytes.  Beyond 128 blocks (NMT > 4) only the nb real rows and one row of
+    // zeros are kept -- the lanes of the last tile that stand for padding blocks read the zero row -- which is what lets
+    // three terms of up to 189 blocks fit beside the histogram words.
+    constexpr bool CLAMP = NMT > 4;
     constexpr int STR = D + 8;                 // LDS row stride in bf16 elements
     constexpr int FSTR = D + 4;                // LDS row stride in float elements (FLY)
     constexpr int KSTEPS = D / 16;
@@ -296,10 +300,12 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
     extern __shared__ __align__(16) unsigned char smem[];
     const int nb_pad = NMT > 0 ? NMT * 32 : ((nb + 31) & ~31);
     const int n_mt = NMT > 0 ? NMT : nb_pad / 32;
-    __bf16* sB = reinterpret_cast<__bf16*>(smem);                                  // [3][nb_pad][STR]
+    const int n_rows = CLAMP ? nb + 1 : nb_pad;                   // rows of a term in LDS
+    auto term_at = [&](int x, int row, int el) { return ((size_t)x * n_rows + row) * STR + el; };
+    __bf16* sB = reinterpret_cast<__bf16*>(smem);                                  // [3][n_rows][STR]
     float* sBf = reinterpret_cast<float*>(smem);                                   // FLY: [nb_pad][FSTR]
     unsigned long long* sPk = FLY ? reinterpret_cast<unsigned long long*>(sBf + (size_t)nb_pad * FSTR)
-                                  : reinterpret_cast<unsigned long long*>(sB + (size_t)3 * nb_pad * STR);   // [1024 << copy_shift]
+                                  : reinterpret_cast<unsigned long long*>(sB + (size_t)3 * n_rows * STR);   // [1024 << copy_shift]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hf = lane >> 5;
@@ -309,7 +315,7 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
     // contiguous array); clears the histogram words
     auto load_means = [&](int bh) {
         const f32x4_t* src4 = reinterpret_cast<const f32x4_t*>(Bmean + ((long long)bh * nb_total + jb0) * D);
-        const int n4 = nb * D / 4, n4_pad = nb_pad * D / 4;
+        const int n4 = nb * D / 4, n4_pad = (FLY ? nb_pad : n_rows) * D / 4;      // rows past nb are zeros
         for (int i0 = tid; i0 < n4_pad; i0 += 4 * SCORE_NT) {
             f32x4_t x4[4];
 #pragma unroll
@@ -338,9 +344,9 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
                         m4[e] = xm;
                         l4[e] = (__bf16)r2;
                     }
-                    *reinterpret_cast<bf16x4_t*>(&sB[(0 * nb_pad + j) * STR + d]) = h4;
-                    *reinterpret_cast<bf16x4_t*>(&sB[(1 * nb_pad + j) * STR + d]) = m4;
-                    *reinterpret_cast<bf16x4_t*>(&sB[(2 * nb_pad + j) * STR + d]) = l4;
+                    *reinterpret_cast<bf16x4_t*>(&sB[term_at(0, j, d)]) = h4;
+                    *reinterpret_cast<bf16x4_t*>(&sB[term_at(1, j, d)]) = m4;
+                    *reinterpret_cast<bf16x4_t*>(&sB[term_at(2, j, d)]) = l4;
                 }
             }
         }
@@ -368,7 +374,9 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
     // turns it into the loop-carried copy at the bottom of the loop, behind the stores, and its wait for the rows there
     // becomes a wait for every store just issued.
     bf16x8_t qf[KSTEPS], qn[KSTEPS];
+    constexpr bool EARLY_ROWS = NMT > 0 && NMT <= 4;                  // see the tile loop
     auto take_next_rows = [&]() {
+        if constexpr (!EARLY_ROWS) return;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
             const u32x4_t src = __builtin_bit_cast(u32x4_t, qn[ks]);
@@ -382,17 +390,21 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
         __builtin_amdgcn_sched_barrier(0);
     };
     if (t0 < t1) {                                       // the first tile's rows come the same way (the matrix phase then
-        load_q(t0, qn);                                  // never reads a register that a load is still to fill)
-        take_next_rows();
+        if constexpr (EARLY_ROWS) {                      // never reads a register that a load is still to fill)
+            load_q(t0, qn);
+            take_next_rows();
+        } else {
+            load_q(t0, qf);
+        }
     }
     int cur_bh = -1, since_flush = 0;
     const int flush_every = max(1, (1 << 20) / (SCORE_QT * nb_pad));   // tiles until a packed histogram word could overflow
     // A tile's P values stay in `outp` until the NEXT tile's matrix phase is over and are entered into the histogram only
     // then.  That keeps them in registers of their own: the matrix phase then writes accumulators that no store still
     // in flight reads (the compiler makes a wavefront wait for such stores before it overwrites their data).
-    // (With NMT = 0 -- up to 8 tiles of accumulators -- there are no registers for a second set: the values stay in the
+    // (With more than 3 tiles of accumulators there are no registers for a second set: the values stay in the
     // accumulators and are counted right after their stores.)
-    constexpr bool DEFER = NMT > 0;
+    constexpr bool DEFER = NMT > 0 && NMT <= 3;
     f32x16_t outp_own[MAX_MT] = {};                                  // never touched unless DEFER
     bool pending = false;                                             // this lane's outp holds a query's row not yet counted
     const bool count = !RAW && hist_cnt != nullptr;
@@ -413,8 +425,12 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
         }
         ++since_flush;
         const int q = tile * SCORE_QT + wave * 32 + l32;
-        load_q(min(flat + 1, t1 - 1), qn);                            // the next tile's rows arrive during this tile's work
-        __builtin_amdgcn_sched_barrier(0);                            // requested here, not after the matrix phase
+        // the next tile's rows: requested here, a whole tile before their use, where the registers allow (up to four
+        // 32-block tiles); else after the matrix phase, which leaves the soft-max arithmetic for them to arrive
+        if constexpr (EARLY_ROWS) {
+            load_q(min(flat + 1, t1 - 1), qn);
+            __builtin_amdgcn_sched_barrier(0);                        // requested here, not after the matrix phase
+        }
         f32x16_t acc[MAX_MT];
 #pragma unroll
         for (int mt = 0; mt < MAX_MT; ++mt) acc[mt] = zero16;
@@ -459,7 +475,7 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
                         for (int mt = 0; mt < MAX_MT; ++mt)
                             if (mt < n_mt)
                                 bf[x][mt] = *reinterpret_cast<const bf16x8_t*>(
-                                    &sB[((size_t)(x0 + x) * nb_pad + mt * 32 + l32) * STR + ks * 16 + hf * 8]);
+                                    &sB[term_at(x0 + x, (CLAMP && mt == NMT - 1) ? min(mt * 32 + l32, nb) : mt * 32 + l32, ks * 16 + hf * 8)]);
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int x = 0; x < XB; ++x)
@@ -470,6 +486,10 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
             }
         }
         __builtin_amdgcn_sched_barrier(0);
+        if constexpr (!EARLY_ROWS) {                                  // straight into the registers the matrix phase has just freed
+            load_q(min(flat + 1, t1 - 1), qf);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         if (DEFER && count && pending) packed_hist_add_rows<MAX_MT>(sPk, copy_shift, hist_copy, outp_own, n_mt);   // the previous tile's row
         pending = false;
         // accumulator value v of tile mt <-> block 32*mt + 8*(v>>2) + 4*hf + (v&3) = 32*mt + 4*hf + c(v).  A value is a
@@ -1415,8 +1435,11 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
     constexpr int SCORE_CHUNK = 256;                        // blocks per launch of the score kernel beyond 256 blocks
     const bool chunked = bf16 && n_blocks > SCORE_CHUNK;
     const int nb_pad = chunked ? SCORE_CHUNK : ((n_blocks + 31) & ~31);
-    const bool fly = n_blocks > 128;
-    const size_t lds_means = fly ? (size_t)nb_pad * (D + 4) * 4 : (size_t)3 * nb_pad * (D + 8) * 2;
+    // three bf16 terms of the means in LDS while they fit beside one copy of the histogram words and the accumulators fit
+    // the registers (D = 128: up to 189 blocks; D = 64: 192), else the means as float32, split after every fetch
+    const size_t lds_terms = (size_t)3 * (nb_pad > 128 ? n_blocks + 1 : nb_pad) * (D + 8) * 2;
+    const bool fly = nb_pad > 192 || lds_terms + (size_t)HIST_BINS * 8 > 160 * 1024;
+    const size_t lds_means = fly ? (size_t)nb_pad * (D + 4) * 4 : lds_terms;
     // the first radix level of the matrix-core kernel keeps up to 8 replicas of its 8 KB of histogram words, as many as fit
     int copy_shift = 3;
     while (copy_shift > 0 && lds_means + ((size_t)HIST_BINS * 8 << copy_shift) > 160 * 1024) --copy_shift;
@@ -1475,18 +1498,20 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
 #define LAUNCH_SCORE_MFMA(DD, FL, RW, NM, NBC, JB0)                                                       \
     do {                                                                                                  \
         auto kfn = score_mfma_kernel<DD, FL, RW, NM>;                                                     \
-        if (allow_full_lds((const void*)kfn, 2 + (DD == 128 ? 0 : 8) + (RW ? 6 : FL ? 5 : NM - 1)) != VMOBA_OK) return VMOBA_ERR_HIP; \
+        if (allow_full_lds((const void*)kfn, 2 + (DD == 128 ? 0 : 8) + (RW ? 7 : FL ? 6 : NM - 1)) != VMOBA_OK) return VMOBA_ERR_HIP; \
         kfn<<<mgrid, dim3(SCORE_NT), lds, st>>>(Qv, Bmean, P, score_hist, ws.hist_sum, BH, Hh, (int)S, NBC, n_blocks, JB0, \
                                                 score_scale, fix_shift, copy_shift, row_stat);            \
     } while (0)
-        // up to 128 blocks: one instantiation per number of 32-block tiles
+        // the bf16 terms fit: one instantiation per number of 32-block tiles
 #define LAUNCH_SCORE_TILES(DD)                                                                            \
     do {                                                                                                  \
         switch ((n_blocks + 31) / 32) {                                                                   \
             case 1: LAUNCH_SCORE_MFMA(DD, false, false, 1, n_blocks, 0); break;                           \
             case 2: LAUNCH_SCORE_MFMA(DD, false, false, 2, n_blocks, 0); break;                           \
             case 3: LAUNCH_SCORE_MFMA(DD, false, false, 3, n_blocks, 0); break;                           \
-            default: LAUNCH_SCORE_MFMA(DD, false, false, 4, n_blocks, 0); break;                          \
+            case 4: LAUNCH_SCORE_MFMA(DD, false, false, 4, n_blocks, 0); break;                           \
+            case 5: LAUNCH_SCORE_MFMA(DD, false, false, 5, n_blocks, 0); break;                           \
+            default: LAUNCH_SCORE_MFMA(DD, false, false, 6, n_blocks, 0); break;                          \
         }                                                                                                 \
     } while (0)
         if (chunked) {
