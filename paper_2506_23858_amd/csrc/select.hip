@@ -277,13 +277,41 @@ __device__ __forceinline__ void packed_hist_add_rows(unsigned long long* sPk, in
         }
     }
 }
+// Reduction over the 32 lanes of a wavefront half (lanes 0..31 and 32..63 separately): three steps inside rows of 16
+// lanes by data-parallel primitives (quad swaps, half-row and row mirror), one across the half's two rows.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float half32_max(float x) {
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
+    x = fmaxf(x, dpp_move<0xB1>(x));      // quad_perm [1, 0, 3, 2]
+    x = fmaxf(x, dpp_move<0x4E>(x));      // quad_perm [2, 3, 0, 1]
+    x = fmaxf(x, dpp_move<0x141>(x));     // row_half_mirror
+    x = fmaxf(x, dpp_move<0x140>(x));     // row_mirror
+    const u2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+}
+__device__ __forceinline__ float half32_sum(float x) {
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
+    x += dpp_move<0xB1>(x);
+    x += dpp_move<0x4E>(x);
+    x += dpp_move<0x141>(x);
+    x += dpp_move<0x140>(x);
+    const u2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r.x) + __uint_as_float(r.y);
+}
 template <bool FIRST, class T>
 __device__ __forceinline__ T& pick_ref(T& a, T& b) {
     if constexpr (FIRST) return a; else return b;
 }
 // NMT > 0: the number of 32-block tiles is that constant (the launch for up to 128 blocks picks the instantiation), so the
 // loops over tiles carry no run-time tests and only the last tile knows padding blocks; NMT = 0: read from nb.
-template <int D, bool FLY, bool RAW, int NMT>
+// TR: the accumulators hold S^T (blocks down a lane's registers, the query on the lane: the soft-max of a row is in-lane,
+// and a lane stores 16-byte runs of its row of P) -- needs rows of P that start 16-byte aligned (N_b a multiple of 4).
+// !TR: they hold S (queries down the registers, the block on the lane): a store instruction then writes 128-byte runs of
+// two rows with 4-byte pieces whatever N_b is, and the row maximum and sum take a reduction over 32 lanes.
+template <int D, bool FLY, bool RAW, int NMT, bool TR>
 __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, const float* __restrict__ Bmean,
                                                          float* __restrict__ P, unsigned int* __restrict__ hist_cnt,
                                                          unsigned long long* __restrict__ hist_sum,
@@ -456,9 +484,9 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
                             bm8[i] = xm;
                             bl8[i] = (__bf16)r2;
                         }
-                        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh8, qf[ks], acc[mt], 0, 0, 0);
-                        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bm8, qf[ks], acc[mt], 0, 0, 0);
-                        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bl8, qf[ks], acc[mt], 0, 0, 0);
+                        acc[mt] = TR ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh8, qf[ks], acc[mt], 0, 0, 0) : __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], bh8, acc[mt], 0, 0, 0);
+                        acc[mt] = TR ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bm8, qf[ks], acc[mt], 0, 0, 0) : __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], bm8, acc[mt], 0, 0, 0);
+                        acc[mt] = TR ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bl8, qf[ks], acc[mt], 0, 0, 0) : __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], bl8, acc[mt], 0, 0, 0);
                     }
                 }
             }
@@ -481,7 +509,7 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
                     for (int x = 0; x < XB; ++x)
 #pragma unroll
                         for (int mt = 0; mt < MAX_MT; ++mt)
-                            if (mt < n_mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[x][mt], qf[ks], acc[mt], 0, 0, 0);
+                            if (mt < n_mt) acc[mt] = TR ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[x][mt], qf[ks], acc[mt], 0, 0, 0) : __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], bf[x][mt], acc[mt], 0, 0, 0);
                 }
             }
         }
@@ -496,6 +524,80 @@ __global__ __launch_bounds__(SCORE_NT) void score_mfma_kernel(TensorView Q, cons
         // real block (not padding up to the tile) when c(v) < lim, lim = nb - 32*mt - 4*hf; a whole group of four
         // consecutive blocks when c(v) + 3 < lim.  With NMT fixed, every tile but the last is all real blocks.
         auto tile_full = [&](int mt) { return NMT > 0 && mt < NMT - 1; };
+        if constexpr (!TR) {
+            // accumulator value v of tile mt <-> query row 8*(v>>2) + 4*hf + (v&3) of the wavefront's 32, block 32*mt + l32
+            const int q_w = tile * SCORE_QT + wave * 32 + 4 * hf;         // + 8*(v>>2) + (v&3)
+            float* prow = P + ((long long)bh * S + q_w) * nb_total + jb0 + l32;
+            auto col_ok = [&](int mt) { return tile_full(mt) || mt * 32 + l32 < nb; };
+            if constexpr (RAW) {
+                take_next_rows();
+#pragma unroll
+                for (int mt = 0; mt < MAX_MT; ++mt) {
+                    if (mt < n_mt && col_ok(mt)) {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const int dq = 8 * (v >> 2) + (v & 3);
+                            if (q_w + dq < S) prow[(long long)dq * nb_total + mt * 32] = acc[mt][v] * score_scale;
+                        }
+                    }
+                }
+                continue;
+            }
+            float mrow[16], den[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float t = -INFINITY;
+#pragma unroll
+                for (int mt = 0; mt < MAX_MT; ++mt) {
+                    if (mt < n_mt) {
+                        float sv = acc[mt][v] * score_scale;
+                        if (!tile_full(mt)) sv = col_ok(mt) ? sv : -INFINITY;
+                        acc[mt][v] = sv;
+                        t = fmaxf(t, sv);
+                    }
+                }
+                mrow[v] = half32_max(t);
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float d = 0.f;
+#pragma unroll
+                for (int mt = 0; mt < MAX_MT; ++mt) {
+                    if (mt < n_mt) {
+                        const float e = __builtin_amdgcn_exp2f((acc[mt][v] - mrow[v]) * 1.44269504088896340736f);
+                        acc[mt][v] = e;
+                        d += e;
+                    }
+                }
+                den[v] = half32_sum(d);
+            }
+            take_next_rows();
+            auto& outp = pick_ref<DEFER>(outp_own, acc);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int dq = 8 * (v >> 2) + (v & 3);
+                const bool live = q_w + dq < S;                   // a row past the end repeats the last query: counted as zeros
+                const float inv_den = 1.f / den[v];
+                if (row_stat && live && l32 == 0) row_stat[(long long)bh * S + q_w + dq] = make_float2(mrow[v], den[v]);
+#pragma unroll
+                for (int mt = 0; mt < MAX_MT; ++mt)
+                    if (mt < n_mt) outp[mt][v] = live ? acc[mt][v] * inv_den : 0.f;
+            }
+#pragma unroll
+            for (int mt = 0; mt < MAX_MT; ++mt) {
+                if (mt < n_mt && col_ok(mt)) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int dq = 8 * (v >> 2) + (v & 3);
+                        if (q_w + dq < S) prow[(long long)dq * nb_total + mt * 32] = outp[mt][v];
+                    }
+                }
+            }
+            // padding blocks and rows past the end hold P = 0 and land in bin 0 (see below)
+            if constexpr (DEFER) pending = true;
+            else if (count) packed_hist_add_rows<MAX_MT>(sPk, copy_shift, hist_copy, acc, n_mt);
+            continue;
+        }
         if constexpr (RAW) {
             take_next_rows();
             if (q < S) {
@@ -1363,7 +1465,7 @@ size_t score_lds_bytes(int nb, int D) {
 // compute unit, once per kernel (slot) and device.
 int allow_full_lds(const void* kernel, int slot) {
     static std::mutex mu;
-    static bool done[24][64] = {};
+    static bool done[40][64] = {};
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return VMOBA_ERR_HIP;
     std::lock_guard<std::mutex> lock(mu);
@@ -1495,12 +1597,19 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
     if (bf16) {
         // one workgroup per compute unit (the LDS holds one), each with an equal share of all (head, query tile) pairs
         dim3 mgrid((unsigned)std::min<int64_t>((int64_t)BH * ceil_div64(S, SCORE_QT), vmoba_num_cus()));
-#define LAUNCH_SCORE_MFMA(DD, FL, RW, NM, NBC, JB0)                                                       \
+#define LAUNCH_SCORE_MFMA_T(DD, FL, RW, NM, TRV, NBC, JB0)                                                \
     do {                                                                                                  \
-        auto kfn = score_mfma_kernel<DD, FL, RW, NM>;                                                     \
-        if (allow_full_lds((const void*)kfn, 2 + (DD == 128 ? 0 : 8) + (RW ? 7 : FL ? 6 : NM - 1)) != VMOBA_OK) return VMOBA_ERR_HIP; \
+        auto kfn = score_mfma_kernel<DD, FL, RW, NM, TRV>;                                                \
+        if (allow_full_lds((const void*)kfn, 2 + (TRV ? 0 : 16) + (DD == 128 ? 0 : 8) + (RW ? 7 : FL ? 6 : NM - 1)) != VMOBA_OK) return VMOBA_ERR_HIP; \
         kfn<<<mgrid, dim3(SCORE_NT), lds, st>>>(Qv, Bmean, P, score_hist, ws.hist_sum, BH, Hh, (int)S, NBC, n_blocks, JB0, \
                                                 score_scale, fix_shift, copy_shift, row_stat);            \
+    } while (0)
+        // rows of P that start 16-byte aligned take the kernel with the query on the lane, others the one with the block there
+#define LAUNCH_SCORE_MFMA(DD, FL, RW, NM, NBC, JB0)                                                       \
+    do {                                                                                                  \
+        /* (193..256 blocks in one launch: eight accumulator tiles leave no registers for the reduction's row values) */ \
+        if ((n_blocks & 3) == 0 || (FL && !RW)) LAUNCH_SCORE_MFMA_T(DD, FL, RW, NM, true, NBC, JB0);      \
+        else LAUNCH_SCORE_MFMA_T(DD, FL, RW, NM, false, NBC, JB0);                                        \
     } while (0)
         // the bf16 terms fit: one instantiation per number of 32-block tiles
 #define LAUNCH_SCORE_TILES(DD)                                                                            \
@@ -1530,6 +1639,7 @@ int select_impl(int B, int Hh, int64_t S, int D, int32_t n_blocks, const int32_t
         else LAUNCH_SCORE_TILES(64);
 #undef LAUNCH_SCORE_TILES
 #undef LAUNCH_SCORE_MFMA
+#undef LAUNCH_SCORE_MFMA_T
     } else if (D == 128) LAUNCH_SCORE(128);
     else LAUNCH_SCORE(64);
 #undef LAUNCH_SCORE
