@@ -354,8 +354,8 @@ def test_bf16_blocks_no_longer_than_one_key_group(block):
 
 @pytest.mark.parametrize("tau", [0.5, 0.9])
 def test_bf16_many_blocks_per_row(tau):
-    """64 blocks of 16 tokens; at tau = 0.9 the query-major entries of 64 consecutive rows exceed what the list
-    kernel collects in LDS (it then writes them directly), at 0.5 they fit."""
+    """64 blocks of 16 tokens; at tau = 0.9 the query-major entries of 64 consecutive rows exceed the window the list
+    kernel collects in LDS (it then takes them in several windows), at 0.5 they fit in one."""
     grid, block = (4, 16, 16), (1, 4, 4)
     S = grid[0] * grid[1] * grid[2]
     Q, K, V, dO = (synth.to_bf16_grid(synth.iid_normal(310 + i, (1, S, 2, 128))) for i in range(4))
@@ -377,6 +377,27 @@ def test_bf16_more_than_256_blocks(grid, block, mode, topk):
     Q, K, V, dO = (synth.to_bf16_grid(synth.iid_normal(330 + i, (1, S, 2, 128))) for i in range(4))
     g, o = compare_layer(Q, K, V, dO, grid, block, 0, 0.3, torch.bfloat16, f"many-blocks-{g_nb(grid, block)}", mode=mode, topk=topk)
     assert g["nb"] == g_nb(grid, block) > 256
+
+
+@pytest.mark.parametrize("grid,block,D", [
+    ((6, 11, 4), (1, 1, 2), 128),      # 132 blocks: five 32-block tiles, rows of P 16-byte aligned
+    ((5, 6, 10), (1, 1, 2), 128),      # 150 blocks: five tiles, rows of P not aligned (block on the lane)
+    ((4, 11, 8), (1, 1, 2), 128),      # 176 blocks: six tiles, aligned
+    ((3, 7, 18), (1, 1, 2), 64),       # 189 blocks, the most with the pre-split means; D = 64
+    ((2, 5, 38), (1, 1, 2), 128),      # 190 blocks: means kept as float32
+    ((3, 101, 2), (1, 1, 2), 128),     # 303 blocks: chunked launches with rows of P not aligned
+    ((1, 7, 10), (1, 1, 2), 128),      # 35 blocks: two tiles, not aligned
+    ((3, 7, 10), (1, 1, 2), 64),       # 105 blocks: four tiles, not aligned; D = 64
+])
+def test_bf16_block_counts_across_the_score_kernel_variants(grid, block, D):
+    """The matrix-core score kernel has one instantiation per number of 32-block tiles (1 to 6 with the block means
+    pre-split in LDS), two accumulator layouts (query on the lane for rows of P that start 16-byte aligned, block on
+    the lane otherwise), a float32-means form (190 to 256 blocks) and a chunked form (beyond 256): one case per
+    combination the larger tests do not reach, each against the oracle in full."""
+    S = grid[0] * grid[1] * grid[2]
+    Q, K, V, dO = (synth.to_bf16_grid(synth.iid_normal(350 + i, (1, S, 2, D))) for i in range(4))
+    g, o = compare_layer(Q, K, V, dO, grid, block, 0, 0.3, torch.bfloat16, f"score-variants-{g_nb(grid, block)}")
+    assert g["nb"] == g_nb(grid, block)
 
 
 def g_nb(grid, block):
