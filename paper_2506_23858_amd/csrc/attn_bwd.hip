@@ -1058,22 +1058,28 @@ __device__ __forceinline__ void dkv_tail_body(
     }
 }
 
-// The dK/dV launch, grid (heads, slots): slots [0, runs of the head) run the pair body on one 128-key run each
-// (longest query list first); the next n_blocks slots run the tail body on one block each.  With the head on grid x
-// the hardware hands out slot 0 of every head, then slot 1 of every head, ...: the order is longest-first over the
-// whole launch rather than per head, and the short tail workgroups fill its end, where the long runs finish unevenly.
+// The dK/dV launch.  Every head has `slots` slots: slots [0, runs of the head) run the pair body on one 128-key run each
+// (longest query list first); the next n_blocks slots run the tail body on one block each; the rest do nothing.  Slots
+// are handed out slot group first, head second (see the kernel): the order is longest-first over the whole launch
+// rather than per head, and the short tail workgroups fill its end, where the long runs finish unevenly.
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
     TensorView Q, TensorView K, TensorView V, TensorView dO, const float* __restrict__ LSE, const float* __restrict__ delta,
     const int* __restrict__ blk_off, const int* __restrict__ blk_ptr, const int* __restrict__ q_idx,
     const int* __restrict__ kb_start, const int* __restrict__ kb_order, TensorView dK, TensorView dV, const int* __restrict__ rows, int Hh, int S, int nb, long long cap,
-    float scale_log2, float scale, const int* __restrict__ kv_rows) {
+    float scale_log2, float scale, const int* __restrict__ kv_rows, int BH, int slots, int group) {
     __shared__ __align__(16) char smem[dkv_pair_lds_bytes<D>()];
-    // grid (heads, slots): workgroups are dispatched x-fastest, so slot s of every head starts before slot s + 1 of any --
-    // with each head's runs sorted by length this is a longest-first order over the whole launch, not per head
-    const int bh = (int)blockIdx.x;
+    // One-dimensional grid.  Workgroup i runs on XCD i % 8 as that XCD's workgroup number i / 8.  A head's slots are cut
+    // into groups of `group` consecutive slots (the runs of one key block, when the blocks are equally long); groups are
+    // numbered slot group first, head second -- longest query lists first over the whole launch -- and dealt to the XCDs
+    // in turn, each XCD taking the slots of a group one after the other: the runs of one block, which all walk the same
+    // query list, run at the same time on the same XCD and share its L2.
+    const int xcd = (int)blockIdx.x & 7, n = (int)blockIdx.x >> 3;
+    const int G = (n / group) * 8 + xcd;
+    if (G >= BH * (slots / group)) return;
+    const int bh = G % BH;
+    const int id = (G / BH) * group + n % group;
     const int runs = kb_start[(long long)bh * (nb + 1) + nb];
-    const int id = (int)blockIdx.y;
     if (id < runs)
         dkv_pair_body<D>(smem, bh, id, Q, K, V, dO, LSE, delta, blk_off, blk_ptr, q_idx, kb_start, kb_order, dK, dV, rows, kv_rows, Hh, S, nb, cap, scale_log2, scale);
     else if (id - runs < nb)
@@ -1276,6 +1282,11 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
         VMOBA_CHECK_LAUNCH();
         // a multiple of 8 so that (workgroup id % 8) is the same for every head; + 8 for the per-XCD rounding
         dim3 grid((unsigned)((S / KPW + n_blocks + 7) / 8 * 8 + 8 + (simple ? 0 : n_blocks)), (unsigned)BH);
+        // slots of the matrix-core kernel in groups of one block's runs (the usual block: S / n_blocks keys, a last run of at
+        // most 32 keys goes to the tail workgroups)
+        const int64_t usual = S / n_blocks;
+        const int group = (int)std::max<int64_t>(1, (usual % KPW > 0 && usual % KPW <= 32) ? usual / KPW : ceil_div64(usual, KPW));
+        const int slots = (int)ceil_div64(grid.x, group) * group;
         VMOBA_PROFILE_BEGIN(2, st);
         const int32_t* krows = key_rows ? key_rows : rows;      // row map of dK and dV
 #define DKV_ARGS Qv, Kv, Vv, dOv, LSE, ws.delta, blk_off, blk_ptr, q_idx, ws.kb_start, ws.kb_order, dKv, dVv, krows, Hh, (int)S, n_blocks, (long long)nnz_capacity, scale_log2, softmax_scale, kv_rows
@@ -1283,9 +1294,9 @@ extern "C" int vmoba_attn_bwd(int B, int Hh, int64_t S, int D, int32_t n_blocks,
             if (D == 128) attn_bwd_dkv_simple_kernel<128><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
             else attn_bwd_dkv_simple_kernel<64><<<grid, dim3(64), 0, st>>>(DKV_ARGS);
         } else {
-            const dim3 hgrid(grid.y, grid.x);       // heads on x (see the kernel)
-            if (D == 128) attn_bwd_dkv_kernel<128><<<hgrid, dim3(256), 0, st>>>(DKV_ARGS);
-            else attn_bwd_dkv_kernel<64><<<hgrid, dim3(256), 0, st>>>(DKV_ARGS);
+            const dim3 hgrid((unsigned)(ceil_div64((int64_t)BH * slots, 8) * 8 + 7 * group));   // see the kernel
+            if (D == 128) attn_bwd_dkv_kernel<128><<<hgrid, dim3(256), 0, st>>>(DKV_ARGS, BH, slots, group);
+            else attn_bwd_dkv_kernel<64><<<hgrid, dim3(256), 0, st>>>(DKV_ARGS, BH, slots, group);
         }
 #undef DKV_ARGS
         VMOBA_PROFILE_END(2, st);
