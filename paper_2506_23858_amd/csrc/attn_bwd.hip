@@ -1115,7 +1115,8 @@ __global__ __launch_bounds__(256) void dq_merge_kernel(const float* __restrict__
         for (int u = 0; u < MB; ++u) {
             const float keep = (r + u < r1) ? 1.f : 0.f;
             if constexpr (BF16) {
-                const u32x4_t v = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const uint16_t*>(dQpart) + pair[u] * D + part * 8);
+                // (read once: non-temporal, as in the forward merge)
+                const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(reinterpret_cast<const uint16_t*>(dQpart) + pair[u] * D + part * 8));
                 acc[0] += keep * bf16lo_to_f32(v.x); acc[1] += keep * bf16hi_to_f32(v.x);
                 acc[2] += keep * bf16lo_to_f32(v.y); acc[3] += keep * bf16hi_to_f32(v.y);
                 acc[4] += keep * bf16lo_to_f32(v.z); acc[5] += keep * bf16hi_to_f32(v.z);
