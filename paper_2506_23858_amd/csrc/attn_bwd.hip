@@ -37,8 +37,8 @@ __global__ __launch_bounds__(256) void delta_kernel(TensorView O, TensorView dO,
         const int qs = rows ? rows[q] : q;
         const char* po = O.ptr + ((long long)b * O.stride_b + (long long)qs * O.stride_s + (long long)h * O.stride_h) * (BF16 ? 2 : 4) + part * 16;
         const char* pd = dO.ptr + ((long long)b * dO.stride_b + (long long)qs * dO.stride_s + (long long)h * dO.stride_h) * (BF16 ? 2 : 4) + part * 16;
-        const u32x4_t a = *reinterpret_cast<const u32x4_t*>(po);
-        const u32x4_t c = *reinterpret_cast<const u32x4_t*>(pd);
+        const u32x4_t a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(po));
+        const u32x4_t c = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(pd));
         if (rows) *reinterpret_cast<u32x4_t*>(dO_copy + ((long long)bh * S + q) * D * (BF16 ? 2 : 4) + part * 16) = c;
         if constexpr (BF16) {
             acc = bf16lo_to_f32(a.x) * bf16lo_to_f32(c.x) + bf16hi_to_f32(a.x) * bf16hi_to_f32(c.x) +

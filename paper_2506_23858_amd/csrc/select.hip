@@ -95,7 +95,7 @@ __global__ __launch_bounds__(256) void block_mean_kernel(TensorView K, const int
     for (int r = r0 + grp; r < r1; r += GROUPS) {
         const int row = kv_rows ? kv_rows[r] : r;
         const char* src = base + (long long)row * K.stride_s * (BF16 ? 2 : 4) + piece * 16;
-        u32x4_t v = *reinterpret_cast<const u32x4_t*>(src);
+        u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(src));
         if constexpr (BF16) {
             acc[0] += bf16lo_to_f32(v.x); acc[1] += bf16hi_to_f32(v.x);
             acc[2] += bf16lo_to_f32(v.y); acc[3] += bf16hi_to_f32(v.y);
