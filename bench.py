@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0              # MI355X HBM3E peak (published)
 # HBM bytes per launch of the MFMA kernels at the 480p workload (mean over the 1d/2d/3d partitions, tau = 0.25),
 # from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/layer_480p_tau025_hbm_traffic_pmc.md
 # (FETCH_SIZE scaled by 1.992, WRITE_SIZE by 1.000: the factors kernels of known traffic give in the same runs).
-MEASURED_TRAFFIC_BYTES_480P = {"attn_fwd_tile": 1.969e9, "attn_bwd_dq_tile": 2.958e9, "attn_bwd_dkv": 3.124e9}
+MEASURED_TRAFFIC_BYTES_480P = {"attn_fwd_tile": 1.969e9, "attn_bwd_dq_tile": 2.952e9, "attn_bwd_dkv": 3.121e9}
 METRIC = "VMoBA attn fwd+bwd ms/layer + effective TFLOP/s (%MFMA peak), 480p shape"
 
 
